@@ -1,0 +1,308 @@
+"""ctypes binding of the CPU oracle (oracle/dhq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The GPU library never imports or calls this.
+All arithmetic lives in the C file; this module only marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dhq_oracle.c")
+_LIB = os.path.join(_HERE, "libdhq_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (+OpenMP). Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        _lib = C.CDLL(_LIB)
+        _declare(_lib)
+    return _lib
+
+
+_dp = C.POINTER(C.c_double)
+_fp = C.POINTER(C.c_float)
+_i8p = C.POINTER(C.c_int8)
+_i32p = C.POINTER(C.c_int32)
+
+
+def _declare(L: C.CDLL) -> None:
+    L.dhqo_next_pow2.argtypes = [C.c_int]
+    L.dhqo_next_pow2.restype = C.c_int
+    L.dhqo_qmax.argtypes = [C.c_int]
+    L.dhqo_qmax.restype = C.c_int
+    L.dhqo_hadamard.argtypes = [C.c_int, _dp]
+    L.dhqo_rotate_rows.argtypes = [_dp, C.c_int64, C.c_int, _dp]
+    L.dhqo_rotate_two_sided.argtypes = [_dp, C.c_int, C.c_int, _dp]
+    L.dhqo_absmax_scale.argtypes = [_dp, C.c_int64, C.c_int]
+    L.dhqo_absmax_scale.restype = C.c_float
+    L.dhqo_quantize.argtypes = [_dp, C.c_int64, C.c_float, C.c_int, _i8p]
+    L.dhqo_dequantize.argtypes = [_i8p, C.c_int64, C.c_float, _dp]
+    L.dhqo_dequantize.restype = None
+    L.dhqo_igemm.argtypes = [_i8p, _i8p, C.c_int64, C.c_int, C.c_int, _i32p]
+    L.dhqo_epilogue.argtypes = [_i32p, C.c_int64, C.c_int, C.c_float, C.c_float, _fp, C.c_int,
+                                C.c_float, _fp]
+    L.dhqo_quantize_weights.argtypes = [_fp, C.c_int, C.c_int, C.c_int, _i8p, _fp, _dp]
+    L.dhqo_layer.argtypes = [_fp, C.c_int64, C.c_int, C.c_int, _i8p, C.c_float, _fp, _fp, C.c_int,
+                             C.c_int, C.c_int, C.c_float, _fp, _dp, _i8p, _i32p]
+    L.dhqo_forward.argtypes = [C.c_int, _i32p, C.c_float, C.c_int, C.POINTER(_i8p), _fp,
+                               C.POINTER(_fp), _fp, C.c_int, _fp, C.c_int64, _fp,
+                               C.POINTER(_dp), C.POINTER(_i8p), C.POINTER(_i32p), C.POINTER(_fp)]
+    L.dhqo_mlp_float.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp), _fp,
+                                 C.c_int64, _dp, _fp]
+    L.dhqo_mlp_rotated_f64.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp),
+                                       _fp, C.c_int64, _dp]
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        names = {-1: "invalid argument", -2: "out of memory", -3: "int32 accumulator overflow"}
+        raise OracleError(f"{what}: {names.get(rc, rc)}")
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a: Optional[np.ndarray], ptype):
+    return a.ctypes.data_as(ptype) if a is not None else ptype()
+
+
+def next_pow2(k: int) -> int:
+    return lib().dhqo_next_pow2(int(k))
+
+
+def qmax(bits: int) -> int:
+    return lib().dhqo_qmax(int(bits))
+
+
+def hadamard(n: int) -> np.ndarray:
+    H = np.empty((n, n), dtype=np.float64)
+    _check(lib().dhqo_hadamard(n, _ptr(H, _dp)), "hadamard")
+    return H
+
+
+def rotate_rows(x: np.ndarray) -> np.ndarray:
+    x = _c(np.atleast_2d(x), np.float64)
+    rows, K = x.shape
+    out = np.empty((rows, next_pow2(K)), dtype=np.float64)
+    _check(lib().dhqo_rotate_rows(_ptr(x, _dp), rows, K, _ptr(out, _dp)), "rotate_rows")
+    return out
+
+
+def rotate_two_sided(W: np.ndarray) -> np.ndarray:
+    W = _c(W, np.float64)
+    m, n = W.shape
+    out = np.empty_like(W)
+    _check(lib().dhqo_rotate_two_sided(_ptr(W, _dp), m, n, _ptr(out, _dp)), "rotate_two_sided")
+    return out
+
+
+def absmax_scale(x: np.ndarray, bits: int) -> np.float32:
+    x = _c(x, np.float64)
+    return np.float32(lib().dhqo_absmax_scale(_ptr(x, _dp), x.size, bits))
+
+
+def quantize(x: np.ndarray, s: float, bits: int) -> np.ndarray:
+    x = _c(x, np.float64)
+    q = np.empty(x.shape, dtype=np.int8)
+    _check(lib().dhqo_quantize(_ptr(x, _dp), x.size, C.c_float(s), bits, _ptr(q, _i8p)), "quantize")
+    return q
+
+
+def dequantize(q: np.ndarray, s: float) -> np.ndarray:
+    q = _c(q, np.int8)
+    x = np.empty(q.shape, dtype=np.float64)
+    lib().dhqo_dequantize(_ptr(q, _i8p), q.size, C.c_float(s), _ptr(x, _dp))
+    return x
+
+
+def igemm(q: np.ndarray, w: np.ndarray) -> np.ndarray:
+    q = _c(q, np.int8)
+    w = _c(w, np.int8)
+    N, Kp = q.shape
+    M, Kp2 = w.shape
+    assert Kp == Kp2
+    acc = np.empty((N, M), dtype=np.int32)
+    _check(lib().dhqo_igemm(_ptr(q, _i8p), _ptr(w, _i8p), N, M, Kp, _ptr(acc, _i32p)), "igemm")
+    return acc
+
+
+def epilogue(acc: np.ndarray, s_a: float, s_w: float, b: np.ndarray, apply_sine: bool,
+             omega0: float) -> np.ndarray:
+    acc = _c(acc, np.int32)
+    b = _c(b, np.float32)
+    N, M = acc.shape
+    out = np.empty((N, M), dtype=np.float32)
+    _check(lib().dhqo_epilogue(_ptr(acc, _i32p), N, M, C.c_float(s_a), C.c_float(s_w),
+                               _ptr(b, _fp), int(apply_sine), C.c_float(omega0), _ptr(out, _fp)),
+           "epilogue")
+    return out
+
+
+def quantize_weights(W: np.ndarray, bits: int, want_rot: bool = False):
+    """Rotate over the input dim, per-tensor scale, quantize. Returns (Wq, s_w[, rot])."""
+    W = _c(W, np.float32)
+    M, K = W.shape
+    Kp = next_pow2(K)
+    Wq = np.empty((M, Kp), dtype=np.int8)
+    s = C.c_float(0)
+    rot = np.empty((M, Kp), dtype=np.float64) if want_rot else None
+    _check(lib().dhqo_quantize_weights(_ptr(W, _fp), M, K, bits, _ptr(Wq, _i8p), C.byref(s),
+                                       _ptr(rot, _dp)), "quantize_weights")
+    if want_rot:
+        return Wq, np.float32(s.value), rot
+    return Wq, np.float32(s.value)
+
+
+@dataclass
+class QuantizedNet:
+    dims: List[int]
+    omega0: float
+    bits_w: int
+    bits_a: int
+    Wq: List[np.ndarray]
+    s_w: np.ndarray
+    bias: List[np.ndarray]
+    s_a: Optional[np.ndarray] = None
+
+
+@dataclass
+class ForwardDump:
+    rot: List[np.ndarray] = field(default_factory=list)
+    codes: List[np.ndarray] = field(default_factory=list)
+    acc: List[np.ndarray] = field(default_factory=list)
+    act: List[np.ndarray] = field(default_factory=list)
+
+
+def quantize_net(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int,
+                 W: Sequence[np.ndarray], bias: Sequence[np.ndarray]) -> QuantizedNet:
+    Wq, s_w = [], []
+    for Wl in W:
+        q, s = quantize_weights(Wl, bits_w)
+        Wq.append(q)
+        s_w.append(s)
+    return QuantizedNet(list(dims), float(omega0), bits_w, bits_a, Wq,
+                        np.asarray(s_w, dtype=np.float32),
+                        [_c(b, np.float32) for b in bias])
+
+
+def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump: bool = False):
+    """Quantized forward. With calibrate=True the per-layer activation scales are
+    measured (sequentially, per tensor) and stored in net.s_a. Returns out or (out, dump)."""
+    L = len(net.dims) - 1
+    coords = _c(coords, np.float32)
+    N = coords.shape[0]
+    assert coords.shape[1] == net.dims[0]
+    dimsa = np.asarray(net.dims, dtype=np.int32)
+    if calibrate:
+        s_a = np.zeros(L, dtype=np.float32)
+    else:
+        if net.s_a is None:
+            raise OracleError("forward: activation scales not set")
+        s_a = _c(net.s_a, np.float32).copy()
+    out = np.empty((N, net.dims[-1]), dtype=np.float32)
+    Wq_p = (_i8p * L)(*[_ptr(w, _i8p) for w in net.Wq])
+    b_p = (_fp * L)(*[_ptr(b, _fp) for b in net.bias])
+    d = ForwardDump()
+    rot_p = cod_p = acc_p = act_p = None
+    if dump:
+        for l in range(L):
+            Kp = next_pow2(net.dims[l])
+            d.rot.append(np.empty((N, Kp), dtype=np.float64))
+            d.codes.append(np.empty((N, Kp), dtype=np.int8))
+            d.acc.append(np.empty((N, net.dims[l + 1]), dtype=np.int32))
+            d.act.append(np.empty((N, net.dims[l + 1]), dtype=np.float32))
+        rot_p = (_dp * L)(*[_ptr(a, _dp) for a in d.rot])
+        cod_p = (_i8p * L)(*[_ptr(a, _i8p) for a in d.codes])
+        acc_p = (_i32p * L)(*[_ptr(a, _i32p) for a in d.acc])
+        act_p = (_fp * L)(*[_ptr(a, _fp) for a in d.act])
+    rc = lib().dhqo_forward(L, _ptr(dimsa, _i32p), C.c_float(net.omega0), net.bits_a, Wq_p,
+                            _ptr(net.s_w, _fp), b_p, _ptr(s_a, _fp), int(calibrate),
+                            _ptr(coords, _fp), N, _ptr(out, _fp), rot_p, cod_p, acc_p, act_p)
+    _check(rc, "forward")
+    if calibrate:
+        net.s_a = s_a
+    return (out, d) if dump else out
+
+
+def layer(a_in: np.ndarray, Wq: np.ndarray, s_w: float, bias: np.ndarray, s_a: Optional[float],
+          bits_a: int, apply_sine: bool, omega0: float):
+    """One quantized layer. s_a=None measures the scale on this input.
+    Returns dict(rot, codes, acc, act, s_a)."""
+    a_in = _c(a_in, np.float32)
+    N, K = a_in.shape
+    M, Kp = Wq.shape
+    assert Kp == next_pow2(K)
+    Wq = _c(Wq, np.int8)
+    bias = _c(bias, np.float32)
+    rot = np.empty((N, Kp), dtype=np.float64)
+    codes = np.empty((N, Kp), dtype=np.int8)
+    acc = np.empty((N, M), dtype=np.int32)
+    out = np.empty((N, M), dtype=np.float32)
+    s = C.c_float(0.0 if s_a is None else s_a)
+    rc = lib().dhqo_layer(_ptr(a_in, _fp), N, K, M, _ptr(Wq, _i8p), C.c_float(s_w), _ptr(bias, _fp),
+                          C.byref(s), int(s_a is None), bits_a, int(apply_sine), C.c_float(omega0),
+                          _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p))
+    _check(rc, "layer")
+    return dict(rot=rot, codes=codes, acc=acc, act=out, s_a=np.float32(s.value))
+
+
+def mlp_float(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],
+              bias: Sequence[np.ndarray], coords: np.ndarray, want_f32: bool = True):
+    """Plain un-rotated, un-quantized MLP: returns (out_fp64, out_fp32 or None)."""
+    L = len(dims) - 1
+    Wc = [_c(w, np.float32) for w in W]
+    bc = [_c(b, np.float32) for b in bias]
+    coords = _c(coords, np.float32)
+    N = coords.shape[0]
+    dimsa = np.asarray(dims, dtype=np.int32)
+    o64 = np.empty((N, dims[-1]), dtype=np.float64)
+    o32 = np.empty((N, dims[-1]), dtype=np.float32) if want_f32 else None
+    W_p = (_fp * L)(*[_ptr(w, _fp) for w in Wc])
+    b_p = (_fp * L)(*[_ptr(b, _fp) for b in bc])
+    _check(lib().dhqo_mlp_float(L, _ptr(dimsa, _i32p), C.c_float(omega0), W_p, b_p,
+                                _ptr(coords, _fp), N, _ptr(o64, _dp), _ptr(o32, _fp)), "mlp_float")
+    return o64, o32
+
+
+def mlp_rotated_f64(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],
+                    bias: Sequence[np.ndarray], coords: np.ndarray) -> np.ndarray:
+    """Rotation on, quantizer off (fp64)."""
+    L = len(dims) - 1
+    Wc = [_c(w, np.float32) for w in W]
+    bc = [_c(b, np.float32) for b in bias]
+    coords = _c(coords, np.float32)
+    N = coords.shape[0]
+    dimsa = np.asarray(dims, dtype=np.int32)
+    o64 = np.empty((N, dims[-1]), dtype=np.float64)
+    W_p = (_fp * L)(*[_ptr(w, _fp) for w in Wc])
+    b_p = (_fp * L)(*[_ptr(b, _fp) for b in bc])
+    _check(lib().dhqo_mlp_rotated_f64(L, _ptr(dimsa, _i32p), C.c_float(omega0), W_p, b_p,
+                                      _ptr(coords, _fp), N, _ptr(o64, _dp)), "mlp_rotated_f64")
+    return o64
