@@ -1,0 +1,142 @@
+/*
+ * libdhq -- DHQ (distribution-aware Hadamard quantization) inference of a
+ * SIREN-style coordinate MLP on one AMD MI355X (gfx950).
+ *
+ * The library evaluates f_theta(x) -> y (paper Sec. 2.1) with every linear
+ * layer run as in Sec. 3.2-3.3 of the paper:
+ *
+ *   for each layer l (fan-in K, fan-out M, Kp = next power of two >= K):
+ *     x^  = pad(a_{l-1}) * H_Kp / sqrt(Kp)        Walsh-Hadamard rotation, Eq. 3-5
+ *     q   = clamp(rne(x^ / s_a[l]), -qmax, qmax)  the "standard quantizer", Sec. 3.2
+ *     acc = q * Wq[l]^T   (int8 x int8 -> int32)  MAC array + adder tree, Sec. 3.3
+ *     y   = acc * (s_a[l] * s_w[l]) + b[l]
+ *     a_l = sin(omega0 * y)   (all layers but the last; the last returns y)
+ *
+ * with Wq[l] = clamp(rne((pad(W[l]) * H_Kp / sqrt(Kp)) / s_w[l])) produced once,
+ * offline, by dhq_quantize_weights, and qmax = 2^(bits-1) - 1.  The rotation is
+ * applied over the input-feature dimension of both operands, so it cancels in
+ * the product; all scales are per tensor.
+ *
+ * Conventions
+ *   - Every function returns DHQ_OK (0) or a negative dhq_status; nothing throws
+ *     or aborts.  dhq_strerror() names a status.
+ *   - "host" pointers are ordinary CPU memory, "dev" pointers are device memory
+ *     of the current HIP device, owned by the caller.  Matrices are row-major.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     dhq_forward, dhq_forward_debug and dhq_gemm_i8 only enqueue work on it and
+ *     return without synchronising; dhq_calibrate synchronises the stream.
+ *   - A model owns device buffers (quantized weights, biases, a workspace for the
+ *     layer-by-layer path).  Calls that use the same model concurrently from
+ *     several streams or threads are not supported.
+ *   - Limits: 1 <= n_layers <= 16, every dims[] entry in [1, 512], bits in
+ *     {4, 6, 8}.  Anything else is DHQ_EUNSUPPORTED / DHQ_EINVAL.
+ */
+#ifndef DHQ_H
+#define DHQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DHQ_OK = 0,
+    DHQ_EINVAL = -1,       /* null pointer, negative size, bad bit width, non-finite scale ... */
+    DHQ_EUNSUPPORTED = -2, /* a shape or flag this build has no kernel for */
+    DHQ_ENOMEM = -3,       /* host or device allocation failed */
+    DHQ_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
+    DHQ_ENOSCALE = -5      /* forward called before activation scales exist */
+} dhq_status;
+
+/* dhq_forward flags: which implementation runs.  0 picks the fused kernel when the
+ * network shape has one and the layer-by-layer path otherwise. */
+#define DHQ_AUTO 0u
+#define DHQ_LAYERWISE 1u /* three kernels per layer, activations round-trip device memory */
+#define DHQ_FUSED 2u     /* one kernel for the whole network; DHQ_EUNSUPPORTED if the shape has none */
+
+typedef struct dhq_model dhq_model; /* opaque */
+
+/* Network description (the SIREN of Sec. 3.1: sine after every layer but the last). */
+typedef struct {
+    int32_t n_layers;    /* number of linear layers including the output layer */
+    const int32_t *dims; /* host, n_layers + 1 entries: fan-in of layer 0, then every fan-out */
+    float omega0;        /* sine frequency factor, applied after every layer but the last */
+    int32_t bits_w;      /* weight bit width, 4 / 6 / 8; codes are stored in int8 */
+    int32_t bits_a;      /* activation bit width, 4 / 6 / 8 */
+} dhq_net_desc;
+
+/*
+ * Offline weight step (Sec. 3.2, Eq. 4-5 restricted to the input-feature side;
+ * "a standard quantizer" after the transform): rotates, scales and quantizes
+ * every layer's weights on the host in fp64, uploads them and creates a model.
+ *   W_host[l]  host, dims[l+1] x dims[l] fp32, row-major (out x in)
+ *   b_host[l]  host, dims[l+1] fp32
+ *   *out       receives the model; release it with dhq_free
+ * The inputs are not referenced after the call returns.
+ */
+int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
+                         const float *const *b_host, dhq_model **out);
+
+/* Static per-layer activation scales s_a (host, n_layers entries, each finite and > 0). */
+int dhq_set_act_scales(dhq_model *m, const float *s_a_host);
+
+/*
+ * The "dynamic quantization module" between layers (Sec. 3.3) run once over a
+ * coordinate set: layer by layer, s_a[l] = max|x^| / qmax over the whole rotated
+ * n x Kp input of layer l, that input being produced by the already quantized
+ * layers before it.  An all-zero tensor gets scale 1.  Stores the scales in the
+ * model (as dhq_set_act_scales would).  Synchronises `stream`.
+ *   coords_dev  dev, n x dims[0] fp32
+ */
+int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream);
+
+/* Copies the scales out (either pointer may be NULL): host arrays of n_layers floats.
+ * s_a_host is filled with zeros if no activation scales are set yet. */
+int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_host);
+
+/* Copies layer l's quantized, rotated weights out: host, dims[l+1] x Kp int8, row-major. */
+int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
+
+/*
+ * The hot path (Sec. 3.3 pipeline, all layers): coordinates in, signal values out.
+ *   coords_dev  dev, n x dims[0] fp32
+ *   out_dev     dev, n x dims[n_layers] fp32
+ *   n           number of coordinates; 0 is a successful no-op
+ *   flags       DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED
+ * Uses the activation scales stored in the model (DHQ_ENOSCALE if there are none).
+ */
+int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev,
+                void *stream, uint32_t flags);
+
+/*
+ * Test hook: one layer of the layer-by-layer path on a caller-supplied input,
+ * with every intermediate exposed (any output pointer may be NULL).
+ *   in_dev     dev, n x dims[layer] fp32   (the layer's un-rotated input)
+ *   codes_dev  dev, n x Kp int8            rotated + quantized input
+ *   acc_dev    dev, n x dims[layer+1] int32
+ *   act_dev    dev, n x dims[layer+1] fp32 (after bias and, except for the last layer, sine)
+ * n is limited to the model's workspace chunk (65536 rows).
+ */
+int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_t n, int32_t layer,
+                      int8_t *codes_dev, int32_t *acc_dev, float *act_dev, void *stream);
+
+/*
+ * Test hook: the integer GEMM of one layer alone (Sec. 3.3 MAC array) on
+ * caller-supplied codes: acc = codes * Wq[layer]^T.
+ *   codes_dev  dev, n x Kp int8;  acc_dev  dev, n x dims[layer+1] int32
+ */
+int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int64_t n,
+                int32_t *acc_dev, void *stream);
+
+/* 1 if DHQ_FUSED can run this model's shape, else 0 (negative status on error). */
+int dhq_has_fused(const dhq_model *m);
+
+void dhq_free(dhq_model *m);
+const char *dhq_strerror(int status);
+int dhq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DHQ_H */

@@ -1,0 +1,356 @@
+// Host side of libdhq: the C ABI of include/dhq.h.
+//
+//   dhq_quantize_weights  offline rotation (fast Walsh-Hadamard transform in fp64 over the
+//                         input-feature side, paper Eq. 3-5) + per-tensor symmetric quantizer
+//   dhq_calibrate         per-layer activation scales measured on a coordinate set
+//   dhq_forward           layer-by-layer or fused whole-network evaluation
+//   dhq_forward_debug / dhq_gemm_i8   test hooks exposing one layer's intermediates
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "dhq_internal.h"
+
+#define DHQ_VERSION_NUM 100
+
+static int next_pow2(int k)
+{
+    int p = 1;
+    while (p < k) p <<= 1;
+    return p;
+}
+
+static bool bits_ok(int b) { return b == 4 || b == 6 || b == 8; }
+
+// In-place un-normalised fast Walsh-Hadamard transform of n = 2^k doubles
+// (butterflies over the index bits from the lowest up).
+static void fwht_f64(double *v, int n)
+{
+    for (int h = 1; h < n; h <<= 1)
+        for (int i = 0; i < n; i += 2 * h)
+            for (int j = i; j < i + h; ++j) {
+                const double a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+}
+
+static void free_layer(dhq_layer &L)
+{
+    if (L.wq_dev) (void)hipFree(L.wq_dev);
+    if (L.wfrag_dev) (void)hipFree(L.wfrag_dev);
+    if (L.bias_dev) (void)hipFree(L.bias_dev);
+    if (L.bias_rev_dev) (void)hipFree(L.bias_rev_dev);
+    L.wq_dev = L.wfrag_dev = nullptr;
+    L.bias_dev = L.bias_rev_dev = nullptr;
+}
+
+extern "C" void dhq_free(dhq_model *m)
+{
+    if (!m) return;
+    for (int l = 0; l < m->n_layers; ++l) free_layer(m->layer[l]);
+    if (m->act0) (void)hipFree(m->act0);
+    if (m->act1) (void)hipFree(m->act1);
+    if (m->codes) (void)hipFree(m->codes);
+    if (m->absmax_dev) (void)hipFree(m->absmax_dev);
+    dhq_fused_destroy(m->fused);
+    delete m;
+}
+
+extern "C" const char *dhq_strerror(int status)
+{
+    switch (status) {
+        case DHQ_OK: return "ok";
+        case DHQ_EINVAL: return "invalid argument";
+        case DHQ_EUNSUPPORTED: return "unsupported shape or flag";
+        case DHQ_ENOMEM: return "out of memory";
+        case DHQ_EHIP: return "HIP runtime error";
+        case DHQ_ENOSCALE: return "activation scales not set";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int dhq_version(void) { return DHQ_VERSION_NUM; }
+
+template <typename T>
+static int upload(T **dst, const T *src, size_t count)
+{
+    if (hipMalloc((void **)dst, sizeof(T) * (count ? count : 1)) != hipSuccess) {
+        *dst = nullptr;
+        return DHQ_ENOMEM;
+    }
+    if (count && hipMemcpy(*dst, src, sizeof(T) * count, hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
+    return DHQ_OK;
+}
+
+extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
+                                    const float *const *b_host, dhq_model **out)
+{
+    if (!desc || !W_host || !b_host || !out || !desc->dims) return DHQ_EINVAL;
+    *out = nullptr;
+    const int L = desc->n_layers;
+    if (L < 1) return DHQ_EINVAL;
+    if (L > DHQ_MAX_LAYERS) return DHQ_EUNSUPPORTED;
+    if (!bits_ok(desc->bits_w) || !bits_ok(desc->bits_a)) return DHQ_EINVAL;
+    if (!isfinite(desc->omega0)) return DHQ_EINVAL;
+    for (int l = 0; l <= L; ++l) {
+        if (desc->dims[l] < 1) return DHQ_EINVAL;
+        if (desc->dims[l] > DHQ_MAX_DIM) return DHQ_EUNSUPPORTED;
+    }
+    for (int l = 0; l < L; ++l)
+        if (!W_host[l] || !b_host[l]) return DHQ_EINVAL;
+
+    dhq_model *m = new (std::nothrow) dhq_model();
+    if (!m) return DHQ_ENOMEM;
+    m->n_layers = L;
+    for (int l = 0; l <= L; ++l) m->dims[l] = desc->dims[l];
+    m->omega0 = desc->omega0;
+    m->bits_w = desc->bits_w;
+    m->bits_a = desc->bits_a;
+    m->qmax_a = (1 << (desc->bits_a - 1)) - 1;
+    if (hipGetDevice(&m->device) != hipSuccess) {
+        delete m;
+        return DHQ_EHIP;
+    }
+    const double qmax_w = (double)((1 << (desc->bits_w - 1)) - 1);
+    const double two_pi = 6.283185307179586476925286766559;
+    int rc = DHQ_OK;
+
+    for (int l = 0; l < L && rc == DHQ_OK; ++l) {
+        dhq_layer &Ly = m->layer[l];
+        Ly.K = m->dims[l];
+        Ly.M = m->dims[l + 1];
+        Ly.Kp = next_pow2(Ly.K);
+        Ly.Kb = (Ly.Kp + 31) / 32;
+        Ly.Mt = (Ly.M + 31) / 32;
+        const int K = Ly.K, M = Ly.M, Kp = Ly.Kp;
+        // rotate every row over the input-feature dimension: W^ = pad(W) H_Kp / sqrt(Kp)
+        std::vector<double> rot((size_t)M * Kp, 0.0);
+        const double inv = 1.0 / sqrt((double)Kp);
+        double amax = 0.0;
+        for (int r = 0; r < M; ++r) {
+            double *row = rot.data() + (size_t)r * Kp;
+            for (int k = 0; k < K; ++k) {
+                const float w = W_host[l][(size_t)r * K + k];
+                if (!isfinite(w)) rc = DHQ_EINVAL;
+                row[k] = (double)w;
+            }
+            fwht_f64(row, Kp);
+            for (int k = 0; k < Kp; ++k) {
+                row[k] *= inv;
+                const double a = fabs(row[k]);
+                if (a > amax) amax = a;
+            }
+        }
+        if (rc != DHQ_OK) break;
+        Ly.s_w = amax == 0.0 ? 1.0f : (float)(amax / qmax_w);
+        // the quantizer: clamp(rne(w^ / s_w)); nearbyint rounds half to even
+        Ly.wq_host.resize((size_t)M * Kp);
+        const double sd = (double)Ly.s_w;
+        for (size_t i = 0; i < rot.size(); ++i) {
+            double q = nearbyint(rot[i] / sd);
+            if (q > qmax_w) q = qmax_w;
+            if (q < -qmax_w) q = -qmax_w;
+            Ly.wq_host[i] = (int8_t)q;
+        }
+        // MFMA A fragments, natural k order: lane (i, u) of (tile T, k block kb) holds
+        // Wq[32T + i][32 kb + 16 u .. + 15]
+        std::vector<int8_t> frag((size_t)Ly.Mt * Ly.Kb * 1024, 0);
+        for (int T = 0; T < Ly.Mt; ++T)
+            for (int kb = 0; kb < Ly.Kb; ++kb)
+                for (int ln = 0; ln < 64; ++ln) {
+                    const int row = 32 * T + (ln & 31);
+                    if (row >= M) continue;
+                    for (int jj = 0; jj < 16; ++jj) {
+                        const int k = 32 * kb + 16 * (ln >> 5) + jj;
+                        if (k < Kp)
+                            frag[((size_t)(T * Ly.Kb + kb) * 64 + ln) * 16 + jj] = Ly.wq_host[(size_t)row * Kp + k];
+                    }
+                }
+        Ly.bias_host.assign(b_host[l], b_host[l] + M);
+        Ly.bias_rev_host.resize(M);
+        for (int j = 0; j < M; ++j) {
+            if (!isfinite(b_host[l][j])) rc = DHQ_EINVAL;
+            Ly.bias_rev_host[j] = (float)((double)b_host[l][j] * (double)m->omega0 / two_pi);
+        }
+        if (rc != DHQ_OK) break;
+        rc = upload(&Ly.wq_dev, Ly.wq_host.data(), Ly.wq_host.size());
+        if (rc == DHQ_OK) rc = upload(&Ly.wfrag_dev, frag.data(), frag.size());
+        if (rc == DHQ_OK) rc = upload(&Ly.bias_dev, Ly.bias_host.data(), (size_t)M);
+        if (rc == DHQ_OK) rc = upload(&Ly.bias_rev_dev, Ly.bias_rev_host.data(), (size_t)M);
+        if (M > m->max_dim) m->max_dim = M;
+        if (K > m->max_dim) m->max_dim = K;
+        if (Kp > m->max_kp) m->max_kp = Kp;
+    }
+    if (rc == DHQ_OK) {
+        const size_t act_bytes = sizeof(float) * (size_t)DHQ_CHUNK * m->max_dim;
+        if (hipMalloc((void **)&m->act0, act_bytes) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->act1, act_bytes) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->codes, (size_t)DHQ_CHUNK * m->max_kp) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->absmax_dev, sizeof(unsigned)) != hipSuccess) rc = DHQ_ENOMEM;
+    }
+    if (rc == DHQ_OK) rc = dhq_fused_create(m, &m->fused);
+    if (rc != DHQ_OK) {
+        dhq_free(m);
+        return rc;
+    }
+    *out = m;
+    return DHQ_OK;
+}
+
+extern "C" int dhq_set_act_scales(dhq_model *m, const float *s_a_host)
+{
+    if (!m || !s_a_host) return DHQ_EINVAL;
+    for (int l = 0; l < m->n_layers; ++l)
+        if (!(s_a_host[l] > 0.0f) || !isfinite(s_a_host[l])) return DHQ_EINVAL;
+    for (int l = 0; l < m->n_layers; ++l) m->layer[l].s_a = s_a_host[l];
+    m->have_scales = true;
+    return dhq_fused_update_scales(m, m->fused);
+}
+
+extern "C" int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_host)
+{
+    if (!m) return DHQ_EINVAL;
+    for (int l = 0; l < m->n_layers; ++l) {
+        if (s_w_host) s_w_host[l] = m->layer[l].s_w;
+        if (s_a_host) s_a_host[l] = m->have_scales ? m->layer[l].s_a : 0.0f;
+    }
+    return DHQ_OK;
+}
+
+extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host)
+{
+    if (!m || !Wq_host || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    const dhq_layer &Ly = m->layer[layer];
+    memcpy(Wq_host, Ly.wq_host.data(), Ly.wq_host.size());
+    return DHQ_OK;
+}
+
+extern "C" int dhq_has_fused(const dhq_model *m)
+{
+    if (!m) return DHQ_EINVAL;
+    return m->fused ? 1 : 0;
+}
+
+// Per-layer constants of the layer-by-layer kernels.
+static float quant_inv(const dhq_layer &Ly) { return (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp))); }
+
+static float epi_c1(const dhq_model *m, int l)
+{
+    const dhq_layer &Ly = m->layer[l];
+    const double sc = (double)Ly.s_a * (double)Ly.s_w;
+    const double two_pi = 6.283185307179586476925286766559;
+    return l == m->n_layers - 1 ? (float)sc : (float)(sc * (double)m->omega0 / two_pi);
+}
+
+// Runs layers [0, upto) of the layer-by-layer path on `rows` coordinates of one chunk.
+// The result of layer upto-1 lands in *result (one of the workspace buffers, or `final_out`
+// for the network's last layer when it is given).
+static hipError_t run_layers(const dhq_model *m, const float *in, int64_t rows, int upto, float *final_out,
+                             const float **result, hipStream_t st)
+{
+    const float *cur = in;
+    float *bufs[2] = {m->act0, m->act1};
+    int which = 0;
+    for (int l = 0; l < upto; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const bool last = (l == m->n_layers - 1);
+        hipError_t e = dhq_launch_wht_quant(cur, rows, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, m->codes, nullptr, st);
+        if (e != hipSuccess) return e;
+        float *dst = (last && final_out) ? final_out : bufs[which];
+        e = dhq_launch_gemm(Ly, m->codes, rows, nullptr, dst, epi_c1(m, l), last ? Ly.bias_dev : Ly.bias_rev_dev, !last, st);
+        if (e != hipSuccess) return e;
+        cur = dst;
+        which ^= 1;
+    }
+    *result = cur;
+    return hipSuccess;
+}
+
+extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream)
+{
+    if (!m || n < 0 || (n > 0 && !coords_dev)) return DHQ_EINVAL;
+    if (n == 0) return DHQ_EINVAL;  // a scale cannot be measured on nothing
+    hipStream_t st = (hipStream_t)stream;
+    const int K0 = m->dims[0];
+    for (int l = 0; l < m->n_layers; ++l) {
+        dhq_layer &Ly = m->layer[l];
+        if (hipMemsetAsync(m->absmax_dev, 0, sizeof(unsigned), st) != hipSuccess) return DHQ_EHIP;
+        for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
+            const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;
+            const float *res = nullptr;
+            // the input of layer l is the output of the already calibrated quantized layers before it
+            if (run_layers(m, coords_dev + off * K0, rows, l, nullptr, &res, st) != hipSuccess) return DHQ_EHIP;
+            if (dhq_launch_wht_quant(res, rows, Ly.K, Ly.Kp, 0.0f, m->qmax_a, nullptr, m->absmax_dev, st) != hipSuccess)
+                return DHQ_EHIP;
+        }
+        unsigned bits = 0;
+        if (hipMemcpyAsync(&bits, m->absmax_dev, sizeof(unsigned), hipMemcpyDeviceToHost, st) != hipSuccess) return DHQ_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return DHQ_EHIP;
+        float mx;
+        memcpy(&mx, &bits, sizeof(float));
+        // the kernel's transform is un-normalised: max|x^| = mx / sqrt(Kp)
+        const double amax = (double)mx / sqrt((double)Ly.Kp);
+        Ly.s_a = amax == 0.0 ? 1.0f : (float)(amax / (double)m->qmax_a);
+    }
+    m->have_scales = true;
+    return dhq_fused_update_scales(m, m->fused);
+}
+
+extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, void *stream,
+                           uint32_t flags)
+{
+    if (!m || n < 0) return DHQ_EINVAL;
+    if (flags > DHQ_FUSED) return DHQ_EINVAL;
+    if (n == 0) return DHQ_OK;
+    if (!coords_dev || !out_dev) return DHQ_EINVAL;
+    if (!m->have_scales) return DHQ_ENOSCALE;
+    hipStream_t st = (hipStream_t)stream;
+    if (flags == DHQ_FUSED && !m->fused) return DHQ_EUNSUPPORTED;
+    if (flags != DHQ_LAYERWISE && m->fused)
+        return dhq_fused_launch(m, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    const int K0 = m->dims[0], Mo = m->dims[m->n_layers];
+    for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
+        const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;
+        const float *res = nullptr;
+        if (run_layers(m, coords_dev + off * K0, rows, m->n_layers, out_dev + off * Mo, &res, st) != hipSuccess)
+            return DHQ_EHIP;
+    }
+    return DHQ_OK;
+}
+
+extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_t n, int32_t layer, int8_t *codes_dev,
+                                 int32_t *acc_dev, float *act_dev, void *stream)
+{
+    if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    if (n > DHQ_CHUNK) return DHQ_EUNSUPPORTED;
+    if (n == 0) return DHQ_OK;
+    if (!in_dev) return DHQ_EINVAL;
+    if (!m->have_scales) return DHQ_ENOSCALE;
+    hipStream_t st = (hipStream_t)stream;
+    const dhq_layer &Ly = m->layer[layer];
+    const bool last = (layer == m->n_layers - 1);
+    int8_t *codes = codes_dev ? codes_dev : m->codes;
+    if (dhq_launch_wht_quant(in_dev, n, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, codes, nullptr, st) != hipSuccess) return DHQ_EHIP;
+    if (!acc_dev && !act_dev) return DHQ_OK;
+    // the int32 accumulators go through the workspace when the caller does not want them
+    int32_t *acc = acc_dev ? acc_dev : reinterpret_cast<int32_t *>(m->act0);
+    if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, false, st) != hipSuccess) return DHQ_EHIP;
+    if (act_dev &&
+        dhq_launch_epilogue(acc, n, Ly.M, epi_c1(m, layer), last ? Ly.bias_dev : Ly.bias_rev_dev, !last, act_dev, st) != hipSuccess)
+        return DHQ_EHIP;
+    return DHQ_OK;
+}
+
+extern "C" int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int64_t n, int32_t *acc_dev,
+                           void *stream)
+{
+    if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    if (n == 0) return DHQ_OK;
+    if (!codes_dev || !acc_dev) return DHQ_EINVAL;
+    return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, false, (hipStream_t)stream) == hipSuccess
+               ? DHQ_OK
+               : DHQ_EHIP;
+}

@@ -1,0 +1,50 @@
+// Device-side helpers shared by the layer-by-layer kernels and the fused kernel.
+#ifndef DHQ_DEVICE_H
+#define DHQ_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef int dhq_v4i __attribute__((ext_vector_type(4)));
+typedef int dhq_v16i __attribute__((ext_vector_type(16)));
+
+// 1.5 * 2^23: adding it to a float |v| < 2^22 leaves round-half-to-even(v) in the low
+// mantissa bits, because the sum's unit in the last place is exactly 1.
+#define DHQ_MAGIC_F 12582912.0f
+#define DHQ_MAGIC_I 0x4B400000
+
+// The quantizer of Sec. 3.2 (symmetric, round-half-to-even, clamp to +-qmax) on one value:
+// returns an int whose low byte is the two's-complement code.
+// One fused multiply-add rounds x*inv to an integer exactly once (no double rounding);
+// float bit patterns of positive floats are ordered like integers and negative floats are
+// negative integers, so one integer clamp also handles values far outside the range.
+__device__ __forceinline__ int dhq_quant_bits(float x, float inv, int qmax)
+{
+    float t = __builtin_fmaf(x, inv, DHQ_MAGIC_F);
+    int b = __float_as_int(t);
+    return min(max(b, DHQ_MAGIC_I - qmax), DHQ_MAGIC_I + qmax);
+}
+
+// Packs the low bytes of four quantizer results into one dword (byte 0 = a).
+__device__ __forceinline__ unsigned dhq_pack4(int a, int b, int c, int d)
+{
+    unsigned lo = __builtin_amdgcn_perm((unsigned)b, (unsigned)a, 0x0c0c0400u);
+    unsigned hi = __builtin_amdgcn_perm((unsigned)d, (unsigned)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// sin(2 pi t): the hardware sine takes its argument in revolutions (valid for |t| <= 256).
+__device__ __forceinline__ float dhq_sin_rev(float t)
+{
+    return __builtin_amdgcn_sinf(t);
+}
+
+// Dequantize + bias (+ sine), Sec. 3.3.  For sine layers c1 and bias are pre-multiplied by
+// omega0 / (2 pi) on the host, so the fused multiply-add yields the argument in revolutions.
+__device__ __forceinline__ float dhq_epilogue(int acc, float c1, float bias, bool sine)
+{
+    float y = __builtin_fmaf((float)acc, c1, bias);
+    return sine ? dhq_sin_rev(y) : y;
+}
+
+#endif

@@ -1,0 +1,397 @@
+// Whole-network fused DHQ forward for gfx950 (paper Sec. 3.3 pipeline: input layer, linear
+// layers with a quantization module between them, output layer -- here one kernel).
+//
+// Every wave owns 32 coordinates and carries them through all layers without their
+// activations ever leaving registers; device-memory traffic is the coordinates in and the
+// signal values out.  The only shared state is the current layer's weights in LDS.
+//
+// Data layout.  The GEMM runs "features x coordinates": the int8 weights are the A operand
+// of v_mfma_i32_32x32x32_i8 (32 output features x 32 k), the activation codes the B operand
+// (32 k x 32 coordinates).  With that orientation lane l of a wave holds, for coordinate
+// l % 32, accumulator rows 8g + 4h + e (g = 0..3, h = l / 32, e = 0..3) of every 32-row
+// tile T: half of the feature vector of one coordinate, in registers R = 16T + 4g + e.
+// The Walsh-Hadamard transform over the feature index (Eq. 3) is then
+//   - log2(NF) - 1 butterfly stages over the bits of R: plain register add/sub, no lane
+//     traffic, and
+//   - one stage over h, done with v_permlane32_swap on register pairs (2p, 2p+1): after the
+//     swap the two halves of a pair sit in the same lane, one add and one sub finish it.
+// A butterfly network may visit the index bits in any order, so this computes the same
+// transform as the textbook ordering.  After the last stage register s of lane half u
+// holds rotated feature j(s, u) (see rot_index below); quantizing register s into byte
+// s % 4 of dword s / 4 makes four consecutive dwords exactly the B operand of k block
+// s / 16.  The contraction index of an MFMA can be enumerated in any order as long as both
+// operands agree, so the weights are packed offline with their k positions permuted by
+// j(s, u) and nothing is ever shuffled at run time.
+//
+// The first layer (fan-in <= 4) and the output layer (fan-out <= 32) use the same
+// machinery with the k block / the M tile zero-padded.
+//
+// Weights: each layer's A fragments ([tile][k block][lane] x 16 B) followed by its biases
+// form one contiguous block; while layer l computes, the block of layer l+1 is copied from
+// device memory (L2-resident) straight into the other LDS buffer with 16-byte
+// global->LDS loads, so the copy costs no registers and no VALU work.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "dhq_device.h"
+#include "dhq_internal.h"
+
+#define FUSED_WAVES 8            // waves per workgroup, two per SIMD
+#define FUSED_THREADS (FUSED_WAVES * 64)
+#define FUSED_TILE (FUSED_WAVES * 32)  // coordinates per workgroup pass
+
+struct fused_layer_desc {
+    uint32_t blob_off;   // byte offset of the layer's block in the packed weight blob
+    uint32_t chunks;     // block size in KiB (1 KiB = what one wave copies per instruction)
+    float c1;            // sine layers: s_a s_w omega0 / (2 pi); output layer: s_a s_w
+    float inv_in;        // 1 / (s_a sqrt(Kp)) of this layer's input quantizer
+};
+
+struct fused_args {
+    const float *coords;
+    float *out;
+    const unsigned char *blob;
+    int64_t n;
+    int n_layers;
+    int k0, k0p;   // fan-in of the first layer and its power-of-two padding (<= 4)
+    int m_out;     // fan-out of the output layer (<= 32)
+    int qmax;
+    fused_layer_desc layer[DHQ_MAX_LAYERS];
+};
+
+struct dhq_fused_plan {
+    int nf = 0;                      // hidden width
+    unsigned char *blob_dev = nullptr;
+    size_t blob_bytes = 0;
+    fused_args args;
+    size_t lds_bytes = 0;
+    int n_cu = 0;
+};
+
+// Rotated feature index held, after the in-register transform, by register s of lane half u.
+static inline int rot_index(int s, int u)
+{
+    const int r = (s & ~1) | u;  // register the value came from before the lane swap
+    const int H = s & 1;         // the lane-half bit of the output index
+    return 32 * (r >> 4) + 8 * ((r >> 2) & 3) + 4 * H + (r & 3);
+}
+
+// Position of bias / output feature f inside a layer's bias block: [T][g][h][e].
+static inline int bias_slot(int f)
+{
+    const int T = f >> 5, i = f & 31;
+    const int g = i >> 3, h = (i >> 2) & 1, e = i & 3;
+    return ((T * 4 + g) * 2 + h) * 4 + e;
+}
+
+// ----------------------------------------------------------------------------- device code
+__device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsigned char *lds_dst,
+                                                 int chunks, int wave, int lane)
+{
+    for (int q = wave; q < chunks; q += FUSED_WAVES) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(src + (size_t)q * 1024 + lane * 16),
+            (__attribute__((address_space(3))) void *)(lds_dst + q * 1024), 16, 0, 0);
+    }
+}
+
+template <int NF>
+__global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
+{
+    constexpr int NT = NF / 32;   // M tiles of a hidden layer
+    constexpr int NKB = NF / 32;  // k blocks of a hidden layer
+    constexpr int NR = NF / 2;    // activation registers per lane
+    constexpr int BLK = (NT * NKB + 1) * 1024;  // LDS bytes per weight buffer
+
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int L = A.n_layers;
+    const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
+
+    int p = 0;  // LDS buffer holding the layer about to run
+    if ((int64_t)blockIdx.x < n_tiles)
+        fused_issue_copy(A.blob + A.layer[0].blob_off, lds, (int)A.layer[0].chunks, wave, lane);
+
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t ci = tile * FUSED_TILE + wave * 32 + c;
+        const bool valid = ci < A.n;
+        const int64_t cl = valid ? ci : A.n - 1;
+
+        dhq_v4i cd[NKB];  // activation codes: the B operands of the next GEMM
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        {
+            // input layer: rotate the coordinate vector (fan-in <= 4) and quantize it
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (A.k0 == 2) {
+                const float2 xy = *reinterpret_cast<const float2 *>(A.coords + cl * 2);
+                v[0] = xy.x; v[1] = xy.y;
+            } else {
+                for (int k = 0; k < A.k0; ++k) v[k] = A.coords[cl * A.k0 + k];
+            }
+            if (A.k0p >= 2) {
+                float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
+                a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
+            }
+            if (A.k0p == 4) {
+                float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
+                a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
+            }
+            const float inv = A.layer[0].inv_in;
+            cd[0][0] = (int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
+                                      dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
+        }
+
+        float x[NR];
+        for (int l = 0; l < L - 1; ++l) {
+            // weights of layer l have landed; everyone is done with the other buffer
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            {
+                const fused_layer_desc &nx = A.layer[l + 1];
+                fused_issue_copy(A.blob + nx.blob_off, lds + (p ^ 1) * BLK, (int)nx.chunks, wave, lane);
+            }
+            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
+            const int nkb = (l == 0) ? 1 : NKB;
+            const float4 *wB = reinterpret_cast<const float4 *>(lds + p * BLK + NT * nkb * 1024);
+            const float c1 = A.layer[l].c1;
+#pragma unroll
+            for (int T = 0; T < NT; ++T) {
+                dhq_v16i acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0;
+                if (l == 0) {
+                    const dhq_v4i a = wA[T * 64 + lane];
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[0], acc, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int kb = 0; kb < NKB; ++kb) {
+                        const dhq_v4i a = wA[(T * NKB + kb) * 64 + lane];
+                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
+                    }
+                }
+                // dequantize + bias + sine (arguments pre-scaled to revolutions)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 bb = wB[(T * 4 + g) * 2 + h];
+                    x[16 * T + 4 * g + 0] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 0], c1, bb.x));
+                    x[16 * T + 4 * g + 1] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 1], c1, bb.y));
+                    x[16 * T + 4 * g + 2] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 2], c1, bb.z));
+                    x[16 * T + 4 * g + 3] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 3], c1, bb.w));
+                }
+            }
+            // Walsh-Hadamard transform over the NF features of each coordinate:
+            // stages over the register index bits ...
+#pragma unroll
+            for (int s = 1; s < NR; s <<= 1) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    if ((i & s) == 0) {
+                        const float a = x[i], b = x[i | s];
+                        x[i] = a + b;
+                        x[i | s] = a - b;
+                    }
+                }
+            }
+            // ... then the stage over the lane-half bit, fused with the quantizer
+            const float inv = A.layer[l + 1].inv_in;
+            const int qmax = A.qmax;
+#pragma unroll
+            for (int w = 0; w < NR / 4; ++w) {
+                int qb[4];
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                    const int s0 = 4 * w + 2 * pr;
+                    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
+                                                                    false, false);
+                    const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
+                    qb[2 * pr] = dhq_quant_bits(r0 + r1, inv, qmax);
+                    qb[2 * pr + 1] = dhq_quant_bits(r0 - r1, inv, qmax);
+                }
+                cd[w / 4][w % 4] = (int)dhq_pack4(qb[0], qb[1], qb[2], qb[3]);
+            }
+            p ^= 1;
+        }
+
+        // output layer: one zero-padded M tile, no sine
+        {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tile + gridDim.x < n_tiles)
+                fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane);
+            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
+            const float *wB = reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024);
+            dhq_v16i acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                const dhq_v4i a = wA[kb * 64 + lane];
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
+            }
+            const float c1 = A.layer[L - 1].c1;
+            if (valid) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (row < A.m_out)
+                        A.out[ci * A.m_out + row] =
+                            __builtin_fmaf((float)acc[v], c1, wB[((v >> 2) * 2 + h) * 4 + (v & 3)]);
+                }
+            }
+            p ^= 1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------- host code
+static bool fused_shape_ok(const dhq_model *m, int *nf_out)
+{
+    const int L = m->n_layers;
+    if (L < 2) return false;
+    if (m->dims[0] > 4 || m->dims[L] > 32) return false;
+    const int nf = m->dims[1];
+    if (nf != 32 && nf != 64 && nf != 128 && nf != 256) return false;
+    for (int l = 1; l < L; ++l)
+        if (m->dims[l] != nf) return false;
+    *nf_out = nf;
+    return true;
+}
+
+int dhq_fused_create(const dhq_model *m, dhq_fused_plan **plan_out)
+{
+    *plan_out = nullptr;
+    int nf = 0;
+    if (!fused_shape_ok(m, &nf)) return DHQ_OK;
+    const int L = m->n_layers;
+    const int NT = nf / 32, NKB = nf / 32;
+
+    dhq_fused_plan *P = new (std::nothrow) dhq_fused_plan();
+    if (!P) return DHQ_ENOMEM;
+    P->nf = nf;
+    memset(&P->args, 0, sizeof(P->args));
+
+    // block sizes: fragments [Mt][Kb] KiB + one KiB of biases
+    std::vector<unsigned char> blob;
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const int Mt = (l == L - 1) ? 1 : NT;
+        const int Kb = (l == 0) ? 1 : NKB;
+        const size_t off = blob.size();
+        const size_t bytes = (size_t)(Mt * Kb + 1) * 1024;
+        blob.resize(off + bytes, 0);
+        int8_t *frag = reinterpret_cast<int8_t *>(blob.data() + off);
+        const int8_t *wq = Ly.wq_host.data();  // M x Kp, rotated-index order
+        for (int T = 0; T < Mt; ++T)
+            for (int kb = 0; kb < Kb; ++kb)
+                for (int ln = 0; ln < 64; ++ln) {
+                    const int row = 32 * T + (ln & 31), u = ln >> 5;
+                    for (int jj = 0; jj < 16; ++jj) {
+                        int8_t val = 0;
+                        if (row < Ly.M) {
+                            if (l == 0) {
+                                // un-permuted: the input layer's codes sit in bytes 0..Kp-1 of half 0
+                                if (u == 0 && jj < Ly.Kp) val = wq[(size_t)row * Ly.Kp + jj];
+                            } else {
+                                const int k = rot_index(16 * kb + jj, u);
+                                val = wq[(size_t)row * Ly.Kp + k];
+                            }
+                        }
+                        frag[((size_t)(T * Kb + kb) * 64 + ln) * 16 + jj] = val;
+                    }
+                }
+        P->args.layer[l].blob_off = (uint32_t)off;
+        P->args.layer[l].chunks = (uint32_t)(bytes / 1024);
+    }
+    P->blob_bytes = blob.size();
+    if (hipMalloc((void **)&P->blob_dev, P->blob_bytes) != hipSuccess) {
+        delete P;
+        return DHQ_ENOMEM;
+    }
+    // the bias part of every block is filled in by dhq_fused_update_scales
+    if (hipMemcpy(P->blob_dev, blob.data(), P->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(P->blob_dev);
+        delete P;
+        return DHQ_EHIP;
+    }
+    P->args.blob = P->blob_dev;
+    P->args.n_layers = L;
+    P->args.k0 = m->dims[0];
+    P->args.k0p = m->layer[0].Kp;
+    P->args.m_out = m->dims[L];
+    P->args.qmax = m->qmax_a;
+    P->lds_bytes = (size_t)2 * (NT * NKB + 1) * 1024;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
+        (void)hipFree(P->blob_dev);
+        delete P;
+        return DHQ_EHIP;
+    }
+    P->n_cu = prop.multiProcessorCount;
+    *plan_out = P;
+    return DHQ_OK;
+}
+
+void dhq_fused_destroy(dhq_fused_plan *plan)
+{
+    if (!plan) return;
+    if (plan->blob_dev) (void)hipFree(plan->blob_dev);
+    delete plan;
+}
+
+// Refreshes the per-layer constants and the bias part of each block.
+int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
+{
+    if (!P) return DHQ_OK;
+    const int L = m->n_layers;
+    const int NT = P->nf / 32, NKB = P->nf / 32;
+    const double two_pi = 6.283185307179586476925286766559;
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const bool last = (l == L - 1);
+        const double sc = (double)Ly.s_a * (double)Ly.s_w;
+        P->args.layer[l].c1 = last ? (float)sc : (float)(sc * (double)m->omega0 / two_pi);
+        P->args.layer[l].inv_in = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
+        // bias block
+        const int Mt = last ? 1 : NT, Kb = (l == 0) ? 1 : NKB;
+        std::vector<float> blk(256, 0.0f);
+        const std::vector<float> &src = last ? Ly.bias_host : Ly.bias_rev_host;
+        for (int f = 0; f < Ly.M; ++f) blk[bias_slot(f)] = src[f];
+        unsigned char *dst = P->blob_dev + P->args.layer[l].blob_off + (size_t)Mt * Kb * 1024;
+        if (hipMemcpy(dst, blk.data(), 1024, hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
+    }
+    return DHQ_OK;
+}
+
+template <int NF>
+static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, unsigned grid, hipStream_t st)
+{
+    auto kern = dhq_fused_kernel<NF>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
+    if (e != hipSuccess) return e;
+    kern<<<grid, FUSED_THREADS, P->lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, float *out, hipStream_t st)
+{
+    const dhq_fused_plan *P = m->fused;
+    if (!P) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    fused_args a = P->args;
+    a.coords = coords;
+    a.out = out;
+    a.n = n;
+    const int64_t tiles = (n + FUSED_TILE - 1) / FUSED_TILE;
+    const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    switch (P->nf) {
+        case 32: return fused_launch_t<32>(P, a, grid, st);
+        case 64: return fused_launch_t<64>(P, a, grid, st);
+        case 128: return fused_launch_t<128>(P, a, grid, st);
+        case 256: return fused_launch_t<256>(P, a, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}

@@ -1,0 +1,75 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/dhq.h declares,
+and rejects bad arguments before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_13478_amd as dhq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dhq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dhq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = dhq.lib()
+    declared = _declared_symbols()
+    assert "dhq_quantize_weights" in declared and "dhq_forward" in declared
+    assert set(declared) == set(dhq.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert dhq.dhq_version() >= 100
+    assert dhq.dhq_strerror(0) == "ok"
+    assert "scale" in dhq.dhq_strerror(dhq.DHQ_ENOSCALE)
+
+
+def test_quantize_weights_rejects_bad_arguments_without_gpu():
+    L = dhq.lib()
+    dims = (C.c_int32 * 3)(2, 8, 3)
+    W = [np.zeros((8, 2), np.float32), np.zeros((3, 8), np.float32)]
+    b = [np.zeros(8, np.float32), np.zeros(3, np.float32)]
+    Wp = (C.POINTER(C.c_float) * 2)(*[w.ctypes.data_as(C.POINTER(C.c_float)) for w in W])
+    bp = (C.POINTER(C.c_float) * 2)(*[x.ctypes.data_as(C.POINTER(C.c_float)) for x in b])
+    h = C.c_void_p()
+
+    def call(desc):
+        return L.dhq_quantize_weights(C.byref(desc), Wp, bp, C.byref(h))
+
+    assert call(dhq.dhq_net_desc(2, dims, 30.0, 5, 8)) == dhq.DHQ_EINVAL          # bits not in {4,6,8}
+    assert call(dhq.dhq_net_desc(2, dims, 30.0, 8, 3)) == dhq.DHQ_EINVAL
+    assert call(dhq.dhq_net_desc(0, dims, 30.0, 8, 8)) == dhq.DHQ_EINVAL          # no layers
+    assert call(dhq.dhq_net_desc(17, dims, 30.0, 8, 8)) == dhq.DHQ_EUNSUPPORTED   # too deep
+    big = (C.c_int32 * 3)(2, 1024, 3)
+    assert call(dhq.dhq_net_desc(2, big, 30.0, 8, 8)) == dhq.DHQ_EUNSUPPORTED     # too wide
+    zero = (C.c_int32 * 3)(2, 0, 3)
+    assert call(dhq.dhq_net_desc(2, zero, 30.0, 8, 8)) == dhq.DHQ_EINVAL
+    assert L.dhq_quantize_weights(None, Wp, bp, C.byref(h)) == dhq.DHQ_EINVAL
+    assert h.value is None
+
+
+def test_null_model_is_rejected():
+    L = dhq.lib()
+    assert L.dhq_forward(None, None, 0, None, None, 0) == dhq.DHQ_EINVAL
+    assert L.dhq_set_act_scales(None, None) == dhq.DHQ_EINVAL
+    assert L.dhq_has_fused(None) == dhq.DHQ_EINVAL
+    L.dhq_free(None)  # a no-op
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2508_13478_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle", text, flags=re.M), f
+                assert "dhq_oracle" not in text and "dhqo_" not in text, f
+    for f in ("dhq_oracle.c", "dhq_oracle.py"):
+        text = open(os.path.join(ROOT, "oracle", f)).read()
+        assert "paper_2508_13478_amd" not in text and "libdhq.so" not in text
