@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark of the DHQ W8A8 SIREN forward on one MI355X.
+
+A step is one pass of the whole hot path (coordinates in, signal values out: rotation,
+quantizer, int8 GEMM, dequantize + bias + sine for every layer) over one synthetic coordinate
+grid that is already resident in device memory.  The workload is the C2 configuration
+(SIREN 2 -> 256 x 4 hidden -> 3 on a 256 x 256 grid); other configurations can be selected with
+--workload.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, 5.0 POP/s
+VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz fp32 lane-ops/s
+
+
+def time_forward(model, x, out, flags, steps, warmup):
+    import torch
+    import paper_2508_13478_amd as dhq
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        dhq.dhq_forward(model.handle, x, out, stream, flags)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        dhq.dhq_forward(model.handle, x, out, stream, flags)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def cpu_baseline(name, s_a, max_coords):
+    """The CPU oracle's quantized forward (static scales) timed on a bounded sample."""
+    import numpy as np
+    from oracle import dhq_oracle as o
+    from paper_2508_13478_amd import synth
+    wl, coords, W, b = synth.make(name)
+    stride = max(1, -(-coords.shape[0] // max_coords))
+    sample = coords[::stride]
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
+    net.s_a = np.asarray(s_a, dtype=np.float32)
+    t0 = time.perf_counter()
+    o.forward(net, sample)
+    dt = time.perf_counter() - t0
+    try:
+        threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
+    except OSError:
+        threads = os.cpu_count() or 1
+    return {"value": sample.shape[0] / dt, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{name} grid, every {stride}th coordinate ({sample.shape[0]} coords), one run, "
+                      f"{dt:.2f} s, quantized forward with static scales (weight quantization and "
+                      f"calibration excluded)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (the coordinate grid shards "
+              "trivially, but no multi-GPU path is part of it)", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2508_13478_amd as dhq
+    from paper_2508_13478_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    wl, coords, W, b = synth.make(args.workload)
+    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8)
+    x = torch.from_numpy(coords).to("cuda")
+    out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
+    model.calibrate(x)
+    _, s_a = model.scales()
+    fused = model.has_fused()
+    flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
+
+    ms, wall_ms = time_forward(model, x, out, flags, args.steps, args.warmup)
+    n = x.shape[0]
+    ops = wl.int8_ops_per_coord() * n
+    tops = ops / (ms * 1e-3) / 1e12
+    res = {
+        "metric": "W8A8 SIREN forward coords/sec",
+        "value": n / (ms * 1e-3),
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "i8",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: SIREN {'-'.join(map(str, wl.dims))}, omega0={wl.omega0:g}, "
+                               f"{wl.side}x{wl.side} grid ({n} coords), W8A8, static per-layer scales "
+                               f"from absmax calibration on the same grid",
+                   "path": "fused" if fused else "layerwise", "coords": n},
+        "int8_tops": tops,
+        "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
+        "wall_ms_per_step": wall_ms,
+        # dominant kernel = the fused whole-network kernel: one launch per step, so its average
+        # duration is the event-timed step; algorithmic work = 2 ops per MAC over the un-padded
+        # layer shapes
+        "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "kernel": "dhq_fused_kernel" if fused else "layerwise kernels",
+                     "algorithmic_ops_per_launch": ops},
+    }
+    if fused:
+        ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
+        res["layerwise_ms_per_step"] = ms_lw
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(args.workload, s_a, args.cpu_coords)
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
