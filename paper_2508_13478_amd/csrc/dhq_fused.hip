@@ -97,6 +97,80 @@ __device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsig
     }
 }
 
+// One layer's GEMM with the dequantize + bias + sine epilogue, software-pipelined by hand:
+// step s issues the MFMA of (tile s / KB, k block s % KB) and, in its shadow, the epilogue of
+// 16 / KB accumulators of the previous tile, so the matrix unit and the vector ALU of one
+// wave run concurrently.  A fragments are fetched from LDS PF steps ahead, bias vectors one
+// tile ahead.  sched_barrier pins the step order; the compiler is free inside a step.
+template <int NT, int KB, int NCD>
+__device__ __forceinline__ void fused_gemm_sine(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
+                                                const dhq_v4i (&cd)[NCD], float c1, float (&x)[NT * 16],
+                                                int lane, int h)
+{
+    constexpr int S = NT * KB;    // MFMA steps
+    constexpr int EPS = 16 / KB;  // accumulators finished per step (KB <= 16)
+    constexpr int PF = 2;         // LDS prefetch distance in steps
+    dhq_v4i fr[PF + 1];
+    float4 bq[2][4];
+    dhq_v16i acc[2];
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+        if (s < S) fr[s % (PF + 1)] = wA[s * 64 + lane];
+#pragma unroll
+    for (int T = 0; T <= NT; ++T) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int s = T * KB + kb;
+            if (s + PF < S) fr[(s + PF) % (PF + 1)] = wA[(s + PF) * 64 + lane];
+            if (T < NT) {
+                // bias vectors of this tile, spread over its steps
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    if ((g * KB) / 4 == kb) bq[T & 1][g] = wB[(T * 4 + g) * 2 + h];
+                if (kb == 0) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[T & 1][v] = 0;
+                }
+                acc[T & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[s % (PF + 1)], cd[kb], acc[T & 1], 0, 0, 0);
+            }
+            if (T >= 1) {
+                const int Tp = T - 1;
+#pragma unroll
+                for (int j = 0; j < EPS; ++j) {
+                    const int v = kb * EPS + j;
+                    const float4 bb = bq[Tp & 1][v >> 2];
+                    const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
+                    x[16 * Tp + v] = dhq_sin_rev(__builtin_fmaf((float)acc[Tp & 1][v], c1, bias));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Last butterfly stage (over the lane-half bit) fused with the quantizer: registers
+// (2p, 2p+1) swap halves across the wave, one add and one sub finish the transform, and each
+// result is rounded, clamped and dropped into its byte of the packed code dword.  The final
+// clamp instruction writes that byte directly (sub-dword destination select), so packing
+// costs nothing.
+__device__ __forceinline__ void fused_quant_byte(unsigned &packed, float v, float inv, int lo, int hi, int byte)
+{
+    const float t = __builtin_fmaf(v, inv, DHQ_MAGIC_F);
+    const int b = max(__float_as_int(t), lo);
+    if (byte == 0)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else if (byte == 1)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else if (byte == 2)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+}
+
 template <int NF>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
@@ -110,6 +184,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
     const int c = lane & 31, h = lane >> 5;
     const int L = A.n_layers;
     const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
 
     int p = 0;  // LDS buffer holding the layer about to run
     if ((int64_t)blockIdx.x < n_tiles)
@@ -155,34 +230,13 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
                 fused_issue_copy(A.blob + nx.blob_off, lds + (p ^ 1) * BLK, (int)nx.chunks, wave, lane);
             }
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
-            const int nkb = (l == 0) ? 1 : NKB;
-            const float4 *wB = reinterpret_cast<const float4 *>(lds + p * BLK + NT * nkb * 1024);
             const float c1 = A.layer[l].c1;
-#pragma unroll
-            for (int T = 0; T < NT; ++T) {
-                dhq_v16i acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0;
-                if (l == 0) {
-                    const dhq_v4i a = wA[T * 64 + lane];
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[0], acc, 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int kb = 0; kb < NKB; ++kb) {
-                        const dhq_v4i a = wA[(T * NKB + kb) * 64 + lane];
-                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
-                    }
-                }
-                // dequantize + bias + sine (arguments pre-scaled to revolutions)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 bb = wB[(T * 4 + g) * 2 + h];
-                    x[16 * T + 4 * g + 0] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 0], c1, bb.x));
-                    x[16 * T + 4 * g + 1] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 1], c1, bb.y));
-                    x[16 * T + 4 * g + 2] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 2], c1, bb.z));
-                    x[16 * T + 4 * g + 3] = dhq_sin_rev(__builtin_fmaf((float)acc[4 * g + 3], c1, bb.w));
-                }
-            }
+            if (l == 0)
+                fused_gemm_sine<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, x,
+                                            lane, h);
+            else
+                fused_gemm_sine<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
+                                              c1, x, lane, h);
             // Walsh-Hadamard transform over the NF features of each coordinate:
             // stages over the register index bits ...
 #pragma unroll
@@ -198,20 +252,19 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             }
             // ... then the stage over the lane-half bit, fused with the quantizer
             const float inv = A.layer[l + 1].inv_in;
-            const int qmax = A.qmax;
 #pragma unroll
             for (int w = 0; w < NR / 4; ++w) {
-                int qb[4];
+                unsigned packed = 0;
 #pragma unroll
                 for (int pr = 0; pr < 2; ++pr) {
                     const int s0 = 4 * w + 2 * pr;
                     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
                                                                     false, false);
                     const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
-                    qb[2 * pr] = dhq_quant_bits(r0 + r1, inv, qmax);
-                    qb[2 * pr + 1] = dhq_quant_bits(r0 - r1, inv, qmax);
+                    fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
+                    fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
                 }
-                cd[w / 4][w % 4] = (int)dhq_pack4(qb[0], qb[1], qb[2], qb[3]);
+                cd[w / 4][w % 4] = (int)packed;
             }
             p ^= 1;
         }
