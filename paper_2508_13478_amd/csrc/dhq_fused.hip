@@ -97,54 +97,139 @@ __device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsig
     }
 }
 
-// One layer's GEMM with the dequantize + bias + sine epilogue, software-pipelined by hand:
-// step s issues the MFMA of (tile s / KB, k block s % KB) and, in its shadow, the epilogue of
-// 16 / KB accumulators of the previous tile, so the matrix unit and the vector ALU of one
-// wave run concurrently.  A fragments are fetched from LDS PF steps ahead, bias vectors one
-// tile ahead.  sched_barrier pins the step order; the compiler is free inside a step.
+// Issue schedule of one layer's GEMM.  The M tiles are accumulated by two staggered MFMA
+// chains: even tiles on even steps, odd tiles on odd steps half a tile later, so consecutive
+// MFMAs of a wave never depend on each other and the matrix unit is not left waiting for its
+// own result.  A tile that has received its last k block is drained (dequantize + bias +
+// sine, 16 / KB accumulators per step) during the KB steps that follow, and during the KB
+// steps after that the four Walsh-Hadamard stages that stay inside the tile's 16 registers
+// run on it -- all in the shadow of the other tiles' MFMAs, which keeps the vector ALU and
+// the matrix unit of the wave busy together.  Three accumulator tiles rotate: two
+// accumulating, one draining.
+template <int NT, int KB>
+struct gemm_sched {
+    static constexpr bool STAGGER = (NT >= 2 && KB >= 2);  // with one k block per tile nothing depends
+    static constexpr int STEPS = (STAGGER ? (NT / 2) * 2 * KB + KB + 1 : NT * KB) + 2 * KB + 2;
+    static constexpr int NM = NT * KB;  // MFMAs
+    int tile[STEPS];      // tile whose MFMA issues at this step, -1 if none
+    int kb[STEPS];
+    int seq[STEPS];       // running index of that MFMA
+    int drain[STEPS];     // tile drained at this step, -1 if none
+    int drain_pos[STEPS]; // which slice (0..KB-1) of its 16 accumulators
+    int bfly[STEPS];      // tile whose in-tile butterflies run at this step, -1 if none
+    int bfly_pos[STEPS];  // which slice (0..KB-1) of its 32 butterflies
+    int seq_tile[NM];     // inverse: MFMA number -> tile, k block
+    int seq_kb[NM];
+    constexpr gemm_sched()
+        : tile(), kb(), seq(), drain(), drain_pos(), bfly(), bfly_pos(), seq_tile(), seq_kb()
+    {
+        int done[NT > 0 ? NT : 1] = {};
+        for (int g = 0; g < STEPS; ++g) {
+            tile[g] = -1; kb[g] = 0; seq[g] = -1; drain[g] = -1; drain_pos[g] = 0; bfly[g] = -1; bfly_pos[g] = 0;
+        }
+        for (int t = 0; t < NT; ++t) {
+            const int i = t / 2;
+            const int base = (t & 1) ? 2 * KB * i + KB + 1 : 2 * KB * i;
+            for (int k = 0; k < KB; ++k) {
+                const int g = STAGGER ? base + 2 * k : t * KB + k;
+                tile[g] = t;
+                kb[g] = k;
+                done[t] = g;
+            }
+        }
+        int m = 0;
+        for (int g = 0; g < STEPS; ++g)
+            if (tile[g] >= 0) { seq[g] = m; seq_tile[m] = tile[g]; seq_kb[m] = kb[g]; ++m; }
+        for (int t = 0; t < NT; ++t) {
+            // two tiles may want the same step near the end; take the next free one
+            int g = done[t] + 1;
+            for (int k = 0; k < KB; ++k) {
+                while (drain[g] >= 0) ++g;
+                drain[g] = t;
+                drain_pos[g] = k;
+                ++g;
+            }
+            for (int k = 0; k < KB; ++k) {
+                while (bfly[g] >= 0) ++g;
+                bfly[g] = t;
+                bfly_pos[g] = k;
+                ++g;
+            }
+        }
+    }
+};
+
+// One layer's GEMM with the dequantize + bias + sine epilogue and the in-tile part of the
+// Walsh-Hadamard transform, software-pipelined by hand according to gemm_sched.
+// A fragments are fetched from LDS PF MFMAs ahead, a tile's bias vectors while it
+// accumulates.  sched_barrier pins the step order; the compiler is free inside a step.
+// On return x[] holds sin(...) of this lane's features with the butterfly stages over the
+// register index bits 0..3 already applied.
 template <int NT, int KB, int NCD>
 __device__ __forceinline__ void fused_gemm_sine(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
                                                 const dhq_v4i (&cd)[NCD], float c1, float (&x)[NT * 16],
                                                 int lane, int h)
 {
-    constexpr int S = NT * KB;    // MFMA steps
-    constexpr int EPS = 16 / KB;  // accumulators finished per step (KB <= 16)
-    constexpr int PF = 2;         // LDS prefetch distance in steps
+    constexpr gemm_sched<NT, KB> S{};
+    constexpr int NM = NT * KB;
+    constexpr int EPS = 16 / KB;  // accumulators drained per step (KB <= 16)
+    constexpr int BPS = 32 / KB;  // butterflies per step
+    constexpr int PF = (NM >= 4) ? 4 : (NM >= 2 ? 2 : 1);  // LDS prefetch distance in MFMAs
     dhq_v4i fr[PF + 1];
-    float4 bq[2][4];
-    dhq_v16i acc[2];
+    float4 bq[3][4];
+    dhq_v16i acc[3];
 #pragma unroll
-    for (int s = 0; s < PF; ++s)
-        if (s < S) fr[s % (PF + 1)] = wA[s * 64 + lane];
+    for (int m = 0; m < PF; ++m)
+        if (m < NM) fr[m % (PF + 1)] = wA[(S.seq_tile[m] * KB + S.seq_kb[m]) * 64 + lane];
+    constexpr int GB = 8;  // steps are unrolled in nested groups (keeps each unrolled loop small)
 #pragma unroll
-    for (int T = 0; T <= NT; ++T) {
+    for (int g0 = 0; g0 < S.STEPS; g0 += GB) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const int s = T * KB + kb;
-            if (s + PF < S) fr[(s + PF) % (PF + 1)] = wA[(s + PF) * 64 + lane];
-            if (T < NT) {
-                // bias vectors of this tile, spread over its steps
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    if ((g * KB) / 4 == kb) bq[T & 1][g] = wB[(T * 4 + g) * 2 + h];
-                if (kb == 0) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[T & 1][v] = 0;
-                }
-                acc[T & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[s % (PF + 1)], cd[kb], acc[T & 1], 0, 0, 0);
+      for (int g1 = 0; g1 < GB; ++g1) {
+        const int g = g0 + g1;
+        if (g >= S.STEPS) continue;
+        const int T = S.tile[g];
+        if (T >= 0) {
+            const int m = S.seq[g], kb = S.kb[g];
+            if (m + PF < NM) {
+                fr[(m + PF) % (PF + 1)] = wA[(S.seq_tile[m + PF] * KB + S.seq_kb[m + PF]) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch at the top of the step
             }
-            if (T >= 1) {
-                const int Tp = T - 1;
+            // bias vectors of this tile, spread over its steps
 #pragma unroll
-                for (int j = 0; j < EPS; ++j) {
-                    const int v = kb * EPS + j;
-                    const float4 bb = bq[Tp & 1][v >> 2];
-                    const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
-                    x[16 * Tp + v] = dhq_sin_rev(__builtin_fmaf((float)acc[Tp & 1][v], c1, bias));
-                }
+            for (int gg = 0; gg < 4; ++gg)
+                if ((gg * KB) / 4 == kb) bq[T % 3][gg] = wB[(T * 4 + gg) * 2 + h];
+            if (kb == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[T % 3][v] = 0;
             }
-            __builtin_amdgcn_sched_barrier(0);
+            acc[T % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[m % (PF + 1)], cd[kb], acc[T % 3], 0, 0, 0);
         }
+        const int Td = S.drain[g];
+        if (Td >= 0) {
+#pragma unroll
+            for (int j = 0; j < EPS; ++j) {
+                const int v = S.drain_pos[g] * EPS + j;
+                const float4 bb = bq[Td % 3][v >> 2];
+                const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
+                x[16 * Td + v] = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias));
+            }
+        }
+        const int Tb = S.bfly[g];
+        if (Tb >= 0) {
+            // butterflies b = stage * 8 + pair over the 16 registers of tile Tb, in stage order
+#pragma unroll
+            for (int j = 0; j < BPS; ++j) {
+                const int b = S.bfly_pos[g] * BPS + j;
+                const int st = b >> 3, q = b & 7;
+                const int r = ((q >> st) << (st + 1)) | (q & ((1 << st) - 1));
+                const float u = x[16 * Tb + r], w = x[16 * Tb + (r | (1 << st))];
+                x[16 * Tb + r] = u + w;
+                x[16 * Tb + (r | (1 << st))] = u - w;
+            }
+        }
+        if (T >= 0 || Td >= 0 || Tb >= 0) __builtin_amdgcn_sched_barrier(0);
+      }
     }
 }
 
@@ -237,10 +322,14 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             else
                 fused_gemm_sine<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
                                               c1, x, lane, h);
+            // The two waves of a SIMD overlap well while both feed the matrix unit or both
+            // do vector work, but a wave in its vector phase starves the MFMA chain of the
+            // other; keep the phases aligned across the workgroup.
+            __syncthreads();
             // Walsh-Hadamard transform over the NF features of each coordinate:
             // stages over the register index bits ...
 #pragma unroll
-            for (int s = 1; s < NR; s <<= 1) {
+            for (int s = 16; s < NR; s <<= 1) {  // (the four stages inside a tile were done above)
 #pragma unroll
                 for (int i = 0; i < NR; ++i) {
                     if ((i & s) == 0) {
