@@ -56,6 +56,7 @@ extern "C" void dhq_free(dhq_model *m)
     if (m->codes) (void)hipFree(m->codes);
     if (m->absmax_dev) (void)hipFree(m->absmax_dev);
     dhq_fused_destroy(m->fused);
+    dhq_wide_destroy(m->wide);
     delete m;
 }
 
@@ -192,12 +193,20 @@ extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const
         if (rc == DHQ_OK && hipMalloc((void **)&m->absmax_dev, sizeof(unsigned)) != hipSuccess) rc = DHQ_ENOMEM;
     }
     if (rc == DHQ_OK) rc = dhq_fused_create(m, &m->fused);
+    if (rc == DHQ_OK) rc = dhq_wide_create(m, &m->wide);
     if (rc != DHQ_OK) {
         dhq_free(m);
         return rc;
     }
     *out = m;
     return DHQ_OK;
+}
+
+static int update_fused_scales(dhq_model *m)
+{
+    int rc = dhq_fused_update_scales(m, m->fused);
+    if (rc == DHQ_OK) rc = dhq_wide_update_scales(m, m->wide);
+    return rc;
 }
 
 extern "C" int dhq_set_act_scales(dhq_model *m, const float *s_a_host)
@@ -207,7 +216,7 @@ extern "C" int dhq_set_act_scales(dhq_model *m, const float *s_a_host)
         if (!(s_a_host[l] > 0.0f) || !isfinite(s_a_host[l])) return DHQ_EINVAL;
     for (int l = 0; l < m->n_layers; ++l) m->layer[l].s_a = s_a_host[l];
     m->have_scales = true;
-    return dhq_fused_update_scales(m, m->fused);
+    return update_fused_scales(m);
 }
 
 extern "C" int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_host)
@@ -231,7 +240,7 @@ extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *W
 extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
-    return m->fused ? 1 : 0;
+    return (m->fused || m->wide) ? 1 : 0;
 }
 
 // Per-layer constants of the layer-by-layer kernels.
@@ -296,7 +305,7 @@ extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, v
         Ly.s_a = amax == 0.0 ? 1.0f : (float)(amax / (double)m->qmax_a);
     }
     m->have_scales = true;
-    return dhq_fused_update_scales(m, m->fused);
+    return update_fused_scales(m);
 }
 
 extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, void *stream,
@@ -308,9 +317,11 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
     if (!m->have_scales) return DHQ_ENOSCALE;
     hipStream_t st = (hipStream_t)stream;
-    if (flags == DHQ_FUSED && !m->fused) return DHQ_EUNSUPPORTED;
+    if (flags == DHQ_FUSED && !m->fused && !m->wide) return DHQ_EUNSUPPORTED;
     if (flags != DHQ_LAYERWISE && m->fused)
         return dhq_fused_launch(m, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    if (flags != DHQ_LAYERWISE && m->wide)
+        return dhq_wide_launch(m->wide, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     const int K0 = m->dims[0], Mo = m->dims[m->n_layers];
     for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
         const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;

@@ -36,6 +36,7 @@
 #include <vector>
 
 #include "dhq_device.h"
+#include "dhq_fused_common.h"
 #include "dhq_internal.h"
 
 #define FUSED_WAVES 8            // waves per workgroup, two per SIMD
@@ -69,33 +70,6 @@ struct dhq_fused_plan {
     size_t lds_bytes = 0;
     int n_cu = 0;
 };
-
-// Rotated feature index held, after the in-register transform, by register s of lane half u.
-static inline int rot_index(int s, int u)
-{
-    const int r = (s & ~1) | u;  // register the value came from before the lane swap
-    const int H = s & 1;         // the lane-half bit of the output index
-    return 32 * (r >> 4) + 8 * ((r >> 2) & 3) + 4 * H + (r & 3);
-}
-
-// Position of bias / output feature f inside a layer's bias block: [T][g][h][e].
-static inline int bias_slot(int f)
-{
-    const int T = f >> 5, i = f & 31;
-    const int g = i >> 3, h = (i >> 2) & 1, e = i & 3;
-    return ((T * 4 + g) * 2 + h) * 4 + e;
-}
-
-// ----------------------------------------------------------------------------- device code
-__device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsigned char *lds_dst,
-                                                 int chunks, int wave, int lane)
-{
-    for (int q = wave; q < chunks; q += FUSED_WAVES) {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(src + (size_t)q * 1024 + lane * 16),
-            (__attribute__((address_space(3))) void *)(lds_dst + q * 1024), 16, 0, 0);
-    }
-}
 
 // Issue schedule of one layer's GEMM.  The M tiles are accumulated by two staggered MFMA
 // chains: even tiles on even steps, odd tiles on odd steps half a tile later, so consecutive
@@ -233,29 +207,6 @@ __device__ __forceinline__ void fused_gemm_sine(const dhq_v4i *__restrict__ wA, 
     }
 }
 
-// Last butterfly stage (over the lane-half bit) fused with the quantizer: registers
-// (2p, 2p+1) swap halves across the wave, one add and one sub finish the transform, and each
-// result is rounded, clamped and dropped into its byte of the packed code dword.  The final
-// clamp instruction writes that byte directly (sub-dword destination select), so packing
-// costs nothing.
-__device__ __forceinline__ void fused_quant_byte(unsigned &packed, float v, float inv, int lo, int hi, int byte)
-{
-    const float t = __builtin_fmaf(v, inv, DHQ_MAGIC_F);
-    const int b = max(__float_as_int(t), lo);
-    if (byte == 0)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else if (byte == 1)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else if (byte == 2)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-}
-
 template <int NF>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
@@ -273,7 +224,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
 
     int p = 0;  // LDS buffer holding the layer about to run
     if ((int64_t)blockIdx.x < n_tiles)
-        fused_issue_copy(A.blob + A.layer[0].blob_off, lds, (int)A.layer[0].chunks, wave, lane);
+        fused_issue_copy(A.blob + A.layer[0].blob_off, lds, (int)A.layer[0].chunks, wave, lane, FUSED_WAVES);
 
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t ci = tile * FUSED_TILE + wave * 32 + c;
@@ -312,7 +263,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             __syncthreads();
             {
                 const fused_layer_desc &nx = A.layer[l + 1];
-                fused_issue_copy(A.blob + nx.blob_off, lds + (p ^ 1) * BLK, (int)nx.chunks, wave, lane);
+                fused_issue_copy(A.blob + nx.blob_off, lds + (p ^ 1) * BLK, (int)nx.chunks, wave, lane, FUSED_WAVES);
             }
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const float c1 = A.layer[l].c1;
@@ -363,7 +314,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             if (tile + gridDim.x < n_tiles)
-                fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane);
+                fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane, FUSED_WAVES);
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const float *wB = reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024);
             dhq_v16i acc;

@@ -1,0 +1,58 @@
+// Helpers shared by the fused whole-network kernels (dhq_fused.hip, dhq_fused_wide.hip).
+#ifndef DHQ_FUSED_COMMON_H
+#define DHQ_FUSED_COMMON_H
+
+#include "dhq_device.h"
+
+// Rotated feature index held, after the in-register transform, by register s of lane half u.
+static inline int rot_index(int s, int u)
+{
+    const int r = (s & ~1) | u;  // register the value came from before the lane swap
+    const int H = s & 1;         // the lane-half bit of the output index
+    return 32 * (r >> 4) + 8 * ((r >> 2) & 3) + 4 * H + (r & 3);
+}
+
+// Position of bias / output feature f inside a layer's bias block: [T][g][h][e].
+static inline int bias_slot(int f)
+{
+    const int T = f >> 5, i = f & 31;
+    const int g = i >> 3, h = (i >> 2) & 1, e = i & 3;
+    return ((T * 4 + g) * 2 + h) * 4 + e;
+}
+
+// Copies `chunks` KiB from device memory straight into LDS: each wave moves 1 KiB per
+// instruction (64 lanes x 16 B), the waves of the workgroup take the KiB blocks round-robin.
+__device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsigned char *lds_dst,
+                                                 int chunks, int wave, int lane, int n_waves)
+{
+    for (int q = wave; q < chunks; q += n_waves) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(src + (size_t)q * 1024 + lane * 16),
+            (__attribute__((address_space(3))) void *)(lds_dst + q * 1024), 16, 0, 0);
+    }
+}
+
+// Last butterfly stage (over the lane-half bit) fused with the quantizer: registers
+// (2p, 2p+1) swap halves across the wave, one add and one sub finish the transform, and each
+// result is rounded, clamped and dropped into its byte of the packed code dword.  The final
+// clamp instruction writes that byte directly (sub-dword destination select), so packing
+// costs nothing.
+__device__ __forceinline__ void fused_quant_byte(unsigned &packed, float v, float inv, int lo, int hi, int byte)
+{
+    const float t = __builtin_fmaf(v, inv, DHQ_MAGIC_F);
+    const int b = max(__float_as_int(t), lo);
+    if (byte == 0)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else if (byte == 1)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else if (byte == 2)
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+    else
+        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(b), "v"(hi));
+}
+
+#endif

@@ -31,6 +31,7 @@ struct dhq_layer {
 };
 
 struct dhq_fused_plan;  // defined in dhq_fused.hip
+struct dhq_wide_plan;   // defined in dhq_fused_wide.hip
 
 struct dhq_model {
     int n_layers = 0;
@@ -45,7 +46,8 @@ struct dhq_model {
     int8_t *codes = nullptr;                 // DHQ_CHUNK x max Kp
     unsigned *absmax_dev = nullptr;          // one word for calibration
     int max_dim = 0, max_kp = 0;
-    dhq_fused_plan *fused = nullptr;  // null if the shape has no fused kernel
+    dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
+    dhq_wide_plan *wide = nullptr;    // hidden width 512
     int device = 0;
 };
 
@@ -76,5 +78,12 @@ void dhq_fused_destroy(dhq_fused_plan *plan);
 int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *plan);
 hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, float *out,
                             hipStream_t st);
+
+
+// Hidden width 512 (defined in dhq_fused_wide.hip); same contract as the functions above.
+int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan);
+void dhq_wide_destroy(dhq_wide_plan *plan);
+int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *plan);
+hipError_t dhq_wide_launch(const dhq_wide_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
 #endif
