@@ -47,6 +47,12 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             from . import build as _b
             _b.build(force=True)
+        # PyTorch ships its own HIP runtime; load it first so that this library binds to the
+        # same runtime instance as the tensors and streams it is handed
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         L.dhq_quantize_weights.argtypes = [C.POINTER(dhq_net_desc), _fpp, _fpp, C.POINTER(C.c_void_p)]
         L.dhq_set_act_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
