@@ -77,7 +77,12 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
         for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, fabsf(v[e]));
 #pragma unroll
         for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-        if ((threadIdx.x & 63) == 0 && mx > 0.0f) atomicMax(absmax_bits, __float_as_uint(mx));
+        // one word collects the maximum; a wave only pays for the atomic when it would raise it
+        if ((threadIdx.x & 63) == 0) {
+            const unsigned bits = __float_as_uint(mx);  // non-negative floats order like unsigned ints
+            if (bits > __hip_atomic_load(absmax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                atomicMax(absmax_bits, bits);
+        }
         return;
     }
 

@@ -269,6 +269,40 @@ def test_forward_fused_width_512():
         assert np.array_equal(acc.cpu().numpy(), o.igemm(codes.cpu().numpy(), cs.net.Wq[l]))
 
 
+@pytest.mark.parametrize("name,bits", [("C3", 8), ("C4", 4), ("C4", 6), ("C4", 8), ("C5", 8)])
+def test_full_grid_sampled_outputs(name, bits):
+    """The full-size grids, in the launch configuration the benchmark times (one fused launch
+    over the whole grid, static scales).  The oracle cannot run millions of coordinates, but
+    with static scales every coordinate is independent: it calibrates the scales on a strided
+    sub-grid (an oracle-only step), and the library's outputs are compared with the oracle's
+    on a random sample of coordinates plus the first and last tiles."""
+    torch = _torch()
+    _say(f"full grid {name} bits {bits}")
+    wl, coords, W, b = synth.make(name)
+    n = coords.shape[0]
+    net = o.quantize_net(wl.dims, wl.omega0, bits, bits, W, b)
+    o.forward(net, coords[:: max(1, n // 8192)], calibrate=True)
+    model = dhq.Model(wl.dims, wl.omega0, W, b, bits, bits)
+    model.set_act_scales(net.s_a)
+    assert model.has_fused()
+    x = _dev(coords)
+    out = model.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(17)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 6000), np.arange(0, 300), np.arange(n - 300, n)]))
+    got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    exp = o.forward(net, coords[idx])
+    err = _assert_close(got, exp, frac=flip_frac(wl.dims))
+    _say(f"  {idx.size} sampled coords: max-abs err {err.max():.3e}, {(err > OUT_TOL).sum()} beyond {OUT_TOL}")
+    # properties that hold at any size: finite everywhere, and a coordinate's value does not
+    # depend on which launch or tile it was computed in
+    assert bool(torch.isfinite(out).all())
+    sub = model.forward(_dev(coords[idx]), flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(sub.cpu().numpy(), got)
+    model.close()
+
+
 @pytest.mark.parametrize("bits", [4, 6])
 def test_forward_low_bits(bits):
     _say(f"forward bits {bits}")
