@@ -24,6 +24,24 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, 5.0 POP/s
 VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz fp32 lane-ops/s
 
 
+# HBM bytes per launch of the fused kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (profiles/ has the summaries), each counter scaled by what it reads for a plain
+# 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
+# the hash below is compared with the current sources and the figure is dropped if they differ.
+TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
+TRAFFIC_SHA256 = "86f569a1767684cdc134b16eed9f6d312ca8bc257bc3cedb901c5d8532457ba8"
+TRAFFIC_BYTES = {"C2": (2515.5 + 768.0) * 1024, "C5": (44224.0 + 49152.0) * 1024}
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for name in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, "paper_2508_13478_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def time_forward(model, x, out, flags, steps, warmup):
     import torch
     import paper_2508_13478_amd as dhq
@@ -73,6 +91,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (the coordinate grid shards "
@@ -124,13 +144,24 @@ def main() -> int:
         # duration is the event-timed step; algorithmic work = 2 ops per MAC over the un-padded
         # layer shapes
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                     "kernel": "dhq_fused_kernel" if fused else "layerwise kernels",
+                     "frac": tops / INT8_MFMA_PEAK_TOPS,
+                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and kernel_sources_sha256() == TRAFFIC_SHA256
+                                 else None),
+                     "traffic_unit": "bytes per launch (HBM, measured)",
+                     "kernel": (("dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else f"dhq_fused_kernel<{wl.dims[1]}>")
+                                if fused else "layerwise kernels"),
+                     "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
                      "algorithmic_ops_per_launch": ops},
     }
     if fused:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(args.workload, s_a, args.cpu_coords)
     print(json.dumps(res))
