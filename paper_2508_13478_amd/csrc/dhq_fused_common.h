@@ -21,14 +21,28 @@ static inline int bias_slot(int f)
 }
 
 // Copies `chunks` KiB from device memory straight into LDS: each wave moves 1 KiB per
-// instruction (64 lanes x 16 B), the waves of the workgroup take the KiB blocks round-robin.
+// instruction (64 lanes x 16 B, LDS address = M0 + lane * 16), the waves of the workgroup take
+// the KiB blocks round-robin.
+//
+// The load is written as inline assembly on purpose.  Through the compiler builtin the
+// compiler knows that LDS is being written and, unable to tell which LDS reads could alias,
+// makes the next LDS read wait for the whole copy (vmcnt(0)) -- which turns the copy of the
+// next layer's weights, meant to run underneath this layer's arithmetic, into a synchronous
+// one.  Here the kernels order the copy themselves: the destination buffer is never read
+// between this call and the "s_waitcnt vmcnt(0)" + barrier that precedes its first use.
+// Loads the compiler does not know about can only make its own vmcnt waits longer (memory
+// operations retire in order), never shorter.
 __device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsigned char *lds_dst,
                                                  int chunks, int wave, int lane, int n_waves)
 {
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_dst;
     for (int q = wave; q < chunks; q += n_waves) {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(src + (size_t)q * 1024 + lane * 16),
-            (__attribute__((address_space(3))) void *)(lds_dst + q * 1024), 16, 0, 0);
+        const unsigned char *g = src + (size_t)q * 1024 + lane * 16;
+        const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base + q * 1024);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     :
+                     : "v"(g), "s"(m0v)
+                     : "memory", "m0");
     }
 }
 
