@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "86f569a1767684cdc134b16eed9f6d312ca8bc257bc3cedb901c5d8532457ba8"
-TRAFFIC_BYTES = {"C2": (2515.5 + 768.0) * 1024, "C5": (44224.0 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "79d9845329b400183dcc06259e328e29b5864b81673bbaf8f8916a9f2e840876"
+TRAFFIC_BYTES = {"C2": (2521.6 + 768.0) * 1024, "C5": (44232.4 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -153,6 +153,18 @@ def main() -> int:
                      "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
                      "algorithmic_ops_per_launch": ops},
     }
+    # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
+    # sine layer the fused kernels issue about 14.5 vector instructions (convert, fma, sine,
+    # log2(n) add/sub, half a lane swap, fma, max, min); a SIMD issues one
+    # wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4 per second.
+    import math
+    nf = wl.dims[1]
+    per_feature = 3 + math.log2(nf) + 0.5 + 3
+    lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n
+    valu_peak = 256 * 4 * 2.4e9 / 4
+    res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,
+                  "unit": "wave64 instr/s", "frac": lane_instr / 64 / (ms * 1e-3) / valu_peak,
+                  "model": f"{per_feature:.1f} vector instructions per feature and sine layer"}
     if fused:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
