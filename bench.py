@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "79d9845329b400183dcc06259e328e29b5864b81673bbaf8f8916a9f2e840876"
-TRAFFIC_BYTES = {"C2": (2521.6 + 768.0) * 1024, "C5": (44232.4 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "08db8f1444afe843215022791cb0969a8de36ea80f46401efb99f9c1b6d9e1c0"
+TRAFFIC_BYTES = {"C2": (2521.6 + 768.0) * 1024, "C5": (44556.0 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -142,7 +142,7 @@ def main() -> int:
         "wall_ms_per_step": wall_ms,
         # dominant kernel = the fused whole-network kernel: one launch per step, so its average
         # duration is the event-timed step; algorithmic work = 2 ops per MAC over the un-padded
-        # layer shapes (see DESIGN.md)
+        # layer shapes
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": tops / INT8_MFMA_PEAK_TOPS,
                      "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and kernel_sources_sha256() == TRAFFIC_SHA256
@@ -155,7 +155,7 @@ def main() -> int:
     }
     # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
     # sine layer the fused kernels issue about 14.5 vector instructions (convert, fma, sine,
-    # log2(n) add/sub, half a lane swap, fma, max, min; DESIGN.md section 6); a SIMD issues one
+    # log2(n) add/sub, half a lane swap, fma, max, min); a SIMD issues one
     # wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4 per second.
     import math
     nf = wl.dims[1]

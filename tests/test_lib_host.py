@@ -73,3 +73,29 @@ def test_product_package_does_not_import_the_oracle():
     for f in ("dhq_oracle.c", "dhq_oracle.py"):
         text = open(os.path.join(ROOT, "oracle", f)).read()
         assert "paper_2508_13478_amd" not in text and "libdhq.so" not in text
+
+
+def test_wide_register_map_check_catches_violations():
+    """The build refuses a width-512 kernel whose compiler-generated code touches the
+    accumulation registers the kernel addresses by number, or whose allocation is too small."""
+    from paper_2508_13478_amd import build as b
+    ok = "\n".join([
+        "_Z21dhq_fused_wide_kernelILi512EEv9wide_args: ; @kernel",
+        "\tv_accvgpr_write_b32 a127, v3",
+        "\t;;#ASMSTART",
+        "\tv_mfma_i32_32x32x32_i8 v[0:15], v[16:19], a[0xa0:0xa3], 0",
+        "\tglobal_load_dwordx4 a[224:227], v1, s[2:3]",
+        "\t;;#ASMEND",
+        "\tv_add_f32_e32 v1, v2, v3 ; a200 in a comment does not count",
+        "\t.amdhsa_next_free_vgpr 468",
+        "\t.amdhsa_accum_offset 212",
+    ])
+    b.check_wide_register_map(ok)
+    for planted in ("\tv_accvgpr_read_b32 v5, a160", "\tds_write_b128 v1, a[156:163]", "\tscratch_store_dword off, a[0xff], off"):
+        bad = ok.replace("\tv_add_f32_e32", planted + "\n\tv_add_f32_e32")
+        with pytest.raises(RuntimeError):
+            b.check_wide_register_map(bad)
+    with pytest.raises(RuntimeError):
+        b.check_wide_register_map(ok.replace("accum_offset 212", "accum_offset 216"))
+    with pytest.raises(RuntimeError):
+        b.check_wide_register_map("nothing here")
