@@ -31,6 +31,10 @@
  * form Eq. 5; quantizer brute force and tie table; int32 GEMM against int64;
  * the closed form of layer 1 on the [-1,1]^2 grid; the unquantized rotated
  * path against the plain MLP and against torch's linear+sin.
+ * Two-sided variant: the un-rotated product against the plain product, the
+ * integer un-rotation against an int64 matrix product with scipy's Hadamard
+ * matrix, fan-out 1 against the one-sided path (bitwise), reconstruction
+ * error bound of the de-rotated quantized weights.
  * Parity unpinned: absolute image quality (Table 1) -- it needs the paper's
  * images and trained weights.
  */
@@ -325,6 +329,149 @@ int dhqo_forward(int n_layers, const int32_t *dims, float omega0, int bits_a,
         rc = dhqo_layer(cur, N, K, M, Wq[l], s_w[l], bias[l], &s_a[l], calibrate, bits_a,
                         !last, omega0, dst, dump_rot ? dump_rot[l] : NULL,
                         dump_codes ? dump_codes[l] : NULL, dump_acc ? dump_acc[l] : NULL);
+        if (rc == DHQO_OK && dump_act && dump_act[l])
+            memcpy(dump_act[l], dst, sizeof(float) * (size_t)(N * M));
+        free(owned);
+        owned = last ? NULL : dst;
+        cur = dst;
+        if (rc) break;
+    }
+    free(owned);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * Two-sided variant: the weight transform exactly as Eq. 4-5 print it,
+ * W' = H_m W H_n / sqrt(m n), over BOTH the output-feature side (m) and the
+ * input-feature side (n).  The activations are rotated over the input
+ * features as before, so the integer GEMM now yields the layer output in the
+ * rotated output basis: acc' = q W'q^T ~ (a W^T) H_m / (s_a s_w sqrt(m)).
+ * Because H_m H_m = m I the rotation is undone by one more multiplication by
+ * H_m, which has entries +-1 and is therefore exact on the int32
+ * accumulators; the factor 1/sqrt(m) joins the dequantization scale.
+ * Fan-out M is zero-padded to Mp = next_pow2(M) (rows of zeros), the padded
+ * outputs are dropped after the un-rotation.  Reading of the paper: it
+ * prints only the weight transform; how the output side is undone is this
+ * build's choice (listed in the design notes).
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Offline weight step, two-sided.  W is M x K fp32; Wq is Mp x Kp int8.
+ * If rot_out is not NULL it receives the rotated fp64 weights (Mp x Kp).
+ */
+int dhqo_quantize_weights_two_sided(const float *W, int M, int K, int bits, int8_t *Wq,
+                                    float *s_w, double *rot_out)
+{
+    if (!W || !Wq || !s_w || M < 1 || K < 1 || bits < 2 || bits > 8) return DHQO_EINVAL;
+    int Kp = dhqo_next_pow2(K), Mp = dhqo_next_pow2(M);
+    double *Wd = (double *)calloc((size_t)Mp * Kp, sizeof(double));
+    double *Wr = (double *)malloc(sizeof(double) * (size_t)Mp * Kp);
+    if (!Wd || !Wr) { free(Wd); free(Wr); return DHQO_ENOMEM; }
+    for (int j = 0; j < M; ++j)
+        for (int k = 0; k < K; ++k) Wd[(size_t)j * Kp + k] = (double)W[(size_t)j * K + k];
+    int rc = dhqo_rotate_two_sided(Wd, Mp, Kp, Wr);
+    if (rc == DHQO_OK) {
+        *s_w = dhqo_absmax_scale(Wr, (int64_t)Mp * Kp, bits);
+        rc = dhqo_quantize(Wr, (int64_t)Mp * Kp, *s_w, bits, Wq);
+        if (rot_out) memcpy(rot_out, Wr, sizeof(double) * (size_t)Mp * Kp);
+    }
+    free(Wd); free(Wr);
+    return rc;
+}
+
+/*
+ * Un-rotation of the accumulators: z[i][j] = sum_j' acc[i][j'] H_Mp[j'][j],
+ * acc and z are N x Mp int32.  Computed in int64; DHQO_EOVERFLOW if a result
+ * does not fit int32.
+ */
+int dhqo_unrotate_acc(const int32_t *acc, int64_t N, int Mp, int32_t *z)
+{
+    if (!acc || !z || N < 0 || Mp < 1 || (Mp & (Mp - 1))) return DHQO_EINVAL;
+    double *H = (double *)malloc(sizeof(double) * (size_t)Mp * Mp);
+    if (!H) return DHQO_ENOMEM;
+    dhqo_hadamard(Mp, H);
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t i = 0; i < N; ++i)
+        for (int j = 0; j < Mp; ++j) {
+            int64_t s = 0;
+            for (int jp = 0; jp < Mp; ++jp)
+                s += (H[(size_t)jp * Mp + j] > 0.0) ? (int64_t)acc[i * Mp + jp] : -(int64_t)acc[i * Mp + jp];
+            if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+            z[i * Mp + j] = (int32_t)s;
+        }
+    free(H);
+    return bad ? DHQO_EOVERFLOW : DHQO_OK;
+}
+
+/*
+ * One quantized layer, two-sided.  Same arguments as dhqo_layer except that
+ * Wq is Mp x Kp.  Optional dumps: rot N x Kp fp64, codes N x Kp, acc N x Mp
+ * (the rotated accumulators), unrot N x Mp (after the un-rotation).
+ * y[j] = z[j] * (s_a s_w / sqrt(Mp)) + b[j] for j < M.
+ */
+int dhqo_layer_two_sided(const float *a_in, int64_t N, int K, int M, const int8_t *Wq, float s_w,
+                         const float *bias, float *s_a, int calibrate, int bits_a, int apply_sine,
+                         float omega0, float *out, double *dump_rot, int8_t *dump_codes,
+                         int32_t *dump_acc, int32_t *dump_unrot)
+{
+    if (!a_in || !Wq || !bias || !s_a || !out || N < 0) return DHQO_EINVAL;
+    int Kp = dhqo_next_pow2(K), Mp = dhqo_next_pow2(M);
+    int rc = DHQO_OK;
+    double *ad = (double *)malloc(sizeof(double) * (size_t)(N * K + 1));
+    double *rot = dump_rot ? dump_rot : (double *)malloc(sizeof(double) * (size_t)(N * Kp + 1));
+    int8_t *codes = dump_codes ? dump_codes : (int8_t *)malloc((size_t)(N * Kp + 1));
+    int32_t *acc = dump_acc ? dump_acc : (int32_t *)malloc(sizeof(int32_t) * (size_t)(N * Mp + 1));
+    int32_t *z = dump_unrot ? dump_unrot : (int32_t *)malloc(sizeof(int32_t) * (size_t)(N * Mp + 1));
+    if (!ad || !rot || !codes || !acc || !z) { rc = DHQO_ENOMEM; goto done; }
+    for (int64_t i = 0; i < N * K; ++i) ad[i] = (double)a_in[i];
+    rc = dhqo_rotate_rows(ad, N, K, rot);
+    if (rc) goto done;
+    if (calibrate) *s_a = dhqo_absmax_scale(rot, N * Kp, bits_a);
+    rc = dhqo_quantize(rot, N * Kp, *s_a, bits_a, codes);
+    if (rc) goto done;
+    rc = dhqo_igemm(codes, Wq, N, Mp, Kp, acc);
+    if (rc) goto done;
+    rc = dhqo_unrotate_acc(acc, N, Mp, z);
+    if (rc) goto done;
+    {
+        const double sc = (double)*s_a * (double)s_w / sqrt((double)Mp);
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < N; ++i)
+            for (int j = 0; j < M; ++j) {
+                double y = (double)z[i * Mp + j] * sc + (double)bias[j];
+                out[i * M + j] = apply_sine ? (float)sin((double)omega0 * y) : (float)y;
+            }
+    }
+done:
+    free(ad);
+    if (!dump_rot) free(rot);
+    if (!dump_codes) free(codes);
+    if (!dump_acc) free(acc);
+    if (!dump_unrot) free(z);
+    return rc;
+}
+
+/* Whole quantized forward, two-sided; arguments as dhqo_forward (Wq[l] is Mp x Kp). */
+int dhqo_forward_two_sided(int n_layers, const int32_t *dims, float omega0, int bits_a,
+                           const int8_t *const *Wq, const float *s_w, const float *const *bias,
+                           float *s_a, int calibrate, const float *coords, int64_t N, float *out,
+                           double *const *dump_rot, int8_t *const *dump_codes,
+                           int32_t *const *dump_acc, float *const *dump_act)
+{
+    if (n_layers < 1 || !dims || !Wq || !s_w || !bias || !s_a || !coords || !out || N < 0)
+        return DHQO_EINVAL;
+    int rc = DHQO_OK;
+    const float *cur = coords;
+    float *owned = NULL;
+    for (int l = 0; l < n_layers; ++l) {
+        int K = dims[l], M = dims[l + 1];
+        int last = (l == n_layers - 1);
+        float *dst = last ? out : (float *)malloc(sizeof(float) * (size_t)(N * M + 1));
+        if (!dst) { rc = DHQO_ENOMEM; break; }
+        rc = dhqo_layer_two_sided(cur, N, K, M, Wq[l], s_w[l], bias[l], &s_a[l], calibrate, bits_a,
+                                  !last, omega0, dst, dump_rot ? dump_rot[l] : NULL,
+                                  dump_codes ? dump_codes[l] : NULL, dump_acc ? dump_acc[l] : NULL, NULL);
         if (rc == DHQO_OK && dump_act && dump_act[l])
             memcpy(dump_act[l], dst, sizeof(float) * (size_t)(N * M));
         free(owned);

@@ -69,6 +69,11 @@ def _declare(L: C.CDLL) -> None:
     L.dhqo_forward.argtypes = [C.c_int, _i32p, C.c_float, C.c_int, C.POINTER(_i8p), _fp,
                                C.POINTER(_fp), _fp, C.c_int, _fp, C.c_int64, _fp,
                                C.POINTER(_dp), C.POINTER(_i8p), C.POINTER(_i32p), C.POINTER(_fp)]
+    L.dhqo_quantize_weights_two_sided.argtypes = [_fp, C.c_int, C.c_int, C.c_int, _i8p, _fp, _dp]
+    L.dhqo_unrotate_acc.argtypes = [_i32p, C.c_int64, C.c_int, _i32p]
+    L.dhqo_layer_two_sided.argtypes = [_fp, C.c_int64, C.c_int, C.c_int, _i8p, C.c_float, _fp, _fp, C.c_int,
+                                       C.c_int, C.c_int, C.c_float, _fp, _dp, _i8p, _i32p, _i32p]
+    L.dhqo_forward_two_sided.argtypes = L.dhqo_forward.argtypes
     L.dhqo_mlp_float.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp), _fp,
                                  C.c_int64, _dp, _fp]
     L.dhqo_mlp_rotated_f64.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp),
@@ -180,6 +185,31 @@ def quantize_weights(W: np.ndarray, bits: int, want_rot: bool = False):
     return Wq, np.float32(s.value)
 
 
+def quantize_weights_two_sided(W: np.ndarray, bits: int, want_rot: bool = False):
+    """Eq. 4-5 as printed: rotate over both sides (fan-out zero-padded to a power of two),
+    per-tensor scale, quantize. Returns (Wq [Mp x Kp], s_w[, rot])."""
+    W = _c(W, np.float32)
+    M, K = W.shape
+    Kp, Mp = next_pow2(K), next_pow2(M)
+    Wq = np.empty((Mp, Kp), dtype=np.int8)
+    s = C.c_float(0)
+    rot = np.empty((Mp, Kp), dtype=np.float64) if want_rot else None
+    _check(lib().dhqo_quantize_weights_two_sided(_ptr(W, _fp), M, K, bits, _ptr(Wq, _i8p), C.byref(s),
+                                                 _ptr(rot, _dp)), "quantize_weights_two_sided")
+    if want_rot:
+        return Wq, np.float32(s.value), rot
+    return Wq, np.float32(s.value)
+
+
+def unrotate_acc(acc: np.ndarray) -> np.ndarray:
+    """z = acc H_Mp on int32 rows (exact; raises on int32 overflow)."""
+    acc = _c(acc, np.int32)
+    N, Mp = acc.shape
+    z = np.empty_like(acc)
+    _check(lib().dhqo_unrotate_acc(_ptr(acc, _i32p), N, Mp, _ptr(z, _i32p)), "unrotate_acc")
+    return z
+
+
 @dataclass
 class QuantizedNet:
     dims: List[int]
@@ -190,6 +220,7 @@ class QuantizedNet:
     s_w: np.ndarray
     bias: List[np.ndarray]
     s_a: Optional[np.ndarray] = None
+    two_sided: bool = False
 
 
 @dataclass
@@ -201,15 +232,15 @@ class ForwardDump:
 
 
 def quantize_net(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int,
-                 W: Sequence[np.ndarray], bias: Sequence[np.ndarray]) -> QuantizedNet:
+                 W: Sequence[np.ndarray], bias: Sequence[np.ndarray], two_sided: bool = False) -> QuantizedNet:
     Wq, s_w = [], []
     for Wl in W:
-        q, s = quantize_weights(Wl, bits_w)
+        q, s = (quantize_weights_two_sided if two_sided else quantize_weights)(Wl, bits_w)
         Wq.append(q)
         s_w.append(s)
     return QuantizedNet(list(dims), float(omega0), bits_w, bits_a, Wq,
                         np.asarray(s_w, dtype=np.float32),
-                        [_c(b, np.float32) for b in bias])
+                        [_c(b, np.float32) for b in bias], None, two_sided)
 
 
 def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump: bool = False):
@@ -236,15 +267,17 @@ def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump
             Kp = next_pow2(net.dims[l])
             d.rot.append(np.empty((N, Kp), dtype=np.float64))
             d.codes.append(np.empty((N, Kp), dtype=np.int8))
-            d.acc.append(np.empty((N, net.dims[l + 1]), dtype=np.int32))
+            Mo = next_pow2(net.dims[l + 1]) if net.two_sided else net.dims[l + 1]
+            d.acc.append(np.empty((N, Mo), dtype=np.int32))
             d.act.append(np.empty((N, net.dims[l + 1]), dtype=np.float32))
         rot_p = (_dp * L)(*[_ptr(a, _dp) for a in d.rot])
         cod_p = (_i8p * L)(*[_ptr(a, _i8p) for a in d.codes])
         acc_p = (_i32p * L)(*[_ptr(a, _i32p) for a in d.acc])
         act_p = (_fp * L)(*[_ptr(a, _fp) for a in d.act])
-    rc = lib().dhqo_forward(L, _ptr(dimsa, _i32p), C.c_float(net.omega0), net.bits_a, Wq_p,
-                            _ptr(net.s_w, _fp), b_p, _ptr(s_a, _fp), int(calibrate),
-                            _ptr(coords, _fp), N, _ptr(out, _fp), rot_p, cod_p, acc_p, act_p)
+    fwd = lib().dhqo_forward_two_sided if net.two_sided else lib().dhqo_forward
+    rc = fwd(L, _ptr(dimsa, _i32p), C.c_float(net.omega0), net.bits_a, Wq_p,
+            _ptr(net.s_w, _fp), b_p, _ptr(s_a, _fp), int(calibrate),
+            _ptr(coords, _fp), N, _ptr(out, _fp), rot_p, cod_p, acc_p, act_p)
     _check(rc, "forward")
     if calibrate:
         net.s_a = s_a
@@ -271,6 +304,30 @@ def layer(a_in: np.ndarray, Wq: np.ndarray, s_w: float, bias: np.ndarray, s_a: O
                           _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p))
     _check(rc, "layer")
     return dict(rot=rot, codes=codes, acc=acc, act=out, s_a=np.float32(s.value))
+
+
+def layer_two_sided(a_in: np.ndarray, M: int, Wq: np.ndarray, s_w: float, bias: np.ndarray,
+                    s_a: Optional[float], bits_a: int, apply_sine: bool, omega0: float):
+    """One two-sided layer (Wq is Mp x Kp, M outputs kept). s_a=None measures the scale.
+    Returns dict(rot, codes, acc [N x Mp, rotated], unrot [N x Mp], act [N x M], s_a)."""
+    a_in = _c(a_in, np.float32)
+    N, K = a_in.shape
+    Mp, Kp = Wq.shape
+    assert Kp == next_pow2(K) and Mp == next_pow2(M)
+    Wq = _c(Wq, np.int8)
+    bias = _c(bias, np.float32)
+    rot = np.empty((N, Kp), dtype=np.float64)
+    codes = np.empty((N, Kp), dtype=np.int8)
+    acc = np.empty((N, Mp), dtype=np.int32)
+    unrot = np.empty((N, Mp), dtype=np.int32)
+    out = np.empty((N, M), dtype=np.float32)
+    s = C.c_float(0.0 if s_a is None else s_a)
+    rc = lib().dhqo_layer_two_sided(_ptr(a_in, _fp), N, K, M, _ptr(Wq, _i8p), C.c_float(s_w), _ptr(bias, _fp),
+                                    C.byref(s), int(s_a is None), bits_a, int(apply_sine), C.c_float(omega0),
+                                    _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p),
+                                    _ptr(unrot, _i32p))
+    _check(rc, "layer_two_sided")
+    return dict(rot=rot, codes=codes, acc=acc, unrot=unrot, act=out, s_a=np.float32(s.value))
 
 
 def mlp_float(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],

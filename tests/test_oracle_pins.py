@@ -331,3 +331,124 @@ def test_splitmix64_reference_values():
     """First outputs of splitmix64 with seed 0 (published test vector of the generator)."""
     z = synth.splitmix64(0, 0, 3)
     assert [int(v) for v in z] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+# ------------------------------------------- two-sided variant (Eq. 4-5 as printed)
+def _sylvester(n):
+    sl = pytest.importorskip("scipy.linalg")
+    return sl.hadamard(n).astype(np.int64) if n > 1 else np.ones((1, 1), dtype=np.int64)
+
+
+@pytest.mark.parametrize("M,K", [(3, 5), (48, 100), (64, 2), (3, 256), (1, 7), (256, 256)])
+def test_two_sided_unquantized_product_equals_plain(M, K):
+    """(a Hn)(Hm W Hn)^T Hm = a W^T: placement, padding and scaling of both rotations."""
+    rng = np.random.default_rng(100 * M + K)
+    W = rng.standard_normal((M, K))
+    a = rng.standard_normal((9, K))
+    Mp, Kp = o.next_pow2(M), o.next_pow2(K)
+    Wpad = np.zeros((Mp, Kp)); Wpad[:M, :K] = W
+    Wr = o.rotate_two_sided(Wpad)
+    yr = o.rotate_rows(a) @ Wr.T                        # rotated output basis, 9 x Mp
+    y = (yr @ _sylvester(Mp)) / math.sqrt(Mp)
+    ref = a @ W.T
+    assert np.abs(y[:, :M] - ref).max() <= 1e-12 * max(1.0, np.abs(ref).max())
+    assert np.abs(y[:, M:]).max(initial=0.0) <= 1e-12 * max(1.0, np.abs(ref).max())
+    assert abs(np.linalg.norm(Wr) - np.linalg.norm(W)) <= 1e-12 * np.linalg.norm(W)   # energy preserved
+
+
+@pytest.mark.parametrize("Mp", [1, 2, 4, 64, 512])
+def test_unrotate_acc_matches_int64_product_and_is_an_involution_up_to_m(Mp):
+    rng = np.random.default_rng(Mp)
+    acc = rng.integers(-(1 << 20) // Mp, (1 << 20) // Mp + 1, size=(37, Mp)).astype(np.int32)
+    z = o.unrotate_acc(acc)
+    assert np.array_equal(z.astype(np.int64), acc.astype(np.int64) @ _sylvester(Mp))
+    assert np.array_equal(o.unrotate_acc(z), (Mp * acc.astype(np.int64)).astype(np.int32))     # H H = m I
+
+
+def test_unrotate_acc_overflow_is_reported():
+    acc = np.full((2, 32), 1 << 27, dtype=np.int32)       # column 0 of H is all ones: the sum is 2^32
+    with pytest.raises(o.OracleError):
+        o.unrotate_acc(acc)
+    acc[:, :] = (1 << 26) - 1                             # 32 * (2^26 - 1) < 2^31 fits
+    assert o.unrotate_acc(acc)[0, 0] == 32 * ((1 << 26) - 1)
+
+
+def test_two_sided_with_one_output_is_the_one_sided_path():
+    """H_1 = [1]: with fan-out 1 the output-side rotation does nothing, bit for bit."""
+    rng = np.random.default_rng(5)
+    W = rng.uniform(-0.3, 0.3, size=(1, 48)).astype(np.float32)
+    b = np.array([0.1], dtype=np.float32)
+    a = rng.uniform(-1, 1, size=(50, 48)).astype(np.float32)
+    q1, s1 = o.quantize_weights(W, 8)
+    q2, s2 = o.quantize_weights_two_sided(W, 8)
+    assert np.array_equal(q1, q2) and s1 == s2
+    r1 = o.layer(a, q1, s1, b, None, 8, True, 30.0)
+    r2 = o.layer_two_sided(a, 1, q2, s2, b, None, 8, True, 30.0)
+    assert np.array_equal(r1["codes"], r2["codes"]) and np.array_equal(r1["acc"], r2["unrot"])
+    assert np.array_equal(r1["act"], r2["act"]) and r1["s_a"] == r2["s_a"]
+
+
+@pytest.mark.parametrize("M,K,bits", [(64, 2, 8), (3, 64, 8), (48, 100, 6), (256, 256, 4)])
+def test_two_sided_weight_codes_reconstruct_the_weights_within_half_a_step(M, K, bits):
+    rng = np.random.default_rng(M + K + bits)
+    W = rng.uniform(-0.5, 0.5, size=(M, K)).astype(np.float32)
+    Wq, s_w, rot = o.quantize_weights_two_sided(W, bits, want_rot=True)
+    Mp, Kp = Wq.shape
+    assert np.abs(Wq).max() == o.qmax(bits)                            # the absmax element maps to +-qmax
+    assert np.abs(Wq.astype(np.float64) * float(s_w) - rot).max() <= 0.5 * float(s_w) * (1 + 1e-6)
+    # back through both (orthonormal) rotations the error keeps its Frobenius norm
+    back = _sylvester(Mp) @ (Wq.astype(np.float64) * float(s_w)) @ _sylvester(Kp) / math.sqrt(Mp * Kp)
+    Wpad = np.zeros((Mp, Kp)); Wpad[:M, :K] = W
+    assert np.linalg.norm(back - Wpad) <= 0.5 * float(s_w) * math.sqrt(Mp * Kp) * (1 + 1e-6)
+
+
+def test_two_sided_layer_is_the_composition_of_library_steps():
+    rng = np.random.default_rng(11)
+    M, K, N = 5, 12, 40
+    W = rng.uniform(-0.4, 0.4, size=(M, K)).astype(np.float32)
+    b = rng.uniform(-0.2, 0.2, size=M).astype(np.float32)
+    a = rng.uniform(-1, 1, size=(N, K)).astype(np.float32)
+    Wq, s_w = o.quantize_weights_two_sided(W, 8)
+    r = o.layer_two_sided(a, M, Wq, s_w, b, None, 8, True, 30.0)
+    Mp, Kp = Wq.shape
+    apad = np.zeros((N, Kp)); apad[:, :K] = a
+    xr = apad @ _sylvester(Kp) / math.sqrt(Kp)
+    s_a = np.float32(np.abs(xr).max() / 127.0)
+    assert s_a == r["s_a"]
+    codes = np.clip(np.rint(xr / float(s_a)), -127, 127).astype(np.int64)     # rint rounds half to even
+    assert np.array_equal(codes, r["codes"])
+    acc = codes @ Wq.astype(np.int64).T
+    assert np.array_equal(acc, r["acc"])
+    z = acc @ _sylvester(Mp)
+    assert np.array_equal(z, r["unrot"])
+    y = z[:, :M] * (float(s_a) * float(s_w) / math.sqrt(Mp)) + b.astype(np.float64)
+    assert np.abs(np.sin(30.0 * y).astype(np.float32) - r["act"]).max() <= 1e-6
+
+
+def test_two_sided_rotation_makes_first_layer_weights_bell_shaped():
+    """Sec. 3.2 / Fig. 4: after the transform the weights are close to Gaussian.  The K = 2
+    input layer cannot get there from the input side alone (a sum of two uniforms is
+    triangular, excess kurtosis -0.6); rotating the 256-wide output side as well does."""
+    _, _, W, _ = synth.make("C2")
+    def excess_kurtosis(x):
+        x = x.ravel() - x.mean()
+        return float((x ** 4).mean() / (x ** 2).mean() ** 2 - 3.0)
+    _, _, rot1 = o.quantize_weights(W[0], 8, want_rot=True)
+    _, _, rot2 = o.quantize_weights_two_sided(W[0], 8, want_rot=True)
+    assert excess_kurtosis(W[0]) < -1.0                      # uniform: -1.2
+    assert -0.9 < excess_kurtosis(rot1) < -0.3               # triangular
+    assert abs(excess_kurtosis(rot2)) < 0.35                 # near Gaussian
+
+
+def test_two_sided_forward_tracks_the_float_mlp_and_improves_with_bits():
+    wl, coords, W, b = synth.make("C1")
+    ref, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords)
+    errs = []
+    for bits in (4, 6, 8):
+        net = o.quantize_net(wl.dims, wl.omega0, bits, bits, W, b, two_sided=True)
+        out = o.forward(net, coords, calibrate=True)
+        errs.append(float(np.sqrt(np.mean((out - ref) ** 2))))
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 0.01
+    # static scales reproduce the calibrated run
+    again = o.forward(net, coords[::7])
+    assert np.array_equal(again, out[::7])
