@@ -60,7 +60,7 @@ def time_forward(model, x, out, flags, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def cpu_baseline(name, s_a, max_coords):
+def cpu_baseline(name, s_a, max_coords, two_sided=False):
     """The CPU oracle's quantized forward (static scales) timed on a bounded sample."""
     import numpy as np
     from oracle import dhq_oracle as o
@@ -68,17 +68,22 @@ def cpu_baseline(name, s_a, max_coords):
     wl, coords, W, b = synth.make(name)
     stride = max(1, -(-coords.shape[0] // max_coords))
     sample = coords[::stride]
-    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two_sided)
     net.s_a = np.asarray(s_a, dtype=np.float32)
-    t0 = time.perf_counter()
-    o.forward(net, sample)
-    dt = time.perf_counter() - t0
+    # repeat the sample until about ten seconds of oracle time have been spent
+    runs, t0 = 0, time.perf_counter()
+    while True:
+        o.forward(net, sample)
+        runs += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or runs >= 50:
+            break
     try:
         threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
     except OSError:
         threads = os.cpu_count() or 1
-    return {"value": sample.shape[0] / dt, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{name} grid, every {stride}th coordinate ({sample.shape[0]} coords), one run, "
+    return {"value": runs * sample.shape[0] / dt, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{name} grid, every {stride}th coordinate ({sample.shape[0]} coords), {runs} runs, "
                       f"{dt:.2f} s, quantized forward with static scales (weight quantization and "
                       f"calibration excluded)"}
 
@@ -89,6 +94,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--variant", default="base", choices=["base", "two_sided", "dynamic", "two_sided_dynamic"],
+                    help="base: input-side rotation, static scales (fused kernel where there is one); "
+                         "two_sided: weights rotated on both sides, un-rotation in int32 (layer-by-layer path); "
+                         "dynamic: activation scales measured on line per call (layer-by-layer path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
     ap.add_argument("--copy-probe", action="store_true",
@@ -108,13 +117,17 @@ def main() -> int:
         return 1
     torch.cuda.set_device(0)
     wl, coords, W, b = synth.make(args.workload)
-    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8)
+    two_sided = args.variant.startswith("two_sided")
+    dynamic = args.variant.endswith("dynamic")
+    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN)
     x = torch.from_numpy(coords).to("cuda")
     out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
     model.calibrate(x)
     _, s_a = model.scales()
-    fused = model.has_fused()
+    fused = model.has_fused() and not dynamic
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
+    if dynamic:
+        flags |= dhq.DHQ_DYNAMIC
 
     ms, wall_ms = time_forward(model, x, out, flags, args.steps, args.warmup)
     n = x.shape[0]
@@ -136,7 +149,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: SIREN {'-'.join(map(str, wl.dims))}, omega0={wl.omega0:g}, "
                                f"{wl.side}x{wl.side} grid ({n} coords), W8A8, static per-layer scales "
                                f"from absmax calibration on the same grid",
-                   "path": "fused" if fused else "layerwise", "coords": n},
+                   "path": "fused" if fused else "layerwise", "variant": args.variant, "coords": n},
         "int8_tops": tops,
         "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
         "wall_ms_per_step": wall_ms,
@@ -165,6 +178,23 @@ def main() -> int:
     res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,
                   "unit": "wave64 instr/s", "frac": lane_instr / 64 / (ms * 1e-3) / valu_peak,
                   "model": f"{per_feature:.1f} vector instructions per feature and sine layer"}
+    if not fused:
+        # The layer-by-layer path is bound by device-memory traffic: per coordinate and layer the
+        # transform reads 4 K bytes (twice when the scale is measured on line) and writes Kp codes,
+        # the GEMM reads them and writes 4 M bytes of activations (two-sided: 4 Mp of accumulators,
+        # which the un-rotation kernel reads back before it writes the 4 M).
+        def p2(k):
+            return 1 << (k - 1).bit_length() if k > 1 else 1
+        per_coord = 0
+        for l in range(len(wl.dims) - 1):
+            K, M = wl.dims[l], wl.dims[l + 1]
+            per_coord += 4 * K * (2 if dynamic else 1) + 2 * p2(K) + 4 * M + (8 * p2(M) if two_sided else 0)
+        gbs = per_coord * n / (ms * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                           "traffic": None, "kernel": "layer-by-layer path, all kernels of one forward",
+                           "algorithmic_hbm_bytes_per_launch": per_coord * n,
+                           "algorithmic_ops_per_launch": ops}
+        res.pop("alu", None)
     if fused:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
@@ -175,7 +205,7 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(args.workload, s_a, args.cpu_coords)
+        res["cpu_baseline"] = cpu_baseline(args.workload, s_a, args.cpu_coords, two_sided)
     print(json.dumps(res))
     return 0
 

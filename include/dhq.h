@@ -54,6 +54,14 @@ typedef enum {
 #define DHQ_AUTO 0u
 #define DHQ_LAYERWISE 1u /* three kernels per layer, activations round-trip device memory */
 #define DHQ_FUSED 2u     /* one kernel for the whole network; DHQ_EUNSUPPORTED if the shape has none */
+/* or-ed onto the above: measure every layer's activation scale on line, on this call's own
+ * coordinates, instead of using the scales stored in the model (Sec. 3.3, "dynamic
+ * quantization module ... between layers").  Layer-by-layer path only. */
+#define DHQ_DYNAMIC 4u
+
+/* dhq_quantize_weights_mode: which sides of the weight matrix are rotated. */
+#define DHQ_ROTATE_IN 0u   /* input-feature side only (what dhq_quantize_weights does) */
+#define DHQ_ROTATE_BOTH 1u /* both sides, W' = H_m W H_n / sqrt(m n), Eq. 4-5 as printed */
 
 typedef struct dhq_model dhq_model; /* opaque */
 
@@ -78,6 +86,23 @@ typedef struct {
 int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
                          const float *const *b_host, dhq_model **out);
 
+/*
+ * The same offline step with the rotation of Eq. 4-5 taken on both sides (mode =
+ * DHQ_ROTATE_BOTH): fan-out M is zero-padded to Mp = next power of two, the weights become
+ * W' = H_Mp pad(W) H_Kp / sqrt(Mp Kp) (Mp x Kp codes, one scale), and every layer of the
+ * forward path then computes
+ *     acc' = q * W'q^T                 (n x Mp, the output in the rotated basis)
+ *     z    = acc' * H_Mp               (exact in int32: entries of H are +-1, H H = Mp I)
+ *     y    = z[:, :M] * (s_a s_w / sqrt(Mp)) + b
+ * Weights for which |z| could leave int32 (bound: qmax_a * sum_k |(H_Mp W'q)[j][k]| for some
+ * output j) are refused with DHQ_EUNSUPPORTED.  Such a model runs on the layer-by-layer path
+ * only (dhq_has_fused is 0); dhq_get_weight_codes returns Mp x Kp codes, dhq_gemm_i8 the
+ * rotated accumulators (n x Mp) and dhq_forward_debug the un-rotated ones (n x Mp).
+ * mode = DHQ_ROTATE_IN is dhq_quantize_weights.
+ */
+int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
+                              const float *const *b_host, dhq_model **out);
+
 /* Static per-layer activation scales s_a (host, n_layers entries, each finite and > 0). */
 int dhq_set_act_scales(dhq_model *m, const float *s_a_host);
 
@@ -95,7 +120,8 @@ int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream
  * s_a_host is filled with zeros if no activation scales are set yet. */
 int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_host);
 
-/* Copies layer l's quantized, rotated weights out: host, dims[l+1] x Kp int8, row-major. */
+/* Copies layer l's quantized, rotated weights out: host, dims[l+1] x Kp int8, row-major
+ * (Mp x Kp for a DHQ_ROTATE_BOTH model). */
 int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
 
 /*
@@ -103,18 +129,29 @@ int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
  *   coords_dev  dev, n x dims[0] fp32
  *   out_dev     dev, n x dims[n_layers] fp32
  *   n           number of coordinates; 0 is a successful no-op
- *   flags       DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED
- * Uses the activation scales stored in the model (DHQ_ENOSCALE if there are none).
+ *   flags       DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED, optionally | DHQ_DYNAMIC
+ * Uses the activation scales stored in the model (DHQ_ENOSCALE if there are none), unless
+ * DHQ_DYNAMIC is given: then each layer's scale is max|x^| / qmax over the whole rotated
+ * n x Kp input of that layer in THIS call (two passes over the layer input, the scale never
+ * leaves the device; an all-zero tensor gets scale 1), which gives exactly what
+ * dhq_calibrate on these coordinates followed by a static forward gives.  Dynamic mode keeps
+ * all n rows of a layer in device memory: the model's workspace grows to n rows on the first
+ * such call (an allocation, and a device synchronisation, whenever n exceeds every earlier
+ * dynamic call).  DHQ_DYNAMIC | DHQ_FUSED is DHQ_EUNSUPPORTED.
  */
 int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev,
                 void *stream, uint32_t flags);
+
+/* The scales s_a (host, n_layers floats) that the last DHQ_DYNAMIC forward on this model
+ * measured.  Synchronises `stream` (pass the stream that forward ran on). */
+int dhq_get_dynamic_scales(const dhq_model *m, float *s_a_host, void *stream);
 
 /*
  * Test hook: one layer of the layer-by-layer path on a caller-supplied input,
  * with every intermediate exposed (any output pointer may be NULL).
  *   in_dev     dev, n x dims[layer] fp32   (the layer's un-rotated input)
  *   codes_dev  dev, n x Kp int8            rotated + quantized input
- *   acc_dev    dev, n x dims[layer+1] int32
+ *   acc_dev    dev, n x dims[layer+1] int32 (n x Mp, un-rotated, for a DHQ_ROTATE_BOTH model)
  *   act_dev    dev, n x dims[layer+1] fp32 (after bias and, except for the last layer, sine)
  * n is limited to the model's workspace chunk (65536 rows).
  */
@@ -124,7 +161,7 @@ int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_t n, int32_
 /*
  * Test hook: the integer GEMM of one layer alone (Sec. 3.3 MAC array) on
  * caller-supplied codes: acc = codes * Wq[layer]^T.
- *   codes_dev  dev, n x Kp int8;  acc_dev  dev, n x dims[layer+1] int32
+ *   codes_dev  dev, n x Kp int8;  acc_dev  dev, n x dims[layer+1] int32 (n x Mp for DHQ_ROTATE_BOTH)
  */
 int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int64_t n,
                 int32_t *acc_dev, void *stream);

@@ -18,9 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libdhq.so")
 
 DHQ_OK, DHQ_EINVAL, DHQ_EUNSUPPORTED, DHQ_ENOMEM, DHQ_EHIP, DHQ_ENOSCALE = 0, -1, -2, -3, -4, -5
 DHQ_AUTO, DHQ_LAYERWISE, DHQ_FUSED = 0, 1, 2
+DHQ_DYNAMIC = 4
+DHQ_ROTATE_IN, DHQ_ROTATE_BOTH = 0, 1
 
 # every symbol include/dhq.h declares
-EXPORTS = ("dhq_quantize_weights", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
+EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
            "dhq_get_weight_codes", "dhq_forward", "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
            "dhq_free", "dhq_strerror", "dhq_version")
 
@@ -55,6 +57,8 @@ def lib() -> C.CDLL:
             pass
         L = C.CDLL(LIB_PATH)
         L.dhq_quantize_weights.argtypes = [C.POINTER(dhq_net_desc), _fpp, _fpp, C.POINTER(C.c_void_p)]
+        L.dhq_quantize_weights_mode.argtypes = [C.POINTER(dhq_net_desc), C.c_uint32, _fpp, _fpp, C.POINTER(C.c_void_p)]
+        L.dhq_get_dynamic_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_void_p]
         L.dhq_set_act_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dhq_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.dhq_get_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -103,6 +107,11 @@ def dhq_version() -> int:
 def dhq_quantize_weights(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int,
                          W: Sequence[np.ndarray], b: Sequence[np.ndarray]) -> int:
     """Returns the model handle (an integer address). W[l]: (dims[l+1], dims[l]) fp32 host arrays."""
+    return dhq_quantize_weights_mode(dims, omega0, bits_w, bits_a, DHQ_ROTATE_IN, W, b)
+
+
+def dhq_quantize_weights_mode(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int, mode: int,
+                              W: Sequence[np.ndarray], b: Sequence[np.ndarray]) -> int:
     L = len(dims) - 1
     dims_a = (C.c_int32 * (L + 1))(*[int(d) for d in dims])
     desc = dhq_net_desc(L, dims_a, float(omega0), int(bits_w), int(bits_a))
@@ -110,11 +119,11 @@ def dhq_quantize_weights(dims: Sequence[int], omega0: float, bits_w: int, bits_a
     bc = [np.ascontiguousarray(x, dtype=np.float32) for x in b]
     for l in range(L):
         if Wc[l].shape != (dims[l + 1], dims[l]) or bc[l].shape != (dims[l + 1],):
-            raise DhqError(DHQ_EINVAL, f"dhq_quantize_weights: layer {l} has the wrong shape")
+            raise DhqError(DHQ_EINVAL, f"dhq_quantize_weights_mode: layer {l} has the wrong shape")
     Wp = (C.POINTER(C.c_float) * L)(*[w.ctypes.data_as(C.POINTER(C.c_float)) for w in Wc])
     bp = (C.POINTER(C.c_float) * L)(*[x.ctypes.data_as(C.POINTER(C.c_float)) for x in bc])
     h = C.c_void_p()
-    _ok(lib().dhq_quantize_weights(C.byref(desc), Wp, bp, C.byref(h)), "dhq_quantize_weights")
+    _ok(lib().dhq_quantize_weights_mode(C.byref(desc), int(mode), Wp, bp, C.byref(h)), "dhq_quantize_weights_mode")
     return h.value
 
 
@@ -133,6 +142,13 @@ def dhq_get_scales(model: int, n_layers: int) -> Tuple[np.ndarray, np.ndarray]:
     _ok(lib().dhq_get_scales(model, sw.ctypes.data_as(C.POINTER(C.c_float)),
                              sa.ctypes.data_as(C.POINTER(C.c_float))), "dhq_get_scales")
     return sw, sa
+
+
+def dhq_get_dynamic_scales(model: int, n_layers: int, stream=None) -> np.ndarray:
+    sa = np.zeros(n_layers, dtype=np.float32)
+    _ok(lib().dhq_get_dynamic_scales(model, sa.ctypes.data_as(C.POINTER(C.c_float)), _stream_ptr(stream)),
+        "dhq_get_dynamic_scales")
+    return sa
 
 
 def dhq_get_weight_codes(model: int, layer: int, shape: Tuple[int, int]) -> np.ndarray:
@@ -172,10 +188,12 @@ def dhq_free(model: int) -> None:
 class Model:
     """Owns a dhq_model handle; methods forward to the functions above."""
 
-    def __init__(self, dims: Sequence[int], omega0: float, W, b, bits_w: int = 8, bits_a: int = 8):
+    def __init__(self, dims: Sequence[int], omega0: float, W, b, bits_w: int = 8, bits_a: int = 8,
+                 mode: int = DHQ_ROTATE_IN):
         self.dims: List[int] = [int(d) for d in dims]
         self.n_layers = len(self.dims) - 1
-        self.handle = dhq_quantize_weights(self.dims, omega0, bits_w, bits_a, W, b)
+        self.mode = int(mode)
+        self.handle = dhq_quantize_weights_mode(self.dims, omega0, bits_w, bits_a, mode, W, b)
 
     def close(self) -> None:
         if getattr(self, "handle", None):
@@ -192,6 +210,16 @@ class Model:
         k = self.dims[layer]
         return 1 << (k - 1).bit_length() if k > 1 else 1
 
+    def mg(self, layer: int) -> int:
+        """Rows of layer's code matrix = columns of its accumulators."""
+        m = self.dims[layer + 1]
+        if self.mode == DHQ_ROTATE_BOTH:
+            return 1 << (m - 1).bit_length() if m > 1 else 1
+        return m
+
+    def dynamic_scales(self, stream=None) -> np.ndarray:
+        return dhq_get_dynamic_scales(self.handle, self.n_layers, stream)
+
     def set_act_scales(self, s_a) -> None:
         dhq_set_act_scales(self.handle, s_a)
 
@@ -202,7 +230,7 @@ class Model:
         return dhq_get_scales(self.handle, self.n_layers)
 
     def weight_codes(self, layer: int) -> np.ndarray:
-        return dhq_get_weight_codes(self.handle, layer, (self.dims[layer + 1], self.kp(layer)))
+        return dhq_get_weight_codes(self.handle, layer, (self.mg(layer), self.kp(layer)))
 
     def has_fused(self) -> bool:
         return dhq_has_fused(self.handle)
@@ -218,13 +246,13 @@ class Model:
         import torch
         n = x.shape[0]
         codes = torch.empty((n, self.kp(layer)), dtype=torch.int8, device=x.device)
-        acc = torch.empty((n, self.dims[layer + 1]), dtype=torch.int32, device=x.device)
+        acc = torch.empty((n, self.mg(layer)), dtype=torch.int32, device=x.device)
         act = torch.empty((n, self.dims[layer + 1]), dtype=torch.float32, device=x.device)
         dhq_forward_debug(self.handle, x, layer, codes, acc, act, stream)
         return codes, acc, act
 
     def gemm_i8(self, layer: int, codes, stream=None):
         import torch
-        acc = torch.empty((codes.shape[0], self.dims[layer + 1]), dtype=torch.int32, device=codes.device)
+        acc = torch.empty((codes.shape[0], self.mg(layer)), dtype=torch.int32, device=codes.device)
         dhq_gemm_i8(self.handle, layer, codes, acc, stream)
         return acc

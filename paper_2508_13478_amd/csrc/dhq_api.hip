@@ -1,9 +1,11 @@
 // Host side of libdhq: the C ABI of include/dhq.h.
 //
 //   dhq_quantize_weights  offline rotation (fast Walsh-Hadamard transform in fp64 over the
-//                         input-feature side, paper Eq. 3-5) + per-tensor symmetric quantizer
+//   (_mode)               input-feature side, or over both sides as Eq. 4-5 print it) +
+//                         per-tensor symmetric quantizer
 //   dhq_calibrate         per-layer activation scales measured on a coordinate set
-//   dhq_forward           layer-by-layer or fused whole-network evaluation
+//   dhq_forward           layer-by-layer or fused whole-network evaluation; with DHQ_DYNAMIC
+//                         the scales are measured on line, per call
 //   dhq_forward_debug / dhq_gemm_i8   test hooks exposing one layer's intermediates
 #include <math.h>
 #include <string.h>
@@ -37,6 +39,20 @@ static void fwht_f64(double *v, int n)
             }
 }
 
+// The same transform down a column of a row-major matrix (stride = row length), on doubles
+// or on 64-bit integers.
+template <typename T>
+static void fwht_strided(T *v, int n, size_t stride)
+{
+    for (int h = 1; h < n; h <<= 1)
+        for (int i = 0; i < n; i += 2 * h)
+            for (int j = i; j < i + h; ++j) {
+                const T a = v[(size_t)j * stride], b = v[(size_t)(j + h) * stride];
+                v[(size_t)j * stride] = a + b;
+                v[(size_t)(j + h) * stride] = a - b;
+            }
+}
+
 static void free_layer(dhq_layer &L)
 {
     if (L.wq_dev) (void)hipFree(L.wq_dev);
@@ -55,6 +71,13 @@ extern "C" void dhq_free(dhq_model *m)
     if (m->act1) (void)hipFree(m->act1);
     if (m->codes) (void)hipFree(m->codes);
     if (m->absmax_dev) (void)hipFree(m->absmax_dev);
+    if (m->acc_ws) (void)hipFree(m->acc_ws);
+    if (m->dyn_act0) (void)hipFree(m->dyn_act0);
+    if (m->dyn_act1) (void)hipFree(m->dyn_act1);
+    if (m->dyn_codes) (void)hipFree(m->dyn_codes);
+    if (m->dyn_acc) (void)hipFree(m->dyn_acc);
+    if (m->dyn_absmax) (void)hipFree(m->dyn_absmax);
+    if (m->dyn_params) (void)hipFree(m->dyn_params);
     dhq_fused_destroy(m->fused);
     dhq_wide_destroy(m->wide);
     delete m;
@@ -86,11 +109,106 @@ static int upload(T **dst, const T *src, size_t count)
     return DHQ_OK;
 }
 
-extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
-                                    const float *const *b_host, dhq_model **out)
+// Host-only part of the offline step for one layer: rotation, scale, codes, overflow check.
+static int quantize_layer_host(dhq_model *m, int l, const float *W, const float *b)
+{
+    dhq_layer &Ly = m->layer[l];
+    Ly.K = m->dims[l];
+    Ly.M = m->dims[l + 1];
+    Ly.Kp = next_pow2(Ly.K);
+    Ly.Kb = (Ly.Kp + 31) / 32;
+    Ly.Mp = next_pow2(Ly.M);
+    Ly.Mg = m->rot_out ? Ly.Mp : Ly.M;
+    Ly.Mt = (Ly.Mg + 31) / 32;
+    const int K = Ly.K, M = Ly.M, Kp = Ly.Kp, Mg = Ly.Mg;
+    const double qmax_w = (double)((1 << (m->bits_w - 1)) - 1);
+    // W^ = pad(W) H_Kp / sqrt(Kp) over the input features of every row; in the two-sided variant
+    // also H_Mp / sqrt(Mp) over the (zero-padded) output features: W' = H_Mp pad(W) H_Kp / sqrt(Mp Kp)
+    std::vector<double> rot((size_t)Mg * Kp, 0.0);
+    for (int r = 0; r < M; ++r) {
+        double *row = rot.data() + (size_t)r * Kp;
+        for (int k = 0; k < K; ++k) {
+            const float w = W[(size_t)r * K + k];
+            if (!isfinite(w)) return DHQ_EINVAL;
+            row[k] = (double)w;
+        }
+        fwht_f64(row, Kp);
+    }
+    if (m->rot_out)
+        for (int k = 0; k < Kp; ++k) fwht_strided(rot.data() + k, Mg, (size_t)Kp);
+    const double inv = m->rot_out ? 1.0 / sqrt((double)Mg * (double)Kp) : 1.0 / sqrt((double)Kp);
+    double amax = 0.0;
+    for (size_t i = 0; i < rot.size(); ++i) {
+        rot[i] *= inv;
+        const double a = fabs(rot[i]);
+        if (a > amax) amax = a;
+    }
+    Ly.s_w = amax == 0.0 ? 1.0f : (float)(amax / qmax_w);
+    // the quantizer: clamp(rne(w^ / s_w)); nearbyint rounds half to even
+    Ly.wq_host.resize((size_t)Mg * Kp);
+    const double sd = (double)Ly.s_w;
+    for (size_t i = 0; i < rot.size(); ++i) {
+        double q = nearbyint(rot[i] / sd);
+        if (q > qmax_w) q = qmax_w;
+        if (q < -qmax_w) q = -qmax_w;
+        Ly.wq_host[i] = (int8_t)q;
+    }
+    if (m->rot_out) {
+        // The un-rotation z = acc' H_Mp runs in int32.  z[j] = sum_k q[k] U[j][k] with U = H_Mp Wq, so
+        // |z[j]| <= qmax_a sum_k |U[j][k]|: refuse weights for which that bound leaves int32.
+        std::vector<int64_t> U(Ly.wq_host.begin(), Ly.wq_host.end());
+        for (int k = 0; k < Kp; ++k) fwht_strided(U.data() + k, Mg, (size_t)Kp);
+        for (int j = 0; j < Mg; ++j) {
+            int64_t sum = 0;
+            for (int k = 0; k < Kp; ++k) sum += U[(size_t)j * Kp + k] < 0 ? -U[(size_t)j * Kp + k] : U[(size_t)j * Kp + k];
+            if (sum * (int64_t)m->qmax_a > (int64_t)INT32_MAX) return DHQ_EUNSUPPORTED;
+        }
+    }
+    const double two_pi = 6.283185307179586476925286766559;
+    Ly.bias_host.assign(b, b + M);
+    Ly.bias_rev_host.resize(M);
+    for (int j = 0; j < M; ++j) {
+        if (!isfinite(b[j])) return DHQ_EINVAL;
+        Ly.bias_rev_host[j] = (float)((double)b[j] * (double)m->omega0 / two_pi);
+    }
+    if (M > m->max_dim) m->max_dim = M;
+    if (K > m->max_dim) m->max_dim = K;
+    if (Kp > m->max_kp) m->max_kp = Kp;
+    if (Mg > m->max_mg) m->max_mg = Mg;
+    return DHQ_OK;
+}
+
+// Device part: uploads the codes (row-major and as MFMA A fragments) and the biases.
+static int upload_layer(dhq_layer &Ly)
+{
+    const int Kp = Ly.Kp, Mg = Ly.Mg;
+    // MFMA A fragments, natural k order: lane (i, u) of (tile T, k block kb) holds
+    // Wq[32T + i][32 kb + 16 u .. + 15]
+    std::vector<int8_t> frag((size_t)Ly.Mt * Ly.Kb * 1024, 0);
+    for (int T = 0; T < Ly.Mt; ++T)
+        for (int kb = 0; kb < Ly.Kb; ++kb)
+            for (int ln = 0; ln < 64; ++ln) {
+                const int row = 32 * T + (ln & 31);
+                if (row >= Mg) continue;
+                for (int jj = 0; jj < 16; ++jj) {
+                    const int k = 32 * kb + 16 * (ln >> 5) + jj;
+                    if (k < Kp)
+                        frag[((size_t)(T * Ly.Kb + kb) * 64 + ln) * 16 + jj] = Ly.wq_host[(size_t)row * Kp + k];
+                }
+            }
+    int rc = upload(&Ly.wq_dev, Ly.wq_host.data(), Ly.wq_host.size());
+    if (rc == DHQ_OK) rc = upload(&Ly.wfrag_dev, frag.data(), frag.size());
+    if (rc == DHQ_OK) rc = upload(&Ly.bias_dev, Ly.bias_host.data(), (size_t)Ly.M);
+    if (rc == DHQ_OK) rc = upload(&Ly.bias_rev_dev, Ly.bias_rev_host.data(), (size_t)Ly.M);
+    return rc;
+}
+
+extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
+                                         const float *const *b_host, dhq_model **out)
 {
     if (!desc || !W_host || !b_host || !out || !desc->dims) return DHQ_EINVAL;
     *out = nullptr;
+    if (mode != DHQ_ROTATE_IN && mode != DHQ_ROTATE_BOTH) return DHQ_EINVAL;
     const int L = desc->n_layers;
     if (L < 1) return DHQ_EINVAL;
     if (L > DHQ_MAX_LAYERS) return DHQ_EUNSUPPORTED;
@@ -111,95 +229,39 @@ extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const
     m->bits_w = desc->bits_w;
     m->bits_a = desc->bits_a;
     m->qmax_a = (1 << (desc->bits_a - 1)) - 1;
-    if (hipGetDevice(&m->device) != hipSuccess) {
-        delete m;
-        return DHQ_EHIP;
-    }
-    const double qmax_w = (double)((1 << (desc->bits_w - 1)) - 1);
-    const double two_pi = 6.283185307179586476925286766559;
+    m->rot_out = (mode == DHQ_ROTATE_BOTH);
     int rc = DHQ_OK;
-
-    for (int l = 0; l < L && rc == DHQ_OK; ++l) {
-        dhq_layer &Ly = m->layer[l];
-        Ly.K = m->dims[l];
-        Ly.M = m->dims[l + 1];
-        Ly.Kp = next_pow2(Ly.K);
-        Ly.Kb = (Ly.Kp + 31) / 32;
-        Ly.Mt = (Ly.M + 31) / 32;
-        const int K = Ly.K, M = Ly.M, Kp = Ly.Kp;
-        // rotate every row over the input-feature dimension: W^ = pad(W) H_Kp / sqrt(Kp)
-        std::vector<double> rot((size_t)M * Kp, 0.0);
-        const double inv = 1.0 / sqrt((double)Kp);
-        double amax = 0.0;
-        for (int r = 0; r < M; ++r) {
-            double *row = rot.data() + (size_t)r * Kp;
-            for (int k = 0; k < K; ++k) {
-                const float w = W_host[l][(size_t)r * K + k];
-                if (!isfinite(w)) rc = DHQ_EINVAL;
-                row[k] = (double)w;
-            }
-            fwht_f64(row, Kp);
-            for (int k = 0; k < Kp; ++k) {
-                row[k] *= inv;
-                const double a = fabs(row[k]);
-                if (a > amax) amax = a;
-            }
-        }
-        if (rc != DHQ_OK) break;
-        Ly.s_w = amax == 0.0 ? 1.0f : (float)(amax / qmax_w);
-        // the quantizer: clamp(rne(w^ / s_w)); nearbyint rounds half to even
-        Ly.wq_host.resize((size_t)M * Kp);
-        const double sd = (double)Ly.s_w;
-        for (size_t i = 0; i < rot.size(); ++i) {
-            double q = nearbyint(rot[i] / sd);
-            if (q > qmax_w) q = qmax_w;
-            if (q < -qmax_w) q = -qmax_w;
-            Ly.wq_host[i] = (int8_t)q;
-        }
-        // MFMA A fragments, natural k order: lane (i, u) of (tile T, k block kb) holds
-        // Wq[32T + i][32 kb + 16 u .. + 15]
-        std::vector<int8_t> frag((size_t)Ly.Mt * Ly.Kb * 1024, 0);
-        for (int T = 0; T < Ly.Mt; ++T)
-            for (int kb = 0; kb < Ly.Kb; ++kb)
-                for (int ln = 0; ln < 64; ++ln) {
-                    const int row = 32 * T + (ln & 31);
-                    if (row >= M) continue;
-                    for (int jj = 0; jj < 16; ++jj) {
-                        const int k = 32 * kb + 16 * (ln >> 5) + jj;
-                        if (k < Kp)
-                            frag[((size_t)(T * Ly.Kb + kb) * 64 + ln) * 16 + jj] = Ly.wq_host[(size_t)row * Kp + k];
-                    }
-                }
-        Ly.bias_host.assign(b_host[l], b_host[l] + M);
-        Ly.bias_rev_host.resize(M);
-        for (int j = 0; j < M; ++j) {
-            if (!isfinite(b_host[l][j])) rc = DHQ_EINVAL;
-            Ly.bias_rev_host[j] = (float)((double)b_host[l][j] * (double)m->omega0 / two_pi);
-        }
-        if (rc != DHQ_OK) break;
-        rc = upload(&Ly.wq_dev, Ly.wq_host.data(), Ly.wq_host.size());
-        if (rc == DHQ_OK) rc = upload(&Ly.wfrag_dev, frag.data(), frag.size());
-        if (rc == DHQ_OK) rc = upload(&Ly.bias_dev, Ly.bias_host.data(), (size_t)M);
-        if (rc == DHQ_OK) rc = upload(&Ly.bias_rev_dev, Ly.bias_rev_host.data(), (size_t)M);
-        if (M > m->max_dim) m->max_dim = M;
-        if (K > m->max_dim) m->max_dim = K;
-        if (Kp > m->max_kp) m->max_kp = Kp;
-    }
+    // everything that can be refused is refused before the device is touched
+    for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = quantize_layer_host(m, l, W_host[l], b_host[l]);
+    if (rc == DHQ_OK && hipGetDevice(&m->device) != hipSuccess) rc = DHQ_EHIP;
+    for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = upload_layer(m->layer[l]);
     if (rc == DHQ_OK) {
         const size_t act_bytes = sizeof(float) * (size_t)DHQ_CHUNK * m->max_dim;
         if (hipMalloc((void **)&m->act0, act_bytes) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->act1, act_bytes) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->codes, (size_t)DHQ_CHUNK * m->max_kp) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->absmax_dev, sizeof(unsigned)) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && m->rot_out &&
+            hipMalloc((void **)&m->acc_ws, sizeof(int32_t) * (size_t)DHQ_CHUNK * m->max_mg) != hipSuccess)
+            rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_params, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_ENOMEM;
     }
-    if (rc == DHQ_OK) rc = dhq_fused_create(m, &m->fused);
-    if (rc == DHQ_OK) rc = dhq_wide_create(m, &m->wide);
+    // the whole-network kernels exist for the input-side rotation only
+    if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
+    if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
     if (rc != DHQ_OK) {
         dhq_free(m);
         return rc;
     }
     *out = m;
     return DHQ_OK;
+}
+
+extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
+                                    const float *const *b_host, dhq_model **out)
+{
+    return dhq_quantize_weights_mode(desc, DHQ_ROTATE_IN, W_host, b_host, out);
 }
 
 static int update_fused_scales(dhq_model *m)
@@ -243,33 +305,47 @@ extern "C" int dhq_has_fused(const dhq_model *m)
     return (m->fused || m->wide) ? 1 : 0;
 }
 
-// Per-layer constants of the layer-by-layer kernels.
+// Per-layer constant of the quantizer kernel.
 static float quant_inv(const dhq_layer &Ly) { return (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp))); }
 
-static float epi_c1(const dhq_model *m, int l)
+// Buffers one pass of the layer-by-layer path works in.
+struct layer_ws {
+    float *act[2];
+    int8_t *codes;
+    int32_t *acc;  // two-sided variant only
+};
+
+// GEMM + epilogue of layer l from `codes` into dst (n x M fp32): one kernel, or in the two-sided
+// variant the GEMM into the rotated accumulators followed by the un-rotation kernel.
+// dyn = device constants of the dynamic mode, or null for the model's static scales.
+static hipError_t gemm_epilogue(const dhq_model *m, int l, const int8_t *codes, int64_t rows, int32_t *acc_ws,
+                                const float *dyn, float *dst, hipStream_t st)
 {
     const dhq_layer &Ly = m->layer[l];
-    const double sc = (double)Ly.s_a * (double)Ly.s_w;
-    const double two_pi = 6.283185307179586476925286766559;
-    return l == m->n_layers - 1 ? (float)sc : (float)(sc * (double)m->omega0 / two_pi);
+    const bool last = (l == m->n_layers - 1);
+    const float c1 = dyn ? 0.0f : dhq_c1(m, l);
+    const float *bias = last ? Ly.bias_dev : Ly.bias_rev_dev;
+    if (!m->rot_out) return dhq_launch_gemm(Ly, codes, rows, nullptr, dst, c1, bias, !last, dyn, st);
+    hipError_t e = dhq_launch_gemm(Ly, codes, rows, acc_ws, nullptr, 0.0f, nullptr, false, nullptr, st);
+    if (e != hipSuccess) return e;
+    return dhq_launch_unrotate(acc_ws, rows, Ly.Mp, Ly.M, c1, bias, !last, dyn, nullptr, dst, st);
 }
 
-// Runs layers [0, upto) of the layer-by-layer path on `rows` coordinates of one chunk.
-// The result of layer upto-1 lands in *result (one of the workspace buffers, or `final_out`
-// for the network's last layer when it is given).
-static hipError_t run_layers(const dhq_model *m, const float *in, int64_t rows, int upto, float *final_out,
-                             const float **result, hipStream_t st)
+// Runs layers [0, upto) of the layer-by-layer path on `rows` coordinates with the model's static
+// scales.  The result of layer upto-1 lands in *result (one of the workspace buffers, or
+// `final_out` for the network's last layer when it is given).
+static hipError_t run_layers(const dhq_model *m, const layer_ws &ws, const float *in, int64_t rows, int upto,
+                             float *final_out, const float **result, hipStream_t st)
 {
     const float *cur = in;
-    float *bufs[2] = {m->act0, m->act1};
     int which = 0;
     for (int l = 0; l < upto; ++l) {
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == m->n_layers - 1);
-        hipError_t e = dhq_launch_wht_quant(cur, rows, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, m->codes, nullptr, st);
+        hipError_t e = dhq_launch_wht_quant(cur, rows, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, ws.codes, nullptr, st);
         if (e != hipSuccess) return e;
-        float *dst = (last && final_out) ? final_out : bufs[which];
-        e = dhq_launch_gemm(Ly, m->codes, rows, nullptr, dst, epi_c1(m, l), last ? Ly.bias_dev : Ly.bias_rev_dev, !last, st);
+        float *dst = (last && final_out) ? final_out : ws.act[which];
+        e = gemm_epilogue(m, l, ws.codes, rows, ws.acc, nullptr, dst, st);
         if (e != hipSuccess) return e;
         cur = dst;
         which ^= 1;
@@ -277,6 +353,8 @@ static hipError_t run_layers(const dhq_model *m, const float *in, int64_t rows, 
     *result = cur;
     return hipSuccess;
 }
+
+static layer_ws chunk_ws(const dhq_model *m) { return layer_ws{{m->act0, m->act1}, m->codes, m->acc_ws}; }
 
 extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream)
 {
@@ -286,13 +364,14 @@ extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, v
     const int K0 = m->dims[0];
     for (int l = 0; l < m->n_layers; ++l) {
         dhq_layer &Ly = m->layer[l];
-        if (hipMemsetAsync(m->absmax_dev, 0, sizeof(unsigned), st) != hipSuccess) return DHQ_EHIP;
+        if (dhq_launch_clear_words(m->absmax_dev, 1, st) != hipSuccess) return DHQ_EHIP;
         for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
             const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;
             const float *res = nullptr;
             // the input of layer l is the output of the already calibrated quantized layers before it
-            if (run_layers(m, coords_dev + off * K0, rows, l, nullptr, &res, st) != hipSuccess) return DHQ_EHIP;
-            if (dhq_launch_wht_quant(res, rows, Ly.K, Ly.Kp, 0.0f, m->qmax_a, nullptr, m->absmax_dev, st) != hipSuccess)
+            if (run_layers(m, chunk_ws(m), coords_dev + off * K0, rows, l, nullptr, &res, st) != hipSuccess) return DHQ_EHIP;
+            if (dhq_launch_wht_absmax(res, rows, Ly.K, Ly.Kp, m->absmax_dev, reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS),
+                                      m->qmax_a, 0.0, nullptr, st) != hipSuccess)
                 return DHQ_EHIP;
         }
         unsigned bits = 0;
@@ -308,27 +387,95 @@ extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, v
     return update_fused_scales(m);
 }
 
+// Whole-batch buffers of the dynamic mode, grown when a call brings more rows than any before.
+static int ensure_dyn_workspace(dhq_model *m, int64_t n)
+{
+    if (n <= m->dyn_rows) return DHQ_OK;
+    if (hipDeviceSynchronize() != hipSuccess) return DHQ_EHIP;  // nothing may still be using the old buffers
+    if (m->dyn_act0) (void)hipFree(m->dyn_act0);
+    if (m->dyn_act1) (void)hipFree(m->dyn_act1);
+    if (m->dyn_codes) (void)hipFree(m->dyn_codes);
+    if (m->dyn_acc) (void)hipFree(m->dyn_acc);
+    m->dyn_act0 = m->dyn_act1 = nullptr;
+    m->dyn_codes = nullptr;
+    m->dyn_acc = nullptr;
+    m->dyn_rows = 0;
+    const size_t act_bytes = sizeof(float) * (size_t)n * m->max_dim;
+    if (hipMalloc((void **)&m->dyn_act0, act_bytes) != hipSuccess) return DHQ_ENOMEM;
+    if (hipMalloc((void **)&m->dyn_act1, act_bytes) != hipSuccess) return DHQ_ENOMEM;
+    if (hipMalloc((void **)&m->dyn_codes, (size_t)n * m->max_kp) != hipSuccess) return DHQ_ENOMEM;
+    if (m->rot_out && hipMalloc((void **)&m->dyn_acc, sizeof(int32_t) * (size_t)n * m->max_mg) != hipSuccess) return DHQ_ENOMEM;
+    m->dyn_rows = n;
+    return DHQ_OK;
+}
+
+// The dynamic quantization module between layers (Sec. 3.3) taken literally: every layer first
+// reduces max|x^| over its whole rotated input (all n rows), a one-workgroup kernel turns the
+// maximum into the layer's constants, then the quantizer and the GEMM read them from device
+// memory.  Nothing returns to the host in between.
+static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, hipStream_t st)
+{
+    int rc = ensure_dyn_workspace(m, n);
+    if (rc != DHQ_OK) return rc;
+    const int L = m->n_layers;
+    float *partial = reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS);
+    if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
+    const float *cur = coords_dev;
+    float *bufs[2] = {m->dyn_act0, m->dyn_act1};
+    int which = 0;
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const bool last = (l == L - 1);
+        float *dyn = m->dyn_params + 3 * l;
+        if (dhq_launch_wht_absmax(cur, n, Ly.K, Ly.Kp, m->dyn_absmax + l, partial, m->qmax_a, dhq_c1_over_sa(m, l), dyn, st) !=
+            hipSuccess)
+            return DHQ_EHIP;
+        if (dhq_launch_wht_quant(cur, n, Ly.K, Ly.Kp, 0.0f, m->qmax_a, m->dyn_codes, dyn, st) != hipSuccess) return DHQ_EHIP;
+        float *dst = last ? out_dev : bufs[which];
+        if (gemm_epilogue(m, l, m->dyn_codes, n, m->dyn_acc, dyn, dst, st) != hipSuccess) return DHQ_EHIP;
+        cur = dst;
+        which ^= 1;
+    }
+    return DHQ_OK;
+}
+
 extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, void *stream,
                            uint32_t flags)
 {
     if (!m || n < 0) return DHQ_EINVAL;
-    if (flags > DHQ_FUSED) return DHQ_EINVAL;
+    const uint32_t path = flags & 3u;
+    const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
+    if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
+    if (dynamic && path == DHQ_FUSED) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
-    if (!m->have_scales) return DHQ_ENOSCALE;
     hipStream_t st = (hipStream_t)stream;
-    if (flags == DHQ_FUSED && !m->fused && !m->wide) return DHQ_EUNSUPPORTED;
-    if (flags != DHQ_LAYERWISE && m->fused)
+    // the workspace belongs to the model and is the only thing a forward call changes in it
+    if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, st);
+    if (!m->have_scales) return DHQ_ENOSCALE;
+    if (path == DHQ_FUSED && !m->fused && !m->wide) return DHQ_EUNSUPPORTED;
+    if (path != DHQ_LAYERWISE && m->fused)
         return dhq_fused_launch(m, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
-    if (flags != DHQ_LAYERWISE && m->wide)
+    if (path != DHQ_LAYERWISE && m->wide)
         return dhq_wide_launch(m->wide, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     const int K0 = m->dims[0], Mo = m->dims[m->n_layers];
     for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
         const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;
         const float *res = nullptr;
-        if (run_layers(m, coords_dev + off * K0, rows, m->n_layers, out_dev + off * Mo, &res, st) != hipSuccess)
+        if (run_layers(m, chunk_ws(m), coords_dev + off * K0, rows, m->n_layers, out_dev + off * Mo, &res, st) != hipSuccess)
             return DHQ_EHIP;
     }
+    return DHQ_OK;
+}
+
+extern "C" int dhq_get_dynamic_scales(const dhq_model *m, float *s_a_host, void *stream)
+{
+    if (!m || !s_a_host) return DHQ_EINVAL;
+    float tmp[3 * DHQ_MAX_LAYERS];
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(tmp, m->dyn_params, sizeof(float) * 3 * m->n_layers, hipMemcpyDeviceToHost, st) != hipSuccess) return DHQ_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return DHQ_EHIP;
+    for (int l = 0; l < m->n_layers; ++l) s_a_host[l] = tmp[3 * l + 2];
     return DHQ_OK;
 }
 
@@ -343,15 +490,22 @@ extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_
     hipStream_t st = (hipStream_t)stream;
     const dhq_layer &Ly = m->layer[layer];
     const bool last = (layer == m->n_layers - 1);
+    const float *bias = last ? Ly.bias_dev : Ly.bias_rev_dev;
     int8_t *codes = codes_dev ? codes_dev : m->codes;
-    if (dhq_launch_wht_quant(in_dev, n, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, codes, nullptr, st) != hipSuccess) return DHQ_EHIP;
+    if (dhq_launch_wht_quant(in_dev, n, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, codes, nullptr, st) != hipSuccess)
+        return DHQ_EHIP;
     if (!acc_dev && !act_dev) return DHQ_OK;
+    if (m->rot_out) {
+        // rotated accumulators into the workspace, then un-rotated ones and the activation out
+        if (dhq_launch_gemm(Ly, codes, n, m->acc_ws, nullptr, 0.0f, nullptr, false, nullptr, st) != hipSuccess) return DHQ_EHIP;
+        return dhq_launch_unrotate(m->acc_ws, n, Ly.Mp, Ly.M, dhq_c1(m, layer), bias, !last, nullptr, acc_dev, act_dev, st) == hipSuccess
+                   ? DHQ_OK
+                   : DHQ_EHIP;
+    }
     // the int32 accumulators go through the workspace when the caller does not want them
     int32_t *acc = acc_dev ? acc_dev : reinterpret_cast<int32_t *>(m->act0);
-    if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, false, st) != hipSuccess) return DHQ_EHIP;
-    if (act_dev &&
-        dhq_launch_epilogue(acc, n, Ly.M, epi_c1(m, layer), last ? Ly.bias_dev : Ly.bias_rev_dev, !last, act_dev, st) != hipSuccess)
-        return DHQ_EHIP;
+    if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, false, nullptr, st) != hipSuccess) return DHQ_EHIP;
+    if (act_dev && dhq_launch_epilogue(acc, n, Ly.M, dhq_c1(m, layer), bias, !last, act_dev, st) != hipSuccess) return DHQ_EHIP;
     return DHQ_OK;
 }
 
@@ -361,7 +515,7 @@ extern "C" int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *code
     if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
     if (n == 0) return DHQ_OK;
     if (!codes_dev || !acc_dev) return DHQ_EINVAL;
-    return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, false, (hipStream_t)stream) == hipSuccess
+    return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, false, nullptr, (hipStream_t)stream) == hipSuccess
                ? DHQ_OK
                : DHQ_EHIP;
 }

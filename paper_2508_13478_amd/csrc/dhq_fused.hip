@@ -441,12 +441,10 @@ int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
     if (!P) return DHQ_OK;
     const int L = m->n_layers;
     const int NT = P->nf / 32, NKB = P->nf / 32;
-    const double two_pi = 6.283185307179586476925286766559;
     for (int l = 0; l < L; ++l) {
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == L - 1);
-        const double sc = (double)Ly.s_a * (double)Ly.s_w;
-        P->args.layer[l].c1 = last ? (float)sc : (float)(sc * (double)m->omega0 / two_pi);
+        P->args.layer[l].c1 = dhq_c1(m, l);
         P->args.layer[l].inv_in = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
         // bias block
         const int Mt = last ? 1 : NT, Kb = (l == 0) ? 1 : NKB;

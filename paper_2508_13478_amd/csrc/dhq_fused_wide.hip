@@ -721,12 +721,10 @@ int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *P)
     if (!P) return DHQ_OK;
     const int L = m->n_layers;
     const int NT = P->nf / 32;
-    const double two_pi = 6.283185307179586476925286766559;
     for (int l = 0; l < L; ++l) {
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == L - 1);
-        const double sc = (double)Ly.s_a * (double)Ly.s_w;
-        P->args.c1[l] = last ? (float)sc : (float)(sc * (double)m->omega0 / two_pi);
+        P->args.c1[l] = dhq_c1(m, l);
         P->args.inv_in[l] = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
         const std::vector<float> &src = last ? Ly.bias_host : Ly.bias_rev_host;
         const int Mt = last ? 1 : NT;

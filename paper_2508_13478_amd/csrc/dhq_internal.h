@@ -3,6 +3,7 @@
 #define DHQ_INTERNAL_H
 
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include <vector>
@@ -18,10 +19,12 @@ struct dhq_layer {
     int K = 0, M = 0;     // fan-in, fan-out
     int Kp = 0;           // next power of two >= K: length of the rotated input
     int Kb = 0;           // number of 32-wide K blocks of the MFMA operand (>= 1; K zero-padded)
-    int Mt = 0;           // number of 32-row M tiles (rows zero-padded)
+    int Mp = 0;           // next power of two >= M (two-sided variant: rows of the rotated weights)
+    int Mg = 0;           // rows of the quantized weight matrix = columns the GEMM produces: M, or Mp when two-sided
+    int Mt = 0;           // number of 32-row tiles of those rows (zero-padded)
     float s_w = 0.f;      // weight scale
     float s_a = 0.f;      // activation scale (0 = unset)
-    int8_t *wq_dev = nullptr;     // M x Kp, row-major (rotated index order)
+    int8_t *wq_dev = nullptr;     // Mg x Kp, row-major (rotated index order)
     int8_t *wfrag_dev = nullptr;  // [Mt][Kb][64 lanes][16 B] MFMA A fragments, natural k order
     float *bias_dev = nullptr;    // M, fp32
     float *bias_rev_dev = nullptr;  // M, bias * omega0 / (2 pi): the sine argument in revolutions
@@ -40,12 +43,22 @@ struct dhq_model {
     int bits_w = 8, bits_a = 8;
     int qmax_a = 127;
     bool have_scales = false;
+    bool rot_out = false;  // two-sided variant: weights also rotated over the output features
     dhq_layer layer[DHQ_MAX_LAYERS];
     // workspace of the layer-by-layer path: two activation buffers, one code buffer
     float *act0 = nullptr, *act1 = nullptr;  // DHQ_CHUNK x max dim, fp32
     int8_t *codes = nullptr;                 // DHQ_CHUNK x max Kp
+    int32_t *acc_ws = nullptr;               // two-sided variant: DHQ_CHUNK x max Mg rotated accumulators
     unsigned *absmax_dev = nullptr;          // one word for calibration
-    int max_dim = 0, max_kp = 0;
+    int max_dim = 0, max_kp = 0, max_mg = 0;
+    // dynamic mode (scales measured on line): whole-batch buffers, grown on demand, and per
+    // layer one absmax word and three floats {quantizer multiplier, epilogue multiplier, s_a}
+    float *dyn_act0 = nullptr, *dyn_act1 = nullptr;
+    int8_t *dyn_codes = nullptr;
+    int32_t *dyn_acc = nullptr;
+    int64_t dyn_rows = 0;
+    unsigned *dyn_absmax = nullptr;  // DHQ_MAX_LAYERS absmax words, then DHQ_ABSMAX_PARTIALS floats of scratch
+    float *dyn_params = nullptr;     // DHQ_MAX_LAYERS x 3
     dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
     dhq_wide_plan *wide = nullptr;    // hidden width 512
     int device = 0;
@@ -54,16 +67,44 @@ struct dhq_model {
 // ---- launchers (defined in dhq_layerwise.hip) --------------------------------------------
 // Rotate rows over K (zero-padded to Kp) and quantize: codes = clamp(rne(x^ * inv)).
 // inv = 1 / (s_a * sqrt(Kp)) because the butterflies run un-normalised.
-// If absmax_bits != nullptr the kernel instead records max |un-normalised x^| (as float bits)
-// with atomicMax and writes no codes.
+// If dyn != nullptr, inv is read from dyn[0] on the device.
 hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float inv, int qmax,
-                                int8_t *codes, unsigned *absmax_bits, hipStream_t st);
+                                int8_t *codes, const float *dyn, hipStream_t st);
+
+// The same rotation, reduced to max |un-normalised x^| over all rows: *absmax_bits (float bits;
+// cleared by the caller before the first of several calls that are to accumulate) is raised to
+// that maximum.  `partial` is scratch for DHQ_ABSMAX_PARTIALS floats.  If dyn != nullptr, also
+// dyn[0..2] = {1 / (s_a sqrt(Kp)), s_a * c1_over_sa, s_a} with s_a = (float)(max|x^| / qmax)
+// (1 if the tensor is all zero).  Two launches.
+#define DHQ_ABSMAX_PARTIALS 2048
+hipError_t dhq_launch_wht_absmax(const float *in, int64_t n, int K, int Kp, unsigned *absmax_bits, float *partial,
+                                 int qmax, double c1_over_sa, float *dyn, hipStream_t st);
 
 // acc = codes * Wq^T.  Exactly one of acc_out / act_out is written:
-//   acc_out  n x M int32
-//   act_out  n x M fp32 = sine ? sin(2 pi (acc * c1 + bias[f])) : acc * c1 + bias[f]
+//   acc_out  n x Mg int32
+//   act_out  n x Mg fp32 = sine ? sin(2 pi (acc * c1 + bias[f])) : acc * c1 + bias[f]
+// If dyn != nullptr, c1 is read from dyn[1] on the device.
 hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                           float *act_out, float c1, const float *bias, bool sine, hipStream_t st);
+                           float *act_out, float c1, const float *bias, bool sine, const float *dyn, hipStream_t st);
+
+// Two-sided variant: z = acc H_Mp (int32, n x Mp) and act[:, f < M] = epilogue(z, c1, bias).
+// Either output may be null.  If dyn != nullptr, c1 is read from dyn[1].
+hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
+                               const float *dyn, int32_t *z_out, float *act_out, hipStream_t st);
+
+hipError_t dhq_launch_clear_words(unsigned *p, int n, hipStream_t st);
+
+// Epilogue multiplier divided by the activation scale: s_w, times omega0 / (2 pi) in the sine
+// layers (the sine takes revolutions), over sqrt(Mp) in the two-sided variant.
+static inline double dhq_c1_over_sa(const dhq_model *m, int l)
+{
+    const dhq_layer &Ly = m->layer[l];
+    double c = (double)Ly.s_w;
+    if (l != m->n_layers - 1) c = c * (double)m->omega0 / 6.283185307179586476925286766559;
+    if (m->rot_out) c = c / sqrt((double)Ly.Mp);
+    return c;
+}
+static inline float dhq_c1(const dhq_model *m, int l) { return (float)((double)m->layer[l].s_a * dhq_c1_over_sa(m, l)); }
 
 // act = epilogue(acc) elementwise, same formula as above.
 hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, const float *bias,

@@ -7,6 +7,10 @@
 //               dequantize + bias + sine epilogue fused in
 //   gemm_narrow the same contraction for fan-in < 32, on integer ALU ops
 //   epilogue    dequantize + bias + sine from stored accumulators
+//   unrotate    two-sided variant (Eq. 4-5 with both factors): multiplies the rotated
+//               accumulators by H over the output features, exactly in int32, then the epilogue
+//   dyn_scale   on-line per-tensor scale (the dynamic quantization module of Sec. 3.3): turns
+//               the absmax word of a layer input into the constants the next kernels read
 //
 // Activations travel through device memory between these kernels; the fused whole-network
 // kernel lives in dhq_fused.hip.
@@ -24,20 +28,14 @@ struct wht_shape {
     static constexpr int LPR = KP / EPL;
 };
 
-template <int KP, bool ABSMAX>
-__global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict__ in, int64_t n,
-                                                        int K, float inv, int qmax,
-                                                        int8_t *__restrict__ codes,
-                                                        unsigned *__restrict__ absmax_bits)
+// Loads this lane's EPL values of one row (zero beyond K, zero for a dead row) and runs the
+// butterflies: over the index bits held inside the lane, then over the bits that select the lane.
+template <int KP>
+__device__ __forceinline__ void wht_row(const float *__restrict__ in, int64_t row, int t, bool live, int K,
+                                        float (&v)[wht_shape<KP>::EPL])
 {
     constexpr int EPL = wht_shape<KP>::EPL;
     constexpr int LPR = wht_shape<KP>::LPR;
-    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t row = gtid / LPR;
-    const int t = (int)(gtid % LPR);
-    const bool live = row < n;
-
-    float v[EPL];
     if (live && K == KP && EPL == 4) {
         const float4 x = *reinterpret_cast<const float4 *>(in + row * KP + t * 4);
         v[0] = x.x; v[1 % EPL] = x.y; v[2 % EPL] = x.z; v[3 % EPL] = x.w;
@@ -48,7 +46,6 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
             v[e] = (live && idx < K) ? in[row * K + idx] : 0.0f;
         }
     }
-    // butterflies over the index bits held inside the lane
 #pragma unroll
     for (int h = 1; h < EPL; h *= 2) {
 #pragma unroll
@@ -60,7 +57,6 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
             }
         }
     }
-    // butterflies over the index bits that select the lane
 #pragma unroll
     for (int m = 1; m < LPR; m *= 2) {
         const bool upper = (t & m) != 0;
@@ -70,22 +66,23 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
             v[e] = upper ? p - v[e] : v[e] + p;
         }
     }
+}
 
-    if (ABSMAX) {
-        float mx = 0.0f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, fabsf(v[e]));
-#pragma unroll
-        for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-        // one word collects the maximum; a wave only pays for the atomic when it would raise it
-        if ((threadIdx.x & 63) == 0) {
-            const unsigned bits = __float_as_uint(mx);  // non-negative floats order like unsigned ints
-            if (bits > __hip_atomic_load(absmax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                atomicMax(absmax_bits, bits);
-        }
-        return;
-    }
-
+template <int KP>
+__global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict__ in, int64_t n,
+                                                        int K, float inv, int qmax,
+                                                        int8_t *__restrict__ codes,
+                                                        const float *__restrict__ dyn)
+{
+    if (dyn) inv = dyn[0];  // scale measured on the device (dynamic mode)
+    constexpr int EPL = wht_shape<KP>::EPL;
+    constexpr int LPR = wht_shape<KP>::LPR;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = gtid / LPR;
+    const int t = (int)(gtid % LPR);
+    const bool live = row < n;
+    float v[EPL];
+    wht_row<KP>(in, row, t, live, K, v);
     if (!live) return;
     int8_t *dst = codes + row * KP + t * EPL;
     if constexpr (EPL >= 4) {
@@ -101,35 +98,136 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
     }
 }
 
+// From the absmax word of a layer's (un-normalised) rotated input to the constants of the
+// dynamic mode, in the same fp64 steps the host takes in dhq_calibrate (so both give the same bits):
+//   dyn[0] = 1 / (s_a sqrt(Kp))    the quantizer's multiplier
+//   dyn[1] = s_a * c1_over_sa      the epilogue's multiplier (c1_over_sa = s_w [omega0 / 2 pi] [/ sqrt(Mp)])
+//   dyn[2] = s_a = (float)(max|x^| / qmax), 1 for an all-zero tensor
+__device__ __forceinline__ void dyn_scale_write(unsigned absmax_bits, int Kp, int qmax, double c1_over_sa,
+                                                float *__restrict__ dyn)
+{
+    const float mx = __uint_as_float(absmax_bits);
+    const double amax = (double)mx / sqrt((double)Kp);
+    const float s_a = amax == 0.0 ? 1.0f : (float)(amax / (double)qmax);
+    dyn[0] = (float)(1.0 / ((double)s_a * sqrt((double)Kp)));
+    dyn[1] = (float)((double)s_a * c1_over_sa);
+    dyn[2] = s_a;
+}
+
+// max |un-normalised x^| over all rows.  The grid is a few workgroups per CU, every workgroup
+// strides over the rows keeping its maximum in registers and stores it to partial[blockIdx.x];
+// a second, one-workgroup kernel folds the partial maxima into *absmax_bits (float bits:
+// non-negative floats order like unsigned integers) and, in dynamic mode, into the layer's
+// constants.  No atomics: one atomicMax per wave on a single word made this pass three times
+// slower than the quantizing pass, one per workgroup still 1.7 times.
+#define DHQ_ABSMAX_BLOCKS DHQ_ABSMAX_PARTIALS
+template <int KP>
+__global__ __launch_bounds__(256) void wht_absmax_kernel(const float *__restrict__ in, int64_t n, int K,
+                                                         float *__restrict__ partial)
+{
+    constexpr int EPL = wht_shape<KP>::EPL;
+    constexpr int LPR = wht_shape<KP>::LPR;
+    constexpr int RPB = 256 / LPR;  // rows a workgroup transforms per pass
+    __shared__ float red[4];
+    const int t = threadIdx.x % LPR;
+    float mx = 0.0f;
+    // the loop bound is the same for the whole workgroup: every lane takes part in the shuffles
+    for (int64_t base = (int64_t)blockIdx.x * RPB; base < n; base += (int64_t)gridDim.x * RPB) {
+        const int64_t row = base + threadIdx.x / LPR;
+        float v[EPL];
+        wht_row<KP>(in, row, t, row < n, K, v);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, fabsf(v[e]));
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// One workgroup: *absmax_bits = max(*absmax_bits, partial[0 .. count)); then, if dyn is given,
+// the constants of the dynamic mode for that maximum.
+__global__ __launch_bounds__(256) void absmax_finish_kernel(const float *__restrict__ partial, int count,
+                                                            unsigned *__restrict__ absmax_bits, int Kp, int qmax,
+                                                            double c1_over_sa, float *__restrict__ dyn)
+{
+    __shared__ float red[4];
+    float mx = 0.0f;
+    for (int i = threadIdx.x; i < count; i += 256) mx = fmaxf(mx, partial[i]);
+#pragma unroll
+    for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        unsigned bits = __float_as_uint(mx);
+        if (*absmax_bits > bits) bits = *absmax_bits;
+        *absmax_bits = bits;
+        if (dyn) dyn_scale_write(bits, Kp, qmax, c1_over_sa, dyn);
+    }
+}
+
 template <int KP>
 static hipError_t launch_wht(const float *in, int64_t n, int K, float inv, int qmax, int8_t *codes,
-                             unsigned *absmax_bits, hipStream_t st)
+                             const float *dyn, hipStream_t st)
 {
     constexpr int LPR = wht_shape<KP>::LPR;
     const int64_t threads = n * LPR;
     const unsigned blocks = (unsigned)((threads + 255) / 256);
-    if (absmax_bits)
-        wht_quant_kernel<KP, true><<<blocks, 256, 0, st>>>(in, n, K, inv, qmax, codes, absmax_bits);
-    else
-        wht_quant_kernel<KP, false><<<blocks, 256, 0, st>>>(in, n, K, inv, qmax, codes, absmax_bits);
+    wht_quant_kernel<KP><<<blocks, 256, 0, st>>>(in, n, K, inv, qmax, codes, dyn);
+    return hipGetLastError();
+}
+
+template <int KP>
+static hipError_t launch_absmax(const float *in, int64_t n, int K, unsigned *absmax_bits, float *partial, int qmax,
+                                double c1_over_sa, float *dyn, hipStream_t st)
+{
+    constexpr int LPR = wht_shape<KP>::LPR;
+    const int64_t need = (n * LPR + 255) / 256;
+    const unsigned blocks = (unsigned)(need < DHQ_ABSMAX_BLOCKS ? need : DHQ_ABSMAX_BLOCKS);  // 8 workgroups per CU
+    wht_absmax_kernel<KP><<<blocks, 256, 0, st>>>(in, n, K, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    absmax_finish_kernel<<<1, 256, 0, st>>>(partial, (int)blocks, absmax_bits, KP, qmax, c1_over_sa, dyn);
     return hipGetLastError();
 }
 
 hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float inv, int qmax,
-                                int8_t *codes, unsigned *absmax_bits, hipStream_t st)
+                                int8_t *codes, const float *dyn, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     switch (Kp) {
-        case 1: return launch_wht<1>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 2: return launch_wht<2>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 4: return launch_wht<4>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 8: return launch_wht<8>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 16: return launch_wht<16>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 32: return launch_wht<32>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 64: return launch_wht<64>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 128: return launch_wht<128>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 256: return launch_wht<256>(in, n, K, inv, qmax, codes, absmax_bits, st);
-        case 512: return launch_wht<512>(in, n, K, inv, qmax, codes, absmax_bits, st);
+        case 1: return launch_wht<1>(in, n, K, inv, qmax, codes, dyn, st);
+        case 2: return launch_wht<2>(in, n, K, inv, qmax, codes, dyn, st);
+        case 4: return launch_wht<4>(in, n, K, inv, qmax, codes, dyn, st);
+        case 8: return launch_wht<8>(in, n, K, inv, qmax, codes, dyn, st);
+        case 16: return launch_wht<16>(in, n, K, inv, qmax, codes, dyn, st);
+        case 32: return launch_wht<32>(in, n, K, inv, qmax, codes, dyn, st);
+        case 64: return launch_wht<64>(in, n, K, inv, qmax, codes, dyn, st);
+        case 128: return launch_wht<128>(in, n, K, inv, qmax, codes, dyn, st);
+        case 256: return launch_wht<256>(in, n, K, inv, qmax, codes, dyn, st);
+        case 512: return launch_wht<512>(in, n, K, inv, qmax, codes, dyn, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t dhq_launch_wht_absmax(const float *in, int64_t n, int K, int Kp, unsigned *absmax_bits, float *partial,
+                                 int qmax, double c1_over_sa, float *dyn, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    if (!partial || !absmax_bits) return hipErrorInvalidValue;
+    switch (Kp) {
+        case 1: return launch_absmax<1>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 2: return launch_absmax<2>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 4: return launch_absmax<4>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 8: return launch_absmax<8>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 16: return launch_absmax<16>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 32: return launch_absmax<32>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 64: return launch_absmax<64>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 128: return launch_absmax<128>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 256: return launch_absmax<256>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
+        case 512: return launch_absmax<512>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -149,8 +247,10 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
                                                            const int8_t *__restrict__ wfrag, int M, int Mt,
                                                            int32_t *__restrict__ acc_out,
                                                            float *__restrict__ act_out, float c1,
-                                                           const float *__restrict__ bias, int sine)
+                                                           const float *__restrict__ bias, int sine,
+                                                           const float *__restrict__ dyn)
 {
+    if (ACT && dyn) c1 = dyn[1];
     extern __shared__ __align__(16) unsigned char lds_raw[];
     dhq_v4i *lds = reinterpret_cast<dhq_v4i *>(lds_raw);
     constexpr int KP = NKB * 32;
@@ -226,30 +326,65 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     }
 }
 
-// Fan-in below 32 (the input layer, K = 2): one thread per (coordinate, feature); the
-// contraction is a handful of integer multiply-adds and the kernel is bound by its output.
-template <bool ACT>
+// Fan-in below 32 (the input layer, K = 2): one thread per coordinate and group of VEC
+// consecutive features (4 when the row length allows 16-byte stores); the contraction is a
+// handful of integer multiply-adds and the kernel is bound by its output.
+template <bool ACT, int VEC>
 __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restrict__ codes, int64_t n, int Kp,
                                                           const int8_t *__restrict__ wq, int M,
                                                           int32_t *__restrict__ acc_out,
                                                           float *__restrict__ act_out, float c1,
-                                                          const float *__restrict__ bias, int sine)
+                                                          const float *__restrict__ bias, int sine,
+                                                          const float *__restrict__ dyn)
 {
+    if (ACT && dyn) c1 = dyn[1];
+    const int groups = M / VEC;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n * M) return;
-    const int64_t row = idx / M;
-    const int f = (int)(idx % M);
-    int acc = 0;
-    for (int k = 0; k < Kp; ++k) acc += (int)codes[row * Kp + k] * (int)wq[f * Kp + k];
-    if (ACT)
-        act_out[idx] = dhq_epilogue(acc, c1, bias[f], sine != 0);
+    if (idx >= n * groups) return;
+    const int64_t row = idx / groups;
+    const int f0 = (int)(idx % groups) * VEC;
+    int acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0;
+    for (int k = 0; k < Kp; ++k) {
+        const int q = (int)codes[row * Kp + k];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += q * (int)wq[(f0 + e) * Kp + k];
+    }
+    if (ACT) {
+        float o[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = dhq_epilogue(acc[e], c1, bias[f0 + e], sine != 0);
+        if constexpr (VEC == 4)
+            *reinterpret_cast<float4 *>(act_out + row * M + f0) = make_float4(o[0], o[1], o[2], o[3]);
+        else
+            act_out[row * M + f0] = o[0];
+    } else {
+        if constexpr (VEC == 4)
+            *reinterpret_cast<int4 *>(acc_out + row * M + f0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+        else
+            acc_out[row * M + f0] = acc[0];
+    }
+}
+
+template <bool ACT>
+static hipError_t launch_gemm_narrow(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out, float *act_out,
+                                     float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
+{
+    const int vec = (L.Mg & 3) == 0 ? 4 : 1;
+    const int64_t total = n * (L.Mg / vec);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (vec == 4)
+        gemm_narrow_kernel<ACT, 4><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, sine ? 1 : 0, dyn);
     else
-        acc_out[idx] = acc;
+        gemm_narrow_kernel<ACT, 1><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, sine ? 1 : 0, dyn);
+    return hipGetLastError();
 }
 
 template <int NKB>
 static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                                   float *act_out, float c1, const float *bias, bool sine, hipStream_t st)
+                                   float *act_out, float c1, const float *bias, bool sine, const float *dyn,
+                                   hipStream_t st)
 {
     dim3 grid((unsigned)((n + 127) / 128), (unsigned)((L.Mt + 3) / 4));
     const size_t lds = (size_t)(L.Mt < 4 ? L.Mt : 4) * NKB * 1024;
@@ -259,38 +394,32 @@ static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int6
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.M, L.Mt, nullptr, act_out, c1, bias, sine ? 1 : 0);
+        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, sine ? 1 : 0, dyn);
     } else {
         auto kern = gemm_i8_mfma_kernel<NKB, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.M, L.Mt, acc_out, nullptr, c1, bias, sine ? 1 : 0);
+        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, sine ? 1 : 0, dyn);
     }
     return hipGetLastError();
 }
 
 hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                           float *act_out, float c1, const float *bias, bool sine, hipStream_t st)
+                           float *act_out, float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     if ((acc_out == nullptr) == (act_out == nullptr)) return hipErrorInvalidValue;
-    if (L.Kp < 32) {
-        const int64_t total = n * L.M;
-        const unsigned blocks = (unsigned)((total + 255) / 256);
-        if (act_out)
-            gemm_narrow_kernel<true><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.M, nullptr, act_out, c1, bias, sine ? 1 : 0);
-        else
-            gemm_narrow_kernel<false><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.M, acc_out, nullptr, c1, bias, sine ? 1 : 0);
-        return hipGetLastError();
-    }
+    if (L.Kp < 32)
+        return act_out ? launch_gemm_narrow<true>(L, codes, n, nullptr, act_out, c1, bias, sine, dyn, st)
+                       : launch_gemm_narrow<false>(L, codes, n, acc_out, nullptr, c1, bias, sine, dyn, st);
     switch (L.Kp / 32) {
-        case 1: return launch_gemm_mfma<1>(L, codes, n, acc_out, act_out, c1, bias, sine, st);
-        case 2: return launch_gemm_mfma<2>(L, codes, n, acc_out, act_out, c1, bias, sine, st);
-        case 4: return launch_gemm_mfma<4>(L, codes, n, acc_out, act_out, c1, bias, sine, st);
-        case 8: return launch_gemm_mfma<8>(L, codes, n, acc_out, act_out, c1, bias, sine, st);
-        case 16: return launch_gemm_mfma<16>(L, codes, n, acc_out, act_out, c1, bias, sine, st);
+        case 1: return launch_gemm_mfma<1>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        case 2: return launch_gemm_mfma<2>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        case 4: return launch_gemm_mfma<4>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        case 8: return launch_gemm_mfma<8>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        case 16: return launch_gemm_mfma<16>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -311,5 +440,107 @@ hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, c
     if (n <= 0) return hipSuccess;
     const int64_t total = n * M;
     epilogue_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(acc, total, M, c1, bias, sine ? 1 : 0, act);
+    return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------ two-sided variant: un-rotation
+// z = acc' H_MP over the output features of every row, in int32 (H has entries +-1, and
+// H H = MP I, so this undoes the output-side rotation of the weights up to the factor that
+// c1 carries), then y = z c1 + bias (and the sine) for the first M features.  Same lane
+// layout as the forward transform: a row is spread over LPR lanes of EPL values.
+// Intermediate sums may wrap; the host has checked that the final ones fit.
+template <int MP>
+__global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *__restrict__ acc, int64_t n, int M,
+                                                                float c1, const float *__restrict__ bias, int sine,
+                                                                const float *__restrict__ dyn,
+                                                                int32_t *__restrict__ z_out,
+                                                                float *__restrict__ act_out)
+{
+    if (dyn) c1 = dyn[1];
+    constexpr int EPL = wht_shape<MP>::EPL;
+    constexpr int LPR = wht_shape<MP>::LPR;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = gtid / LPR;
+    const int t = (int)(gtid % LPR);
+    const bool live = row < n;
+    int v[EPL];
+    if (live && EPL == 4) {
+        const int4 x = *reinterpret_cast<const int4 *>(acc + row * MP + t * 4);
+        v[0] = x.x; v[1 % EPL] = x.y; v[2 % EPL] = x.z; v[3 % EPL] = x.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) v[e] = live ? acc[row * MP + t * EPL + e] : 0;
+    }
+#pragma unroll
+    for (int h = 1; h < EPL; h *= 2) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            if ((e & h) == 0) {
+                const int a = v[e], b = v[e | h];
+                v[e] = (int)((unsigned)a + (unsigned)b);
+                v[e | h] = (int)((unsigned)a - (unsigned)b);
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < LPR; m *= 2) {
+        const bool upper = (t & m) != 0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const int p = __shfl_xor(v[e], m, 64);
+            v[e] = upper ? (int)((unsigned)p - (unsigned)v[e]) : (int)((unsigned)v[e] + (unsigned)p);
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int f = t * EPL + e;
+        if (z_out) z_out[row * MP + f] = v[e];
+        if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], sine != 0);
+    }
+}
+
+template <int MP>
+static hipError_t launch_unrotate(const int32_t *acc, int64_t n, int M, float c1, const float *bias, bool sine,
+                                  const float *dyn, int32_t *z_out, float *act_out, hipStream_t st)
+{
+    constexpr int LPR = wht_shape<MP>::LPR;
+    const int64_t threads = n * LPR;
+    unrotate_epilogue_kernel<MP><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(acc, n, M, c1, bias, sine ? 1 : 0, dyn,
+                                                                                   z_out, act_out);
+    return hipGetLastError();
+}
+
+hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
+                               const float *dyn, int32_t *z_out, float *act_out, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    switch (Mp) {
+        case 1: return launch_unrotate<1>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 2: return launch_unrotate<2>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 4: return launch_unrotate<4>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 8: return launch_unrotate<8>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 16: return launch_unrotate<16>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 32: return launch_unrotate<32>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 64: return launch_unrotate<64>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 128: return launch_unrotate<128>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 256: return launch_unrotate<256>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 512: return launch_unrotate<512>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Clears n words (a kernel rather than a memset so that callers may capture the stream).
+__global__ void clear_words_kernel(unsigned *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+hipError_t dhq_launch_clear_words(unsigned *p, int n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    clear_words_kernel<<<(n + 63) / 64, 64, 0, st>>>(p, n);
     return hipGetLastError();
 }

@@ -99,3 +99,27 @@ def test_wide_register_map_check_catches_violations():
         b.check_wide_register_map(ok.replace("accum_offset 212", "accum_offset 216"))
     with pytest.raises(RuntimeError):
         b.check_wide_register_map("nothing here")
+
+
+def test_two_sided_int32_bound_is_enforced_before_the_device_is_touched():
+    """One non-zero weight in a 512 x 512 layer rotates into 512 x 512 equal codes of +-127; with
+    all activation codes at 127 the un-rotated sum reaches 127 * 127 * 512 * 512 > 2^31.  The
+    oracle reports the overflow when it happens, the library refuses the weights up front."""
+    from oracle import dhq_oracle as o
+    W = np.zeros((512, 512), dtype=np.float32)
+    W[0, 0] = 1.0
+    b = np.zeros(512, dtype=np.float32)
+    with pytest.raises(dhq.DhqError) as e:
+        dhq.dhq_quantize_weights_mode([512, 512], 30.0, 8, 8, dhq.DHQ_ROTATE_BOTH, [W], [b])
+    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    Wq, s_w = o.quantize_weights_two_sided(W, 8)
+    assert (np.abs(Wq) == 127).all()
+    a = np.zeros((1, 512), dtype=np.float32)
+    a[0, 0] = 1.0                                   # rotates into 512 equal values -> all codes 127
+    with pytest.raises(o.OracleError):
+        o.layer_two_sided(a, 512, Wq, s_w, b, None, 8, False, 30.0)
+    # the same weights are fine one-sided, and a 256-wide layer stays inside int32 even in the worst case
+    W2 = np.zeros((256, 256), dtype=np.float32)
+    W2[0, 0] = 1.0
+    r = o.layer_two_sided(a[:, :256], 256, *o.quantize_weights_two_sided(W2, 8), b[:256], None, 8, False, 30.0)
+    assert np.abs(r["unrot"]).max() == 127 * 127 * 256 * 256
