@@ -483,6 +483,32 @@ int dhqo_forward_two_sided(int n_layers, const int32_t *dims, float omega0, int 
     return rc;
 }
 
+/* ------------------------------------------------------------------------
+ * Weight-only quantization, "W8A32" (Sec. 1, Fig. 1-2, Table 2): the weights
+ * go through the same offline step (rotation over the input features,
+ * per-tensor scale, quantizer) and are then used de-quantized, the
+ * activations stay in floating point.  De-quantized weights in the original
+ * basis: W~ = (s_w Wq) Hn (Hn is symmetric and orthonormal, so the rotation is
+ * undone by applying it again), columns beyond K dropped, rounded to fp32.
+ * The W8A32 network is the plain MLP (dhqo_mlp_float) run on W~; "W32A32" is
+ * dhqo_mlp_float on the original weights.
+ * ---------------------------------------------------------------------- */
+int dhqo_dequantize_weights(const int8_t *Wq, float s_w, int M, int K, float *Wt)
+{
+    if (!Wq || !Wt || M < 1 || K < 1 || !(s_w > 0.0f)) return DHQO_EINVAL;
+    int Kp = dhqo_next_pow2(K);
+    double *d = (double *)malloc(sizeof(double) * (size_t)M * Kp);
+    double *r = (double *)malloc(sizeof(double) * (size_t)M * Kp);
+    if (!d || !r) { free(d); free(r); return DHQO_ENOMEM; }
+    dhqo_dequantize(Wq, (int64_t)M * Kp, s_w, d);
+    int rc = dhqo_rotate_rows(d, M, Kp, r);
+    if (rc == DHQO_OK)
+        for (int j = 0; j < M; ++j)
+            for (int k = 0; k < K; ++k) Wt[(size_t)j * K + k] = (float)r[(size_t)j * Kp + k];
+    free(d); free(r);
+    return rc;
+}
+
 /*
  * Float reference: the plain MLP, neither rotated nor quantized, in fp64
  * (out64) and, if out32 is not NULL, a second pass in fp32 arithmetic.

@@ -74,6 +74,7 @@ def _declare(L: C.CDLL) -> None:
     L.dhqo_layer_two_sided.argtypes = [_fp, C.c_int64, C.c_int, C.c_int, _i8p, C.c_float, _fp, _fp, C.c_int,
                                        C.c_int, C.c_int, C.c_float, _fp, _dp, _i8p, _i32p, _i32p]
     L.dhqo_forward_two_sided.argtypes = L.dhqo_forward.argtypes
+    L.dhqo_dequantize_weights.argtypes = [_i8p, C.c_float, C.c_int, C.c_int, _fp]
     L.dhqo_mlp_float.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp), _fp,
                                  C.c_int64, _dp, _fp]
     L.dhqo_mlp_rotated_f64.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp),
@@ -328,6 +329,27 @@ def layer_two_sided(a_in: np.ndarray, M: int, Wq: np.ndarray, s_w: float, bias: 
                                     _ptr(unrot, _i32p))
     _check(rc, "layer_two_sided")
     return dict(rot=rot, codes=codes, acc=acc, unrot=unrot, act=out, s_a=np.float32(s.value))
+
+
+def dequantize_weights(Wq: np.ndarray, s_w: float, K: int) -> np.ndarray:
+    """W~ = (s_w Wq) Hn, first K columns, fp32: the weights a weight-only-quantized network uses."""
+    Wq = _c(Wq, np.int8)
+    M = Wq.shape[0]
+    assert Wq.shape[1] == next_pow2(K)
+    Wt = np.empty((M, K), dtype=np.float32)
+    _check(lib().dhqo_dequantize_weights(_ptr(Wq, _i8p), C.c_float(s_w), M, K, _ptr(Wt, _fp)), "dequantize_weights")
+    return Wt
+
+
+def mlp_w8a32(dims: Sequence[int], omega0: float, bits_w: int, W: Sequence[np.ndarray],
+              bias: Sequence[np.ndarray], coords: np.ndarray):
+    """Weight-only quantization: the plain MLP on the de-quantized weights. Returns (out_fp64, out_fp32, W~)."""
+    Wt = []
+    for l, Wl in enumerate(W):
+        q, s = quantize_weights(Wl, bits_w)
+        Wt.append(dequantize_weights(q, s, dims[l]))
+    o64, o32 = mlp_float(dims, omega0, Wt, bias, coords)
+    return o64, o32, Wt
 
 
 def mlp_float(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],

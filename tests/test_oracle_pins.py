@@ -452,3 +452,39 @@ def test_two_sided_forward_tracks_the_float_mlp_and_improves_with_bits():
     # static scales reproduce the calibrated run
     again = o.forward(net, coords[::7])
     assert np.array_equal(again, out[::7])
+
+
+# ------------------------------------------------ weight-only quantization (W8A32, Table 2)
+def test_dequantized_weights_exact_for_a_hadamard_row_and_bounded_otherwise():
+    sl = pytest.importorskip("scipy.linalg")
+    # a weight row that is a multiple of a Hadamard row rotates into a single spike, which the
+    # quantizer represents exactly: the round trip gives the row back
+    K = 64
+    H = sl.hadamard(K).astype(np.float64)
+    W = np.stack([0.25 * H[5] / 8.0, -0.25 * H[17] / 8.0]).astype(np.float32)     # entries +-1/32
+    Wq, s_w = o.quantize_weights(W, 8)
+    assert np.count_nonzero(Wq) == 2 and np.abs(Wq).max() == 127
+    assert np.abs(o.dequantize_weights(Wq, s_w, K) - W).max() <= 1e-8
+    # in general every rotated entry is within half a step, and the rotation keeps the Frobenius norm
+    rng = np.random.default_rng(3)
+    for (M, K, bits) in [(48, 100, 8), (256, 256, 6), (64, 2, 4)]:
+        W = rng.uniform(-0.5, 0.5, size=(M, K)).astype(np.float32)
+        Wq, s_w = o.quantize_weights(W, bits)
+        Wt = o.dequantize_weights(Wq, s_w, K)
+        assert np.linalg.norm(Wt.astype(np.float64) - W) <= 0.5 * float(s_w) * math.sqrt(M * o.next_pow2(K)) * (1 + 1e-5)
+
+
+def test_w8a32_error_shrinks_with_bits_and_stays_below_w8a8():
+    """Fig. 2 of the paper: weight-only quantization keeps the quality, quantizing the activations
+    as well costs more."""
+    wl, coords, W, b = synth.make("C1")
+    ref, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords)
+    errs = []
+    for bits in (4, 6, 8):
+        out, out32, Wt = o.mlp_w8a32(wl.dims, wl.omega0, bits, W, b, coords)
+        errs.append(float(np.sqrt(np.mean((out - ref) ** 2))))
+        assert np.abs(out32 - out).max() <= 1e-5
+    assert errs[0] > 3 * errs[1] > 9 * errs[2]
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
+    w8a8 = o.forward(net, coords, calibrate=True)
+    assert errs[2] < float(np.sqrt(np.mean((w8a8 - ref) ** 2)))
