@@ -88,16 +88,40 @@ def cpu_baseline(name, s_a, max_coords, two_sided=False):
                       f"calibration excluded)"}
 
 
+def cpu_baseline_float(name, max_coords):
+    """The CPU oracle's plain fp64/fp32 MLP timed on a bounded sample."""
+    from oracle import dhq_oracle as o
+    from paper_2508_13478_amd import synth
+    wl, coords, W, b = synth.make(name)
+    stride = max(1, -(-coords.shape[0] // max_coords))
+    sample = coords[::stride]
+    runs, t0 = 0, time.perf_counter()
+    while True:
+        o.mlp_float(wl.dims, wl.omega0, W, b, sample)
+        runs += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or runs >= 50:
+            break
+    try:
+        threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
+    except OSError:
+        threads = os.cpu_count() or 1
+    return {"value": runs * sample.shape[0] / dt, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{name} grid, every {stride}th coordinate ({sample.shape[0]} coords), {runs} runs, {dt:.2f} s, "
+                      f"plain MLP evaluated in fp64 and fp32 side by side"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--variant", default="base", choices=["base", "two_sided", "dynamic", "two_sided_dynamic"],
+    ap.add_argument("--variant", default="base", choices=["base", "two_sided", "dynamic", "two_sided_dynamic", "w8a32", "w32a32"],
                     help="base: input-side rotation, static scales (fused kernel where there is one); "
                          "two_sided: weights rotated on both sides, un-rotation in int32 (layer-by-layer path); "
-                         "dynamic: activation scales measured on line per call (layer-by-layer path)")
+                         "dynamic: activation scales measured on line per call (layer-by-layer path); "
+                         "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
     ap.add_argument("--copy-probe", action="store_true",
@@ -119,10 +143,15 @@ def main() -> int:
     wl, coords, W, b = synth.make(args.workload)
     two_sided = args.variant.startswith("two_sided")
     dynamic = args.variant.endswith("dynamic")
-    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN)
+    floating = args.variant in ("w8a32", "w32a32")
+    mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
+    if floating:
+        mode = dhq.DHQ_W8A32 if args.variant == "w8a32" else dhq.DHQ_W32A32
+    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode)
     x = torch.from_numpy(coords).to("cuda")
     out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
-    model.calibrate(x)
+    if not floating:
+        model.calibrate(x)
     _, s_a = model.scales()
     fused = model.has_fused() and not dynamic
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
@@ -178,6 +207,17 @@ def main() -> int:
     res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,
                   "unit": "wave64 instr/s", "frac": lane_instr / 64 / (ms * 1e-3) / valu_peak,
                   "model": f"{per_feature:.1f} vector instructions per feature and sine layer"}
+    if floating:
+        # fp32 activations: the same multiply-adds on the fp32 MFMA (157.3 TFLOP/s dense)
+        tf = ops / (ms * 1e-3) / 1e12
+        res["metric"] = "fp32-activation SIREN forward coords/sec"
+        res["dtype"] = "f32"
+        res["config"]["workload"] = res["config"]["workload"].replace("W8A8, static per-layer scales from absmax calibration on the same grid", args.variant.upper())
+        res.pop("int8_tops"); res.pop("pct_int8_mfma_peak"); res.pop("alu")
+        res["roofline"] = {"bound": "mfma", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
+                           "traffic": None, "kernel": f"dhq_float_kernel<{wl.dims[1]}>",
+                           "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
+                           "algorithmic_ops_per_launch": ops}
     if not fused:
         # The layer-by-layer path is bound by device-memory traffic: per coordinate and layer the
         # transform reads 4 K bytes (twice when the scale is measured on line) and writes Kp codes,
@@ -195,7 +235,7 @@ def main() -> int:
                            "algorithmic_hbm_bytes_per_launch": per_coord * n,
                            "algorithmic_ops_per_launch": ops}
         res.pop("alu", None)
-    if fused:
+    if fused and not floating:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
     if args.copy_probe:
@@ -205,7 +245,8 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(args.workload, s_a, args.cpu_coords, two_sided)
+        res["cpu_baseline"] = (cpu_baseline_float(args.workload, args.cpu_coords) if floating else
+                               cpu_baseline(args.workload, s_a, args.cpu_coords, two_sided))
     print(json.dumps(res))
     return 0
 

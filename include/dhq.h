@@ -62,6 +62,10 @@ typedef enum {
 /* dhq_quantize_weights_mode: which sides of the weight matrix are rotated. */
 #define DHQ_ROTATE_IN 0u   /* input-feature side only (what dhq_quantize_weights does) */
 #define DHQ_ROTATE_BOTH 1u /* both sides, W' = H_m W H_n / sqrt(m n), Eq. 4-5 as printed */
+/* ... or-ed with what is quantized (the three rows of the paper's Table 2): */
+#define DHQ_W8A8 0x00u   /* weights and activations (the method; bit widths from the descriptor) */
+#define DHQ_W8A32 0x10u  /* weights only: the network runs in fp32 on the de-quantized weights */
+#define DHQ_W32A32 0x20u /* nothing: the plain fp32 network, the full-precision reference */
 
 typedef struct dhq_model dhq_model; /* opaque */
 
@@ -99,6 +103,15 @@ int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
  * only (dhq_has_fused is 0); dhq_get_weight_codes returns Mp x Kp codes, dhq_gemm_i8 the
  * rotated accumulators (n x Mp) and dhq_forward_debug the un-rotated ones (n x Mp).
  * mode = DHQ_ROTATE_IN is dhq_quantize_weights.
+ *
+ * mode | DHQ_W8A32 / DHQ_W32A32 (with DHQ_ROTATE_IN only) builds the comparison networks of
+ * Sec. 1 / Table 2 with floating-point activations: y = W a + b, a = sin(omega0 y) in fp32 on
+ * the fp32 MFMA, one fused kernel, where W is the original weight matrix (DHQ_W32A32) or
+ * W~ = (s_w Wq) H_Kp / sqrt(Kp), the de-quantized weights taken back to the original basis
+ * (DHQ_W8A32; bits_w applies, bits_a is ignored).  Shapes: fan-in <= 4, equal hidden widths of
+ * 32 / 64 / 128 / 256, fan-out <= 32, else DHQ_EUNSUPPORTED.  Such a model has no activation
+ * scales: dhq_set_act_scales, dhq_calibrate, DHQ_DYNAMIC, DHQ_LAYERWISE and the test hooks
+ * return DHQ_EUNSUPPORTED; dhq_forward needs none.
  */
 int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
                               const float *const *b_host, dhq_model **out);

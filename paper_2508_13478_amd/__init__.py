@@ -20,6 +20,7 @@ DHQ_OK, DHQ_EINVAL, DHQ_EUNSUPPORTED, DHQ_ENOMEM, DHQ_EHIP, DHQ_ENOSCALE = 0, -1
 DHQ_AUTO, DHQ_LAYERWISE, DHQ_FUSED = 0, 1, 2
 DHQ_DYNAMIC = 4
 DHQ_ROTATE_IN, DHQ_ROTATE_BOTH = 0, 1
+DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 
 # every symbol include/dhq.h declares
 EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
@@ -213,7 +214,7 @@ class Model:
     def mg(self, layer: int) -> int:
         """Rows of layer's code matrix = columns of its accumulators."""
         m = self.dims[layer + 1]
-        if self.mode == DHQ_ROTATE_BOTH:
+        if (self.mode & 0xF) == DHQ_ROTATE_BOTH:
             return 1 << (m - 1).bit_length() if m > 1 else 1
         return m
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdhq.so")
-SOURCES = ["dhq_api.hip", "dhq_layerwise.hip", "dhq_fused.hip", "dhq_fused_wide.hip"]
+SOURCES = ["dhq_api.hip", "dhq_layerwise.hip", "dhq_fused.hip", "dhq_fused_wide.hip", "dhq_float.hip"]
 HEADERS = ["dhq_internal.h", "dhq_device.h", "dhq_fused_common.h"]
 
 
@@ -37,7 +37,10 @@ CODEGEN_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                  "-mllvm", "-amdgpu-mfma-vgpr-form",
                  "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
-# dhq_fused_wide.hip addresses the accumulation registers from this one up by number
+# Kernels that address accumulation registers by number from inline assembly: source file, a
+# substring of the kernel's (mangled) name, first register the compiler must leave alone.
+FIXED_AGPR_KERNELS = [("dhq_fused_wide.hip", "dhq_fused_wide_kernel", 160),
+                      ("dhq_float.hip", "dhq_float_kernel", 128)]
 WIDE_FIRST_FIXED_AGPR = 160
 
 
@@ -52,14 +55,17 @@ def _agprs_named(line: str):
     return out
 
 
-def check_wide_register_map(asm_text: str) -> None:
-    """The width-512 kernel keeps its codes and its copy staging in accumulation registers
-    a160..a255 that only its inline assembly names.  That is sound only if the compiler's own
-    code never touches them and if they lie inside the kernel's register allocation; both are
-    checked here on the compiler's assembly output, and a violation fails the build."""
+def check_fixed_agprs(asm_text: str, kernel_substr: str, first_fixed: int) -> int:
+    """Some kernels keep operands in accumulation registers a<first_fixed>..a255 that only their
+    inline assembly names.  That is sound only if the compiler's own code never touches those
+    registers and if they lie inside the kernel's register allocation; both are checked here on
+    the compiler's assembly output for every kernel whose name contains kernel_substr, and a
+    violation fails the build.  Returns the number of kernels checked."""
     in_asm = False
-    kernel = False
-    accum_offset = next_free = None
+    current = None          # function whose body is being read
+    descriptor = None       # kernel whose .amdhsa_ block is being read
+    alloc = {}              # kernel -> [accum_offset, next_free_vgpr]
+    seen = set()
     for ln in asm_text.splitlines():
         t = ln.strip()
         if t.startswith(";;#ASMSTART"):
@@ -69,27 +75,42 @@ def check_wide_register_map(asm_text: str) -> None:
             in_asm = False
             continue
         head = t.split(";")[0].strip()
-        if "dhq_fused_wide_kernel" in head and head.endswith(":") and not head.startswith("."):
-            kernel = True
-        if t.startswith(".amdhsa_accum_offset"):
-            accum_offset = int(t.split()[1])
-        if t.startswith(".amdhsa_next_free_vgpr"):
-            next_free = int(t.split()[1])
-        if not kernel or in_asm or not t or t[0] in ";.":
+        if head.endswith(":") and not head.startswith(".") and not head.startswith("$"):
+            current = head[:-1]
+            if kernel_substr in current:
+                seen.add(current)
             continue
-        code = t.split(";")[0]
-        bad = [r for r in _agprs_named(code) if r >= WIDE_FIRST_FIXED_AGPR]
+        if t.startswith(".amdhsa_kernel"):
+            descriptor = t.split()[1]
+            alloc[descriptor] = [None, None]
+        elif t.startswith(".end_amdhsa_kernel"):
+            descriptor = None
+        elif descriptor and t.startswith(".amdhsa_accum_offset"):
+            alloc[descriptor][0] = int(t.split()[1])
+        elif descriptor and t.startswith(".amdhsa_next_free_vgpr"):
+            alloc[descriptor][1] = int(t.split()[1])
+        if current is None or kernel_substr not in current or in_asm or not t or t[0] in ";.":
+            continue
+        bad = [r for r in _agprs_named(head) if r >= first_fixed]
         if bad:
-            raise RuntimeError(f"compiler-generated code touches a fixed accumulation register: {t}")
-    if not kernel or accum_offset is None or next_free is None:
-        raise RuntimeError("dhq_fused_wide_kernel not found in the assembly output")
-    if next_free - accum_offset < 256:
-        raise RuntimeError(f"the kernel is allocated {next_free - accum_offset} accumulation registers, 256 are needed")
+            raise RuntimeError(f"{current}: compiler-generated code touches a fixed accumulation register: {t}")
+    if not seen:
+        raise RuntimeError(f"no kernel named *{kernel_substr}* in the assembly output")
+    for k in seen:
+        off, nxt = alloc.get(k, [None, None])
+        if off is None or nxt is None:
+            raise RuntimeError(f"{k}: register allocation not found in the assembly output")
+        if nxt - off < 256:
+            raise RuntimeError(f"{k} is allocated {nxt - off} accumulation registers, 256 are needed")
+    return len(seen)
 
 
-def wide_asm_cmd(out_path: str):
-    return [_hipcc()] + CODEGEN_FLAGS + ["-S", "--cuda-device-only", "-o", out_path,
-                                         os.path.join(CSRC, "dhq_fused_wide.hip")]
+def check_wide_register_map(asm_text: str) -> None:
+    check_fixed_agprs(asm_text, "dhq_fused_wide_kernel", WIDE_FIRST_FIXED_AGPR)
+
+
+def asm_cmd(source: str, out_path: str):
+    return [_hipcc()] + CODEGEN_FLAGS + ["-S", "--cuda-device-only", "-o", out_path, os.path.join(CSRC, source)]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -100,19 +121,25 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     with tempfile.TemporaryDirectory() as td:
-        asm_path = os.path.join(td, "dhq_fused_wide.s")
-        chk = subprocess.Popen(wide_asm_cmd(asm_path), stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        # the same sources once more to assembly, in parallel with the real build, for the register check
+        checks = []
+        for src, name, first in FIXED_AGPR_KERNELS:
+            asm_path = os.path.join(td, src + ".s")
+            checks.append((subprocess.Popen(asm_cmd(src, asm_path), stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                                            text=True), asm_path, name, first))
         r = subprocess.run(cmd, capture_output=True, text=True)
-        chk_out, _ = chk.communicate()
-        if r.returncode == 0:
-            if chk.returncode != 0:
-                os.remove(LIB)
-                raise RuntimeError("hipcc -S failed:\n" + chk_out)
+        for proc, asm_path, name, first in checks:
+            out_text, _ = proc.communicate()
+            if r.returncode != 0:
+                continue
             try:
+                if proc.returncode != 0:
+                    raise RuntimeError("hipcc -S failed:\n" + out_text)
                 with open(asm_path) as f:
-                    check_wide_register_map(f.read())
+                    check_fixed_agprs(f.read(), name, first)
             except RuntimeError:
-                os.remove(LIB)
+                if os.path.exists(LIB):
+                    os.remove(LIB)
                 raise
     msgs = [ln for ln in (r.stdout + r.stderr).splitlines() if "not a recognized feature" not in ln]
     if r.returncode != 0:

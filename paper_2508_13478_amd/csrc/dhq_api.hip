@@ -80,6 +80,7 @@ extern "C" void dhq_free(dhq_model *m)
     if (m->dyn_params) (void)hipFree(m->dyn_params);
     dhq_fused_destroy(m->fused);
     dhq_wide_destroy(m->wide);
+    dhq_float_destroy(m->flt);
     delete m;
 }
 
@@ -208,7 +209,10 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
 {
     if (!desc || !W_host || !b_host || !out || !desc->dims) return DHQ_EINVAL;
     *out = nullptr;
-    if (mode != DHQ_ROTATE_IN && mode != DHQ_ROTATE_BOTH) return DHQ_EINVAL;
+    const uint32_t rotate = mode & 0xfu, precision = mode & 0xf0u;
+    if ((mode & ~0xffu) != 0 || (rotate != DHQ_ROTATE_IN && rotate != DHQ_ROTATE_BOTH)) return DHQ_EINVAL;
+    if (precision != DHQ_W8A8 && precision != DHQ_W8A32 && precision != DHQ_W32A32) return DHQ_EINVAL;
+    if (precision != DHQ_W8A8 && rotate != DHQ_ROTATE_IN) return DHQ_EUNSUPPORTED;
     const int L = desc->n_layers;
     if (L < 1) return DHQ_EINVAL;
     if (L > DHQ_MAX_LAYERS) return DHQ_EUNSUPPORTED;
@@ -229,11 +233,41 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
     m->bits_w = desc->bits_w;
     m->bits_a = desc->bits_a;
     m->qmax_a = (1 << (desc->bits_a - 1)) - 1;
-    m->rot_out = (mode == DHQ_ROTATE_BOTH);
+    m->rot_out = (rotate == DHQ_ROTATE_BOTH);
+    m->precision = precision;
     int rc = DHQ_OK;
     // everything that can be refused is refused before the device is touched
     for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = quantize_layer_host(m, l, W_host[l], b_host[l]);
+    if (rc == DHQ_OK && precision != DHQ_W8A8 && !dhq_float_shape_ok(m->dims, L)) rc = DHQ_EUNSUPPORTED;
     if (rc == DHQ_OK && hipGetDevice(&m->device) != hipSuccess) rc = DHQ_EHIP;
+    if (rc == DHQ_OK && precision != DHQ_W8A8) {
+        // floating-point activations: the network runs on the original weights (W32A32) or on the
+        // de-quantized ones in the original basis, W~ = (s_w Wq) H_Kp / sqrt(Kp) (W8A32)
+        std::vector<std::vector<float>> Wf(L), bf(L);
+        for (int l = 0; l < L; ++l) {
+            const dhq_layer &Ly = m->layer[l];
+            Wf[l].resize((size_t)Ly.M * Ly.K);
+            bf[l] = Ly.bias_host;
+            if (precision == DHQ_W32A32) {
+                memcpy(Wf[l].data(), W_host[l], sizeof(float) * Wf[l].size());
+                continue;
+            }
+            std::vector<double> row(Ly.Kp);
+            const double inv = 1.0 / sqrt((double)Ly.Kp);
+            for (int r = 0; r < Ly.M; ++r) {
+                for (int k = 0; k < Ly.Kp; ++k) row[k] = (double)Ly.wq_host[(size_t)r * Ly.Kp + k] * (double)Ly.s_w;
+                fwht_f64(row.data(), Ly.Kp);
+                for (int k = 0; k < Ly.K; ++k) Wf[l][(size_t)r * Ly.K + k] = (float)(row[k] * inv);
+            }
+        }
+        rc = dhq_float_create(m->dims, L, m->omega0, Wf, bf, m->device, &m->flt);
+        if (rc != DHQ_OK) {
+            dhq_free(m);
+            return rc;
+        }
+        *out = m;
+        return DHQ_OK;
+    }
     for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = upload_layer(m->layer[l]);
     if (rc == DHQ_OK) {
         const size_t act_bytes = sizeof(float) * (size_t)DHQ_CHUNK * m->max_dim;
@@ -274,6 +308,7 @@ static int update_fused_scales(dhq_model *m)
 extern "C" int dhq_set_act_scales(dhq_model *m, const float *s_a_host)
 {
     if (!m || !s_a_host) return DHQ_EINVAL;
+    if (m->flt) return DHQ_EUNSUPPORTED;  // activations are not quantized in this model
     for (int l = 0; l < m->n_layers; ++l)
         if (!(s_a_host[l] > 0.0f) || !isfinite(s_a_host[l])) return DHQ_EINVAL;
     for (int l = 0; l < m->n_layers; ++l) m->layer[l].s_a = s_a_host[l];
@@ -294,6 +329,7 @@ extern "C" int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_ho
 extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host)
 {
     if (!m || !Wq_host || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    if (m->precision == DHQ_W32A32) return DHQ_EUNSUPPORTED;
     const dhq_layer &Ly = m->layer[layer];
     memcpy(Wq_host, Ly.wq_host.data(), Ly.wq_host.size());
     return DHQ_OK;
@@ -302,7 +338,7 @@ extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *W
 extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
-    return (m->fused || m->wide) ? 1 : 0;
+    return (m->fused || m->wide || m->flt) ? 1 : 0;
 }
 
 // Per-layer constant of the quantizer kernel.
@@ -359,6 +395,7 @@ static layer_ws chunk_ws(const dhq_model *m) { return layer_ws{{m->act0, m->act1
 extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream)
 {
     if (!m || n < 0 || (n > 0 && !coords_dev)) return DHQ_EINVAL;
+    if (m->flt) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_EINVAL;  // a scale cannot be measured on nothing
     hipStream_t st = (hipStream_t)stream;
     const int K0 = m->dims[0];
@@ -447,9 +484,11 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
     if (dynamic && path == DHQ_FUSED) return DHQ_EUNSUPPORTED;
+    if (m->flt && (dynamic || path == DHQ_LAYERWISE)) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    if (m->flt) return dhq_float_launch(m->flt, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     // the workspace belongs to the model and is the only thing a forward call changes in it
     if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, st);
     if (!m->have_scales) return DHQ_ENOSCALE;
@@ -471,6 +510,7 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
 extern "C" int dhq_get_dynamic_scales(const dhq_model *m, float *s_a_host, void *stream)
 {
     if (!m || !s_a_host) return DHQ_EINVAL;
+    if (m->flt) return DHQ_EUNSUPPORTED;
     float tmp[3 * DHQ_MAX_LAYERS];
     hipStream_t st = (hipStream_t)stream;
     if (hipMemcpyAsync(tmp, m->dyn_params, sizeof(float) * 3 * m->n_layers, hipMemcpyDeviceToHost, st) != hipSuccess) return DHQ_EHIP;
@@ -483,7 +523,7 @@ extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_
                                  int32_t *acc_dev, float *act_dev, void *stream)
 {
     if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
-    if (n > DHQ_CHUNK) return DHQ_EUNSUPPORTED;
+    if (n > DHQ_CHUNK || m->flt) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!in_dev) return DHQ_EINVAL;
     if (!m->have_scales) return DHQ_ENOSCALE;
@@ -513,6 +553,7 @@ extern "C" int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *code
                            void *stream)
 {
     if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    if (m->flt) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!codes_dev || !acc_dev) return DHQ_EINVAL;
     return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, false, nullptr, (hipStream_t)stream) == hipSuccess

@@ -35,6 +35,7 @@ struct dhq_layer {
 
 struct dhq_fused_plan;  // defined in dhq_fused.hip
 struct dhq_wide_plan;   // defined in dhq_fused_wide.hip
+struct dhq_float_plan;  // defined in dhq_float.hip
 
 struct dhq_model {
     int n_layers = 0;
@@ -44,6 +45,7 @@ struct dhq_model {
     int qmax_a = 127;
     bool have_scales = false;
     bool rot_out = false;  // two-sided variant: weights also rotated over the output features
+    uint32_t precision = 0;  // DHQ_W8A8 / DHQ_W8A32 / DHQ_W32A32
     dhq_layer layer[DHQ_MAX_LAYERS];
     // workspace of the layer-by-layer path: two activation buffers, one code buffer
     float *act0 = nullptr, *act1 = nullptr;  // DHQ_CHUNK x max dim, fp32
@@ -61,6 +63,7 @@ struct dhq_model {
     float *dyn_params = nullptr;     // DHQ_MAX_LAYERS x 3
     dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
     dhq_wide_plan *wide = nullptr;    // hidden width 512
+    dhq_float_plan *flt = nullptr;    // floating-point activations (DHQ_W8A32 / DHQ_W32A32)
     int device = 0;
 };
 
@@ -126,5 +129,15 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan);
 void dhq_wide_destroy(dhq_wide_plan *plan);
 int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *plan);
 hipError_t dhq_wide_launch(const dhq_wide_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
+
+
+// Floating-point activations (defined in dhq_float.hip): the plain SIREN on the given fp32
+// weights W[l] (dims[l+1] x dims[l]) and biases, fused over all layers.  DHQ_EUNSUPPORTED if
+// the shape has no such kernel.
+bool dhq_float_shape_ok(const int *dims, int n_layers);
+int dhq_float_create(const int *dims, int n_layers, float omega0, const std::vector<std::vector<float>> &W,
+                     const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan);
+void dhq_float_destroy(dhq_float_plan *plan);
+hipError_t dhq_float_launch(const dhq_float_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
 #endif

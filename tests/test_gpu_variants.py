@@ -212,3 +212,80 @@ def test_variant_flags_are_checked():
     with pytest.raises(dhq.DhqError) as e:
         dhq.Model(wl.dims, wl.omega0, W, b, mode=2)
     assert e.value.status == dhq.DHQ_EINVAL
+
+
+# --------------------------------------------- floating-point activations (W32A32, W8A32)
+FLOAT_TOL = 1e-6    # fp32 MFMA accumulation + hardware sine against the fp64 oracle (outputs are O(0.1); measured 1.3e-7)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_w32a32_forward(name):
+    torch = _torch()
+    _say(f"W32A32 {name}")
+    wl, coords, W, b = synth.make(name)
+    exp, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords)
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W32A32)
+    assert m.has_fused()
+    out = m.forward(_dev(coords))
+    again = m.forward(_dev(coords), flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max()
+    _say(f"  max-abs err {err:.3e}")
+    assert err <= FLOAT_TOL
+    assert np.array_equal(out.cpu().numpy(), again.cpu().numpy())
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 5], [4, 128, 128, 2], [1, 256, 256, 32], [2, 64, 1]])
+def test_w32a32_shapes_and_ragged_rows(dims):
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 99 + len(dims))
+    m = dhq.Model(dims, 30.0, W, b, mode=dhq.DHQ_W32A32)
+    rng = np.random.default_rng(dims[1])
+    for n in (1, 129, 5000 + 17):
+        _say(f"W32A32 dims {dims} n={n}")
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        exp, _ = o.mlp_float(dims, 30.0, W, b, x)
+        out = m.forward(_dev(x))
+        torch.cuda.synchronize()
+        assert np.abs(out.cpu().numpy().astype(np.float64) - exp).max() <= FLOAT_TOL
+
+
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_w8a32_forward(bits):
+    torch = _torch()
+    _say(f"W8A32 bits {bits}")
+    wl, coords, W, b = synth.make("C2")
+    coords = coords[::3]
+    exp, _, Wt = o.mlp_w8a32(wl.dims, wl.omega0, bits, W, b, coords)
+    m = dhq.Model(wl.dims, wl.omega0, W, b, bits, 8, mode=dhq.DHQ_W8A32)
+    sw, sa = m.scales()
+    for l in range(len(wl.dims) - 1):
+        q, s = o.quantize_weights(W[l], bits)
+        assert sw[l] == s and np.array_equal(m.weight_codes(l), q)
+    assert (sa == 0).all()
+    out = m.forward(_dev(coords))
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max()
+    ref, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords)
+    _say(f"  max-abs err vs oracle {err:.3e}; weight-quantization effect {np.abs(exp - ref).max():.3e}")
+    assert err <= FLOAT_TOL
+
+
+def test_float_modes_refuse_what_they_do_not_have():
+    wl, coords, W, b = synth.make("C1")
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W32A32)
+    x = _dev(coords[:64])
+    for call in (lambda: m.calibrate(x), lambda: m.set_act_scales(np.ones(4, np.float32)),
+                 lambda: m.forward(x, flags=dhq.DHQ_LAYERWISE), lambda: m.forward(x, flags=dhq.DHQ_DYNAMIC),
+                 lambda: m.weight_codes(0), lambda: m.forward_debug(x, 0), lambda: m.dynamic_scales()):
+        with pytest.raises(dhq.DhqError) as e:
+            call()
+        assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    for dims in ([2, 512, 512, 3], [2, 48, 48, 3], [2, 64, 128, 3], [5, 64, 64, 3]):
+        Wd, bd = synth.siren_init(dims, 30.0, 5)
+        with pytest.raises(dhq.DhqError) as e:
+            dhq.Model(dims, 30.0, Wd, bd, mode=dhq.DHQ_W8A32)
+        assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    with pytest.raises(dhq.DhqError) as e:
+        dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W8A32 | dhq.DHQ_ROTATE_BOTH)
+    assert e.value.status == dhq.DHQ_EUNSUPPORTED

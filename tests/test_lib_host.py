@@ -87,8 +87,11 @@ def test_wide_register_map_check_catches_violations():
         "\tglobal_load_dwordx4 a[224:227], v1, s[2:3]",
         "\t;;#ASMEND",
         "\tv_add_f32_e32 v1, v2, v3 ; a200 in a comment does not count",
+        ".Lfunc_end0:",
+        "\t.amdhsa_kernel _Z21dhq_fused_wide_kernelILi512EEv9wide_args",
         "\t.amdhsa_next_free_vgpr 468",
         "\t.amdhsa_accum_offset 212",
+        "\t.end_amdhsa_kernel",
     ])
     b.check_wide_register_map(ok)
     for planted in ("\tv_accvgpr_read_b32 v5, a160", "\tds_write_b128 v1, a[156:163]", "\tscratch_store_dword off, a[0xff], off"):
@@ -99,6 +102,13 @@ def test_wide_register_map_check_catches_violations():
         b.check_wide_register_map(ok.replace("accum_offset 212", "accum_offset 216"))
     with pytest.raises(RuntimeError):
         b.check_wide_register_map("nothing here")
+    # the float kernels keep their activations in a128 and up; another function's registers do not matter
+    flt = ok.replace("dhq_fused_wide_kernelILi512EEv9wide_args", "dhq_float_kernelILi256EEv10float_args").replace("_Z21", "_Z16")
+    assert b.check_fixed_agprs(flt, "dhq_float_kernel", 128) == 1
+    with pytest.raises(RuntimeError):
+        b.check_fixed_agprs(flt.replace("a127", "a128"), "dhq_float_kernel", 128)
+    other = "helper_function:\n\tv_accvgpr_write_b32 a200, v1\n" + ok
+    b.check_wide_register_map(other)
 
 
 def test_two_sided_int32_bound_is_enforced_before_the_device_is_touched():
