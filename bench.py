@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "08db8f1444afe843215022791cb0969a8de36ea80f46401efb99f9c1b6d9e1c0"
-TRAFFIC_BYTES = {"C2": (2521.6 + 768.0) * 1024, "C5": (44556.0 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "4cd4f6d5f6669a36284387ab716c59ef2f3649d3378c0b4f4943c534ed513b50"
+TRAFFIC_BYTES = {"C2": (2513.5 + 768.0) * 1024, "C5": (44555.9 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -238,6 +238,20 @@ def main() -> int:
     if fused and not floating:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
+    if not floating and not two_sided and not dynamic and wl.dims[1] <= 256:
+        # the paper's W32A32-versus-W8A8 comparison (Table 2) on this GPU: the plain fp32 network through
+        # the library's own fused fp32 kernel, and how far the quantized output is from it
+        ref_model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=dhq.DHQ_W32A32)
+        ref_out = torch.empty_like(out)
+        ms_f, _ = time_forward(ref_model, x, ref_out, dhq.DHQ_AUTO, max(10, args.steps // 20), 5)
+        dhq.dhq_forward(model.handle, x, out, torch.cuda.current_stream(), flags)
+        torch.cuda.synchronize()
+        mse = float(((out.double() - ref_out.double()) ** 2).mean())
+        peak = float(ref_out.max() - ref_out.min())
+        res["w32a32_ms_per_step"] = ms_f
+        res["speedup_vs_w32a32"] = ms_f / ms
+        res["psnr_vs_w32a32_db"] = 10.0 * math.log10(peak * peak / mse) if mse > 0 else float("inf")
+        ref_model.close()
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
