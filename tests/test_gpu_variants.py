@@ -289,3 +289,102 @@ def test_float_modes_refuse_what_they_do_not_have():
     with pytest.raises(dhq.DhqError) as e:
         dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W8A32 | dhq.DHQ_ROTATE_BOTH)
     assert e.value.status == dhq.DHQ_EUNSUPPORTED
+
+
+# ------------------------------------------------ wide layers, full-size grids, graph replay
+def test_variants_on_width_512():
+    """Two-sided rotation and dynamic scales on the C5 network (512-wide layers: the widest
+    transform, un-rotation and GEMM shapes of the layer-by-layer path) on a strided sample."""
+    torch = _torch()
+    wl, coords, W, b = synth.make("C5")
+    coords = coords[::1201]                                  # 3493 coordinates
+    for two in (False, True):
+        _say(f"width 512 two_sided={two}")
+        net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two)
+        exp = o.forward(net, coords, calibrate=True)
+        m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH if two else dhq.DHQ_ROTATE_IN)
+        if two:
+            for l in range(len(wl.dims) - 1):
+                assert np.array_equal(m.weight_codes(l), net.Wq[l])
+        dyn = m.forward(_dev(coords), flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
+        s_dyn = m.dynamic_scales()
+        m.set_act_scales(net.s_a)
+        sta = m.forward(_dev(coords), flags=dhq.DHQ_LAYERWISE)
+        torch.cuda.synchronize()
+        assert (np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a).max() <= 1e-5
+        _gate(sta.cpu().numpy(), exp, wl.dims, False, "static")
+        _gate(dyn.cpu().numpy(), exp, wl.dims, False, "dynamic")
+        m.close()
+
+
+@pytest.mark.parametrize("mode_name", ["w32a32", "w8a32", "two_sided"])
+def test_full_grid_sampled_outputs_of_the_variants(mode_name):
+    """C4's 1024 x 1024 grid (1 048 576 coordinates) in one call, as the benchmark times it; the
+    oracle evaluates a random sample of coordinates plus the first and last tiles one by one."""
+    torch = _torch()
+    _say(f"full grid C4 {mode_name}")
+    wl, coords, W, b = synth.make("C4")
+    n = coords.shape[0]
+    rng = np.random.default_rng(23)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 5000), np.arange(0, 300), np.arange(n - 300, n)]))
+    if mode_name == "two_sided":
+        net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=True)
+        o.forward(net, coords[:: n // 8192], calibrate=True)
+        exp = o.forward(net, coords[idx])
+        m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH)
+        m.set_act_scales(net.s_a)
+    elif mode_name == "w8a32":
+        exp, _, _ = o.mlp_w8a32(wl.dims, wl.omega0, 8, W, b, coords[idx])
+        m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W8A32)
+    else:
+        exp, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords[idx])
+        m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W32A32)
+    out = m.forward(_dev(coords))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    if mode_name == "two_sided":
+        _gate(got, exp, wl.dims, False, "sampled")
+    else:
+        err = np.abs(got.astype(np.float64) - exp).max()
+        _say(f"  {idx.size} sampled coords: max-abs err {err:.3e}")
+        assert err <= FLOAT_TOL
+    sub = m.forward(_dev(coords[idx]))                       # a coordinate's value does not depend on the launch
+    torch.cuda.synchronize()
+    assert np.array_equal(sub.cpu().numpy(), got)
+    m.close()
+
+
+@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "w32a32"])
+def test_forward_replays_from_a_captured_graph(variant):
+    """dhq_forward only enqueues kernels (no memset, no allocation, no synchronisation once the
+    workspace exists), so a stream capture of it replays to the same bits as the eager call --
+    several times, with eager work and synchronisations in between."""
+    torch = _torch()
+    _say(f"graph replay {variant}")
+    wl, coords, W, b = synth.make("C1")
+    x = _dev(coords)
+    mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
+    flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode)
+    if variant != "w32a32":
+        m.calibrate(x)
+    out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
+    eager = m.forward(x, flags=flags).clone()                # also grows the dynamic workspace before capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            dhq.dhq_forward(m.handle, x, out, s, flags)
+    torch.cuda.current_stream().wait_stream(s)
+    for rep in range(3):
+        out.zero_()
+        scratch = m.forward(x[: 100 + rep], flags=flags)     # eager work on the same model in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), eager.cpu().numpy()), f"replay {rep}"
+        assert bool(torch.isfinite(scratch).all())
+    m.close()
