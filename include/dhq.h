@@ -25,6 +25,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     dhq_forward, dhq_forward_debug and dhq_gemm_i8 only enqueue work on it and
  *     return without synchronising; dhq_calibrate synchronises the stream.
+ *     dhq_forward enqueues kernels only (no memset, no copy), so a stream capture of it
+ *     can be replayed as a HIP graph; with DHQ_DYNAMIC make one eager call of at least the
+ *     captured size first, so that the workspace does not grow during capture.
  *   - A model owns device buffers (quantized weights, biases, a workspace for the
  *     layer-by-layer path).  Calls that use the same model concurrently from
  *     several streams or threads are not supported.
