@@ -187,10 +187,11 @@ def main() -> int:
         # layer shapes
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": tops / INT8_MFMA_PEAK_TOPS,
-                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and kernel_sources_sha256() == TRAFFIC_SHA256
+                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and kernel_sources_sha256() == TRAFFIC_SHA256
                                  else None),
                      "traffic_unit": "bytes per launch (HBM, measured)",
-                     "kernel": (("dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else f"dhq_fused_kernel<{wl.dims[1]}>")
+                     "kernel": ((f"dhq_fused2_kernel<{wl.dims[1]}>" if two_sided else
+                                 "dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else f"dhq_fused_kernel<{wl.dims[1]}>")
                                 if fused else "layerwise kernels"),
                      "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
                      "algorithmic_ops_per_launch": ops},
@@ -202,6 +203,8 @@ def main() -> int:
     import math
     nf = wl.dims[1]
     per_feature = 3 + math.log2(nf) + 0.5 + 3
+    if two_sided:
+        per_feature += math.log2(nf) + 0.5   # the integer un-rotation: as many add/sub and lane swaps again
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n
     valu_peak = 256 * 4 * 2.4e9 / 4
     res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,

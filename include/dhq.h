@@ -102,9 +102,11 @@ int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
  *     z    = acc' * H_Mp               (exact in int32: entries of H are +-1, H H = Mp I)
  *     y    = z[:, :M] * (s_a s_w / sqrt(Mp)) + b
  * Weights for which |z| could leave int32 (bound: qmax_a * sum_k |(H_Mp W'q)[j][k]| for some
- * output j) are refused with DHQ_EUNSUPPORTED.  Such a model runs on the layer-by-layer path
- * only (dhq_has_fused is 0); dhq_get_weight_codes returns Mp x Kp codes, dhq_gemm_i8 the
- * rotated accumulators (n x Mp) and dhq_forward_debug the un-rotated ones (n x Mp).
+ * output j) are refused with DHQ_EUNSUPPORTED.  Such a model has a fused kernel when fan-in
+ * <= 4, all hidden widths are equal and 32 / 64 / 128 / 256, and fan-out <= 4; otherwise it
+ * runs on the layer-by-layer path only.  dhq_get_weight_codes returns Mp x Kp codes,
+ * dhq_gemm_i8 the rotated accumulators (n x Mp) and dhq_forward_debug the un-rotated ones
+ * (n x Mp).
  * mode = DHQ_ROTATE_IN is dhq_quantize_weights.
  *
  * mode | DHQ_W8A32 / DHQ_W32A32 (with DHQ_ROTATE_IN only) builds the comparison networks of

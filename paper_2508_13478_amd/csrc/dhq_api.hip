@@ -81,6 +81,7 @@ extern "C" void dhq_free(dhq_model *m)
     dhq_fused_destroy(m->fused);
     dhq_wide_destroy(m->wide);
     dhq_float_destroy(m->flt);
+    dhq_fused2_destroy(m->fused2);
     delete m;
 }
 
@@ -281,9 +282,9 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_params, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_ENOMEM;
     }
-    // the whole-network kernels exist for the input-side rotation only
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
+    if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
         return rc;
@@ -302,6 +303,7 @@ static int update_fused_scales(dhq_model *m)
 {
     int rc = dhq_fused_update_scales(m, m->fused);
     if (rc == DHQ_OK) rc = dhq_wide_update_scales(m, m->wide);
+    if (rc == DHQ_OK) rc = dhq_fused2_update_scales(m, m->fused2);
     return rc;
 }
 
@@ -338,7 +340,7 @@ extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *W
 extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
-    return (m->fused || m->wide || m->flt) ? 1 : 0;
+    return (m->fused || m->wide || m->flt || m->fused2) ? 1 : 0;
 }
 
 // Per-layer constant of the quantizer kernel.
@@ -492,7 +494,9 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     // the workspace belongs to the model and is the only thing a forward call changes in it
     if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, st);
     if (!m->have_scales) return DHQ_ENOSCALE;
-    if (path == DHQ_FUSED && !m->fused && !m->wide) return DHQ_EUNSUPPORTED;
+    if (path == DHQ_FUSED && !m->fused && !m->wide && !m->fused2) return DHQ_EUNSUPPORTED;
+    if (path != DHQ_LAYERWISE && m->fused2)
+        return dhq_fused2_launch(m->fused2, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     if (path != DHQ_LAYERWISE && m->fused)
         return dhq_fused_launch(m, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     if (path != DHQ_LAYERWISE && m->wide)

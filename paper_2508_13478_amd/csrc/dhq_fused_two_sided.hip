@@ -1,0 +1,409 @@
+// Whole-network fused forward for the two-sided variant (weights rotated over input AND output
+// features, Eq. 4-5 as printed), hidden widths 32 .. 256, gfx950.
+//
+// Same orientation as dhq_fused.hip: features are the MFMA M dimension, a wave carries 32
+// coordinates through all layers in registers, lane (c, h) holds rows 8g + 4h + e of every
+// 32-row tile T in registers R = 16T + 4g + e.  Per layer:
+//   G   acc' = W'q q: all tiles accumulate straight into the lane's registers (as int32);
+//   U   un-rotation z = H acc' over the output features, exactly in int32: butterflies over
+//       the bits of R in place, then the stage over h with v_permlane32_swap on register pairs;
+//   E   y = z c1 + b, a = sin(2 pi y) on every register;
+//   W   the forward transform of the next layer's input over the same registers (fp32), its
+//       last stage again the lane swap, fused with the quantizer.
+// Index bookkeeping.  Call "location" (s, u) register s of lane half u.  Before U, location
+// (R, h) holds rotated output m = 32T + 8g + 4h + e =: P0(R, h).  Butterflies over register
+// bits are in place; the swap stage moves data: location (s, u) receives the h-butterfly of
+// register (s & ~1) | u, output bit s & 1 -- i.e. the roles of bit 0 of s and of u are
+// exchanged.  So after U, location (s, u) holds true feature f = P0((s & ~1) | u, s & 1)
+// (= rot_index(s, u)); the biases are laid out accordingly.  W starts from that arrangement
+// (a bit permutation of the feature index, which is all a butterfly network needs) and its
+// swap stage exchanges the two roles once more: after W, location (s, u) holds rotated index
+// P0(s, u) -- the natural accumulator order.  Hence the next layer's weights are packed with
+// their k positions in P0 order, and again nothing is shuffled at run time.
+//
+// The output layer needs fan-out padded to at most 4 (one tile, rows e = 0..3 of lane half 0):
+// its un-rotation is two butterfly stages on four registers.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "dhq_device.h"
+#include "dhq_fused_common.h"
+#include "dhq_internal.h"
+
+#define F2_WAVES 8
+#define F2_THREADS (F2_WAVES * 64)
+#define F2_TILE (F2_WAVES * 32)
+
+struct f2_layer_desc {
+    uint32_t blob_off;   // byte offset of the layer's block (A fragments, then 1 KiB of biases)
+    uint32_t chunks;     // block size in KiB
+    float c1;            // s_a s_w / sqrt(Mp) [omega0 / (2 pi) in sine layers]
+    float inv_in;        // 1 / (s_a sqrt(Kp)) of this layer's input quantizer
+};
+
+struct f2_args {
+    const float *coords;
+    float *out;
+    const unsigned char *blob;
+    int64_t n;
+    int n_layers;
+    int k0, k0p;
+    int m_out, m_out_p;  // fan-out of the output layer and its power-of-two padding (<= 4)
+    int qmax;
+    f2_layer_desc layer[DHQ_MAX_LAYERS];
+};
+
+struct dhq_fused2_plan {
+    int nf = 0;
+    unsigned char *blob_dev = nullptr;
+    size_t blob_bytes = 0;
+    f2_args args;
+    size_t lds_bytes = 0;
+    int n_cu = 0;
+};
+
+// ----------------------------------------------------------------------------- device code
+// All tiles of one layer: x[16 T + v] = sum over k blocks.  Two tiles are accumulated
+// alternately so that consecutive MFMAs do not depend on each other; A fragments are
+// fetched from LDS PF MFMAs ahead.
+template <int NT, int KB, int NCD>
+__device__ __forceinline__ void f2_gemm(const dhq_v4i *__restrict__ wA, const dhq_v4i (&cd)[NCD], dhq_v16i (&acc)[NT], int lane)
+{
+    constexpr int NM = NT * KB;
+    constexpr int PF = (NM >= 4) ? 4 : (NM >= 2 ? 2 : 1);
+    constexpr int CH = (NT >= 2) ? 2 : 1;
+    // MFMA number m -> (tile, k block): tiles in groups of CH, k blocks outer inside a group
+    auto tile_of = [](int m) { return (m / (CH * KB)) * CH + (m % CH); };
+    auto kb_of = [](int m) { return (m % (CH * KB)) / CH; };
+    dhq_v4i fr[PF + 1];
+#pragma unroll
+    for (int m = 0; m < PF; ++m)
+        if (m < NM) fr[m % (PF + 1)] = wA[(tile_of(m) * KB + kb_of(m)) * 64 + lane];
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+        const int T = tile_of(m), kb = kb_of(m);
+        if (m + PF < NM) fr[(m + PF) % (PF + 1)] = wA[(tile_of(m + PF) * KB + kb_of(m + PF)) * 64 + lane];
+        if (kb == 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[T][v] = 0;
+        }
+        acc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[m % (PF + 1)], cd[kb], acc[T], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int NF>
+__global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
+{
+    constexpr int NT = NF / 32;
+    constexpr int NKB = NF / 32;
+    constexpr int NR = NF / 2;
+    constexpr int BLK = (NT * NKB + 1) * 1024;
+
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int L = A.n_layers;
+    const int64_t n_tiles = (A.n + F2_TILE - 1) / F2_TILE;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+
+    int p = 0;
+    if ((int64_t)blockIdx.x < n_tiles)
+        fused_issue_copy(A.blob + A.layer[0].blob_off, lds, (int)A.layer[0].chunks, wave, lane, F2_WAVES);
+
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t ci = tile * F2_TILE + wave * 32 + c;
+        const bool valid = ci < A.n;
+        const int64_t cl = valid ? ci : A.n - 1;
+
+        dhq_v4i cd[NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        {
+            // input layer: rotate the coordinate vector (fan-in <= 4) and quantize it
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (A.k0 == 2) {
+                const float2 xy = *reinterpret_cast<const float2 *>(A.coords + cl * 2);
+                v[0] = xy.x; v[1] = xy.y;
+            } else {
+                for (int k = 0; k < A.k0; ++k) v[k] = A.coords[cl * A.k0 + k];
+            }
+            if (A.k0p >= 2) {
+                float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
+                a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
+            }
+            if (A.k0p == 4) {
+                float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
+                a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
+            }
+            const float inv = A.layer[0].inv_in;
+            cd[0][0] = (int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
+                                      dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
+        }
+
+        for (int l = 0; l < L - 1; ++l) {
+            // weights of layer l have landed; everyone is done with the other buffer
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            {
+                const f2_layer_desc &nx = A.layer[l + 1];
+                fused_issue_copy(A.blob + nx.blob_off, lds + (p ^ 1) * BLK, (int)nx.chunks, wave, lane, F2_WAVES);
+            }
+            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
+            const int Kb = (l == 0) ? 1 : NKB;
+            const float4 *wB = reinterpret_cast<const float4 *>(lds + p * BLK + NT * Kb * 1024);
+            // G: rotated accumulators of all output tiles
+            dhq_v16i acc[NT];
+            if (l == 0)
+                f2_gemm<NT, 1, NKB>(wA, cd, acc, lane);
+            else
+                f2_gemm<NT, NKB, NKB>(wA, cd, acc, lane);
+            int z[NR];
+#pragma unroll
+            for (int T = 0; T < NT; ++T)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[16 * T + v] = acc[T][v];
+            // U: z = H acc' in int32 (wrapping adds; the host has checked that the results fit)
+#pragma unroll
+            for (int s = 1; s < NR; s <<= 1) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    if ((i & s) == 0) {
+                        const unsigned a = (unsigned)z[i], b = (unsigned)z[i | s];
+                        z[i] = (int)(a + b);
+                        z[i | s] = (int)(a - b);
+                    }
+                }
+            }
+            float x[NR];
+            const float c1 = A.layer[l].c1;
+            // the stage over the lane-half bit, then E: dequantize + bias + sine (biases in location order)
+#pragma unroll
+            for (int pr = 0; pr < NR / 2; ++pr) {
+                const auto r = __builtin_amdgcn_permlane32_swap((unsigned)z[2 * pr], (unsigned)z[2 * pr + 1], false, false);
+                const int z0 = (int)(r[0] + r[1]), z1 = (int)(r[0] - r[1]);
+                const float4 bb = wB[(pr >> 1) * 2 + h];
+                const float b0 = (pr & 1) ? bb.z : bb.x, b1 = (pr & 1) ? bb.w : bb.y;
+                x[2 * pr] = dhq_sin_rev(__builtin_fmaf((float)z0, c1, b0));
+                x[2 * pr + 1] = dhq_sin_rev(__builtin_fmaf((float)z1, c1, b1));
+            }
+            // W: forward transform of the next layer's input, fused with its quantizer
+#pragma unroll
+            for (int s = 1; s < NR; s <<= 1) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    if ((i & s) == 0) {
+                        const float a = x[i], b = x[i | s];
+                        x[i] = a + b;
+                        x[i | s] = a - b;
+                    }
+                }
+            }
+            const float inv = A.layer[l + 1].inv_in;
+#pragma unroll
+            for (int w = 0; w < NR / 4; ++w) {
+                unsigned packed = 0;
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                    const int s0 = 4 * w + 2 * pr;
+                    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
+                                                                    false, false);
+                    const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
+                    fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
+                    fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
+                }
+                cd[w / 4][w % 4] = (int)packed;
+            }
+            p ^= 1;
+        }
+
+        // output layer: one zero-padded tile; rows e = 0..3 of lane half 0 carry the (<= 4) rotated outputs
+        {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tile + gridDim.x < n_tiles)
+                fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane, F2_WAVES);
+            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
+            const float *wB = reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024);
+            dhq_v16i acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                const dhq_v4i a = wA[kb * 64 + lane];
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
+            }
+            unsigned z[4] = {(unsigned)acc[0], (unsigned)acc[1], (unsigned)acc[2], (unsigned)acc[3]};
+            if (A.m_out_p >= 2) {
+                unsigned a = z[0], b = z[1]; z[0] = a + b; z[1] = a - b;
+                a = z[2]; b = z[3]; z[2] = a + b; z[3] = a - b;
+            }
+            if (A.m_out_p == 4) {
+                unsigned a = z[0], b = z[2]; z[0] = a + b; z[2] = a - b;
+                a = z[1]; b = z[3]; z[1] = a + b; z[3] = a - b;
+            }
+            const float c1 = A.layer[L - 1].c1;
+            if (valid && h == 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (e < A.m_out) A.out[ci * A.m_out + e] = __builtin_fmaf((float)(int)z[e], c1, wB[e]);
+            }
+            p ^= 1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------- host code
+// Natural accumulator order: rotated index held by register s of lane half u.
+static int p0_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
+
+static bool fused2_shape_ok(const dhq_model *m, int *nf_out)
+{
+    const int L = m->n_layers;
+    if (!m->rot_out || L < 2) return false;
+    if (m->dims[0] > 4 || m->dims[L] > 4) return false;
+    const int nf = m->dims[1];
+    if (nf != 32 && nf != 64 && nf != 128 && nf != 256) return false;
+    for (int l = 1; l < L; ++l)
+        if (m->dims[l] != nf) return false;
+    *nf_out = nf;
+    return true;
+}
+
+int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan_out)
+{
+    *plan_out = nullptr;
+    int nf = 0;
+    if (!fused2_shape_ok(m, &nf)) return DHQ_OK;
+    const int L = m->n_layers;
+    const int NT = nf / 32, NKB = nf / 32;
+    dhq_fused2_plan *P = new (std::nothrow) dhq_fused2_plan();
+    if (!P) return DHQ_ENOMEM;
+    P->nf = nf;
+    memset(&P->args, 0, sizeof(P->args));
+    std::vector<unsigned char> blob;
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const int Mt = (l == L - 1) ? 1 : NT;
+        const int Kb = (l == 0) ? 1 : NKB;
+        const size_t off = blob.size();
+        const size_t bytes = (size_t)(Mt * Kb + 1) * 1024;
+        blob.resize(off + bytes, 0);
+        int8_t *frag = reinterpret_cast<int8_t *>(blob.data() + off);
+        const int8_t *wq = Ly.wq_host.data();  // Mp x Kp, rows = rotated output index
+        for (int T = 0; T < Mt; ++T)
+            for (int kb = 0; kb < Kb; ++kb)
+                for (int ln = 0; ln < 64; ++ln) {
+                    const int row = 32 * T + (ln & 31), u = ln >> 5;
+                    for (int jj = 0; jj < 16; ++jj) {
+                        int8_t val = 0;
+                        if (row < Ly.Mg) {
+                            if (l == 0) {
+                                if (u == 0 && jj < Ly.Kp) val = wq[(size_t)row * Ly.Kp + jj];
+                            } else {
+                                val = wq[(size_t)row * Ly.Kp + p0_index(16 * kb + jj, u)];
+                            }
+                        }
+                        frag[((size_t)(T * Kb + kb) * 64 + ln) * 16 + jj] = val;
+                    }
+                }
+        P->args.layer[l].blob_off = (uint32_t)off;
+        P->args.layer[l].chunks = (uint32_t)(bytes / 1024);
+    }
+    P->blob_bytes = blob.size();
+    if (hipMalloc((void **)&P->blob_dev, P->blob_bytes) != hipSuccess) {
+        delete P;
+        return DHQ_ENOMEM;
+    }
+    if (hipMemcpy(P->blob_dev, blob.data(), P->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(P->blob_dev);
+        delete P;
+        return DHQ_EHIP;
+    }
+    P->args.blob = P->blob_dev;
+    P->args.n_layers = L;
+    P->args.k0 = m->dims[0];
+    P->args.k0p = m->layer[0].Kp;
+    P->args.m_out = m->dims[L];
+    P->args.m_out_p = m->layer[L - 1].Mp;
+    P->args.qmax = m->qmax_a;
+    P->lds_bytes = (size_t)2 * (NT * NKB + 1) * 1024;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
+        (void)hipFree(P->blob_dev);
+        delete P;
+        return DHQ_EHIP;
+    }
+    P->n_cu = prop.multiProcessorCount;
+    *plan_out = P;
+    return DHQ_OK;
+}
+
+void dhq_fused2_destroy(dhq_fused2_plan *P)
+{
+    if (!P) return;
+    if (P->blob_dev) (void)hipFree(P->blob_dev);
+    delete P;
+}
+
+// Per-layer constants and the bias part of each block.  Hidden layers: location (s, u) holds
+// true feature rot_index(s, u) after the un-rotation, and lane half u reads the biases of
+// registers s .. s+3 as one float4 at index (s / 4) * 2 + u.  Output layer: plain order.
+int dhq_fused2_update_scales(const dhq_model *m, dhq_fused2_plan *P)
+{
+    if (!P) return DHQ_OK;
+    const int L = m->n_layers;
+    const int NT = P->nf / 32, NKB = P->nf / 32, NR = P->nf / 2;
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const bool last = (l == L - 1);
+        P->args.layer[l].c1 = dhq_c1(m, l);
+        P->args.layer[l].inv_in = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
+        const int Mt = last ? 1 : NT, Kb = (l == 0) ? 1 : NKB;
+        std::vector<float> blk(256, 0.0f);
+        if (last) {
+            for (int f = 0; f < Ly.M; ++f) blk[f] = Ly.bias_host[f];
+        } else {
+            for (int s = 0; s < NR; ++s)
+                for (int u = 0; u < 2; ++u) {
+                    const int f = rot_index(s, u);
+                    if (f < Ly.M) blk[((s >> 2) * 2 + u) * 4 + (s & 3)] = Ly.bias_rev_host[f];
+                }
+        }
+        unsigned char *dst = P->blob_dev + P->args.layer[l].blob_off + (size_t)Mt * Kb * 1024;
+        if (hipMemcpy(dst, blk.data(), 1024, hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
+    }
+    return DHQ_OK;
+}
+
+template <int NF>
+static hipError_t fused2_launch_t(const dhq_fused2_plan *P, const f2_args &a, unsigned grid, hipStream_t st)
+{
+    auto kern = dhq_fused2_kernel<NF>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
+    if (e != hipSuccess) return e;
+    kern<<<grid, F2_THREADS, P->lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t dhq_fused2_launch(const dhq_fused2_plan *P, const float *coords, int64_t n, float *out, hipStream_t st)
+{
+    if (!P) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    f2_args a = P->args;
+    a.coords = coords;
+    a.out = out;
+    a.n = n;
+    const int64_t tiles = (n + F2_TILE - 1) / F2_TILE;
+    const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    switch (P->nf) {
+        case 32: return fused2_launch_t<32>(P, a, grid, st);
+        case 64: return fused2_launch_t<64>(P, a, grid, st);
+        case 128: return fused2_launch_t<128>(P, a, grid, st);
+        case 256: return fused2_launch_t<256>(P, a, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}

@@ -36,6 +36,7 @@ struct dhq_layer {
 struct dhq_fused_plan;  // defined in dhq_fused.hip
 struct dhq_wide_plan;   // defined in dhq_fused_wide.hip
 struct dhq_float_plan;  // defined in dhq_float.hip
+struct dhq_fused2_plan; // defined in dhq_fused_two_sided.hip
 
 struct dhq_model {
     int n_layers = 0;
@@ -64,6 +65,7 @@ struct dhq_model {
     dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
     dhq_wide_plan *wide = nullptr;    // hidden width 512
     dhq_float_plan *flt = nullptr;    // floating-point activations (DHQ_W8A32 / DHQ_W32A32)
+    dhq_fused2_plan *fused2 = nullptr;  // two-sided variant, hidden width 32..256, fan-out <= 4
     int device = 0;
 };
 
@@ -130,6 +132,13 @@ void dhq_wide_destroy(dhq_wide_plan *plan);
 int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *plan);
 hipError_t dhq_wide_launch(const dhq_wide_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
+
+// Two-sided variant, whole network in one kernel (defined in dhq_fused_two_sided.hip); same
+// contract as the dhq_fused_* functions.
+int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan);
+void dhq_fused2_destroy(dhq_fused2_plan *plan);
+int dhq_fused2_update_scales(const dhq_model *m, dhq_fused2_plan *plan);
+hipError_t dhq_fused2_launch(const dhq_fused2_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
 // Floating-point activations (defined in dhq_float.hip): the plain SIREN on the given fp32
 // weights W[l] (dims[l+1] x dims[l]) and biases, fused over all layers.  DHQ_EUNSUPPORTED if

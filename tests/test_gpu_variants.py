@@ -57,7 +57,7 @@ def test_two_sided_weight_codes_bit_identical(name):
     for l in range(len(cs.dims) - 1):
         q = cs.model.weight_codes(l)
         assert q.shape == cs.net.Wq[l].shape and np.array_equal(q, cs.net.Wq[l]), f"layer {l}"
-    assert not cs.model.has_fused()
+    assert cs.model.has_fused()
 
 
 def test_two_sided_weight_codes_odd_shapes():
@@ -105,14 +105,39 @@ def test_two_sided_forward(name):
     torch = _torch()
     _say(f"two-sided forward {name}")
     cs = two_sided(name)
-    out = cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_LAYERWISE)
-    auto = cs.model.forward(_dev(cs.coords))             # no fused kernel: the same path
+    lw = cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_LAYERWISE)
+    fu = cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
+    auto = cs.model.forward(_dev(cs.coords))             # picks the fused kernel
     torch.cuda.synchronize()
-    assert np.array_equal(out.cpu().numpy(), auto.cpu().numpy())
-    _gate(out.cpu().numpy(), cs.out, cs.dims, name == "C1", "two-sided")
-    with pytest.raises(dhq.DhqError) as e:
-        cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
-    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    lw, fu = lw.cpu().numpy(), fu.cpu().numpy()
+    assert np.array_equal(fu, auto.cpu().numpy())
+    _gate(lw, cs.out, cs.dims, name == "C1", "two-sided layer-by-layer")
+    _gate(fu, cs.out, cs.dims, name == "C1", "two-sided fused")
+    d = np.abs(lw - fu).max(axis=1)
+    _say(f"  fused vs layer-by-layer: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
+    assert (d > OUT_TOL).mean() <= flip_frac(cs.dims)
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 1], [4, 128, 128, 2], [2, 256, 256, 256, 256, 256, 4]])
+def test_two_sided_fused_shapes_and_ragged_rows(dims):
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 31 + len(dims))
+    rng = np.random.default_rng(dims[1])
+    x = rng.uniform(-1, 1, size=(3000 + 45, dims[0])).astype(np.float32)
+    net = o.quantize_net(dims, 30.0, 8, 8, W, b, two_sided=True)
+    exp = o.forward(net, x, calibrate=True)
+    m = dhq.Model(dims, 30.0, W, b, mode=dhq.DHQ_ROTATE_BOTH)
+    assert m.has_fused()
+    m.set_act_scales(net.s_a)
+    for n in (1, 257, x.shape[0]):
+        _say(f"two-sided fused dims {dims} n={n}")
+        out = m.forward(_dev(x[:n]), flags=dhq.DHQ_FUSED)
+        torch.cuda.synchronize()
+        _gate(out.cpu().numpy(), exp[:n], dims, False, f"n={n}")
+    # a fan-out above 4 has no fused kernel
+    dims5 = dims[:-1] + [5]
+    W5, b5 = synth.siren_init(dims5, 30.0, 7)
+    assert not dhq.Model(dims5, 30.0, W5, b5, mode=dhq.DHQ_ROTATE_BOTH).has_fused()
 
 
 def test_two_sided_forward_odd_shapes_ragged_rows_and_chunks():
@@ -333,6 +358,7 @@ def test_full_grid_sampled_outputs_of_the_variants(mode_name):
         exp = o.forward(net, coords[idx])
         m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH)
         m.set_act_scales(net.s_a)
+        assert m.has_fused()
     elif mode_name == "w8a32":
         exp, _, _ = o.mlp_w8a32(wl.dims, wl.omega0, 8, W, b, coords[idx])
         m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W8A32)
