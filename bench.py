@@ -122,6 +122,8 @@ def main() -> int:
                          "two_sided: weights rotated on both sides, un-rotation in int32 (layer-by-layer path); "
                          "dynamic: activation scales measured on line per call (layer-by-layer path); "
                          "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
+    ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
+                    help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
     ap.add_argument("--copy-probe", action="store_true",
@@ -153,7 +155,7 @@ def main() -> int:
     if not floating:
         model.calibrate(x)
     _, s_a = model.scales()
-    fused = model.has_fused() and not dynamic
+    fused = model.has_fused() and not dynamic and (args.path == "auto" or floating)
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
     if dynamic:
         flags |= dhq.DHQ_DYNAMIC
