@@ -161,7 +161,7 @@ int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *o
                 void *stream, uint32_t flags);
 
 /* The scales s_a (host, n_layers floats) that the last DHQ_DYNAMIC forward on this model
- * measured.  Synchronises `stream` (pass the stream that forward ran on). */
+ * measured (zeros if there has been none).  Synchronises `stream` (pass the stream that forward ran on). */
 int dhq_get_dynamic_scales(const dhq_model *m, float *s_a_host, void *stream);
 
 /*

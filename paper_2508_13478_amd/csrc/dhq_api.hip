@@ -281,6 +281,8 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
             rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_params, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_ENOMEM;
+        // dhq_get_dynamic_scales before any dynamic forward reports zeros
+        if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
     }
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);

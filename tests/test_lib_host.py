@@ -133,3 +133,19 @@ def test_two_sided_int32_bound_is_enforced_before_the_device_is_touched():
     W2[0, 0] = 1.0
     r = o.layer_two_sided(a[:, :256], 256, *o.quantize_weights_two_sided(W2, 8), b[:256], None, 8, False, 30.0)
     assert np.abs(r["unrot"]).max() == 127 * 127 * 256 * 256
+
+
+def test_header_is_plain_c_and_entry_points_link_from_c(tmp_path):
+    """include/dhq.h compiled as C99 with warnings as errors, linked against libdhq.so and run:
+    version, status names and the argument checks that are decided before the device is touched."""
+    import subprocess
+    dhq.lib()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(dhq.LIB_PATH)
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c", "c_abi_check.c"), "-o", exe, "-L", libdir, "-l:libdhq.so",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "c_abi_check ok" in r.stdout
