@@ -36,6 +36,9 @@ CODEGEN_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                  # MFMA accumulators in ordinary vector registers even in kernels that also park values
                  # in accumulation registers: the epilogue then reads them without a register move
                  "-mllvm", "-amdgpu-mfma-vgpr-form",
+                 # the hand-scheduled GEMM loops must unroll completely (their schedule tables fold to
+                 # constants only then); the default size limit for "#pragma unroll" is too small for them
+                 "-mllvm", "-pragma-unroll-threshold=131072",
                  "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 # Kernels that address accumulation registers by number from inline assembly: source file, a

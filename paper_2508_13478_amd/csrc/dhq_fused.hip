@@ -207,7 +207,155 @@ __device__ __forceinline__ void fused_gemm_sine(const dhq_v4i *__restrict__ wA, 
     }
 }
 
-template <int NF>
+// ---- variant with the in-tile part of the transform on the matrix unit ---------------------
+// The 32 features of an M tile are one factor of the Sylvester matrix, H_NF = H_NT (x) H_32, so
+// the five butterfly stages over the within-tile index (four over register bits, one over the
+// lane half) are the product H_32 * (tile of activations): a 32 x 32 x 32 contraction whose B
+// operand the lanes already hold.  The matrix unit has no fp32 input at a useful rate, so an
+// activation a (|a| <= 1) is split into two binary16 pieces, hi = a rounded toward zero and
+// lo = (a - hi) rounded toward zero (a - hi is exact in fp32), which carry a to within 2^-22
+// (2^-24 absolute below 2^-10: the pieces may be subnormal, which v_mfma_f32_32x32x16_f16
+// takes as they are); the products with +-1 are exact and the sum is accumulated in fp32 like
+// the butterflies' sums.  Per tile: 8 + 8 packed conversions, 16 mixed-precision subtractions
+// and 4 MFMAs replace 80 add/sub and 8 lane swaps.  The three stages over the tile index stay
+// on the vector ALU.  Afterwards register s of lane half u holds rotated feature hm_index(s, u).
+typedef _Float16 dhq_v8h __attribute__((ext_vector_type(8)));
+typedef float dhq_v16f __attribute__((ext_vector_type(16)));
+
+static inline int hm_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
+
+template <int NT, int KB>
+struct hm_sched {
+    static constexpr bool STAGGER = (NT >= 2 && KB >= 2);
+    static constexpr int STEPS = (STAGGER ? (NT / 2) * 2 * KB + KB + 1 : NT * KB) + KB + 6;
+    static constexpr int NM = NT * KB;
+    int tile[STEPS], kb[STEPS], seq[STEPS];   // GEMM MFMA issued at this step (tile -1: none)
+    int drain[STEPS], drain_pos[STEPS];       // tile drained at this step and which slice of it
+    int hm_n[STEPS], hm_tile[STEPS][4], hm_k[STEPS][4];  // transform MFMAs issued at this step
+    int seq_tile[NM], seq_kb[NM];
+    int last;                                 // last step with any work
+    constexpr hm_sched()
+        : tile(), kb(), seq(), drain(), drain_pos(), hm_n(), hm_tile(), hm_k(), seq_tile(), seq_kb(), last(0)
+    {
+        int done[NT > 0 ? NT : 1] = {};
+        for (int g = 0; g < STEPS; ++g) { tile[g] = -1; kb[g] = 0; seq[g] = -1; drain[g] = -1; drain_pos[g] = 0; hm_n[g] = 0; }
+        for (int t = 0; t < NT; ++t) {
+            const int i = t / 2;
+            const int base = (t & 1) ? 2 * KB * i + KB + 1 : 2 * KB * i;
+            for (int k = 0; k < KB; ++k) {
+                const int g = STAGGER ? base + 2 * k : t * KB + k;
+                tile[g] = t; kb[g] = k; done[t] = g;
+            }
+        }
+        int m = 0;
+        for (int g = 0; g < STEPS; ++g)
+            if (tile[g] >= 0) { seq[g] = m; seq_tile[m] = tile[g]; seq_kb[m] = kb[g]; ++m; }
+        for (int t = 0; t < NT; ++t) {
+            int at[KB + 3] = {};
+            int g = done[t] + 1;
+            for (int k = 0; k < KB; ++k) {
+                while (drain[g] >= 0) ++g;
+                drain[g] = t; drain_pos[g] = k; at[k] = g;
+                ++g;
+            }
+            at[KB] = at[KB - 1] + 1; at[KB + 1] = at[KB - 1] + 2;
+            // pieces of block 0 (accumulators 0..7) are complete after slice KB/2 - 1, of block 1 after the last
+            int when[4] = {at[KB], at[KB], at[KB], at[KB]};
+            if (KB >= 4) { when[0] = at[KB / 2]; when[1] = at[KB / 2 + 1]; when[2] = at[KB]; when[3] = at[KB + 1]; }
+            for (int k = 0; k < 4; ++k) {
+                const int w = when[k];
+                hm_tile[w][hm_n[w]] = t; hm_k[w][hm_n[w]] = k; ++hm_n[w];
+                if (w > last) last = w;
+            }
+        }
+    }
+};
+
+// One layer's GEMM with the dequantize + bias + sine epilogue, the split into binary16 pieces and
+// the H_32 products, software-pipelined by hand according to hm_sched.  On return xt[T][v]
+// holds, for this lane's coordinate, row 8 (v / 4) + 4 h + v % 4 of H_32 * (activations of tile T).
+template <int NT, int KB, int NCD>
+__device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
+                                                   const dhq_v4i (&cd)[NCD], float c1, dhq_v16f (&xt)[NT],
+                                                   const dhq_v4i (&hA)[2], int lane, int h)
+{
+    constexpr hm_sched<NT, KB> S{};
+    constexpr int LAST = S.last;
+    constexpr int NM = NT * KB;
+    constexpr int EPS = 16 / KB;  // accumulators drained per step (KB <= 8: an even number)
+    constexpr int PF = (NM >= 4) ? 4 : (NM >= 2 ? 2 : 1);  // LDS prefetch distance in MFMAs
+    dhq_v4i fr[PF + 1];
+    float4 bq[3][4];
+    dhq_v16i acc[3];
+    unsigned hp[2][8], lp[2][8];  // packed pieces of the tile being drained (and of the one before)
+#pragma unroll
+    for (int m = 0; m < PF; ++m)
+        if (m < NM) fr[m % (PF + 1)] = wA[(S.seq_tile[m] * KB + S.seq_kb[m]) * 64 + lane];
+    constexpr int GB = 8;
+#pragma unroll
+    for (int g0 = 0; g0 <= LAST; g0 += GB) {
+#pragma unroll
+      for (int g1 = 0; g1 < GB; ++g1) {
+        const int g = g0 + g1;
+        if (g > LAST) continue;
+        const int T = S.tile[g];
+        if (T >= 0) {
+            const int m = S.seq[g], kb = S.kb[g];
+            if (m + PF < NM) {
+                fr[(m + PF) % (PF + 1)] = wA[(S.seq_tile[m + PF] * KB + S.seq_kb[m + PF]) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch at the top of the step
+            }
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg)
+                if ((gg * KB) / 4 == kb) bq[T % 3][gg] = wB[(T * 4 + gg) * 2 + h];
+            if (kb == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[T % 3][v] = 0;
+            }
+            acc[T % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[m % (PF + 1)], cd[kb], acc[T % 3], 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (q < S.hm_n[g]) {
+                const int Th = S.hm_tile[g][q], k = S.hm_k[g][q];
+                const int blk = k >> 1;
+                dhq_v4i b;  // small pieces first
+#pragma unroll
+                for (int d = 0; d < 4; ++d) b[d] = (int)((k & 1) ? hp[Th & 1][4 * blk + d] : lp[Th & 1][4 * blk + d]);
+                dhq_v16f d;
+                if (k == 0) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) d[v] = 0.f;
+                } else {
+                    d = xt[Th];
+                }
+                xt[Th] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(dhq_v8h, hA[blk]),
+                                                                __builtin_bit_cast(dhq_v8h, b), d, 0, 0, 0);
+            }
+        }
+        const int Td = S.drain[g];
+        if (Td >= 0) {
+#pragma unroll
+            for (int j = 0; j < EPS; j += 2) {
+                const int v = S.drain_pos[g] * EPS + j;
+                const float4 bb = bq[Td % 3][v >> 2];
+                const float bias0 = (v & 2) ? bb.z : bb.x, bias1 = (v & 2) ? bb.w : bb.y;
+                const float a0 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0));
+                const float a1 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1));
+                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a0, a1));
+                float r0, r1;  // a - hi, exact; the binary16 operand is read in place
+                asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
+                asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
+                hp[Td & 1][v >> 1] = hi;
+                lp[Td & 1][v >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(r0, r1));
+            }
+        }
+        if (T >= 0 || Td >= 0 || S.hm_n[g] > 0) __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+}
+
+template <int NF, bool HM>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
     constexpr int NT = NF / 32;   // M tiles of a hidden layer
@@ -221,6 +369,25 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
     const int L = A.n_layers;
     const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
     const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+
+    // A operand of the H_32 products: this lane supplies row c of H_32 at the eight contraction
+    // slots 8 h + j of block kk, which stand for tile row 8 (v / 4) + 4 h + v % 4 with v = 8 kk + j
+    // (the row lane half h holds in accumulator v), as binary16 +-1.
+    dhq_v4i hA[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            unsigned word = 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int v = 8 * kk + 2 * d + e;
+                const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+                word |= ((__builtin_popcount(c & row) & 1) ? 0xBC00u : 0x3C00u) << (16 * e);
+            }
+            hA[kk][d] = (int)word;
+        }
+    }
 
     int p = 0;  // LDS buffer holding the layer about to run
     if ((int64_t)blockIdx.x < n_tiles)
@@ -256,7 +423,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
                                       dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
         }
 
-        float x[NR];
+        float x[HM ? 1 : NR];
+        dhq_v16f xt[HM ? NT : 1];
         for (int l = 0; l < L - 1; ++l) {
             // weights of layer l have landed; everyone is done with the other buffer
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -267,44 +435,78 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             }
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const float c1 = A.layer[l].c1;
-            if (l == 0)
-                fused_gemm_sine<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, x,
-                                            lane, h);
-            else
-                fused_gemm_sine<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
-                                              c1, x, lane, h);
+            if constexpr (HM) {
+                if (l == 0)
+                    fused_gemm_sine_hm<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1,
+                                                   xt, hA, lane, h);
+                else
+                    fused_gemm_sine_hm<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024),
+                                                     cd, c1, xt, hA, lane, h);
+            } else {
+                if (l == 0)
+                    fused_gemm_sine<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, x,
+                                                lane, h);
+                else
+                    fused_gemm_sine<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
+                                                  c1, x, lane, h);
+            }
             // The two waves of a SIMD overlap well while both feed the matrix unit or both
             // do vector work, but a wave in its vector phase starves the MFMA chain of the
             // other; keep the phases aligned across the workgroup.
             __syncthreads();
-            // Walsh-Hadamard transform over the NF features of each coordinate:
-            // stages over the register index bits ...
+            const float inv = A.layer[l + 1].inv_in;
+            if constexpr (HM) {
+                // the stages over the tile index, then the quantizer
 #pragma unroll
-            for (int s = 16; s < NR; s <<= 1) {  // (the four stages inside a tile were done above)
+                for (int s = 1; s < NT; s <<= 1) {
 #pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    if ((i & s) == 0) {
-                        const float a = x[i], b = x[i | s];
-                        x[i] = a + b;
-                        x[i | s] = a - b;
+                    for (int T = 0; T < NT; ++T) {
+                        if ((T & s) == 0) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                const float a = xt[T][v], b = xt[T | s][v];
+                                xt[T][v] = a + b;
+                                xt[T | s][v] = a - b;
+                            }
+                        }
                     }
                 }
-            }
-            // ... then the stage over the lane-half bit, fused with the quantizer
-            const float inv = A.layer[l + 1].inv_in;
 #pragma unroll
-            for (int w = 0; w < NR / 4; ++w) {
-                unsigned packed = 0;
+                for (int w = 0; w < NR / 4; ++w) {
+                    unsigned packed = 0;
 #pragma unroll
-                for (int pr = 0; pr < 2; ++pr) {
-                    const int s0 = 4 * w + 2 * pr;
-                    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
-                                                                    false, false);
-                    const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
-                    fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
-                    fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
+                    for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
+                    cd[w / 4][w % 4] = (int)packed;
                 }
-                cd[w / 4][w % 4] = (int)packed;
+            } else {
+                // Walsh-Hadamard transform over the NF features of each coordinate:
+                // stages over the register index bits ...
+#pragma unroll
+                for (int s = 16; s < NR; s <<= 1) {  // (the four stages inside a tile were done above)
+#pragma unroll
+                    for (int i = 0; i < NR; ++i) {
+                        if ((i & s) == 0) {
+                            const float a = x[i], b = x[i | s];
+                            x[i] = a + b;
+                            x[i | s] = a - b;
+                        }
+                    }
+                }
+                // ... then the stage over the lane-half bit, fused with the quantizer
+#pragma unroll
+                for (int w = 0; w < NR / 4; ++w) {
+                    unsigned packed = 0;
+#pragma unroll
+                    for (int pr = 0; pr < 2; ++pr) {
+                        const int s0 = 4 * w + 2 * pr;
+                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
+                                                                        false, false);
+                        const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
+                        fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
+                        fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
+                    }
+                    cd[w / 4][w % 4] = (int)packed;
+                }
             }
             p ^= 1;
         }
@@ -341,6 +543,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
 }
 
 // ------------------------------------------------------------------------------- host code
+static constexpr bool FUSED_HM = true;
 static bool fused_shape_ok(const dhq_model *m, int *nf_out)
 {
     const int L = m->n_layers;
@@ -389,7 +592,7 @@ int dhq_fused_create(const dhq_model *m, dhq_fused_plan **plan_out)
                                 // un-permuted: the input layer's codes sit in bytes 0..Kp-1 of half 0
                                 if (u == 0 && jj < Ly.Kp) val = wq[(size_t)row * Ly.Kp + jj];
                             } else {
-                                const int k = rot_index(16 * kb + jj, u);
+                                const int k = FUSED_HM ? hm_index(16 * kb + jj, u) : rot_index(16 * kb + jj, u);
                                 val = wq[(size_t)row * Ly.Kp + k];
                             }
                         }
@@ -460,7 +663,7 @@ int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
 template <int NF>
 static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused_kernel<NF>;
+    auto kern = dhq_fused_kernel<NF, FUSED_HM>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
     if (e != hipSuccess) return e;
     kern<<<grid, FUSED_THREADS, P->lds_bytes, st>>>(a);

@@ -326,11 +326,14 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     }
 }
 
-// Fan-in below 32 (the input layer, K = 2): one thread per coordinate and group of VEC
-// consecutive features (4 when the row length allows 16-byte stores); the contraction is a
-// handful of integer multiply-adds and the kernel is bound by its output.
-template <bool ACT, int VEC>
-__global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restrict__ codes, int64_t n, int Kp,
+// Fan-in below 32 (the input layer, K = 2): the contraction is a handful of integer
+// multiply-adds and the kernel is bound by its output.  Workgroup = 64 feature groups x 4
+// coordinates, so no thread needs an integer division to find its place; a thread keeps the
+// weights of its VEC consecutive features (4 when the row length allows 16-byte stores) in
+// registers and walks over NARROW_ROWS coordinates.  KP = 0 takes the fan-in at run time.
+#define NARROW_ROWS 8
+template <bool ACT, int VEC, int KP>
+__global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restrict__ codes, int64_t n, int Kp_rt,
                                                           const int8_t *__restrict__ wq, int M,
                                                           int32_t *__restrict__ acc_out,
                                                           float *__restrict__ act_out, float c1,
@@ -338,46 +341,74 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restri
                                                           const float *__restrict__ dyn)
 {
     if (ACT && dyn) c1 = dyn[1];
+    const int Kp = KP ? KP : Kp_rt;
+    constexpr int KMAX = KP ? KP : 16;
     const int groups = M / VEC;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n * groups) return;
-    const int64_t row = idx / groups;
-    const int f0 = (int)(idx % groups) * VEC;
-    int acc[VEC];
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + threadIdx.y) * NARROW_ROWS;
+    for (int g = threadIdx.x; g < groups; g += 64) {
+        const int f0 = g * VEC;
+        int w[VEC][KMAX];
+        float bv[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0;
-    for (int k = 0; k < Kp; ++k) {
-        const int q = (int)codes[row * Kp + k];
+        for (int e = 0; e < VEC; ++e) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += q * (int)wq[(f0 + e) * Kp + k];
+            for (int k = 0; k < KMAX; ++k) w[e][k] = k < Kp ? (int)wq[(f0 + e) * Kp + k] : 0;
+            bv[e] = ACT ? bias[f0 + e] : 0.f;
+        }
+#pragma unroll 2
+        for (int r = 0; r < NARROW_ROWS; ++r) {
+            const int64_t row = row0 + r;
+            if (row >= n) break;
+            int acc[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = 0;
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const int q = k < Kp ? (int)codes[row * Kp + k] : 0;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] += q * w[e][k];
+            }
+            if (ACT) {
+                float o[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) o[e] = dhq_epilogue(acc[e], c1, bv[e], sine != 0);
+                if constexpr (VEC == 4)
+                    *reinterpret_cast<float4 *>(act_out + row * M + f0) = make_float4(o[0], o[1], o[2], o[3]);
+                else
+                    act_out[row * M + f0] = o[0];
+            } else {
+                if constexpr (VEC == 4)
+                    *reinterpret_cast<int4 *>(acc_out + row * M + f0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+                else
+                    acc_out[row * M + f0] = acc[0];
+            }
+        }
     }
-    if (ACT) {
-        float o[VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) o[e] = dhq_epilogue(acc[e], c1, bias[f0 + e], sine != 0);
-        if constexpr (VEC == 4)
-            *reinterpret_cast<float4 *>(act_out + row * M + f0) = make_float4(o[0], o[1], o[2], o[3]);
-        else
-            act_out[row * M + f0] = o[0];
-    } else {
-        if constexpr (VEC == 4)
-            *reinterpret_cast<int4 *>(acc_out + row * M + f0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
-        else
-            acc_out[row * M + f0] = acc[0];
-    }
+}
+
+template <bool ACT, int VEC>
+static void launch_gemm_narrow_kp(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out, float *act_out,
+                                  float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
+{
+    const unsigned blocks = (unsigned)((n + 4 * NARROW_ROWS - 1) / (4 * NARROW_ROWS));
+    const dim3 block(64, 4);
+    const int s = sine ? 1 : 0;
+    if (L.Kp == 2)
+        gemm_narrow_kernel<ACT, VEC, 2><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
+    else if (L.Kp == 4)
+        gemm_narrow_kernel<ACT, VEC, 4><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
+    else
+        gemm_narrow_kernel<ACT, VEC, 0><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
 }
 
 template <bool ACT>
 static hipError_t launch_gemm_narrow(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out, float *act_out,
                                      float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
 {
-    const int vec = (L.Mg & 3) == 0 ? 4 : 1;
-    const int64_t total = n * (L.Mg / vec);
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (vec == 4)
-        gemm_narrow_kernel<ACT, 4><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, sine ? 1 : 0, dyn);
+    if ((L.Mg & 3) == 0)
+        launch_gemm_narrow_kp<ACT, 4>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
     else
-        gemm_narrow_kernel<ACT, 1><<<blocks, 256, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, sine ? 1 : 0, dyn);
+        launch_gemm_narrow_kp<ACT, 1>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
     return hipGetLastError();
 }
 

@@ -187,6 +187,28 @@ def _coords_with_code_diffs(cs, n):
     return diff
 
 
+# A code may legitimately differ from the oracle's only where the exact rotated activation lies
+# within the fp32 path's own error of a rounding boundary.  That error is dominated by the sine
+# layer before it: the argument in revolutions reaches |t| ~ 10 where one fp32 ulp is 1e-6
+# revolutions = 6e-6 rad, so an activation is off by up to ~6e-6 (rms ~1e-6) and a sum of Kp = 256
+# of them with signs by ~2e-5 rms.  BOUNDARY_EPS (un-normalised units, i.e. before the 1/sqrt(Kp))
+# is five times that; the transform's own rounding (a few ulp of |x^| <= 100, ~1e-5) fits inside.
+BOUNDARY_EPS = 1e-4
+
+
+def _near_boundary(net, dmp, bits):
+    """Per coordinate: does any in-range code of any layer come from a rotated activation within
+    BOUNDARY_EPS of a rounding boundary?  (dmp.rot holds the oracle's exact, normalised x^.)"""
+    qm = (1 << (bits - 1)) - 1
+    near = np.zeros(dmp.rot[0].shape[0], dtype=bool)
+    for l, rot in enumerate(dmp.rot):
+        t = rot / float(net.s_a[l])
+        dist = np.abs(t - np.floor(t) - 0.5)                    # in quantization steps
+        eps = BOUNDARY_EPS / (float(net.s_a[l]) * np.sqrt(rot.shape[1]))
+        near |= ((dist < eps) & (np.abs(t) < qm)).any(axis=1)          # boundaries lie at +-(k + 0.5), k < qmax
+    return near
+
+
 def _assert_close(out, exp, strict=False, frac=FLIP_FRAC):
     """Free-running comparison of final values: strict max-abs, or max-abs on all but the
     small fraction of coordinates that a code difference may have moved."""
@@ -291,9 +313,23 @@ def test_full_grid_sampled_outputs(name, bits):
     rng = np.random.default_rng(17)
     idx = np.unique(np.concatenate([rng.integers(0, n, 6000), np.arange(0, 300), np.arange(n - 300, n)]))
     got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
-    exp = o.forward(net, coords[idx])
-    err = _assert_close(got, exp, frac=flip_frac(wl.dims))
-    _say(f"  {idx.size} sampled coords: max-abs err {err.max():.3e}, {(err > OUT_TOL).sum()} beyond {OUT_TOL}")
+    exp, dmp = o.forward(net, coords[idx], dump=True)
+    err = np.abs(got.astype(np.float64) - exp).max(axis=1)
+    over = err > OUT_TOL
+    near = _near_boundary(net, dmp, bits)
+    # coordinates that share their first-layer codes share everything after them; at 4 bits the
+    # whole grid collapses to about a hundred such cases, so the share of coordinates that moved
+    # is counted over distinct cases
+    _, case_of = np.unique(dmp.codes[0], axis=0, return_inverse=True)
+    case_of = np.asarray(case_of).reshape(-1)
+    n_cases = int(case_of.max()) + 1
+    moved_cases = np.unique(case_of[over]).size
+    _say(f"  {idx.size} sampled coords ({n_cases} distinct cases): max-abs err {err.max():.3e}, {over.sum()} beyond "
+         f"{OUT_TOL} in {moved_cases} cases; {near.sum()} coords have a code within {BOUNDARY_EPS} of a rounding boundary")
+    assert err.max() <= FLIP_BOUND
+    assert not (over & ~near).any()       # away from every rounding boundary the tolerance holds strictly
+    # (a count of two or three carries its own sampling noise, hence the floor and the factor)
+    assert moved_cases <= max(3, 2 * flip_frac(wl.dims) * n_cases)
     # properties that hold at any size: finite everywhere, and a coordinate's value does not
     # depend on which launch or tile it was computed in
     assert bool(torch.isfinite(out).all())
