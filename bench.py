@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "4cd4f6d5f6669a36284387ab716c59ef2f3649d3378c0b4f4943c534ed513b50"
-TRAFFIC_BYTES = {"C2": (2513.5 + 768.0) * 1024, "C5": (44555.9 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "1c51bec2e2191c14243e2cedf525871ffb37d181b976d8a4e8dc2d32a4ce4c2f"
+TRAFFIC_BYTES = {"C2": (2524.4 + 768.0) * 1024, "C5": (44555.8 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -199,12 +199,16 @@ def main() -> int:
                      "algorithmic_ops_per_launch": ops},
     }
     # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
-    # sine layer the fused kernels issue about 14.5 vector instructions (convert, fma, sine,
-    # log2(n) add/sub, half a lane swap, fma, max, min); a SIMD issues one
-    # wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4 per second.
+    # sine layer the fused kernels issue convert, fma, sine, the transform, fma, max, min.  The
+    # transform is log2(n) add/sub and half a lane swap at width 512 and in the two-sided kernel;
+    # the kernel for widths <= 256 gives the 32-row factor to the matrix unit (two vector
+    # instructions to split an activation into binary16 pieces) and keeps log2(n / 32) add/sub.
+    # A SIMD issues one wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4
+    # per second.
     import math
     nf = wl.dims[1]
-    per_feature = 3 + math.log2(nf) + 0.5 + 3
+    on_matrix_unit = fused and nf <= 256 and not two_sided
+    per_feature = 3 + (2 + math.log2(nf / 32) if on_matrix_unit else math.log2(nf) + 0.5) + 3
     if two_sided:
         per_feature += math.log2(nf) + 0.5   # the integer un-rotation: as many add/sub and lane swaps again
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n

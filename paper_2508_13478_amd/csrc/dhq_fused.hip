@@ -10,18 +10,17 @@
 // (32 k x 32 coordinates).  With that orientation lane l of a wave holds, for coordinate
 // l % 32, accumulator rows 8g + 4h + e (g = 0..3, h = l / 32, e = 0..3) of every 32-row
 // tile T: half of the feature vector of one coordinate, in registers R = 16T + 4g + e.
-// The Walsh-Hadamard transform over the feature index (Eq. 3) is then
-//   - log2(NF) - 1 butterfly stages over the bits of R: plain register add/sub, no lane
-//     traffic, and
-//   - one stage over h, done with v_permlane32_swap on register pairs (2p, 2p+1): after the
-//     swap the two halves of a pair sit in the same lane, one add and one sub finish it.
-// A butterfly network may visit the index bits in any order, so this computes the same
-// transform as the textbook ordering.  After the last stage register s of lane half u
-// holds rotated feature j(s, u) (see rot_index below); quantizing register s into byte
-// s % 4 of dword s / 4 makes four consecutive dwords exactly the B operand of k block
-// s / 16.  The contraction index of an MFMA can be enumerated in any order as long as both
-// operands agree, so the weights are packed offline with their k positions permuted by
-// j(s, u) and nothing is ever shuffled at run time.
+// The Walsh-Hadamard transform over the feature index (Eq. 3) factors as H_NF = H_NT (x) H_32
+// and is done in two parts:
+//   - H_32 over the 32 rows of each tile on the matrix unit (see fused_gemm_sine_hm below):
+//     the tile's activations are already laid out as an MFMA B operand, H_32 is the A operand;
+//   - log2(NT) butterfly stages over the tile index, i.e. over bits 4.. of R: plain register
+//     add/sub, no lane traffic.
+// After the last stage register s of lane half u holds rotated feature j(s, u) (hm_index
+// below); quantizing register s into byte s % 4 of dword s / 4 makes four consecutive dwords
+// exactly the B operand of k block s / 16.  The contraction index of an MFMA can be enumerated
+// in any order as long as both operands agree, so the weights are packed offline with their k
+// positions permuted by j(s, u) and nothing is ever shuffled at run time.
 //
 // The first layer (fan-in <= 4) and the output layer (fan-out <= 32) use the same
 // machinery with the k block / the M tile zero-padded.
@@ -71,156 +70,31 @@ struct dhq_fused_plan {
     int n_cu = 0;
 };
 
-// Issue schedule of one layer's GEMM.  The M tiles are accumulated by two staggered MFMA
-// chains: even tiles on even steps, odd tiles on odd steps half a tile later, so consecutive
-// MFMAs of a wave never depend on each other and the matrix unit is not left waiting for its
-// own result.  A tile that has received its last k block is drained (dequantize + bias +
-// sine, 16 / KB accumulators per step) during the KB steps that follow, and during the KB
-// steps after that the four Walsh-Hadamard stages that stay inside the tile's 16 registers
-// run on it -- all in the shadow of the other tiles' MFMAs, which keeps the vector ALU and
-// the matrix unit of the wave busy together.  Three accumulator tiles rotate: two
-// accumulating, one draining.
-template <int NT, int KB>
-struct gemm_sched {
-    static constexpr bool STAGGER = (NT >= 2 && KB >= 2);  // with one k block per tile nothing depends
-    static constexpr int STEPS = (STAGGER ? (NT / 2) * 2 * KB + KB + 1 : NT * KB) + 2 * KB + 2;
-    static constexpr int NM = NT * KB;  // MFMAs
-    int tile[STEPS];      // tile whose MFMA issues at this step, -1 if none
-    int kb[STEPS];
-    int seq[STEPS];       // running index of that MFMA
-    int drain[STEPS];     // tile drained at this step, -1 if none
-    int drain_pos[STEPS]; // which slice (0..KB-1) of its 16 accumulators
-    int bfly[STEPS];      // tile whose in-tile butterflies run at this step, -1 if none
-    int bfly_pos[STEPS];  // which slice (0..KB-1) of its 32 butterflies
-    int seq_tile[NM];     // inverse: MFMA number -> tile, k block
-    int seq_kb[NM];
-    constexpr gemm_sched()
-        : tile(), kb(), seq(), drain(), drain_pos(), bfly(), bfly_pos(), seq_tile(), seq_kb()
-    {
-        int done[NT > 0 ? NT : 1] = {};
-        for (int g = 0; g < STEPS; ++g) {
-            tile[g] = -1; kb[g] = 0; seq[g] = -1; drain[g] = -1; drain_pos[g] = 0; bfly[g] = -1; bfly_pos[g] = 0;
-        }
-        for (int t = 0; t < NT; ++t) {
-            const int i = t / 2;
-            const int base = (t & 1) ? 2 * KB * i + KB + 1 : 2 * KB * i;
-            for (int k = 0; k < KB; ++k) {
-                const int g = STAGGER ? base + 2 * k : t * KB + k;
-                tile[g] = t;
-                kb[g] = k;
-                done[t] = g;
-            }
-        }
-        int m = 0;
-        for (int g = 0; g < STEPS; ++g)
-            if (tile[g] >= 0) { seq[g] = m; seq_tile[m] = tile[g]; seq_kb[m] = kb[g]; ++m; }
-        for (int t = 0; t < NT; ++t) {
-            // two tiles may want the same step near the end; take the next free one
-            int g = done[t] + 1;
-            for (int k = 0; k < KB; ++k) {
-                while (drain[g] >= 0) ++g;
-                drain[g] = t;
-                drain_pos[g] = k;
-                ++g;
-            }
-            for (int k = 0; k < KB; ++k) {
-                while (bfly[g] >= 0) ++g;
-                bfly[g] = t;
-                bfly_pos[g] = k;
-                ++g;
-            }
-        }
-    }
-};
-
-// One layer's GEMM with the dequantize + bias + sine epilogue and the in-tile part of the
-// Walsh-Hadamard transform, software-pipelined by hand according to gemm_sched.
-// A fragments are fetched from LDS PF MFMAs ahead, a tile's bias vectors while it
-// accumulates.  sched_barrier pins the step order; the compiler is free inside a step.
-// On return x[] holds sin(...) of this lane's features with the butterfly stages over the
-// register index bits 0..3 already applied.
-template <int NT, int KB, int NCD>
-__device__ __forceinline__ void fused_gemm_sine(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
-                                                const dhq_v4i (&cd)[NCD], float c1, float (&x)[NT * 16],
-                                                int lane, int h)
-{
-    constexpr gemm_sched<NT, KB> S{};
-    constexpr int NM = NT * KB;
-    constexpr int EPS = 16 / KB;  // accumulators drained per step (KB <= 16)
-    constexpr int BPS = 32 / KB;  // butterflies per step
-    constexpr int PF = (NM >= 4) ? 4 : (NM >= 2 ? 2 : 1);  // LDS prefetch distance in MFMAs
-    dhq_v4i fr[PF + 1];
-    float4 bq[3][4];
-    dhq_v16i acc[3];
-#pragma unroll
-    for (int m = 0; m < PF; ++m)
-        if (m < NM) fr[m % (PF + 1)] = wA[(S.seq_tile[m] * KB + S.seq_kb[m]) * 64 + lane];
-    constexpr int GB = 8;  // steps are unrolled in nested groups (keeps each unrolled loop small)
-#pragma unroll
-    for (int g0 = 0; g0 < S.STEPS; g0 += GB) {
-#pragma unroll
-      for (int g1 = 0; g1 < GB; ++g1) {
-        const int g = g0 + g1;
-        if (g >= S.STEPS) continue;
-        const int T = S.tile[g];
-        if (T >= 0) {
-            const int m = S.seq[g], kb = S.kb[g];
-            if (m + PF < NM) {
-                fr[(m + PF) % (PF + 1)] = wA[(S.seq_tile[m + PF] * KB + S.seq_kb[m + PF]) * 64 + lane];
-                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch at the top of the step
-            }
-            // bias vectors of this tile, spread over its steps
-#pragma unroll
-            for (int gg = 0; gg < 4; ++gg)
-                if ((gg * KB) / 4 == kb) bq[T % 3][gg] = wB[(T * 4 + gg) * 2 + h];
-            if (kb == 0) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[T % 3][v] = 0;
-            }
-            acc[T % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[m % (PF + 1)], cd[kb], acc[T % 3], 0, 0, 0);
-        }
-        const int Td = S.drain[g];
-        if (Td >= 0) {
-#pragma unroll
-            for (int j = 0; j < EPS; ++j) {
-                const int v = S.drain_pos[g] * EPS + j;
-                const float4 bb = bq[Td % 3][v >> 2];
-                const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
-                x[16 * Td + v] = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias));
-            }
-        }
-        const int Tb = S.bfly[g];
-        if (Tb >= 0) {
-            // butterflies b = stage * 8 + pair over the 16 registers of tile Tb, in stage order
-#pragma unroll
-            for (int j = 0; j < BPS; ++j) {
-                const int b = S.bfly_pos[g] * BPS + j;
-                const int st = b >> 3, q = b & 7;
-                const int r = ((q >> st) << (st + 1)) | (q & ((1 << st) - 1));
-                const float u = x[16 * Tb + r], w = x[16 * Tb + (r | (1 << st))];
-                x[16 * Tb + r] = u + w;
-                x[16 * Tb + (r | (1 << st))] = u - w;
-            }
-        }
-        if (T >= 0 || Td >= 0 || Tb >= 0) __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-}
-
-// ---- variant with the in-tile part of the transform on the matrix unit ---------------------
+// ---- the in-tile part of the transform on the matrix unit ------------------------------------
 // The 32 features of an M tile are one factor of the Sylvester matrix, H_NF = H_NT (x) H_32, so
 // the five butterfly stages over the within-tile index (four over register bits, one over the
 // lane half) are the product H_32 * (tile of activations): a 32 x 32 x 32 contraction whose B
 // operand the lanes already hold.  The matrix unit has no fp32 input at a useful rate, so an
 // activation a (|a| <= 1) is split into two binary16 pieces, hi = a rounded toward zero and
-// lo = (a - hi) rounded toward zero (a - hi is exact in fp32), which carry a to within 2^-22
-// (2^-24 absolute below 2^-10: the pieces may be subnormal, which v_mfma_f32_32x32x16_f16
-// takes as they are); the products with +-1 are exact and the sum is accumulated in fp32 like
+// lo = (a - hi) rounded toward zero (a - hi is exact in fp32), which carry a to within 2^-21 |a|
+// (2^-24 absolute below 2^-10, where lo is subnormal; v_mfma_f32_32x32x16_f16 takes subnormal
+// inputs as they are).  That is up to four units in the last place of a, still below the error
+// of the sine that produced a, and the rotated activations come out with about the same error
+// as from fp32 butterflies (1.3e-6 against 0.9e-6 rms at width 256, un-normalised).  The
+// products with +-1 are exact and the sum is accumulated in fp32 like
 // the butterflies' sums.  Per tile: 8 + 8 packed conversions, 16 mixed-precision subtractions
 // and 4 MFMAs replace 80 add/sub and 8 lane swaps.  The three stages over the tile index stay
 // on the vector ALU.  Afterwards register s of lane half u holds rotated feature hm_index(s, u).
 typedef _Float16 dhq_v8h __attribute__((ext_vector_type(8)));
 typedef float dhq_v16f __attribute__((ext_vector_type(16)));
+
+// Two floats to packed binary16, rounded toward zero; element 0 in the low half.  (The
+// round-to-nearest form, v_cvt_pk_f16_f32, issues at half the rate and would cost the kernel
+// 3 % for a quarter less rounding error in the rotated activations.)
+__device__ __forceinline__ unsigned hm_pack_half2(float a, float b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
 
 static inline int hm_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
 
@@ -342,12 +216,12 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
                 const float bias0 = (v & 2) ? bb.z : bb.x, bias1 = (v & 2) ? bb.w : bb.y;
                 const float a0 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0));
                 const float a1 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1));
-                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a0, a1));
+                const unsigned hi = hm_pack_half2(a0, a1);
                 float r0, r1;  // a - hi, exact; the binary16 operand is read in place
                 asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
                 asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
                 hp[Td & 1][v >> 1] = hi;
-                lp[Td & 1][v >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(r0, r1));
+                lp[Td & 1][v >> 1] = hm_pack_half2(r0, r1);
             }
         }
         if (T >= 0 || Td >= 0 || S.hm_n[g] > 0) __builtin_amdgcn_sched_barrier(0);
@@ -355,7 +229,7 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
     }
 }
 
-template <int NF, bool HM>
+template <int NF>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
     constexpr int NT = NF / 32;   // M tiles of a hidden layer
@@ -423,8 +297,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
                                       dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
         }
 
-        float x[HM ? 1 : NR];
-        dhq_v16f xt[HM ? NT : 1];
+        dhq_v16f xt[NT];
         for (int l = 0; l < L - 1; ++l) {
             // weights of layer l have landed; everyone is done with the other buffer
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -435,78 +308,39 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             }
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const float c1 = A.layer[l].c1;
-            if constexpr (HM) {
-                if (l == 0)
-                    fused_gemm_sine_hm<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1,
-                                                   xt, hA, lane, h);
-                else
-                    fused_gemm_sine_hm<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024),
-                                                     cd, c1, xt, hA, lane, h);
-            } else {
-                if (l == 0)
-                    fused_gemm_sine<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, x,
-                                                lane, h);
-                else
-                    fused_gemm_sine<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
-                                                  c1, x, lane, h);
-            }
+            if (l == 0)
+                fused_gemm_sine_hm<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, xt,
+                                               hA, lane, h);
+            else
+                fused_gemm_sine_hm<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
+                                                 c1, xt, hA, lane, h);
             // The two waves of a SIMD overlap well while both feed the matrix unit or both
             // do vector work, but a wave in its vector phase starves the MFMA chain of the
             // other; keep the phases aligned across the workgroup.
             __syncthreads();
             const float inv = A.layer[l + 1].inv_in;
-            if constexpr (HM) {
-                // the stages over the tile index, then the quantizer
+            // the stages of the transform over the tile index (plain register add/sub) ...
 #pragma unroll
-                for (int s = 1; s < NT; s <<= 1) {
+            for (int s = 1; s < NT; s <<= 1) {
 #pragma unroll
-                    for (int T = 0; T < NT; ++T) {
-                        if ((T & s) == 0) {
+                for (int T = 0; T < NT; ++T) {
+                    if ((T & s) == 0) {
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) {
-                                const float a = xt[T][v], b = xt[T | s][v];
-                                xt[T][v] = a + b;
-                                xt[T | s][v] = a - b;
-                            }
+                        for (int v = 0; v < 16; ++v) {
+                            const float a = xt[T][v], b = xt[T | s][v];
+                            xt[T][v] = a + b;
+                            xt[T | s][v] = a - b;
                         }
                     }
                 }
+            }
+            // ... then the quantizer: register s = 16 T + v becomes byte s % 4 of dword s / 4
 #pragma unroll
-                for (int w = 0; w < NR / 4; ++w) {
-                    unsigned packed = 0;
+            for (int w = 0; w < NR / 4; ++w) {
+                unsigned packed = 0;
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
-                    cd[w / 4][w % 4] = (int)packed;
-                }
-            } else {
-                // Walsh-Hadamard transform over the NF features of each coordinate:
-                // stages over the register index bits ...
-#pragma unroll
-                for (int s = 16; s < NR; s <<= 1) {  // (the four stages inside a tile were done above)
-#pragma unroll
-                    for (int i = 0; i < NR; ++i) {
-                        if ((i & s) == 0) {
-                            const float a = x[i], b = x[i | s];
-                            x[i] = a + b;
-                            x[i | s] = a - b;
-                        }
-                    }
-                }
-                // ... then the stage over the lane-half bit, fused with the quantizer
-#pragma unroll
-                for (int w = 0; w < NR / 4; ++w) {
-                    unsigned packed = 0;
-#pragma unroll
-                    for (int pr = 0; pr < 2; ++pr) {
-                        const int s0 = 4 * w + 2 * pr;
-                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
-                                                                        false, false);
-                        const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
-                        fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
-                        fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
-                    }
-                    cd[w / 4][w % 4] = (int)packed;
-                }
+                for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
+                cd[w / 4][w % 4] = (int)packed;
             }
             p ^= 1;
         }
@@ -543,7 +377,6 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
 }
 
 // ------------------------------------------------------------------------------- host code
-static constexpr bool FUSED_HM = true;
 static bool fused_shape_ok(const dhq_model *m, int *nf_out)
 {
     const int L = m->n_layers;
@@ -592,7 +425,7 @@ int dhq_fused_create(const dhq_model *m, dhq_fused_plan **plan_out)
                                 // un-permuted: the input layer's codes sit in bytes 0..Kp-1 of half 0
                                 if (u == 0 && jj < Ly.Kp) val = wq[(size_t)row * Ly.Kp + jj];
                             } else {
-                                const int k = FUSED_HM ? hm_index(16 * kb + jj, u) : rot_index(16 * kb + jj, u);
+                                const int k = hm_index(16 * kb + jj, u);
                                 val = wq[(size_t)row * Ly.Kp + k];
                             }
                         }
@@ -663,7 +496,7 @@ int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
 template <int NF>
 static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused_kernel<NF, FUSED_HM>;
+    auto kern = dhq_fused_kernel<NF>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
     if (e != hipSuccess) return e;
     kern<<<grid, FUSED_THREADS, P->lds_bytes, st>>>(a);
