@@ -233,12 +233,16 @@ hipError_t dhq_launch_wht_absmax(const float *in, int64_t n, int K, int Kp, unsi
 }
 
 // ------------------------------------------------------------------------- int8 GEMM, MFMA
-// D[feature][coord] = sum_k Wq[feature][k] * q[coord][k] with v_mfma_i32_32x32x32_i8:
-// the weights are the A operand (32 features x 32 k), the codes the B operand (32 k x 32
-// coords).  Lane l supplies row/column l % 32 and the 16 consecutive k of half l / 32 for
-// both operands; it receives D rows 8*(v/4) + 4*(l/32) + v%4 (v = 0..15) of column l % 32.
+// D[coord][feature] = sum_k q[coord][k] * Wq[feature][k] with v_mfma_i32_32x32x32_i8: the
+// codes are the A operand (32 coords x 32 k), the weights the B operand (32 k x 32 features).
+// Lane l supplies row/column l % 32 and the 16 consecutive k of half l / 32 for both operands
+// (so a weight fragment has the same bytes whichever operand it feeds); it receives D rows
+// 8*(v/4) + 4*(l/32) + v%4 (v = 0..15) of column l % 32.  With coordinates as rows the 32
+// lanes of a wave half write 32 consecutive features of one coordinate per store: whole
+// 128-byte lines (the other orientation, which the fused kernels need for their in-register
+// transform, would write 32-byte pieces of 32 different lines).
 //
-// A workgroup of 4 waves covers 128 coordinates x up to 4 M tiles (128 features); the A
+// A workgroup of 4 waves covers 128 coordinates x up to 4 M tiles (128 features); the weight
 // fragments of its tiles are copied once into LDS ([tile][k block][lane] x 16 B, the order
 // they are stored in device memory) and read back conflict-free with one 16-byte LDS load
 // per lane.  Codes are read straight from device memory.
@@ -256,23 +260,23 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     constexpr int KP = NKB * 32;
     const int tile0 = blockIdx.y * 4;
     const int ntile = min(4, Mt - tile0);
-    // stage this block's A fragments: ntile * NKB * 64 vectors of 16 B
-    {
-        const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(wfrag) + (size_t)tile0 * NKB * 64;
-        const int total = ntile * NKB * 64;
-        for (int i = threadIdx.x; i < total; i += 256) lds[i] = src[i];
-    }
-    __syncthreads();
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int64_t row = (int64_t)blockIdx.x * 128 + wave * 32 + c;
     const int64_t rrow = row < n ? row : n - 1;  // tail lanes read a valid row, store nothing
     const dhq_v4i *brow = reinterpret_cast<const dhq_v4i *>(codes + rrow * KP + 16 * h);
 
+    // this lane's codes (from device memory) are requested first, so that they travel while the
+    // block's A fragments are staged: ntile * NKB * 64 vectors of 16 B
     dhq_v4i b[NKB];
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) b[kb] = brow[kb * 2];
+    {
+        const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(wfrag) + (size_t)tile0 * NKB * 64;
+        const int total = ntile * NKB * 64;
+        for (int i = threadIdx.x; i < total; i += 256) lds[i] = src[i];
+    }
+    __syncthreads();
 
     dhq_v16i acc[4];
 #pragma unroll
@@ -285,43 +289,27 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
         if (t < ntile) {
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb) {
-                const dhq_v4i a = lds[(t * NKB + kb) * 64 + lane];
-                acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[kb], acc[t], 0, 0, 0);
+                const dhq_v4i w = lds[(t * NKB + kb) * 64 + lane];
+                acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kb], w, acc[t], 0, 0, 0);
             }
         }
     }
-    if (row >= n) return;
+    // accumulator v of this lane: coordinate row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (tile0 + t) + c
+    const int64_t row0 = (int64_t)blockIdx.x * 128 + wave * 32;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         if (t >= ntile) break;
+        const int f = (tile0 + t) * 32 + c;
+        if (f >= M) continue;
+        const float bf = ACT ? bias[f] : 0.f;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int f = (tile0 + t) * 32 + 8 * g + 4 * h;  // first of 4 consecutive features
-            if (f >= M) continue;
-            if (ACT) {
-                float o[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    o[e] = (f + e < M) ? dhq_epilogue(acc[t][4 * g + e], c1, bias[f + e], sine != 0) : 0.0f;
-                float *dst = act_out + row * M + f;
-                if ((M & 3) == 0) {
-                    *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (f + e < M) dst[e] = o[e];
-                }
-            } else {
-                int32_t *dst = acc_out + row * M + f;
-                if ((M & 3) == 0) {
-                    *reinterpret_cast<int4 *>(dst) =
-                        make_int4(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (f + e < M) dst[e] = acc[t][4 * g + e];
-                }
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int64_t r = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (r >= n) continue;
+            if (ACT)
+                act_out[r * M + f] = dhq_epilogue(acc[t][v], c1, bf, sine != 0);
+            else
+                acc_out[r * M + f] = acc[t][v];
         }
     }
 }
