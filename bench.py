@@ -200,17 +200,17 @@ def main() -> int:
     }
     # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
     # sine layer the fused kernels issue convert, fma, sine, the transform, fma, max, min.  The
-    # transform is log2(n) add/sub and half a lane swap at width 512 and in the two-sided kernel;
-    # the kernel for widths <= 256 gives the 32-row factor to the matrix unit (two vector
-    # instructions to split an activation into binary16 pieces) and keeps log2(n / 32) add/sub.
+    # transform is log2(n) add/sub and half a lane swap at width 512; the kernels for widths <= 256
+    # give the 32-row factor to the matrix unit (two vector instructions to split an activation
+    # into binary16 pieces) and keep log2(n / 32) add/sub.
     # A SIMD issues one wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4
     # per second.
     import math
     nf = wl.dims[1]
-    on_matrix_unit = fused and nf <= 256 and not two_sided
+    on_matrix_unit = fused and nf <= 256
     per_feature = 3 + (2 + math.log2(nf / 32) if on_matrix_unit else math.log2(nf) + 0.5) + 3
     if two_sided:
-        per_feature += math.log2(nf) + 0.5   # the integer un-rotation: as many add/sub and lane swaps again
+        per_feature += math.log2(nf) + 0.5   # the integer un-rotation: log2(n) add/sub and half a lane swap
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n
     valu_peak = 256 * 4 * 2.4e9 / 4
     res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,

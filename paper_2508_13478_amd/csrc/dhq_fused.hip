@@ -85,17 +85,6 @@ struct dhq_fused_plan {
 // the butterflies' sums.  Per tile: 8 + 8 packed conversions, 16 mixed-precision subtractions
 // and 4 MFMAs replace 80 add/sub and 8 lane swaps.  The three stages over the tile index stay
 // on the vector ALU.  Afterwards register s of lane half u holds rotated feature hm_index(s, u).
-typedef _Float16 dhq_v8h __attribute__((ext_vector_type(8)));
-typedef float dhq_v16f __attribute__((ext_vector_type(16)));
-
-// Two floats to packed binary16, rounded toward zero; element 0 in the low half.  (The
-// round-to-nearest form, v_cvt_pk_f16_f32, issues at half the rate and would cost the kernel
-// 3 % for a quarter less rounding error in the rotated activations.)
-__device__ __forceinline__ unsigned hm_pack_half2(float a, float b)
-{
-    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
-}
-
 static inline int hm_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
 
 template <int NT, int KB>
@@ -216,12 +205,7 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
                 const float bias0 = (v & 2) ? bb.z : bb.x, bias1 = (v & 2) ? bb.w : bb.y;
                 const float a0 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0));
                 const float a1 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1));
-                const unsigned hi = hm_pack_half2(a0, a1);
-                float r0, r1;  // a - hi, exact; the binary16 operand is read in place
-                asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
-                asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
-                hp[Td & 1][v >> 1] = hi;
-                lp[Td & 1][v >> 1] = hm_pack_half2(r0, r1);
+                hm_split_pair(a0, a1, hp[Td & 1][v >> 1], lp[Td & 1][v >> 1]);
             }
         }
         if (T >= 0 || Td >= 0 || S.hm_n[g] > 0) __builtin_amdgcn_sched_barrier(0);
@@ -252,14 +236,9 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
     for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-            unsigned word = 0;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int v = 8 * kk + 2 * d + e;
-                const int row = 8 * (v >> 2) + 4 * h + (v & 3);
-                word |= ((__builtin_popcount(c & row) & 1) ? 0xBC00u : 0x3C00u) << (16 * e);
-            }
-            hA[kk][d] = (int)word;
+            const int v = 8 * kk + 2 * d;  // accumulators v and v + 1: consecutive tile rows
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
         }
     }
 

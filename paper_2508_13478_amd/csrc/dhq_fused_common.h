@@ -46,6 +46,38 @@ __device__ __forceinline__ void fused_issue_copy(const unsigned char *src, unsig
     }
 }
 
+// ---- pieces for running a 32-point Hadamard factor on the matrix unit ------------------------
+typedef _Float16 dhq_v8h __attribute__((ext_vector_type(8)));
+typedef float dhq_v16f __attribute__((ext_vector_type(16)));
+
+// Two floats to packed binary16, rounded toward zero; element 0 in the low half.  (The
+// round-to-nearest form, v_cvt_pk_f16_f32, issues at half the rate and would cost the kernels
+// 3 % for a quarter less rounding error in the rotated activations.)
+__device__ __forceinline__ unsigned hm_pack_half2(float a, float b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+// Splits two activations into binary16 pieces: hi = (a0, a1) rounded toward zero, lo = the
+// remainders a - hi (exact in fp32; v_fma_mix_f32 reads the binary16 half in place) rounded
+// toward zero.  hi + lo carries a to within 2^-21 |a| (2^-24 absolute below 2^-10).
+__device__ __forceinline__ void hm_split_pair(float a0, float a1, unsigned &hi, unsigned &lo)
+{
+    hi = hm_pack_half2(a0, a1);
+    float r0, r1;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
+    lo = hm_pack_half2(r0, r1);
+}
+
+// One dword of the A operand of an H_32 product: entries +-1 (binary16) of row `row` of the
+// Sylvester matrix at the two tile rows i0 (low half) and i1 (high half).
+__device__ __forceinline__ unsigned hm_h32_pair(int row, int i0, int i1)
+{
+    return ((__builtin_popcount(row & i0) & 1) ? 0xBC00u : 0x3C00u) |
+           (((__builtin_popcount(row & i1) & 1) ? 0xBC00u : 0x3C00u) << 16);
+}
+
 // Last butterfly stage (over the lane-half bit) fused with the quantizer: registers
 // (2p, 2p+1) swap halves across the wave, one add and one sub finish the transform, and each
 // result is rounded, clamped and dropped into its byte of the packed code dword.  The final

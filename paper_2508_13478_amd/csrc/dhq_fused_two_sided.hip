@@ -8,17 +8,18 @@
 //   U   un-rotation z = H acc' over the output features, exactly in int32: butterflies over
 //       the bits of R in place, then the stage over h with v_permlane32_swap on register pairs;
 //   E   y = z c1 + b, a = sin(2 pi y) on every register;
-//   W   the forward transform of the next layer's input over the same registers (fp32), its
-//       last stage again the lane swap, fused with the quantizer.
+//   W   the forward transform of the next layer's input (fp32): the 32-point factor inside
+//       each tile as a product on the matrix unit, the stages over the tile index in
+//       registers, then the quantizer.
 // Index bookkeeping.  Call "location" (s, u) register s of lane half u.  Before U, location
 // (R, h) holds rotated output m = 32T + 8g + 4h + e =: P0(R, h).  Butterflies over register
 // bits are in place; the swap stage moves data: location (s, u) receives the h-butterfly of
 // register (s & ~1) | u, output bit s & 1 -- i.e. the roles of bit 0 of s and of u are
 // exchanged.  So after U, location (s, u) holds true feature f = P0((s & ~1) | u, s & 1)
-// (= rot_index(s, u)); the biases are laid out accordingly.  W starts from that arrangement
-// (a bit permutation of the feature index, which is all a butterfly network needs) and its
-// swap stage exchanges the two roles once more: after W, location (s, u) holds rotated index
-// P0(s, u) -- the natural accumulator order.  Hence the next layer's weights are packed with
+// (= rot_index(s, u)); the biases are laid out accordingly.  W starts from that arrangement:
+// the H_32 operand of its MFMAs is built for it, and an MFMA delivers its result in the
+// accumulator layout, so after W location (s, u) holds rotated index P0(s, u) -- the natural
+// accumulator order.  Hence the next layer's weights are packed with
 // their k positions in P0 order, and again nothing is shuffled at run time.
 //
 // The output layer needs fan-out padded to at most 4 (one tile, rows e = 0..3 of lane half 0):
@@ -110,6 +111,20 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
     const int64_t n_tiles = (A.n + F2_TILE - 1) / F2_TILE;
     const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
 
+    // A operand of the H_32 products of W: this lane supplies row c of H_32 at the contraction
+    // slots 8 h + j of block kk; slot j of lane half u carries the value at location (s, u),
+    // s % 16 = 8 kk + j, i.e. (after U) feature 8 ((s >> 2) & 3) + 4 (s & 1) + (s & 2) + u of its tile.
+    dhq_v4i hA[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int v = 8 * kk + 2 * d;  // locations v (bit 0 clear) and v + 1
+            const int i0 = 8 * (v >> 2) + (v & 2) + h;
+            hA[kk][d] = (int)hm_h32_pair(c, i0, i0 + 4);
+        }
+    }
+
     int p = 0;
     if ((int64_t)blockIdx.x < n_tiles)
         fused_issue_copy(A.blob + A.layer[0].blob_off, lds, (int)A.layer[0].chunks, wave, lane, F2_WAVES);
@@ -190,15 +205,41 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
                 x[2 * pr] = dhq_sin_rev(__builtin_fmaf((float)z0, c1, b0));
                 x[2 * pr + 1] = dhq_sin_rev(__builtin_fmaf((float)z1, c1, b1));
             }
-            // W: forward transform of the next layer's input, fused with its quantizer
+            // W: forward transform of the next layer's input and its quantizer.  The factor H_32 over
+            // the 32 features of a tile goes to the matrix unit as in dhq_fused.hip (activations split
+            // into two binary16 pieces, four MFMAs per tile); the stages over the tile index follow in
+            // registers.  The MFMA's D layout is the natural accumulator order P0 again.
+            dhq_v16f xt[NT];
 #pragma unroll
-            for (int s = 1; s < NR; s <<= 1) {
+            for (int T = 0; T < NT; ++T) {
+                unsigned hp[8], lp[8];
 #pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    if ((i & s) == 0) {
-                        const float a = x[i], b = x[i | s];
-                        x[i] = a + b;
-                        x[i | s] = a - b;
+                for (int d = 0; d < 8; ++d) hm_split_pair(x[16 * T + 2 * d], x[16 * T + 2 * d + 1], hp[d], lp[d]);
+                dhq_v16f acc_t;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc_t[v] = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {  // small pieces first: lo, hi of block 0, then of block 1
+                    const int blk = k >> 1;
+                    dhq_v4i b;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) b[d] = (int)((k & 1) ? hp[4 * blk + d] : lp[4 * blk + d]);
+                    acc_t = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(dhq_v8h, hA[blk]),
+                                                                   __builtin_bit_cast(dhq_v8h, b), acc_t, 0, 0, 0);
+                }
+                xt[T] = acc_t;
+            }
+#pragma unroll
+            for (int s = 1; s < NT; s <<= 1) {
+#pragma unroll
+                for (int T = 0; T < NT; ++T) {
+                    if ((T & s) == 0) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float a = xt[T][v], b = xt[T | s][v];
+                            xt[T][v] = a + b;
+                            xt[T | s][v] = a - b;
+                        }
                     }
                 }
             }
@@ -207,14 +248,7 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
             for (int w = 0; w < NR / 4; ++w) {
                 unsigned packed = 0;
 #pragma unroll
-                for (int pr = 0; pr < 2; ++pr) {
-                    const int s0 = 4 * w + 2 * pr;
-                    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[s0]), __float_as_uint(x[s0 + 1]),
-                                                                    false, false);
-                    const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
-                    fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
-                    fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
-                }
+                for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
                 cd[w / 4][w % 4] = (int)packed;
             }
             p ^= 1;
