@@ -43,9 +43,9 @@ CODEGEN_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
 
 # Kernels that address accumulation registers by number from inline assembly: source file, a
 # substring of the kernel's (mangled) name, first register the compiler must leave alone.
-FIXED_AGPR_KERNELS = [("dhq_fused_wide.hip", "dhq_fused_wide_kernel", 160),
+FIXED_AGPR_KERNELS = [("dhq_fused_wide.hip", "dhq_fused_wide_kernel", 0),
                       ("dhq_float.hip", "dhq_float_kernel", 128)]
-WIDE_FIRST_FIXED_AGPR = 160
+WIDE_FIRST_FIXED_AGPR = 0
 
 
 def _agprs_named(line: str):

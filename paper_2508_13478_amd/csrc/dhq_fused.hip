@@ -16,8 +16,8 @@
 //     the tile's activations are already laid out as an MFMA B operand, H_32 is the A operand;
 //   - log2(NT) butterfly stages over the tile index, i.e. over bits 4.. of R: plain register
 //     add/sub, no lane traffic.
-// After the last stage register s of lane half u holds rotated feature j(s, u) (hm_index
-// below); quantizing register s into byte s % 4 of dword s / 4 makes four consecutive dwords
+// After the last stage register s of lane half u holds rotated feature j(s, u) (hm_index in
+// dhq_fused_common.h); quantizing register s into byte s % 4 of dword s / 4 makes four consecutive dwords
 // exactly the B operand of k block s / 16.  The contraction index of an MFMA can be enumerated
 // in any order as long as both operands agree, so the weights are packed offline with their k
 // positions permuted by j(s, u) and nothing is ever shuffled at run time.
@@ -85,8 +85,6 @@ struct dhq_fused_plan {
 // the butterflies' sums.  Per tile: 8 + 8 packed conversions, 16 mixed-precision subtractions
 // and 4 MFMAs replace 80 add/sub and 8 lane swaps.  The three stages over the tile index stay
 // on the vector ALU.  Afterwards register s of lane half u holds rotated feature hm_index(s, u).
-static inline int hm_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
-
 template <int NT, int KB>
 struct hm_sched {
     static constexpr bool STAGGER = (NT >= 2 && KB >= 2);

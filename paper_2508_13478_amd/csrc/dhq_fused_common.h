@@ -4,13 +4,18 @@
 
 #include "dhq_device.h"
 
-// Rotated feature index held, after the in-register transform, by register s of lane half u.
+// Feature index held by register s of lane half u after an in-register butterfly network whose
+// last stage is the lane swap (the integer un-rotation of the two-sided kernel).
 static inline int rot_index(int s, int u)
 {
     const int r = (s & ~1) | u;  // register the value came from before the lane swap
     const int H = s & 1;         // the lane-half bit of the output index
     return 32 * (r >> 4) + 8 * ((r >> 2) & 3) + 4 * H + (r & 3);
 }
+
+// Rotated feature index held by register s of lane half u when the 32-point factor of the
+// transform runs on the matrix unit (its result arrives in the MFMA accumulator layout).
+static inline int hm_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
 
 // Position of bias / output feature f inside a layer's bias block: [T][g][h][e].
 static inline int bias_slot(int f)
@@ -61,12 +66,16 @@ __device__ __forceinline__ unsigned hm_pack_half2(float a, float b)
 // Splits two activations into binary16 pieces: hi = (a0, a1) rounded toward zero, lo = the
 // remainders a - hi (exact in fp32; v_fma_mix_f32 reads the binary16 half in place) rounded
 // toward zero.  hi + lo carries a to within 2^-21 |a| (2^-24 absolute below 2^-10).
+__device__ __forceinline__ void hm_remainders(float a0, float a1, unsigned hi, float &r0, float &r1)
+{
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
+}
 __device__ __forceinline__ void hm_split_pair(float a0, float a1, unsigned &hi, unsigned &lo)
 {
     hi = hm_pack_half2(a0, a1);
     float r0, r1;
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(a0), "v"(hi));
-    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(a1), "v"(hi));
+    hm_remainders(a0, a1, hi, r0, r1);
     lo = hm_pack_half2(r0, r1);
 }
 

@@ -8,16 +8,15 @@
 //   - one wave per SIMD (4 waves per workgroup, 128 coordinates per pass) so that a wave owns
 //     the whole 512-entry register file; the matrix unit and the vector ALU overlap inside
 //     the wave (every MFMA issues in the shadow of about eight vector instructions);
-//   - the activations of a layer are kept as two halves (rows 0-7 / rows 8-15 of every
-//     32-row tile).  The butterfly stages over the tile index never mix the halves, so the
-//     second half waits in accumulation registers (which the vector ALU cannot compute on,
-//     but which cost one move in and one move out) while the first is transformed and
-//     quantized;
+//   - the transformed activations of a layer (the outputs of the H_32 products on the matrix
+//     unit, see dhq_fused.hip) are written by those MFMAs straight into accumulation
+//     registers, which the vector ALU cannot compute on but which cost one move out; the
+//     stages over the tile index and the quantizer then fetch them a quarter at a time (rows
+//     4q .. 4q+3 of every tile: those stages never mix rows of a tile);
 //   - a 512 x 512 layer is 256 KiB of int8, more than LDS holds: it is streamed in four
 //     chunks of four M tiles (64 KiB of A fragments + their biases) through two LDS buffers,
 //     each chunk copied global -> registers -> LDS in small pieces between the GEMM steps of
-//     the previous one;
-//   - the codes (the MFMA B operand) live in accumulation registers too.
+//     the previous one.
 #include <math.h>
 #include <string.h>
 
@@ -112,15 +111,14 @@ __device__ __forceinline__ void wide_enter_chunk(wide_stream &S, int cc)
 // vmcnt(N), N = number of this wave's loads issued after the one it consumes (loads retire in
 // order; anything else outstanding only makes the wait longer).
 //
-// Register map of the accumulation registers (the kernel caps the compiler at 256 + 160
-// vector registers, so it never touches a160 and up; these are addressed by number in the
-// assembly below and nothing the compiler does can move or copy them):
-//   a0   .. a159  the compiler's: the parked half of the activations, spills
-//   a160 .. a223  the codes of the current layer input (MFMA B operand), dword d of k block kb
-//                 in a[160 + 4 kb + d]
+// Register map of the accumulation registers (the kernel caps the compiler at 256 vector
+// registers, so it never touches an accumulation register; these are addressed by number in
+// the assembly below and nothing the compiler does can move or copy them):
+//   a0   .. a223  the transformed activations of tiles 0 .. 13, tile T in a[16 T .. 16 T + 15]
+//                 (the D operand of its H_32 products); tiles 14 and 15 stay in vector registers
 //   a224 .. a255  eight staging tuples of the weight copy
-#define WIDE_AGPR_COMPILER 160
-#define WIDE_AGPR_CODES 160
+#define WIDE_AGPR_COMPILER 0
+#define WIDE_AGPR_TILES 14
 #define WIDE_AGPR_STAGE 224
 #define WIDE_STAGE 8    // staging tuples = loads in flight per wave
 #define WIDE_SLOTS 17   // 1 KiB blocks per wave and chunk (chunks are at most 65 KiB)
@@ -213,78 +211,58 @@ __device__ __forceinline__ void wide_copy_step(const wide_stream &S)
         wide_copy_step_impl<KB, CHM, PF, NC, G>(S, std::make_integer_sequence<int, NC * WIDE_SLOTS>{});
 }
 
-__device__ __forceinline__ int wide_park(float v)
+// Row v of transformed tile T (< WIDE_AGPR_TILES), fetched from its accumulation register.
+template <int T, int V>
+__device__ __forceinline__ float wide_tile_read()
 {
-    int a;
-    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a) : "v"(v));
-    return a;
-}
-// dword D of the codes (see the register map above)
-template <int D>
-__device__ __forceinline__ void wide_code_write(int v)
-{
-    asm volatile("v_accvgpr_write_b32 a[%1], %0" : : "v"(v), "n"(WIDE_AGPR_CODES + D));
-}
-__device__ __forceinline__ float wide_unpark(int a)
-{
-    float v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
-    return v;
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(16 * T + V));
+    return x;
 }
 
-// The MFMA with its B operand (the codes) read from the fixed accumulation registers, which
-// frees 64 vector registers.  The compiler has no builtin form for that, so it is inline assembly,
-// and the wait states the matrix unit needs before the vector ALU reads its result are kept
-// by construction: a tile's accumulators are first read a whole pipeline step (more than
-// eleven instructions) after the tile's last MFMA was issued, plus an explicit s_nop.
-template <int KBI>
-__device__ __forceinline__ void wide_mfma_first(dhq_v16i &acc, const dhq_v4i &a)
+// H_32 product number K (0: low pieces of block 0, 1: high pieces of block 0, 2 and 3: the same
+// for block 1; small pieces first) of tile T, accumulated in a[16 T .. 16 T + 15].  The
+// compiler has no way to pin an MFMA result to given accumulation registers, so it is inline
+// assembly.  The compiler may have gathered an operand with a vector move just before it and
+// cannot know that an MFMA follows, hence the two wait states in front.  A chain on one
+// accumulator needs none between its links; the first read of the result (wide_tile_read)
+// comes a whole transform phase later.
+template <int T, int K>
+__device__ __forceinline__ void wide_h32_mfma(const dhq_v4i &ha, const dhq_v4i &b)
 {
-    constexpr int R = WIDE_AGPR_CODES + 4 * KBI;
-    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, a[%2:%3], 0" : "=&v"(acc) : "v"(a), "n"(R), "n"(R + 3));
-}
-template <int KBI>
-__device__ __forceinline__ void wide_mfma_next(dhq_v16i &acc, const dhq_v4i &a)
-{
-    constexpr int R = WIDE_AGPR_CODES + 4 * KBI;
-    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, a[%2:%3], %0" : "+v"(acc) : "v"(a), "n"(R), "n"(R + 3));
-}
-
-// N idle issue slots that the accumulators' readers cannot be moved ahead of.
-template <int N>
-__device__ __forceinline__ void wide_mfma_settle(dhq_v16i &acc)
-{
-    static_assert(N == 4 || N == 16, "");
-    if (N == 4)
-        asm volatile("s_nop 3" : "+v"(acc));
+    constexpr int R = 16 * T;
+    if constexpr (K == 0)
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[%2:%3], %0, %1, 0" : : "v"(ha), "v"(b), "n"(R), "n"(R + 15));
     else
-        asm volatile("s_nop 7\n\ts_nop 7" : "+v"(acc));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[%2:%3], %0, %1, a[%2:%3]" : : "v"(ha), "v"(b), "n"(R), "n"(R + 15));
 }
 
 __device__ __forceinline__ float wide_comp(const float4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
-// One layer's GEMM + epilogue + in-tile butterflies, tiles one after the other, as a
-// software pipeline over steps g (every step is its own template instance, so all register
-// indices are compile-time constants):
+// One layer's GEMM + epilogue + the H_32 factor of the transform, tiles one after the other,
+// as a software pipeline over steps g (every step is its own template instance, so all
+// register indices are compile-time constants):
 //   step g                MFMA (tile g / KB, k block g % KB); its A fragment was fetched from
 //                         LDS PF steps earlier; when that prefetch crosses into the next
 //                         chunk of CH tiles the chunk is entered first
 //   hidden layers (KB = 16, one accumulator per step): value e = g - KB is converted, value
 //                         e - 1 gets its multiply-add with the bias, value e - 2 its sine --
 //                         the three dependent instructions of one value sit in three
-//                         different steps; the four butterfly stages of a tile follow, two
-//                         butterflies per step
-//   input layer (KB = 1): step g runs the 32 butterflies of tile g - 1, then drains all 16
-//                         accumulators of tile g
-// After its last butterfly, rows 0-7 of a tile go to xlo and rows 8-15 are parked in xhi.
+//                         different steps; so do the three steps of splitting a finished
+//                         pair of activations into binary16 pieces, and the four H_32
+//                         products of a tile issue one per step once their pieces exist: two
+//                         after the tile's 8th value, two after its 16th
+//   input layer (KB = 1): step g issues the four H_32 products of tile g - 1, then drains all
+//                         16 accumulators of tile g and splits them
 // Biases are read from LDS a few steps before use; those of tile T sit in the bias block
 // of the chunk that is resident while T is drained (see the host-side packing).
 template <int NT, int KB, int NCD>
 struct wide_gemm_ctx {
     static constexpr int PF = (NT * KB >= 4) ? 4 : (NT * KB >= 2 ? 2 : 1);
     wide_stream &S;
-    float (&xlo)[NT * 8];
-    int (&xhi)[NT * 8];
+    const dhq_v4i (&cd)[NCD];                    // codes of the layer input: the B operands
+    dhq_v16f (&xtop)[NT - WIDE_AGPR_TILES];      // transformed tiles that stay in vector registers
+    const dhq_v4i (&hA)[2];                      // H_32 as an MFMA A operand, two k blocks
     const unsigned char *bufs[2];
     int cc;
     float c1;
@@ -293,10 +271,13 @@ struct wide_gemm_ctx {
     float4 bq[2];
     float4 bq0[4];  // input layer: the 16 biases of the tile drained next
     dhq_v16i acc[2];
-    float tv[2][16];
+    unsigned hp[2][8], lp[2][8];  // binary16 pieces of the tile being drained and of the one before
     float ex, ey;
-    __device__ __forceinline__ wide_gemm_ctx(wide_stream &S_, float (&xlo_)[NT * 8], int (&xhi_)[NT * 8])
-        : S(S_), xlo(xlo_), xhi(xhi_)
+    float ar[4];  // the last four activations
+    float er[2];  // remainders of the pair being split
+    __device__ __forceinline__ wide_gemm_ctx(wide_stream &S_, const dhq_v4i (&cd_)[NCD],
+                                             dhq_v16f (&xtop_)[NT - WIDE_AGPR_TILES], const dhq_v4i (&hA_)[2])
+        : S(S_), cd(cd_), xtop(xtop_), hA(hA_)
     {
     }
 };
@@ -308,6 +289,29 @@ __device__ __forceinline__ void wide_load_bias0(wide_gemm_ctx<NT, KB, NCD> &C, i
 #pragma unroll
     for (int gg = 0; gg < 4; ++gg)
         C.bq0[gg] = *reinterpret_cast<const float4 *>(C.bufs[0] + CHM * 1024 + T * 128 + gg * 32 + C.h * 16);
+}
+
+// H_32 product K of tile T from the pieces in hp / lp [T & 1].
+template <int NT, int KB, int NCD, int T, int K>
+__device__ __forceinline__ void wide_h32_step(wide_gemm_ctx<NT, KB, NCD> &C)
+{
+    constexpr int blk = K >> 1;
+    dhq_v4i b;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) b[d] = (int)((K & 1) ? C.hp[T & 1][4 * blk + d] : C.lp[T & 1][4 * blk + d]);
+    if constexpr (T < WIDE_AGPR_TILES) {
+        wide_h32_mfma<T, K>(C.hA[blk], b);
+    } else {
+        dhq_v16f d;
+        if constexpr (K == 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[v] = 0.f;
+        } else {
+            d = C.xtop[T - WIDE_AGPR_TILES];
+        }
+        C.xtop[T - WIDE_AGPR_TILES] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+            __builtin_bit_cast(dhq_v8h, C.hA[blk]), __builtin_bit_cast(dhq_v8h, b), d, 0, 0, 0);
+    }
 }
 
 template <int NT, int KB, int CH, int NCD, int G>
@@ -330,54 +334,66 @@ __device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
     if constexpr (G < NM) {
         constexpr int T = G / KB, kb = G % KB;
         constexpr int ab = (KB == 1) ? 0 : (T & 1);
-        if constexpr (kb == 0)
-            wide_mfma_first<kb>(C.acc[ab], C.fr[G % (PF + 1)]);
-        else
-            wide_mfma_next<kb>(C.acc[ab], C.fr[G % (PF + 1)]);
-    }
-    // the MFMA stays ahead of the step's vector work (this is what keeps the distance between
-    // a tile's last MFMA and the first read of its accumulators)
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (KB == 1) {
-        // input layer: one MFMA per tile; the previous tile's butterflies come first, which
-        // also gives this tile's MFMA time to finish before its accumulators are read
-        if constexpr (G >= 1 && G <= NT) {
-            constexpr int Tb = G - 1;
+        if constexpr (kb == 0) {
 #pragma unroll
-            for (int b = 0; b < 32; ++b) {
-                const int st = b >> 3, q = b & 7;
-                const int r = ((q >> st) << (st + 1)) | (q & ((1 << st) - 1));
-                const float u = C.tv[0][r], w = C.tv[0][r | (1 << st)];
-                C.tv[0][r] = u + w;
-                C.tv[0][r | (1 << st)] = u - w;
-            }
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                C.xlo[8 * Tb + r] = C.tv[0][r];
-                C.xhi[8 * Tb + r] = wide_park(C.tv[0][8 + r]);
-            }
+            for (int v = 0; v < 16; ++v) C.acc[ab][v] = 0;
         }
+        C.acc[ab] = __builtin_amdgcn_mfma_i32_32x32x32_i8(C.fr[G % (PF + 1)], C.cd[kb], C.acc[ab], 0, 0, 0);
+    }
+    if constexpr (KB == 1) {
+        // input layer: the previous tile's H_32 products, then this tile's drain
+        if constexpr (G >= 1 && G <= NT) {
+            wide_h32_step<NT, KB, NCD, G - 1, 0>(C);
+            wide_h32_step<NT, KB, NCD, G - 1, 1>(C);
+            wide_h32_step<NT, KB, NCD, G - 1, 2>(C);
+            wide_h32_step<NT, KB, NCD, G - 1, 3>(C);
+        }
+        // the matrix unit's work stays ahead of the step's vector work
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (G < NT) {
-            if constexpr (G == 0) wide_mfma_settle<16>(C.acc[0]);
             float x[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) x[v] = (float)C.acc[0][v];
 #pragma unroll
             for (int v = 0; v < 16; ++v) x[v] = __builtin_fmaf(x[v], C.c1, wide_comp(C.bq0[v >> 2], v & 3));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) C.tv[0][v] = dhq_sin_rev(x[v]);
+            for (int v = 0; v < 16; ++v) x[v] = dhq_sin_rev(x[v]);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) hm_split_pair(x[2 * d], x[2 * d + 1], C.hp[G & 1][d], C.lp[G & 1][d]);
         }
         if constexpr (G + 1 < NT) wide_load_bias0<NT, KB, NCD, CHM>(C, G + 1);  // for the next step
     } else {
         static_assert(KB == 1 || KB == 16, "one accumulator per step");
         constexpr int e0 = G - KB, e1 = e0 - 1, e2 = e0 - 2;
-        if constexpr (e2 >= 0 && e2 < NE) C.tv[(e2 / 16) & 1][e2 % 16] = dhq_sin_rev(C.ey);
-        if constexpr (e1 >= 0 && e1 < NE) C.ey = __builtin_fmaf(C.ex, C.c1, wide_comp(C.bq[(e1 / 4) & 1], e1 % 4));
-        if constexpr (e0 >= 0 && e0 < NE) {
-            if constexpr (e0 % 16 == 0) wide_mfma_settle<4>(C.acc[(e0 / 16) & 1]);
-            C.ex = (float)C.acc[(e0 / 16) & 1][e0 % 16];
+        // A lone wave pays for every instruction that needs the result of the one before it, so
+        // the chain convert -> multiply-add -> sine -> pack high pieces -> two remainders -> pack low
+        // pieces of a value is spread over six steps: value e2 gets its sine here, the pair finished
+        // one step ago its high pieces, the pair before its remainders or its low pieces.
+        // H_32 products: the pieces of block 0 (values 0..7) of tile t are complete after the step
+        // with e2 = 16 t + 10, those of block 1 after e2 = 16 t + 18.
+        constexpr int hq = e2 - 11;  // 16 t + {0, 1, 8, 9} -> product 0, 1, 2, 3 of tile t
+        if constexpr (hq >= 0 && hq / 16 < NT) {
+            constexpr int Th = hq / 16, r = hq % 16;
+            if constexpr (r == 0) wide_h32_step<NT, KB, NCD, Th, 0>(C);
+            if constexpr (r == 1) wide_h32_step<NT, KB, NCD, Th, 1>(C);
+            if constexpr (r == 8) wide_h32_step<NT, KB, NCD, Th, 2>(C);
+            if constexpr (r == 9) wide_h32_step<NT, KB, NCD, Th, 3>(C);
         }
+        // the matrix unit's work stays ahead of the step's vector work
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr ((e2 & 1) == 0) {
+            constexpr int pl = (e2 - 4) / 2, ph = (e2 - 2) / 2;  // pairs whose low / high pieces are packed now
+            if constexpr (e2 >= 4 && pl < NE / 2) C.lp[(pl / 8) & 1][pl % 8] = hm_pack_half2(C.er[0], C.er[1]);
+            if constexpr (e2 >= 2 && ph < NE / 2)
+                C.hp[(ph / 8) & 1][ph % 8] = hm_pack_half2(C.ar[(e2 - 2) & 3], C.ar[(e2 - 1) & 3]);
+        } else {
+            constexpr int pm = (e2 - 3) / 2;  // pair whose remainders are taken now
+            if constexpr (e2 >= 3 && pm < NE / 2)
+                hm_remainders(C.ar[(e2 - 3) & 3], C.ar[(e2 - 2) & 3], C.hp[(pm / 8) & 1][pm % 8], C.er[0], C.er[1]);
+        }
+        if constexpr (e2 >= 0 && e2 < NE) C.ar[e2 & 3] = dhq_sin_rev(C.ey);
+        if constexpr (e1 >= 0 && e1 < NE) C.ey = __builtin_fmaf(C.ex, C.c1, wide_comp(C.bq[(e1 / 4) & 1], e1 % 4));
+        if constexpr (e0 >= 0 && e0 < NE) C.ex = (float)C.acc[(e0 / 16) & 1][e0 % 16];
         if constexpr (e0 + 4 >= 0 && (e0 + 4) % 4 == 0 && e0 + 4 < NE) {
             // biases of values e0+4 .. e0+7: tile Tg, rows group gg; chunk cT is resident while Tg is drained
             constexpr int ge = (e0 + 4) / 4, Tg = ge / 4, gg = ge % 4;
@@ -385,30 +401,6 @@ __device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
             constexpr int tg = Tg - (cT * CH - 1);
             C.bq[ge & 1] =
                 *reinterpret_cast<const float4 *>(C.bufs[cT & 1] + CHM * 1024 + tg * 128 + gg * 32 + C.h * 16);
-        }
-    }
-    if constexpr (KB > 1) {
-        constexpr int SK = 2;
-        constexpr int BPS = 32 / KB;
-        constexpr int gb = G - 2 * KB - SK;
-        if constexpr (gb >= 0 && gb < NM) {
-            constexpr int Tb = gb / KB, pos = gb % KB;
-#pragma unroll
-            for (int j = 0; j < BPS; ++j) {
-                const int b = pos * BPS + j;
-                const int st = b >> 3, q = b & 7;
-                const int r = ((q >> st) << (st + 1)) | (q & ((1 << st) - 1));
-                const float u = C.tv[Tb & 1][r], w = C.tv[Tb & 1][r | (1 << st)];
-                C.tv[Tb & 1][r] = u + w;
-                C.tv[Tb & 1][r | (1 << st)] = u - w;
-            }
-            if constexpr (pos == KB - 1) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    C.xlo[8 * Tb + r] = C.tv[Tb & 1][r];
-                    C.xhi[8 * Tb + r] = wide_park(C.tv[Tb & 1][8 + r]);
-                }
-            }
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -427,14 +419,15 @@ __device__ __forceinline__ void wide_copy_prologue(const wide_stream &S, std::in
 
 // cc is the running chunk count on entry and is advanced by the chunks consumed.
 template <int NT, int KB, int CH, int NCD>
-__device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1, float (&xlo)[NT * 8], int (&xhi)[NT * 8],
-                                               int h)
+__device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1, const dhq_v4i (&cd)[NCD],
+                                               dhq_v16f (&xtop)[NT - WIDE_AGPR_TILES], const dhq_v4i (&hA)[2], int h)
 {
     constexpr int NM = NT * KB;
     constexpr int PF = wide_gemm_ctx<NT, KB, NCD>::PF;
-    constexpr int NSTEPS = (KB == 1) ? NT + 1 : NM + 2 * KB + 2;
+    // last step with work: the fourth H_32 product of the last tile (e2 - 11 = 16 (NT - 1) + 9)
+    constexpr int NSTEPS = (KB == 1) ? NT + 1 : 16 * (NT - 1) + 9 + 11 + 2 + KB + 1;
     static_assert(CH * KB >= PF, "a chunk must be longer than the prefetch distance");
-    wide_gemm_ctx<NT, KB, NCD> C(S, xlo, xhi);
+    wide_gemm_ctx<NT, KB, NCD> C(S, cd, xtop, hA);
     C.cc = cc;
     C.c1 = c1;
     C.h = h;
@@ -451,38 +444,31 @@ __device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1
     cc += NT / CH;
 }
 
-// Remaining transform stages and the quantizer on one half (128 values, index 8 T + r):
-// the stages over the tile index, then per group of four registers the stage over the
-// lane-half bit fused with the quantizer.  The codes of rows r..r+3 of tile T become dword
-// DW0 + r / 4 of k block T, kept in an accumulation register (the MFMA reads them there).
-template <int DW0, int W>
-__device__ __forceinline__ void wide_quant_group(const float *xv, float inv, int qlo, int qhi)
+// The stages of the transform over the tile index and the quantizer, on rows 4 Q .. 4 Q + 3 of
+// every tile (64 values, index 4 T + b): fetched from the accumulation registers (tiles 14 and 15
+// from their vector registers), NT / 2 x log2(NT) butterflies per row, and per tile the four codes
+// of these rows: dword Q of k block T of the next layer's B operand.
+template <int NT, int Q, int... Ts>
+__device__ __forceinline__ void wide_fetch_rows(float (&xv)[NT * 4], std::integer_sequence<int, Ts...>)
 {
-    unsigned packed = 0;
-#pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {
-        const int s0 = 4 * W + 2 * pr;
-        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(xv[s0]), __float_as_uint(xv[s0 + 1]), false, false);
-        const float r0 = __uint_as_float(r[0]), r1 = __uint_as_float(r[1]);
-        fused_quant_byte(packed, r0 + r1, inv, qlo, qhi, 2 * pr);
-        fused_quant_byte(packed, r0 - r1, inv, qlo, qhi, 2 * pr + 1);
-    }
-    wide_code_write<(W / 2) * 4 + DW0 + (W & 1)>((int)packed);
+    ((xv[4 * Ts + 0] = wide_tile_read<Ts, 4 * Q + 0>(), xv[4 * Ts + 1] = wide_tile_read<Ts, 4 * Q + 1>(),
+      xv[4 * Ts + 2] = wide_tile_read<Ts, 4 * Q + 2>(), xv[4 * Ts + 3] = wide_tile_read<Ts, 4 * Q + 3>()),
+     ...);
 }
-template <int DW0, int NV, int... Ws>
-__device__ __forceinline__ void wide_quant_groups(const float (&xv)[NV], float inv, int qlo, int qhi,
-                                                  std::integer_sequence<int, Ws...>)
+template <int NT, int NCD, int Q>
+__device__ __forceinline__ void wide_transform_quant(const dhq_v16f (&xtop)[NT - WIDE_AGPR_TILES], dhq_v4i (&cd)[NCD],
+                                                     float inv, int qlo, int qhi)
 {
-    (wide_quant_group<DW0, Ws>(xv, inv, qlo, qhi), ...);
-}
-template <int NT, int DW0>
-__device__ __forceinline__ void wide_transform_quant(float (&xv)[NT * 8], float inv, int qlo, int qhi)
-{
-    constexpr int NV = NT * 8;
+    float xv[NT * 4];
+    wide_fetch_rows<NT, Q>(xv, std::make_integer_sequence<int, WIDE_AGPR_TILES>{});
 #pragma unroll
-    for (int s = 8; s < NV; s <<= 1) {
+    for (int T = WIDE_AGPR_TILES; T < NT; ++T)
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
+        for (int b = 0; b < 4; ++b) xv[4 * T + b] = xtop[T - WIDE_AGPR_TILES][4 * Q + b];
+#pragma unroll
+    for (int s = 4; s < NT * 4; s <<= 1) {
+#pragma unroll
+        for (int i = 0; i < NT * 4; ++i) {
             if ((i & s) == 0) {
                 const float a = xv[i], b = xv[i | s];
                 xv[i] = a + b;
@@ -490,13 +476,13 @@ __device__ __forceinline__ void wide_transform_quant(float (&xv)[NT * 8], float 
             }
         }
     }
-    wide_quant_groups<DW0, NV>(xv, inv, qlo, qhi, std::make_integer_sequence<int, NV / 4>{});
-}
-
-template <int NKB, int... Ks>
-__device__ __forceinline__ void wide_out_mfmas(dhq_v16i &acc, const dhq_v4i *wA, int lane, std::integer_sequence<int, Ks...>)
-{
-    ((Ks == 0 ? wide_mfma_first<Ks>(acc, wA[Ks * 64 + lane]) : wide_mfma_next<Ks>(acc, wA[Ks * 64 + lane])), ...);
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+        unsigned packed = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xv[4 * T + b], inv, qlo, qhi, b);
+        cd[T][Q] = (int)packed;
+    }
 }
 
 template <int NF>
@@ -534,7 +520,25 @@ void dhq_fused_wide_kernel(const wide_args A)
 
     // the registers addressed by number count towards the kernel's register allocation
     asm volatile("" ::: "a255");
-    static_assert(WIDE_AGPR_CODES + 4 * NKB <= WIDE_AGPR_STAGE && WIDE_AGPR_STAGE + 4 * WIDE_STAGE <= 256, "register map");
+    static_assert(16 * WIDE_AGPR_TILES <= WIDE_AGPR_STAGE && WIDE_AGPR_STAGE + 4 * WIDE_STAGE <= 256 && WIDE_AGPR_TILES < NT,
+                  "register map");
+
+    // A operand of the H_32 products: this lane supplies row c of H_32 at the eight contraction
+    // slots 8 h + j of block kk, which stand for tile row 8 (v / 4) + 4 h + v % 4 with v = 8 kk + j
+    // (the row lane half h holds in accumulator v), as binary16 +-1.
+    dhq_v4i hA[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int v = 8 * kk + 2 * d;
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
+        }
+    }
+    dhq_v4i cd[NKB];  // activation codes: the B operands of the next GEMM
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
 
     for (int it = 0; it < my_tiles; ++it) {
         const int64_t tile = (int64_t)blockIdx.x + (int64_t)it * gridDim.x;
@@ -562,23 +566,21 @@ void dhq_fused_wide_kernel(const wide_args A)
             const float inv = A.inv_in[0];
             // only k positions 0..3 of the input layer's fragments are non-zero, so whatever the
             // other code dwords still hold from the previous pass is multiplied by zero
-            wide_code_write<0>((int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
-                                              dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax)));
+            cd[0][0] = (int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
+                                      dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
         }
 
-        float xlo[NT * 8];
-        int xhi[NT * 8];
-        wide_gemm_sine<NT, 1, NT, NKB>(S, cc, A.c1[0], xlo, xhi, h);
+        dhq_v16f xtop[NT - WIDE_AGPR_TILES];
+        wide_gemm_sine<NT, 1, NT, NKB>(S, cc, A.c1[0], cd, xtop, hA, h);
         for (int l = 1;; ++l) {
-            // transform + quantize the output of layer l-1 (first rows 0-7 of every tile, then
-            // the parked rows 8-15), which is the input of layer l
+            // finish the transform of the output of layer l-1 and quantize it: the input of layer l
             const float inv = A.inv_in[l];
-            wide_transform_quant<NT, 0>(xlo, inv, qlo, qhi);
-#pragma unroll
-            for (int i = 0; i < NT * 8; ++i) xlo[i] = wide_unpark(xhi[i]);
-            wide_transform_quant<NT, 2>(xlo, inv, qlo, qhi);
+            wide_transform_quant<NT, NKB, 0>(xtop, cd, inv, qlo, qhi);
+            wide_transform_quant<NT, NKB, 1>(xtop, cd, inv, qlo, qhi);
+            wide_transform_quant<NT, NKB, 2>(xtop, cd, inv, qlo, qhi);
+            wide_transform_quant<NT, NKB, 3>(xtop, cd, inv, qlo, qhi);
             if (l == L - 1) break;
-            wide_gemm_sine<NT, NKB, WIDE_CH, NKB>(S, cc, A.c1[l], xlo, xhi, h);
+            wide_gemm_sine<NT, NKB, WIDE_CH, NKB>(S, cc, A.c1[l], cd, xtop, hA, h);
         }
 
         // output layer: one zero-padded M tile, no sine; meanwhile the next pass's first chunk
@@ -591,13 +593,16 @@ void dhq_fused_wide_kernel(const wide_args A)
             wide_copy_load<0, false>(S); wide_copy_load<1, false>(S); wide_copy_load<2, false>(S); wide_copy_load<3, false>(S);
             wide_copy_load<4, false>(S);
             dhq_v16i acc;
-            wide_out_mfmas<NKB>(acc, wA, lane, std::make_integer_sequence<int, NKB>{});
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wA[kb * 64 + lane], cd[kb], acc, 0, 0, 0);
             float bias[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) bias[v] = wB[((v >> 2) * 2 + h) * 4 + (v & 3)];
             wide_copy_store<0, false, 4>(S); wide_copy_store<1, false, 3>(S); wide_copy_store<2, false, 2>(S);
             wide_copy_store<3, false, 1>(S); wide_copy_store<4, false, 0>(S);
-            wide_mfma_settle<16>(acc);
             const float c1 = A.c1[L - 1];
             if (valid) {
 #pragma unroll
@@ -666,7 +671,7 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
                                 if (l == 0) {
                                     if (u == 0 && jj < Ly.Kp) val = wq[(size_t)row * Ly.Kp + jj];
                                 } else {
-                                    val = wq[(size_t)row * Ly.Kp + rot_index(16 * kb + jj, u)];
+                                    val = wq[(size_t)row * Ly.Kp + hm_index(16 * kb + jj, u)];
                                 }
                             }
                             frag[((size_t)(tl * Kb + kb) * 64 + ln) * 16 + jj] = val;

@@ -81,9 +81,9 @@ def test_wide_register_map_check_catches_violations():
     from paper_2508_13478_amd import build as b
     ok = "\n".join([
         "_Z21dhq_fused_wide_kernelILi512EEv9wide_args: ; @kernel",
-        "\tv_accvgpr_write_b32 a127, v3",
+        "\tv_mov_b32_e32 v5, v3",
         "\t;;#ASMSTART",
-        "\tv_mfma_i32_32x32x32_i8 v[0:15], v[16:19], a[0xa0:0xa3], 0",
+        "\tv_mfma_f32_32x32x16_f16 a[0x10:0x1f], v[16:19], v[20:23], 0",
         "\tglobal_load_dwordx4 a[224:227], v1, s[2:3]",
         "\t;;#ASMEND",
         "\tv_add_f32_e32 v1, v2, v3 ; a200 in a comment does not count",
@@ -94,7 +94,7 @@ def test_wide_register_map_check_catches_violations():
         "\t.end_amdhsa_kernel",
     ])
     b.check_wide_register_map(ok)
-    for planted in ("\tv_accvgpr_read_b32 v5, a160", "\tds_write_b128 v1, a[156:163]", "\tscratch_store_dword off, a[0xff], off"):
+    for planted in ("\tv_accvgpr_read_b32 v5, a0", "\tds_write_b128 v1, a[156:163]", "\tscratch_store_dword off, a[0xff], off"):
         bad = ok.replace("\tv_add_f32_e32", planted + "\n\tv_add_f32_e32")
         with pytest.raises(RuntimeError):
             b.check_wide_register_map(bad)
@@ -104,6 +104,7 @@ def test_wide_register_map_check_catches_violations():
         b.check_wide_register_map("nothing here")
     # the float kernels keep their activations in a128 and up; another function's registers do not matter
     flt = ok.replace("dhq_fused_wide_kernelILi512EEv9wide_args", "dhq_float_kernelILi256EEv10float_args").replace("_Z21", "_Z16")
+    flt = flt.replace("\tv_mov_b32_e32 v5, v3", "\tv_accvgpr_write_b32 a127, v3")
     assert b.check_fixed_agprs(flt, "dhq_float_kernel", 128) == 1
     with pytest.raises(RuntimeError):
         b.check_fixed_agprs(flt.replace("a127", "a128"), "dhq_float_kernel", 128)
