@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "1c51bec2e2191c14243e2cedf525871ffb37d181b976d8a4e8dc2d32a4ce4c2f"
-TRAFFIC_BYTES = {"C2": (2524.4 + 768.0) * 1024, "C5": (44555.8 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "22a8d52def20f706382c1a0b3f1aa3729c4ee18e34abd9f5517cdd7d891ad708"
+TRAFFIC_BYTES = {"C2": (2524.5 + 768.0) * 1024, "C5": (44537.9 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -200,15 +200,14 @@ def main() -> int:
     }
     # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
     # sine layer the fused kernels issue convert, fma, sine, the transform, fma, max, min.  The
-    # transform is log2(n) add/sub and half a lane swap at width 512; the kernels for widths <= 256
-    # give the 32-row factor to the matrix unit (two vector instructions to split an activation
-    # into binary16 pieces) and keep log2(n / 32) add/sub.
+    # transform: the fused kernels give its 32-row factor to the matrix unit (two vector
+    # instructions to split an activation into binary16 pieces) and keep log2(n / 32) add/sub
+    # (width 512: plus one move out of the accumulation registers).
     # A SIMD issues one wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4
     # per second.
     import math
     nf = wl.dims[1]
-    on_matrix_unit = fused and nf <= 256
-    per_feature = 3 + (2 + math.log2(nf / 32) if on_matrix_unit else math.log2(nf) + 0.5) + 3
+    per_feature = 3 + 2 + math.log2(nf / 32) + (1 if nf == 512 else 0) + 3
     if two_sided:
         per_feature += math.log2(nf) + 0.5   # the integer un-rotation: log2(n) add/sub and half a lane swap
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n
