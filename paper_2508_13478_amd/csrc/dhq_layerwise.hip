@@ -18,54 +18,125 @@
 #include "dhq_internal.h"
 
 // ------------------------------------------------------------------ rotation + quantizer
-// Row-parallel transform.  A row of KP values is spread over LPR lanes holding EPL
-// consecutive values each; butterflies over the low index bits stay inside a lane, the
-// others exchange through wavefront shuffles.  The transform runs un-normalised
-// (entries of H are +-1); 1/sqrt(KP) is folded into `inv`.
+// Row-parallel transform.  A row of KP values is spread over LPR lanes holding EPL values
+// each; butterflies over the index bits held inside a lane are plain add/sub, the others
+// exchange between lanes.  The transform runs un-normalised (entries of H are +-1);
+// 1/sqrt(KP) is folded into `inv`.
+//   KP >= 64: 16 lanes per row (one DPP row), lane t holds values 64 j + 4 t + e (e = 0..3,
+//             j = 0..KP/64-1): every 16-byte load of a row's 16 lanes covers 256 contiguous
+//             bytes, and the four stages over t run as data-parallel-primitive moves (quad
+//             permutes for t ^ 1 and t ^ 2, two bank-masked row shifts for t ^ 4, a row
+//             rotation for t ^ 8) instead of going through the LDS crossbar;
+//   KP <  64: EPL = min(4, KP) consecutive values per lane, wavefront shuffles between lanes.
 template <int KP>
 struct wht_shape {
-    static constexpr int EPL = KP >= 256 ? KP / 64 : (KP >= 4 ? 4 : KP);
+    static constexpr bool ROW16 = KP >= 64;
+    static constexpr int EPL = ROW16 ? KP / 16 : (KP >= 4 ? 4 : KP);
     static constexpr int LPR = KP / EPL;
+    // index within the row of value i of lane t; values 4 g .. 4 g + 3 of a lane are consecutive
+    static __device__ __forceinline__ constexpr int index(int t, int i)
+    {
+        return ROW16 ? 64 * (i / 4) + 4 * t + (i % 4) : t * EPL + i;
+    }
 };
 
-// Loads this lane's EPL values of one row (zero beyond K, zero for a dead row) and runs the
-// butterflies: over the index bits held inside the lane, then over the bits that select the lane.
-template <int KP>
-__device__ __forceinline__ void wht_row(const float *__restrict__ in, int64_t row, int t, bool live, int K,
-                                        float (&v)[wht_shape<KP>::EPL])
+// Value of lane (t ^ M) of the same 16-lane row, M = 1, 2, 4, 8.
+template <int M>
+__device__ __forceinline__ int wht_row16_xor(int x)
+{
+    static_assert(M == 1 || M == 2 || M == 4 || M == 8, "");
+    if constexpr (M == 1) return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);   // quad_perm:[1,0,3,2]
+    if constexpr (M == 2) return __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true);   // quad_perm:[2,3,0,1]
+    if constexpr (M == 8) return __builtin_amdgcn_mov_dpp(x, 0x128, 0xF, 0xF, true);  // row_ror:8
+    // lanes 0-3 and 8-11 of a row read four lanes up (row_shl:4), lanes 4-7 and 12-15 four lanes down (row_shr:4)
+    const int up = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xF, 0x5, false);
+    return __builtin_amdgcn_update_dpp(up, x, 0x114, 0xF, 0xA, false);
+}
+
+// One butterfly stage over lane bit M: the lane with the bit clear keeps v + p, the other p - v
+// (p = the partner lane's value).  Float: p + (v with its sign flipped in the upper lane), which
+// lets the partner's value come in through the add's own data-parallel-primitive operand.
+__device__ __forceinline__ int wht_add(int a, int b) { return (int)((unsigned)a + (unsigned)b); }
+__device__ __forceinline__ int wht_sub(int a, int b) { return (int)((unsigned)a - (unsigned)b); }
+__device__ __forceinline__ float wht_add(float a, float b) { return a + b; }
+__device__ __forceinline__ float wht_sub(float a, float b) { return a - b; }
+
+template <int KP, int M>
+__device__ __forceinline__ void wht_lane_stage(float (&v)[wht_shape<KP>::EPL], int t)
+{
+    constexpr int EPL = wht_shape<KP>::EPL;
+    if constexpr (wht_shape<KP>::ROW16) {
+        const int flip = (t & M) ? (int)0x80000000 : 0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const float p = __int_as_float(wht_row16_xor<M>(__float_as_int(v[e])));
+            v[e] = p + __int_as_float(__float_as_int(v[e]) ^ flip);
+        }
+    } else {
+        const bool upper = (t & M) != 0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const float p = __shfl_xor(v[e], M, 64);
+            v[e] = upper ? p - v[e] : v[e] + p;
+        }
+    }
+}
+template <int KP, int M>
+__device__ __forceinline__ void wht_lane_stage(int (&v)[wht_shape<KP>::EPL], int t)
+{
+    constexpr int EPL = wht_shape<KP>::EPL;
+    const bool upper = (t & M) != 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int p = wht_shape<KP>::ROW16 ? wht_row16_xor<M>(v[e]) : __shfl_xor(v[e], M, 64);
+        v[e] = upper ? wht_sub(p, v[e]) : wht_add(v[e], p);
+    }
+}
+
+template <int KP, typename T>
+__device__ __forceinline__ void wht_butterflies(T (&v)[wht_shape<KP>::EPL], int t)
 {
     constexpr int EPL = wht_shape<KP>::EPL;
     constexpr int LPR = wht_shape<KP>::LPR;
-    if (live && K == KP && EPL == 4) {
-        const float4 x = *reinterpret_cast<const float4 *>(in + row * KP + t * 4);
-        v[0] = x.x; v[1 % EPL] = x.y; v[2 % EPL] = x.z; v[3 % EPL] = x.w;
-    } else {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            const int idx = t * EPL + e;
-            v[e] = (live && idx < K) ? in[row * K + idx] : 0.0f;
-        }
-    }
 #pragma unroll
     for (int h = 1; h < EPL; h *= 2) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
             if ((e & h) == 0) {
-                const float a = v[e], b = v[e | h];
-                v[e] = a + b;
-                v[e | h] = a - b;
+                const T a = v[e], b = v[e | h];
+                v[e] = wht_add(a, b);
+                v[e | h] = wht_sub(a, b);
             }
         }
     }
+    if constexpr (LPR > 1) wht_lane_stage<KP, 1>(v, t);
+    if constexpr (LPR > 2) wht_lane_stage<KP, 2>(v, t);
+    if constexpr (LPR > 4) wht_lane_stage<KP, 4>(v, t);
+    if constexpr (LPR > 8) wht_lane_stage<KP, 8>(v, t);
+    static_assert(LPR <= 16, "a row spans at most 16 lanes");
+}
+
+// Loads this lane's EPL values of one row (zero beyond K, zero for a dead row) and transforms the row.
+template <int KP>
+__device__ __forceinline__ void wht_row(const float *__restrict__ in, int64_t row, int t, bool live, int K,
+                                        float (&v)[wht_shape<KP>::EPL])
+{
+    using S = wht_shape<KP>;
+    constexpr int EPL = S::EPL;
+    if (live && K == KP && EPL >= 4) {
 #pragma unroll
-    for (int m = 1; m < LPR; m *= 2) {
-        const bool upper = (t & m) != 0;
+        for (int g = 0; g < EPL / 4; ++g) {
+            const float4 x = *reinterpret_cast<const float4 *>(in + row * KP + S::index(t, 4 * g));
+            v[(4 * g) % EPL] = x.x; v[(4 * g + 1) % EPL] = x.y; v[(4 * g + 2) % EPL] = x.z; v[(4 * g + 3) % EPL] = x.w;
+        }
+    } else {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            const float p = __shfl_xor(v[e], m, 64);
-            v[e] = upper ? p - v[e] : v[e] + p;
+            const int idx = S::index(t, e);
+            v[e] = (live && idx < K) ? in[row * K + idx] : 0.0f;
         }
     }
+    wht_butterflies<KP>(v, t);
 }
 
 template <int KP>
@@ -84,17 +155,17 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
     float v[EPL];
     wht_row<KP>(in, row, t, live, K, v);
     if (!live) return;
-    int8_t *dst = codes + row * KP + t * EPL;
     if constexpr (EPL >= 4) {
 #pragma unroll
         for (int e = 0; e < EPL; e += 4) {
             const unsigned w = dhq_pack4(dhq_quant_bits(v[e], inv, qmax), dhq_quant_bits(v[e + 1], inv, qmax),
                                          dhq_quant_bits(v[e + 2], inv, qmax), dhq_quant_bits(v[e + 3], inv, qmax));
-            *reinterpret_cast<unsigned *>(dst + e) = w;
+            *reinterpret_cast<unsigned *>(codes + row * KP + wht_shape<KP>::index(t, e)) = w;
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) dst[e] = (int8_t)(dhq_quant_bits(v[e], inv, qmax) & 0xff);
+        for (int e = 0; e < EPL; ++e)
+            codes[row * KP + wht_shape<KP>::index(t, e)] = (int8_t)(dhq_quant_bits(v[e], inv, qmax) & 0xff);
     }
 }
 
@@ -467,7 +538,7 @@ hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, c
 // z = acc' H_MP over the output features of every row, in int32 (H has entries +-1, and
 // H H = MP I, so this undoes the output-side rotation of the weights up to the factor that
 // c1 carries), then y = z c1 + bias (and the sine) for the first M features.  Same lane
-// layout as the forward transform: a row is spread over LPR lanes of EPL values.
+// layout and the same butterfly network as the forward transform (wht_shape, wht_butterflies).
 // Intermediate sums may wrap; the host has checked that the final ones fit.
 template <int MP>
 __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *__restrict__ acc, int64_t n, int M,
@@ -483,40 +554,44 @@ __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *_
     const int64_t row = gtid / LPR;
     const int t = (int)(gtid % LPR);
     const bool live = row < n;
+    using S = wht_shape<MP>;
     int v[EPL];
-    if (live && EPL == 4) {
-        const int4 x = *reinterpret_cast<const int4 *>(acc + row * MP + t * 4);
-        v[0] = x.x; v[1 % EPL] = x.y; v[2 % EPL] = x.z; v[3 % EPL] = x.w;
+    if (live && EPL >= 4) {
+#pragma unroll
+        for (int g = 0; g < EPL / 4; ++g) {
+            const int4 x = *reinterpret_cast<const int4 *>(acc + row * MP + S::index(t, 4 * g));
+            v[(4 * g) % EPL] = x.x; v[(4 * g + 1) % EPL] = x.y; v[(4 * g + 2) % EPL] = x.z; v[(4 * g + 3) % EPL] = x.w;
+        }
     } else {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) v[e] = live ? acc[row * MP + t * EPL + e] : 0;
+        for (int e = 0; e < EPL; ++e) v[e] = live ? acc[row * MP + S::index(t, e)] : 0;
     }
+    wht_butterflies<MP>(v, t);
+    if (!live) return;
+    if constexpr (EPL >= 4) {
 #pragma unroll
-    for (int h = 1; h < EPL; h *= 2) {
+        for (int g = 0; g < EPL / 4; ++g) {
+            const int f = S::index(t, 4 * g);  // first of four consecutive features
+            if (z_out) *reinterpret_cast<int4 *>(z_out + row * MP + f) = make_int4(v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]);
+            if (act_out && f < M) {
+                if ((M & 3) == 0) {
+                    *reinterpret_cast<float4 *>(act_out + row * M + f) =
+                        make_float4(dhq_epilogue(v[4 * g], c1, bias[f], sine != 0), dhq_epilogue(v[4 * g + 1], c1, bias[f + 1], sine != 0),
+                                    dhq_epilogue(v[4 * g + 2], c1, bias[f + 2], sine != 0), dhq_epilogue(v[4 * g + 3], c1, bias[f + 3], sine != 0));
+                } else {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            if ((e & h) == 0) {
-                const int a = v[e], b = v[e | h];
-                v[e] = (int)((unsigned)a + (unsigned)b);
-                v[e | h] = (int)((unsigned)a - (unsigned)b);
+                    for (int e = 0; e < 4; ++e)
+                        if (f + e < M) act_out[row * M + f + e] = dhq_epilogue(v[4 * g + e], c1, bias[f + e], sine != 0);
+                }
             }
         }
-    }
-#pragma unroll
-    for (int m = 1; m < LPR; m *= 2) {
-        const bool upper = (t & m) != 0;
+    } else {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            const int p = __shfl_xor(v[e], m, 64);
-            v[e] = upper ? (int)((unsigned)p - (unsigned)v[e]) : (int)((unsigned)v[e] + (unsigned)p);
+            const int f = S::index(t, e);
+            if (z_out) z_out[row * MP + f] = v[e];
+            if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], sine != 0);
         }
-    }
-    if (!live) return;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-        const int f = t * EPL + e;
-        if (z_out) z_out[row * MP + f] = v[e];
-        if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], sine != 0);
     }
 }
 
