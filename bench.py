@@ -157,8 +157,11 @@ def main() -> int:
     _, s_a = model.scales()
     fused = model.has_fused() and not dynamic and (args.path == "auto" or floating)
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
+    # dynamic scales: one fused kernel per layer where the library has them (input-side rotation,
+    # hidden width <= 256), the layer-by-layer kernels otherwise or with --path layerwise
+    dyn_fused = dynamic and not two_sided and args.path == "auto" and model.has_fused() and wl.dims[1] <= 256
     if dynamic:
-        flags |= dhq.DHQ_DYNAMIC
+        flags = (dhq.DHQ_FUSED if dyn_fused else dhq.DHQ_LAYERWISE) | dhq.DHQ_DYNAMIC
 
     ms, wall_ms = time_forward(model, x, out, flags, args.steps, args.warmup)
     n = x.shape[0]
@@ -237,9 +240,16 @@ def main() -> int:
         for l in range(len(wl.dims) - 1):
             K, M = wl.dims[l], wl.dims[l + 1]
             per_coord += 4 * K * (2 if dynamic else 1) + 2 * p2(K) + 4 * M + (8 * p2(M) if two_sided else 0)
+        if dyn_fused:
+            # one kernel per layer: the coordinates are read twice (scale of the input layer, then the layer),
+            # every hidden boundary is one write and one read of the transformed activations (fp32)
+            per_coord = 2 * 4 * wl.dims[0] + 4 * wl.dims[-1] + sum(2 * 4 * p2(k) for k in wl.dims[1:-1])
+            res["config"]["path"] = "one fused kernel per layer"
         gbs = per_coord * n / (ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
-                           "traffic": None, "kernel": "layer-by-layer path, all kernels of one forward",
+                           "traffic": None,
+                           "kernel": ("dhq_fused_layer_kernel, all launches of one forward" if dyn_fused
+                                      else "layer-by-layer path, all kernels of one forward"),
                            "algorithmic_hbm_bytes_per_launch": per_coord * n,
                            "algorithmic_ops_per_launch": ops}
         res.pop("alu", None)

@@ -59,7 +59,11 @@ typedef enum {
 #define DHQ_FUSED 2u     /* one kernel for the whole network; DHQ_EUNSUPPORTED if the shape has none */
 /* or-ed onto the above: measure every layer's activation scale on line, on this call's own
  * coordinates, instead of using the scales stored in the model (Sec. 3.3, "dynamic
- * quantization module ... between layers").  Layer-by-layer path only. */
+ * quantization module ... between layers").  With DHQ_LAYERWISE: three kernels per layer on any
+ * shape.  With DHQ_FUSED (and DHQ_AUTO where available): one kernel per layer that keeps the
+ * layer's arithmetic in registers and passes only the transformed activations through device
+ * memory; exists for input-side rotation on the shapes the whole-network kernel for hidden
+ * widths 32 .. 256 covers, DHQ_EUNSUPPORTED otherwise. */
 #define DHQ_DYNAMIC 4u
 
 /* dhq_quantize_weights_mode: which sides of the weight matrix are rotated. */
@@ -150,12 +154,14 @@ int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
  *   flags       DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED, optionally | DHQ_DYNAMIC
  * Uses the activation scales stored in the model (DHQ_ENOSCALE if there are none), unless
  * DHQ_DYNAMIC is given: then each layer's scale is max|x^| / qmax over the whole rotated
- * n x Kp input of that layer in THIS call (two passes over the layer input, the scale never
- * leaves the device; an all-zero tensor gets scale 1), which gives exactly what
- * dhq_calibrate on these coordinates followed by a static forward gives.  Dynamic mode keeps
- * all n rows of a layer in device memory: the model's workspace grows to n rows on the first
- * such call (an allocation, and a device synchronisation, whenever n exceeds every earlier
- * dynamic call).  DHQ_DYNAMIC | DHQ_FUSED is DHQ_EUNSUPPORTED.
+ * n x Kp input of that layer in THIS call (the scale never leaves the device; an all-zero
+ * tensor gets scale 1).  DHQ_DYNAMIC | DHQ_LAYERWISE gives exactly what dhq_calibrate on these
+ * coordinates followed by a static DHQ_LAYERWISE forward gives; DHQ_DYNAMIC | DHQ_FUSED gives
+ * exactly what a static DHQ_FUSED forward with the scales it measured gives (the two transform
+ * the activations with differently rounded fp32 arithmetic, so their scales can differ in the
+ * last place).  Dynamic mode keeps all n rows of a layer in device memory: the model's
+ * workspace grows to n rows on the first such call (an allocation, and a device
+ * synchronisation, whenever n exceeds every earlier dynamic call).
  */
 int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev,
                 void *stream, uint32_t flags);

@@ -441,7 +441,9 @@ static int ensure_dyn_workspace(dhq_model *m, int64_t n)
     m->dyn_codes = nullptr;
     m->dyn_acc = nullptr;
     m->dyn_rows = 0;
-    const size_t act_bytes = sizeof(float) * (size_t)n * m->max_dim;
+    // the per-layer fused kernels store whole workgroup tiles
+    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (size_t)n;
+    const size_t act_bytes = sizeof(float) * rows * m->max_dim;
     if (hipMalloc((void **)&m->dyn_act0, act_bytes) != hipSuccess) return DHQ_ENOMEM;
     if (hipMalloc((void **)&m->dyn_act1, act_bytes) != hipSuccess) return DHQ_ENOMEM;
     if (hipMalloc((void **)&m->dyn_codes, (size_t)n * m->max_kp) != hipSuccess) return DHQ_ENOMEM;
@@ -454,13 +456,24 @@ static int ensure_dyn_workspace(dhq_model *m, int64_t n)
 // reduces max|x^| over its whole rotated input (all n rows), a one-workgroup kernel turns the
 // maximum into the layer's constants, then the quantizer and the GEMM read them from device
 // memory.  Nothing returns to the host in between.
-static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, hipStream_t st)
+//
+// Two realisations: layer by layer (absmax pass, quantizer, GEMM: three launches per layer, any
+// shape), or -- where the whole-network fused kernel exists -- one launch per layer that keeps
+// the layer's arithmetic in registers and passes only the transformed activations through
+// device memory (dhq_fused_dynamic_launch).
+static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, bool per_layer_fused,
+                           hipStream_t st)
 {
     int rc = ensure_dyn_workspace(m, n);
     if (rc != DHQ_OK) return rc;
     const int L = m->n_layers;
     float *partial = reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS);
     if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
+    if (per_layer_fused)
+        return dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, m->dyn_absmax, partial,
+                                        m->dyn_params, st) == hipSuccess
+                   ? DHQ_OK
+                   : DHQ_EHIP;
     const float *cur = coords_dev;
     float *bufs[2] = {m->dyn_act0, m->dyn_act1};
     int which = 0;
@@ -487,14 +500,15 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     const uint32_t path = flags & 3u;
     const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
-    if (dynamic && path == DHQ_FUSED) return DHQ_EUNSUPPORTED;
+    const bool dyn_fused_ok = m->fused && !m->rot_out;  // per-layer fused kernels of the dynamic mode
+    if (dynamic && path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
     if (m->flt && (dynamic || path == DHQ_LAYERWISE)) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     if (m->flt) return dhq_float_launch(m->flt, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     // the workspace belongs to the model and is the only thing a forward call changes in it
-    if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, st);
+    if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, path != DHQ_LAYERWISE && dyn_fused_ok, st);
     if (!m->have_scales) return DHQ_ENOSCALE;
     if (path == DHQ_FUSED && !m->fused && !m->wide && !m->fused2) return DHQ_EUNSUPPORTED;
     if (path != DHQ_LAYERWISE && m->fused2)

@@ -211,6 +211,100 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
     }
 }
 
+// A operand of the H_32 products: a lane supplies row c of H_32 at the eight contraction slots
+// 8 h + j of block kk, which stand for tile row 8 (v / 4) + 4 h + v % 4 with v = 8 kk + j (the row
+// lane half h holds in accumulator v), as binary16 +-1.
+__device__ __forceinline__ void fused_h32_operand(int c, int h, dhq_v4i (&hA)[2])
+{
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int v = 8 * kk + 2 * d;  // accumulators v and v + 1: consecutive tile rows
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
+        }
+    }
+}
+
+// The coordinate vector of the input layer (fan-in <= 4): rotated and quantized into code dword 0.
+__device__ __forceinline__ int fused_input_codes(const float *__restrict__ coords, int64_t cl, int k0, int k0p, float inv, int qmax)
+{
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (k0 == 2) {
+        const float2 xy = *reinterpret_cast<const float2 *>(coords + cl * 2);
+        v[0] = xy.x; v[1] = xy.y;
+    } else {
+        for (int k = 0; k < k0; ++k) v[k] = coords[cl * k0 + k];
+    }
+    if (k0p >= 2) {
+        float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
+        a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
+    }
+    if (k0p == 4) {
+        float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
+        a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
+    }
+    return (int)dhq_pack4(dhq_quant_bits(v[0], inv, qmax), dhq_quant_bits(v[1], inv, qmax),
+                          dhq_quant_bits(v[2], inv, qmax), dhq_quant_bits(v[3], inv, qmax));
+}
+
+// The stages of the transform over the tile index: plain register add/sub.
+template <int NT>
+__device__ __forceinline__ void fused_tile_stages(dhq_v16f (&xt)[NT])
+{
+#pragma unroll
+    for (int s = 1; s < NT; s <<= 1) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            if ((T & s) == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float a = xt[T][v], b = xt[T | s][v];
+                    xt[T][v] = a + b;
+                    xt[T | s][v] = a - b;
+                }
+            }
+        }
+    }
+}
+
+// The quantizer: register s = 16 T + v becomes byte s % 4 of dword s / 4 of the codes.
+template <int NT>
+__device__ __forceinline__ void fused_quantize(const dhq_v16f (&xt)[NT], dhq_v4i (&cd)[NT], float inv, int qlo, int qhi)
+{
+#pragma unroll
+    for (int w = 0; w < NT * 4; ++w) {
+        unsigned packed = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
+        cd[w / 4][w % 4] = (int)packed;
+    }
+}
+
+// The output layer: one zero-padded M tile, no sine.
+template <int NKB>
+__device__ __forceinline__ void fused_output_layer(const dhq_v4i *__restrict__ wA, const float *__restrict__ wB,
+                                                   const dhq_v4i (&cd)[NKB], float c1, float *__restrict__ out, int64_t ci,
+                                                   bool valid, int m_out, int lane, int h)
+{
+    dhq_v16i acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+        const dhq_v4i a = wA[kb * 64 + lane];
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
+    }
+    if (valid) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            if (row < m_out) out[ci * m_out + row] = __builtin_fmaf((float)acc[v], c1, wB[((v >> 2) * 2 + h) * 4 + (v & 3)]);
+        }
+    }
+}
+
 template <int NF>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
@@ -226,19 +320,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
     const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
     const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
 
-    // A operand of the H_32 products: this lane supplies row c of H_32 at the eight contraction
-    // slots 8 h + j of block kk, which stand for tile row 8 (v / 4) + 4 h + v % 4 with v = 8 kk + j
-    // (the row lane half h holds in accumulator v), as binary16 +-1.
     dhq_v4i hA[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int v = 8 * kk + 2 * d;  // accumulators v and v + 1: consecutive tile rows
-            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
-            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
-        }
-    }
+    fused_h32_operand(c, h, hA);
 
     int p = 0;  // LDS buffer holding the layer about to run
     if ((int64_t)blockIdx.x < n_tiles)
@@ -252,27 +335,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
         dhq_v4i cd[NKB];  // activation codes: the B operands of the next GEMM
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
-        {
-            // input layer: rotate the coordinate vector (fan-in <= 4) and quantize it
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (A.k0 == 2) {
-                const float2 xy = *reinterpret_cast<const float2 *>(A.coords + cl * 2);
-                v[0] = xy.x; v[1] = xy.y;
-            } else {
-                for (int k = 0; k < A.k0; ++k) v[k] = A.coords[cl * A.k0 + k];
-            }
-            if (A.k0p >= 2) {
-                float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
-                a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
-            }
-            if (A.k0p == 4) {
-                float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
-                a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
-            }
-            const float inv = A.layer[0].inv_in;
-            cd[0][0] = (int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
-                                      dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
-        }
+        cd[0][0] = fused_input_codes(A.coords, cl, A.k0, A.k0p, A.layer[0].inv_in, A.qmax);
 
         dhq_v16f xt[NT];
         for (int l = 0; l < L - 1; ++l) {
@@ -295,30 +358,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             // do vector work, but a wave in its vector phase starves the MFMA chain of the
             // other; keep the phases aligned across the workgroup.
             __syncthreads();
-            const float inv = A.layer[l + 1].inv_in;
-            // the stages of the transform over the tile index (plain register add/sub) ...
-#pragma unroll
-            for (int s = 1; s < NT; s <<= 1) {
-#pragma unroll
-                for (int T = 0; T < NT; ++T) {
-                    if ((T & s) == 0) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float a = xt[T][v], b = xt[T | s][v];
-                            xt[T][v] = a + b;
-                            xt[T | s][v] = a - b;
-                        }
-                    }
-                }
-            }
-            // ... then the quantizer: register s = 16 T + v becomes byte s % 4 of dword s / 4
-#pragma unroll
-            for (int w = 0; w < NR / 4; ++w) {
-                unsigned packed = 0;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
-                cd[w / 4][w % 4] = (int)packed;
-            }
+            fused_tile_stages<NT>(xt);
+            fused_quantize<NT>(xt, cd, A.layer[l + 1].inv_in, qlo, qhi);
             p ^= 1;
         }
 
@@ -328,27 +369,111 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             __syncthreads();
             if (tile + gridDim.x < n_tiles)
                 fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane, FUSED_WAVES);
-            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
-            const float *wB = reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024);
-            dhq_v16i acc;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0;
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const dhq_v4i a = wA[kb * 64 + lane];
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
-            }
-            const float c1 = A.layer[L - 1].c1;
-            if (valid) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (row < A.m_out)
-                        A.out[ci * A.m_out + row] =
-                            __builtin_fmaf((float)acc[v], c1, wB[((v >> 2) * 2 + h) * 4 + (v & 3)]);
-                }
-            }
+            fused_output_layer<NKB>(reinterpret_cast<const dhq_v4i *>(lds + p * BLK),
+                                    reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024), cd, A.layer[L - 1].c1, A.out, ci,
+                                    valid, A.m_out, lane, h);
             p ^= 1;
+        }
+    }
+}
+
+// ---- one layer per launch: the dynamic quantization module (Sec. 3.3) ------------------------
+// With scales measured on line, a layer's quantizer needs max |x^| over the whole batch before
+// it can emit a single code, so the network cannot stay in registers from end to end.  These
+// kernels cut the fused kernel at exactly that point: a launch quantizes its input with the
+// scale found by the previous one, runs the layer (GEMM, epilogue, transform of the output)
+// and writes the transformed output x^ (fp32) plus each workgroup's max |x^|; a one-workgroup
+// kernel in between turns the maxima into the next layer's constants on the device.  Per hidden
+// layer the activations cross device memory once in each direction, in the lanes' register order
+// ([wave tile][float4 q][lane]: every 16-byte access of a wave is 1 KiB contiguous).
+//   MODE 0  input layer: coordinates in, x^ out        MODE 1  hidden layer: x^ in, x^ out
+//   MODE 2  output layer: x^ in, signal values out
+struct fusedl_args {
+    const float *coords;       // MODE 0
+    const float4 *xin;         // MODE 1, 2
+    float4 *xout;              // MODE 0, 1
+    float *out;                // MODE 2
+    const unsigned char *blk;  // this layer's block of the packed weights (fragments, then biases)
+    const float *dyn;          // this layer's {1 / (s_a sqrt(Kp)), epilogue multiplier, s_a}, on the device
+    float *partial;            // MODE 0, 1: max |x^| of the output per workgroup
+    int64_t n;
+    int chunks;                // block size in KiB
+    int k0, k0p, m_out, qmax;
+};
+
+template <int NF, int MODE>
+__global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fusedl_args A)
+{
+    constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
+    constexpr int KB = (MODE == 0) ? 1 : NKB;      // k blocks of this layer's GEMM
+    constexpr int MT = (MODE == 2) ? 1 : NT;       // M tiles of this layer's GEMM
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ float red[FUSED_WAVES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+    dhq_v4i hA[2];
+    fused_h32_operand(c, h, hA);
+    fused_issue_copy(A.blk, lds, A.chunks, wave, lane, FUSED_WAVES);
+    const float inv = A.dyn[0], c1 = A.dyn[1];
+    const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds);
+    float mx = 0.f;
+    bool landed = false;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t ci = tile * FUSED_TILE + wave * 32 + c;
+        const bool valid = ci < A.n;
+        const int64_t cl = valid ? ci : A.n - 1;  // lanes past the end repeat the last coordinate: no effect on the maximum
+        const size_t slot = ((size_t)tile * FUSED_WAVES + wave) * (NR / 4) * 64 + lane;
+        dhq_v4i cd[NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        if constexpr (MODE == 0) {
+            cd[0][0] = fused_input_codes(A.coords, cl, A.k0, A.k0p, inv, A.qmax);
+        } else {
+#pragma unroll
+            for (int q = 0; q < NR / 4; ++q) {
+                const float4 x = A.xin[slot + (size_t)q * 64];
+                unsigned packed = 0;
+                fused_quant_byte(packed, x.x, inv, qlo, qhi, 0);
+                fused_quant_byte(packed, x.y, inv, qlo, qhi, 1);
+                fused_quant_byte(packed, x.z, inv, qlo, qhi, 2);
+                fused_quant_byte(packed, x.w, inv, qlo, qhi, 3);
+                cd[q / 4][q % 4] = (int)packed;
+            }
+        }
+        if (!landed) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            landed = true;
+        }
+        __syncthreads();  // the weights are in LDS; later passes: keeps the waves' phases aligned
+        if constexpr (MODE == 2) {
+            fused_output_layer<NKB>(wA, reinterpret_cast<const float *>(lds + MT * KB * 1024), cd, c1, A.out, ci, valid, A.m_out,
+                                    lane, h);
+        } else {
+            dhq_v16f xt[NT];
+            fused_gemm_sine_hm<NT, KB, NKB>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, xt, hA, lane, h);
+            __syncthreads();
+            fused_tile_stages<NT>(xt);
+#pragma unroll
+            for (int q = 0; q < NR / 4; ++q) {
+                const float4 x = make_float4(xt[q >> 2][4 * (q & 3)], xt[q >> 2][4 * (q & 3) + 1], xt[q >> 2][4 * (q & 3) + 2],
+                                             xt[q >> 2][4 * (q & 3) + 3]);
+                mx = fmaxf(fmaxf(mx, fmaxf(fabsf(x.x), fabsf(x.y))), fmaxf(fabsf(x.z), fabsf(x.w)));
+                A.xout[slot + (size_t)q * 64] = x;
+            }
+        }
+    }
+    if constexpr (MODE != 2) {
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        if (lane == 0) red[wave] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float r = red[0];
+#pragma unroll
+            for (int w = 1; w < FUSED_WAVES; ++w) r = fmaxf(r, red[w]);
+            A.partial[blockIdx.x] = r;
         }
     }
 }
@@ -409,6 +534,12 @@ int dhq_fused_create(const dhq_model *m, dhq_fused_plan **plan_out)
                         frag[((size_t)(T * Kb + kb) * 64 + ln) * 16 + jj] = val;
                     }
                 }
+        // the bias block: [T][g][h][e], in revolutions for the sine layers
+        {
+            float *bias = reinterpret_cast<float *>(blob.data() + off + (size_t)Mt * Kb * 1024);
+            const std::vector<float> &src = (l == L - 1) ? Ly.bias_host : Ly.bias_rev_host;
+            for (int f = 0; f < Ly.M; ++f) bias[bias_slot(f)] = src[f];
+        }
         P->args.layer[l].blob_off = (uint32_t)off;
         P->args.layer[l].chunks = (uint32_t)(bytes / 1024);
     }
@@ -417,7 +548,6 @@ int dhq_fused_create(const dhq_model *m, dhq_fused_plan **plan_out)
         delete P;
         return DHQ_ENOMEM;
     }
-    // the bias part of every block is filled in by dhq_fused_update_scales
     if (hipMemcpy(P->blob_dev, blob.data(), P->blob_bytes, hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipFree(P->blob_dev);
         delete P;
@@ -448,24 +578,14 @@ void dhq_fused_destroy(dhq_fused_plan *plan)
     delete plan;
 }
 
-// Refreshes the per-layer constants and the bias part of each block.
+// Refreshes the per-layer constants after the activation scales changed.
 int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
 {
     if (!P) return DHQ_OK;
-    const int L = m->n_layers;
-    const int NT = P->nf / 32, NKB = P->nf / 32;
-    for (int l = 0; l < L; ++l) {
+    for (int l = 0; l < m->n_layers; ++l) {
         const dhq_layer &Ly = m->layer[l];
-        const bool last = (l == L - 1);
         P->args.layer[l].c1 = dhq_c1(m, l);
         P->args.layer[l].inv_in = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
-        // bias block
-        const int Mt = last ? 1 : NT, Kb = (l == 0) ? 1 : NKB;
-        std::vector<float> blk(256, 0.0f);
-        const std::vector<float> &src = last ? Ly.bias_host : Ly.bias_rev_host;
-        for (int f = 0; f < Ly.M; ++f) blk[bias_slot(f)] = src[f];
-        unsigned char *dst = P->blob_dev + P->args.layer[l].blob_off + (size_t)Mt * Kb * 1024;
-        if (hipMemcpy(dst, blk.data(), 1024, hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
     }
     return DHQ_OK;
 }
@@ -498,4 +618,74 @@ hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, 
         case 256: return fused_launch_t<256>(P, a, grid, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+// The dynamic mode on the per-layer kernels above.  ws0 / ws1: two buffers of rows(n) x width
+// floats (rows(n) = n rounded up to a whole workgroup tile); absmax: one word per layer, cleared
+// by the caller; partial: room for one float per workgroup; dyn: three floats per layer.
+size_t dhq_fused_dynamic_rows(int64_t n) { return (size_t)((n + FUSED_TILE - 1) / FUSED_TILE) * FUSED_TILE; }
+
+template <int NF, int MODE>
+static hipError_t fusedl_launch_t(const dhq_fused_plan *P, const fusedl_args &a, unsigned grid, hipStream_t st)
+{
+    auto kern = dhq_fused_layer_kernel<NF, MODE>;
+    const size_t lds = (size_t)a.chunks * 1024;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, FUSED_THREADS, lds, st>>>(a);
+    return hipGetLastError();
+}
+template <int NF>
+static hipError_t fusedl_launch_mode(const dhq_fused_plan *P, int mode, const fusedl_args &a, unsigned grid, hipStream_t st)
+{
+    switch (mode) {
+        case 0: return fusedl_launch_t<NF, 0>(P, a, grid, st);
+        case 1: return fusedl_launch_t<NF, 1>(P, a, grid, st);
+        default: return fusedl_launch_t<NF, 2>(P, a, grid, st);
+    }
+}
+
+hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                    unsigned *absmax, float *partial, float *dyn, hipStream_t st)
+{
+    const dhq_fused_plan *P = m->fused;
+    if (!P) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    const int L = m->n_layers;
+    const int64_t tiles = (n + FUSED_TILE - 1) / FUSED_TILE;
+    const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    // the input layer's scale: max over the rotated coordinates
+    hipError_t e = dhq_launch_wht_absmax(coords, n, m->layer[0].K, m->layer[0].Kp, absmax, partial, m->qmax_a,
+                                         dhq_c1_over_sa(m, 0), dyn, st);
+    if (e != hipSuccess) return e;
+    float *bufs[2] = {ws0, ws1};
+    for (int l = 0; l < L; ++l) {
+        fusedl_args a;
+        memset(&a, 0, sizeof(a));
+        a.coords = coords;
+        a.xin = reinterpret_cast<const float4 *>(bufs[(l + 1) & 1]);
+        a.xout = reinterpret_cast<float4 *>(bufs[l & 1]);
+        a.out = out;
+        a.blk = P->blob_dev + P->args.layer[l].blob_off;
+        a.chunks = (int)P->args.layer[l].chunks;
+        a.dyn = dyn + 3 * l;
+        a.partial = partial;
+        a.n = n;
+        a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.qmax = P->args.qmax;
+        const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
+        switch (P->nf) {
+            case 32: e = fusedl_launch_mode<32>(P, mode, a, grid, st); break;
+            case 64: e = fusedl_launch_mode<64>(P, mode, a, grid, st); break;
+            case 128: e = fusedl_launch_mode<128>(P, mode, a, grid, st); break;
+            case 256: e = fusedl_launch_mode<256>(P, mode, a, grid, st); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+        if (l < L - 1) {
+            e = dhq_launch_absmax_finish(partial, (int)grid, absmax + l + 1, m->layer[l + 1].Kp, m->qmax_a,
+                                         dhq_c1_over_sa(m, l + 1), dyn + 3 * (l + 1), st);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
 }

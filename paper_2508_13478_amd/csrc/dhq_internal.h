@@ -97,6 +97,11 @@ hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, i
 hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
                                const float *dyn, int32_t *z_out, float *act_out, hipStream_t st);
 
+// One workgroup: *absmax_bits = max(*absmax_bits, partial[0 .. count)) and, if dyn != nullptr, the
+// dynamic-mode constants dyn[0..2] for that maximum (see dhq_launch_wht_absmax).
+hipError_t dhq_launch_absmax_finish(const float *partial, int count, unsigned *absmax_bits, int Kp, int qmax,
+                                    double c1_over_sa, float *dyn, hipStream_t st);
+
 hipError_t dhq_launch_clear_words(unsigned *p, int n, hipStream_t st);
 
 // Epilogue multiplier divided by the activation scale: s_w, times omega0 / (2 pi) in the sine
@@ -124,6 +129,12 @@ void dhq_fused_destroy(dhq_fused_plan *plan);
 int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *plan);
 hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, float *out,
                             hipStream_t st);
+// Dynamic mode, one launch per layer with the transformed activations passing through ws0 / ws1
+// (dhq_fused_dynamic_rows(n) x hidden width floats each); absmax: one cleared word per layer;
+// partial: one float per workgroup (at most the number of CUs); dyn: three floats per layer.
+size_t dhq_fused_dynamic_rows(int64_t n);
+hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                    unsigned *absmax, float *partial, float *dyn, hipStream_t st);
 
 
 // Hidden width 512 (defined in dhq_fused_wide.hip); same contract as the functions above.

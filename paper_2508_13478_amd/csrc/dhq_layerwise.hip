@@ -239,6 +239,14 @@ __global__ __launch_bounds__(256) void absmax_finish_kernel(const float *__restr
     }
 }
 
+hipError_t dhq_launch_absmax_finish(const float *partial, int count, unsigned *absmax_bits, int Kp, int qmax,
+                                    double c1_over_sa, float *dyn, hipStream_t st)
+{
+    if (count <= 0 || !partial || !absmax_bits) return hipErrorInvalidValue;
+    absmax_finish_kernel<<<1, 256, 0, st>>>(partial, count, absmax_bits, Kp, qmax, c1_over_sa, dyn);
+    return hipGetLastError();
+}
+
 template <int KP>
 static hipError_t launch_wht(const float *in, int64_t n, int K, float inv, int qmax, int8_t *codes,
                              const float *dyn, hipStream_t st)

@@ -188,12 +188,64 @@ def test_dynamic_forward_equals_calibrate_then_static(name, mode):
     _gate(dyn.cpu().numpy(), exp, wl.dims, False, "dynamic vs oracle")
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_dynamic_per_layer_fused_equals_static_fused_with_its_scales(name):
+    """The one-kernel-per-layer realisation of the dynamic mode: it runs the fused kernel's own
+    arithmetic, so a static fused forward with the scales it measured gives the same bits; the scales
+    agree with the oracle's (and with the layer-by-layer dynamic path's) to fp32 rounding."""
+    torch = _torch()
+    _say(f"dynamic per-layer fused {name}")
+    wl, coords, W, b = synth.make(name)
+    if name == "C3":
+        coords = coords[:100000 + 37]                    # several passes per workgroup, ragged tail
+    x = _dev(coords)
+    m = dhq.Model(wl.dims, wl.omega0, W, b)
+    dyn = m.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    s_dyn = m.dynamic_scales()
+    auto = m.forward(x, flags=dhq.DHQ_DYNAMIC)                      # AUTO picks the same kernels
+    lw = m.forward(x, flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
+    s_lw = m.dynamic_scales()
+    m.set_act_scales(s_dyn)
+    sta = m.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+    assert np.array_equal(dyn.cpu().numpy(), auto.cpu().numpy())
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
+    exp = o.forward(net, coords, calibrate=True)
+    rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+    _say(f"  scale rel err vs oracle max {rel.max():.2e}; vs layer-by-layer {np.abs(s_dyn / s_lw - 1).max():.2e}")
+    assert rel.max() <= 1e-5 and np.abs(s_dyn / s_lw - 1).max() <= 1e-5
+    _gate(dyn.cpu().numpy(), exp, wl.dims, False, "dynamic per-layer fused vs oracle")
+    d = np.abs(dyn.cpu().numpy() - lw.cpu().numpy()).max(axis=1)
+    assert (d > OUT_TOL).mean() <= 2 * 1e-3
+    m.close()
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 5], [4, 128, 128, 2], [1, 256, 256, 32], [2, 64, 1]])
+def test_dynamic_per_layer_fused_shapes_and_ragged_rows(dims):
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 123 + len(dims))
+    m = dhq.Model(dims, 30.0, W, b)
+    net = o.quantize_net(dims, 30.0, 8, 8, W, b)
+    rng = np.random.default_rng(dims[1] + 1)
+    for n in (1, 257, 3000 + 11):
+        _say(f"dynamic per-layer fused dims {dims} n={n}")
+        xs = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        exp = o.forward(net, xs, calibrate=True)
+        dyn = m.forward(_dev(xs), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+        s_dyn = m.dynamic_scales()
+        torch.cuda.synchronize()
+        assert (np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a).max() <= 1e-5
+        _gate(dyn.cpu().numpy(), exp, dims, False, f"dims {dims} n={n}")
+    m.close()
+
+
 def test_dynamic_scales_follow_the_batch_and_workspace_grows():
     torch = _torch()
     wl, coords, W, b = synth.make("C2")
     m = dhq.Model(wl.dims, wl.omega0, W, b)
     small = _dev(coords[:1000])
-    out_small = m.forward(small, flags=dhq.DHQ_DYNAMIC)            # AUTO | DYNAMIC -> layer-by-layer
+    out_small = m.forward(small, flags=dhq.DHQ_DYNAMIC)            # AUTO | DYNAMIC -> one kernel per layer
     s_small = m.dynamic_scales()
     full = m.forward(_dev(coords), flags=dhq.DHQ_DYNAMIC)          # the workspace grows here
     s_full = m.dynamic_scales()
@@ -227,10 +279,18 @@ def test_variant_flags_are_checked():
     wl, coords, W, b = synth.make("C1")
     m = dhq.Model(wl.dims, wl.omega0, W, b)
     x = _dev(coords[:64])
-    for flags, status in ((dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC, dhq.DHQ_EUNSUPPORTED), (8, dhq.DHQ_EINVAL), (3, dhq.DHQ_EINVAL)):
+    for flags, status in ((8, dhq.DHQ_EINVAL), (3, dhq.DHQ_EINVAL)):
         with pytest.raises(dhq.DhqError) as e:
             m.forward(x, flags=flags)
         assert e.value.status == status
+    # the per-layer fused kernels of the dynamic mode exist for input-side rotation and widths <= 256
+    wide_dims = [2, 512, 512, 3]
+    Ww, bw = synth.siren_init(wide_dims, 30.0, 3)
+    for mm in (dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH), dhq.Model(wide_dims, 30.0, Ww, bw)):
+        with pytest.raises(dhq.DhqError) as e:
+            mm.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+        assert e.value.status == dhq.DHQ_EUNSUPPORTED
+        mm.close()
     with pytest.raises(dhq.DhqError) as e:
         m.forward(x)                                           # static path without scales
     assert e.value.status == dhq.DHQ_ENOSCALE
