@@ -441,7 +441,7 @@ def test_full_grid_sampled_outputs_of_the_variants(mode_name):
     m.close()
 
 
-@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "w32a32"])
+@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "w32a32"])
 def test_forward_replays_from_a_captured_graph(variant):
     """dhq_forward only enqueues kernels (no memset, no allocation, no synchronisation once the
     workspace exists), so a stream capture of it replays to the same bits as the eager call --
@@ -451,7 +451,8 @@ def test_forward_replays_from_a_captured_graph(variant):
     wl, coords, W, b = synth.make("C1")
     x = _dev(coords)
     mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
-    flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
+    flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC,
+             "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
     m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode)
     if variant != "w32a32":
         m.calibrate(x)
