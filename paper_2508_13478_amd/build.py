@@ -122,6 +122,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
         return LIB
     import tempfile
     cmd = [_hipcc()] + CODEGEN_FLAGS + ["-fPIC", "-shared", "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    if os.path.exists(LIB):
+        os.remove(LIB)  # a failed build must not leave an older library behind to be loaded in its place
     if verbose:
         print(" ".join(cmd), flush=True)
     with tempfile.TemporaryDirectory() as td:

@@ -279,7 +279,7 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
         if (rc == DHQ_OK && m->rot_out &&
             hipMalloc((void **)&m->acc_ws, sizeof(int32_t) * (size_t)DHQ_CHUNK * m->max_mg) != hipSuccess)
             rc = DHQ_ENOMEM;
-        if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
+        if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + 2 * DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_params, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_ENOMEM;
         // dhq_get_dynamic_scales before any dynamic forward reports zeros
         if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
@@ -468,12 +468,12 @@ static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, flo
     if (rc != DHQ_OK) return rc;
     const int L = m->n_layers;
     float *partial = reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS);
-    if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
     if (per_layer_fused)
-        return dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, m->dyn_absmax, partial,
-                                        m->dyn_params, st) == hipSuccess
+        return dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st) ==
+                       hipSuccess
                    ? DHQ_OK
                    : DHQ_EHIP;
+    if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
     const float *cur = coords_dev;
     float *bufs[2] = {m->dyn_act0, m->dyn_act1};
     int which = 0;

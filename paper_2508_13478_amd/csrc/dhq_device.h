@@ -47,4 +47,18 @@ __device__ __forceinline__ float dhq_epilogue(int acc, float c1, float bias, boo
     return sine ? dhq_sin_rev(y) : y;
 }
 
+// From max |un-normalised x^| of a layer input to the constants of the dynamic mode, in the same
+// fp64 steps the host takes when it calibrates (so both give the same bits):
+//   inv = 1 / (s_a sqrt(Kp))    the quantizer's multiplier
+//   c1  = s_a * c1_over_sa      the epilogue's multiplier (c1_over_sa = s_w [omega0 / 2 pi] [/ sqrt(Mp)])
+//   s_a = (float)(max|x^| / qmax), 1 for an all-zero tensor
+__device__ __forceinline__ void dhq_dyn_constants(float mx, int Kp, int qmax, double c1_over_sa, float &inv, float &c1,
+                                                  float &s_a)
+{
+    const double amax = (double)mx / sqrt((double)Kp);
+    s_a = amax == 0.0 ? 1.0f : (float)(amax / (double)qmax);
+    inv = (float)(1.0 / ((double)s_a * sqrt((double)Kp)));
+    c1 = (float)((double)s_a * c1_over_sa);
+}
+
 #endif

@@ -380,10 +380,11 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
 // ---- one layer per launch: the dynamic quantization module (Sec. 3.3) ------------------------
 // With scales measured on line, a layer's quantizer needs max |x^| over the whole batch before
 // it can emit a single code, so the network cannot stay in registers from end to end.  These
-// kernels cut the fused kernel at exactly that point: a launch quantizes its input with the
-// scale found by the previous one, runs the layer (GEMM, epilogue, transform of the output)
-// and writes the transformed output x^ (fp32) plus each workgroup's max |x^|; a one-workgroup
-// kernel in between turns the maxima into the next layer's constants on the device.  Per hidden
+// kernels cut the fused kernel at exactly that point: a launch folds the maxima the previous
+// launch's workgroups left into this layer's constants (every workgroup for itself: a few hundred
+// floats and three fp64 operations cost less than a launch in between), quantizes its input
+// with them, runs the layer (GEMM, epilogue, transform of the output) and writes the
+// transformed output x^ (fp32) plus each workgroup's max |x^|.  Per hidden
 // layer the activations cross device memory once in each direction, in the lanes' register order
 // ([wave tile][float4 q][lane]: every 16-byte access of a wave is 1 KiB contiguous).
 //   MODE 0  input layer: coordinates in, x^ out        MODE 1  hidden layer: x^ in, x^ out
@@ -394,8 +395,12 @@ struct fusedl_args {
     float4 *xout;              // MODE 0, 1
     float *out;                // MODE 2
     const unsigned char *blk;  // this layer's block of the packed weights (fragments, then biases)
-    const float *dyn;          // this layer's {1 / (s_a sqrt(Kp)), epilogue multiplier, s_a}, on the device
-    float *partial;            // MODE 0, 1: max |x^| of the output per workgroup
+    const float *partial_in;   // max |x^| of this layer's input, one float per workgroup of the launch before
+    int partial_count;
+    int kp;                    // length of this layer's rotated input
+    double c1_over_sa;         // epilogue multiplier divided by the activation scale
+    float *dyn;                // this layer's {1 / (s_a sqrt(Kp)), epilogue multiplier, s_a}: written by workgroup 0
+    float *partial;            // MODE 0, 1: max |x^| of the output per workgroup (not the buffer partial_in points to)
     int64_t n;
     int chunks;                // block size in KiB
     int k0, k0p, m_out, qmax;
@@ -408,7 +413,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fu
     constexpr int KB = (MODE == 0) ? 1 : NKB;      // k blocks of this layer's GEMM
     constexpr int MT = (MODE == 2) ? 1 : NT;       // M tiles of this layer's GEMM
     extern __shared__ __align__(16) unsigned char lds[];
-    __shared__ float red[FUSED_WAVES];
+    __shared__ float red_in[FUSED_WAVES], red[FUSED_WAVES];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int64_t n_tiles = (A.n + FUSED_TILE - 1) / FUSED_TILE;
@@ -416,7 +421,23 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fu
     dhq_v4i hA[2];
     fused_h32_operand(c, h, hA);
     fused_issue_copy(A.blk, lds, A.chunks, wave, lane, FUSED_WAVES);
-    const float inv = A.dyn[0], c1 = A.dyn[1];
+    // this layer's constants from the maxima of its input
+    float inv, c1, s_a;
+    {
+        float mi = 0.f;
+        for (int i = threadIdx.x; i < A.partial_count; i += FUSED_THREADS) mi = fmaxf(mi, A.partial_in[i]);
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mi = fmaxf(mi, __shfl_xor(mi, m, 64));
+        if (lane == 0) red_in[wave] = mi;
+        __syncthreads();
+        mi = red_in[0];
+#pragma unroll
+        for (int w = 1; w < FUSED_WAVES; ++w) mi = fmaxf(mi, red_in[w]);
+        dhq_dyn_constants(mi, A.kp, A.qmax, A.c1_over_sa, inv, c1, s_a);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            A.dyn[0] = inv; A.dyn[1] = c1; A.dyn[2] = s_a;
+        }
+    }
     const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds);
     float mx = 0.f;
     bool landed = false;
@@ -621,8 +642,10 @@ hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, 
 }
 
 // The dynamic mode on the per-layer kernels above.  ws0 / ws1: two buffers of rows(n) x width
-// floats (rows(n) = n rounded up to a whole workgroup tile); absmax: one word per layer, cleared
-// by the caller; partial: room for one float per workgroup; dyn: three floats per layer.
+// floats (rows(n) = n rounded up to a whole workgroup tile); partial: room for 2 x
+// DHQ_ABSMAX_PARTIALS floats (two sets of per-workgroup maxima, used alternately: a layer's
+// slower workgroups still read one set while its faster ones already write the other);
+// dyn: three floats per layer.
 size_t dhq_fused_dynamic_rows(int64_t n) { return (size_t)((n + FUSED_TILE - 1) / FUSED_TILE) * FUSED_TILE; }
 
 template <int NF, int MODE>
@@ -646,7 +669,7 @@ static hipError_t fusedl_launch_mode(const dhq_fused_plan *P, int mode, const fu
 }
 
 hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
-                                    unsigned *absmax, float *partial, float *dyn, hipStream_t st)
+                                    float *partial, float *dyn, hipStream_t st)
 {
     const dhq_fused_plan *P = m->fused;
     if (!P) return hipErrorInvalidValue;
@@ -654,9 +677,10 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
     const int L = m->n_layers;
     const int64_t tiles = (n + FUSED_TILE - 1) / FUSED_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
-    // the input layer's scale: max over the rotated coordinates
-    hipError_t e = dhq_launch_wht_absmax(coords, n, m->layer[0].K, m->layer[0].Kp, absmax, partial, m->qmax_a,
-                                         dhq_c1_over_sa(m, 0), dyn, st);
+    // the input layer's scale: max over the rotated coordinates, left as per-workgroup maxima
+    float *pbuf[2] = {partial, partial + DHQ_ABSMAX_PARTIALS};
+    int count = 0;
+    hipError_t e = dhq_launch_wht_absmax_partials(coords, n, m->layer[0].K, m->layer[0].Kp, pbuf[0], &count, st);
     if (e != hipSuccess) return e;
     float *bufs[2] = {ws0, ws1};
     for (int l = 0; l < L; ++l) {
@@ -668,8 +692,12 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
         a.out = out;
         a.blk = P->blob_dev + P->args.layer[l].blob_off;
         a.chunks = (int)P->args.layer[l].chunks;
+        a.partial_in = pbuf[l & 1];
+        a.partial_count = count;
+        a.kp = m->layer[l].Kp;
+        a.c1_over_sa = dhq_c1_over_sa(m, l);
         a.dyn = dyn + 3 * l;
-        a.partial = partial;
+        a.partial = pbuf[(l + 1) & 1];
         a.n = n;
         a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.qmax = P->args.qmax;
         const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
@@ -681,11 +709,7 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
             default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;
-        if (l < L - 1) {
-            e = dhq_launch_absmax_finish(partial, (int)grid, absmax + l + 1, m->layer[l + 1].Kp, m->qmax_a,
-                                         dhq_c1_over_sa(m, l + 1), dyn + 3 * (l + 1), st);
-            if (e != hipSuccess) return e;
-        }
+        count = (int)grid;
     }
     return hipSuccess;
 }

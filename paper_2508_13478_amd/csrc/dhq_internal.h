@@ -60,7 +60,7 @@ struct dhq_model {
     int8_t *dyn_codes = nullptr;
     int32_t *dyn_acc = nullptr;
     int64_t dyn_rows = 0;
-    unsigned *dyn_absmax = nullptr;  // DHQ_MAX_LAYERS absmax words, then DHQ_ABSMAX_PARTIALS floats of scratch
+    unsigned *dyn_absmax = nullptr;  // DHQ_MAX_LAYERS absmax words, then 2 x DHQ_ABSMAX_PARTIALS floats of scratch
     float *dyn_params = nullptr;     // DHQ_MAX_LAYERS x 3
     dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
     dhq_wide_plan *wide = nullptr;    // hidden width 512
@@ -97,10 +97,10 @@ hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, i
 hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
                                const float *dyn, int32_t *z_out, float *act_out, hipStream_t st);
 
-// One workgroup: *absmax_bits = max(*absmax_bits, partial[0 .. count)) and, if dyn != nullptr, the
-// dynamic-mode constants dyn[0..2] for that maximum (see dhq_launch_wht_absmax).
-hipError_t dhq_launch_absmax_finish(const float *partial, int count, unsigned *absmax_bits, int Kp, int qmax,
-                                    double c1_over_sa, float *dyn, hipStream_t st);
+// The first of the two launches of dhq_launch_wht_absmax only: partial[0 .. *count) holds the
+// workgroups' maxima and the caller folds them.
+hipError_t dhq_launch_wht_absmax_partials(const float *in, int64_t n, int K, int Kp, float *partial, int *count,
+                                          hipStream_t st);
 
 hipError_t dhq_launch_clear_words(unsigned *p, int n, hipStream_t st);
 
@@ -130,11 +130,11 @@ int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *plan);
 hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, float *out,
                             hipStream_t st);
 // Dynamic mode, one launch per layer with the transformed activations passing through ws0 / ws1
-// (dhq_fused_dynamic_rows(n) x hidden width floats each); absmax: one cleared word per layer;
-// partial: one float per workgroup (at most the number of CUs); dyn: three floats per layer.
+// (dhq_fused_dynamic_rows(n) x hidden width floats each); partial: 2 x DHQ_ABSMAX_PARTIALS floats of
+// scratch; dyn: three floats per layer.
 size_t dhq_fused_dynamic_rows(int64_t n);
 hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
-                                    unsigned *absmax, float *partial, float *dyn, hipStream_t st);
+                                    float *partial, float *dyn, hipStream_t st);
 
 
 // Hidden width 512 (defined in dhq_fused_wide.hip); same contract as the functions above.

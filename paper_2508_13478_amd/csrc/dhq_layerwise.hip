@@ -169,20 +169,12 @@ __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict_
     }
 }
 
-// From the absmax word of a layer's (un-normalised) rotated input to the constants of the
-// dynamic mode, in the same fp64 steps the host takes in dhq_calibrate (so both give the same bits):
-//   dyn[0] = 1 / (s_a sqrt(Kp))    the quantizer's multiplier
-//   dyn[1] = s_a * c1_over_sa      the epilogue's multiplier (c1_over_sa = s_w [omega0 / 2 pi] [/ sqrt(Mp)])
-//   dyn[2] = s_a = (float)(max|x^| / qmax), 1 for an all-zero tensor
+// The constants of the dynamic mode (dhq_dyn_constants) for the absmax word of a layer input, stored
+// as dyn[0..2] = {inv, c1, s_a}.
 __device__ __forceinline__ void dyn_scale_write(unsigned absmax_bits, int Kp, int qmax, double c1_over_sa,
                                                 float *__restrict__ dyn)
 {
-    const float mx = __uint_as_float(absmax_bits);
-    const double amax = (double)mx / sqrt((double)Kp);
-    const float s_a = amax == 0.0 ? 1.0f : (float)(amax / (double)qmax);
-    dyn[0] = (float)(1.0 / ((double)s_a * sqrt((double)Kp)));
-    dyn[1] = (float)((double)s_a * c1_over_sa);
-    dyn[2] = s_a;
+    dhq_dyn_constants(__uint_as_float(absmax_bits), Kp, qmax, c1_over_sa, dyn[0], dyn[1], dyn[2]);
 }
 
 // max |un-normalised x^| over all rows.  The grid is a few workgroups per CU, every workgroup
@@ -239,14 +231,6 @@ __global__ __launch_bounds__(256) void absmax_finish_kernel(const float *__restr
     }
 }
 
-hipError_t dhq_launch_absmax_finish(const float *partial, int count, unsigned *absmax_bits, int Kp, int qmax,
-                                    double c1_over_sa, float *dyn, hipStream_t st)
-{
-    if (count <= 0 || !partial || !absmax_bits) return hipErrorInvalidValue;
-    absmax_finish_kernel<<<1, 256, 0, st>>>(partial, count, absmax_bits, Kp, qmax, c1_over_sa, dyn);
-    return hipGetLastError();
-}
-
 template <int KP>
 static hipError_t launch_wht(const float *in, int64_t n, int K, float inv, int qmax, int8_t *codes,
                              const float *dyn, hipStream_t st)
@@ -260,7 +244,7 @@ static hipError_t launch_wht(const float *in, int64_t n, int K, float inv, int q
 
 template <int KP>
 static hipError_t launch_absmax(const float *in, int64_t n, int K, unsigned *absmax_bits, float *partial, int qmax,
-                                double c1_over_sa, float *dyn, hipStream_t st)
+                                double c1_over_sa, float *dyn, int *count_out, hipStream_t st)
 {
     constexpr int LPR = wht_shape<KP>::LPR;
     const int64_t need = (n * LPR + 255) / 256;
@@ -268,6 +252,10 @@ static hipError_t launch_absmax(const float *in, int64_t n, int K, unsigned *abs
     wht_absmax_kernel<KP><<<blocks, 256, 0, st>>>(in, n, K, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (count_out) {  // the caller folds the partial maxima itself
+        *count_out = (int)blocks;
+        return hipSuccess;
+    }
     absmax_finish_kernel<<<1, 256, 0, st>>>(partial, (int)blocks, absmax_bits, KP, qmax, c1_over_sa, dyn);
     return hipGetLastError();
 }
@@ -291,24 +279,37 @@ hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float
     }
 }
 
+static hipError_t wht_absmax_dispatch(const float *in, int64_t n, int K, int Kp, unsigned *absmax_bits, float *partial,
+                                      int qmax, double c1_over_sa, float *dyn, int *count_out, hipStream_t st)
+{
+    switch (Kp) {
+        case 1: return launch_absmax<1>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 2: return launch_absmax<2>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 4: return launch_absmax<4>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 8: return launch_absmax<8>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 16: return launch_absmax<16>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 32: return launch_absmax<32>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 64: return launch_absmax<64>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 128: return launch_absmax<128>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 256: return launch_absmax<256>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        case 512: return launch_absmax<512>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, count_out, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t dhq_launch_wht_absmax(const float *in, int64_t n, int K, int Kp, unsigned *absmax_bits, float *partial,
                                  int qmax, double c1_over_sa, float *dyn, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     if (!partial || !absmax_bits) return hipErrorInvalidValue;
-    switch (Kp) {
-        case 1: return launch_absmax<1>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 2: return launch_absmax<2>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 4: return launch_absmax<4>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 8: return launch_absmax<8>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 16: return launch_absmax<16>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 32: return launch_absmax<32>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 64: return launch_absmax<64>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 128: return launch_absmax<128>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 256: return launch_absmax<256>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        case 512: return launch_absmax<512>(in, n, K, absmax_bits, partial, qmax, c1_over_sa, dyn, st);
-        default: return hipErrorInvalidValue;
-    }
+    return wht_absmax_dispatch(in, n, K, Kp, absmax_bits, partial, qmax, c1_over_sa, dyn, nullptr, st);
+}
+
+hipError_t dhq_launch_wht_absmax_partials(const float *in, int64_t n, int K, int Kp, float *partial, int *count,
+                                          hipStream_t st)
+{
+    if (n <= 0 || !partial || !count) return hipErrorInvalidValue;
+    return wht_absmax_dispatch(in, n, K, Kp, nullptr, partial, 0, 0.0, nullptr, count, st);
 }
 
 // ------------------------------------------------------------------------- int8 GEMM, MFMA
