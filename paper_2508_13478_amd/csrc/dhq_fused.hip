@@ -465,16 +465,15 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fu
         }
         if (!landed) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // the weights are in LDS
             landed = true;
         }
-        __syncthreads();  // the weights are in LDS; later passes: keeps the waves' phases aligned
         if constexpr (MODE == 2) {
             fused_output_layer<NKB>(wA, reinterpret_cast<const float *>(lds + MT * KB * 1024), cd, c1, A.out, ci, valid, A.m_out,
                                     lane, h);
         } else {
             dhq_v16f xt[NT];
             fused_gemm_sine_hm<NT, KB, NKB>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, xt, hA, lane, h);
-            __syncthreads();
             fused_tile_stages<NT>(xt);
 #pragma unroll
             for (int q = 0; q < NR / 4; ++q) {
