@@ -358,27 +358,21 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     }
     __syncthreads();
 
-    dhq_v16i acc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0;
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        if (t < ntile) {
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const dhq_v4i w = lds[(t * NKB + kb) * 64 + lane];
-                acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kb], w, acc[t], 0, 0, 0);
-            }
-        }
-    }
+    // tile after tile: a tile's epilogue and stores follow its MFMAs directly, so the stores of one
+    // tile travel while the next one is multiplied
     // accumulator v of this lane: coordinate row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (tile0 + t) + c
     const int64_t row0 = (int64_t)blockIdx.x * 128 + wave * 32;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         if (t >= ntile) break;
+        dhq_v16i acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            const dhq_v4i w = lds[(t * NKB + kb) * 64 + lane];
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kb], w, acc, 0, 0, 0);
+        }
         const int f = (tile0 + t) * 32 + c;
         if (f >= M) continue;
         const float bf = ACT ? bias[f] : 0.f;
@@ -387,9 +381,9 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
             const int64_t r = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (r >= n) continue;
             if (ACT)
-                act_out[r * M + f] = dhq_epilogue(acc[t][v], c1, bf, sine != 0);
+                act_out[r * M + f] = dhq_epilogue(acc[v], c1, bf, sine != 0);
             else
-                acc_out[r * M + f] = acc[t][v];
+                acc_out[r * M + f] = acc[v];
         }
     }
 }
