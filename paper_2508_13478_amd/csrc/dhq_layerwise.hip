@@ -322,12 +322,13 @@ hipError_t dhq_launch_wht_absmax_partials(const float *in, int64_t n, int K, int
 // 128-byte lines (the other orientation, which the fused kernels need for their in-register
 // transform, would write 32-byte pieces of 32 different lines).
 //
-// A workgroup of 4 waves covers 128 coordinates x up to 4 M tiles (128 features); the weight
+// A workgroup of GEMM_WAVES waves covers 32 coordinates per wave x up to 4 M tiles (128 features); the weight
 // fragments of its tiles are copied once into LDS ([tile][k block][lane] x 16 B, the order
 // they are stored in device memory) and read back conflict-free with one 16-byte LDS load
 // per lane.  Codes are read straight from device memory.
+#define GEMM_WAVES 8  // waves per workgroup: 32 coordinates each, sharing the staged weight fragments
 template <int NKB, bool ACT>
-__global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restrict__ codes, int64_t n,
+__global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int8_t *__restrict__ codes, int64_t n,
                                                            const int8_t *__restrict__ wfrag, int M, int Mt,
                                                            int32_t *__restrict__ acc_out,
                                                            float *__restrict__ act_out, float c1,
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     const int ntile = min(4, Mt - tile0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
-    const int64_t row = (int64_t)blockIdx.x * 128 + wave * 32 + c;
+    const int64_t row = (int64_t)blockIdx.x * (32 * GEMM_WAVES) + wave * 32 + c;
     const int64_t rrow = row < n ? row : n - 1;  // tail lanes read a valid row, store nothing
     const dhq_v4i *brow = reinterpret_cast<const dhq_v4i *>(codes + rrow * KP + 16 * h);
 
@@ -354,14 +355,14 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(const int8_t *__restr
     {
         const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(wfrag) + (size_t)tile0 * NKB * 64;
         const int total = ntile * NKB * 64;
-        for (int i = threadIdx.x; i < total; i += 256) lds[i] = src[i];
+        for (int i = threadIdx.x; i < total; i += 64 * GEMM_WAVES) lds[i] = src[i];
     }
     __syncthreads();
 
     // tile after tile: a tile's epilogue and stores follow its MFMAs directly, so the stores of one
     // tile travel while the next one is multiplied
     // accumulator v of this lane: coordinate row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (tile0 + t) + c
-    const int64_t row0 = (int64_t)blockIdx.x * 128 + wave * 32;
+    const int64_t row0 = (int64_t)blockIdx.x * (32 * GEMM_WAVES) + wave * 32;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         if (t >= ntile) break;
@@ -479,7 +480,7 @@ static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int6
                                    float *act_out, float c1, const float *bias, bool sine, const float *dyn,
                                    hipStream_t st)
 {
-    dim3 grid((unsigned)((n + 127) / 128), (unsigned)((L.Mt + 3) / 4));
+    dim3 grid((unsigned)((n + 32 * GEMM_WAVES - 1) / (32 * GEMM_WAVES)), (unsigned)((L.Mt + 3) / 4));
     const size_t lds = (size_t)(L.Mt < 4 ? L.Mt : 4) * NKB * 1024;
     if (act_out) {
         auto kern = gemm_i8_mfma_kernel<NKB, true>;
@@ -487,14 +488,14 @@ static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int6
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, sine ? 1 : 0, dyn);
+        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, sine ? 1 : 0, dyn);
     } else {
         auto kern = gemm_i8_mfma_kernel<NKB, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 256, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, sine ? 1 : 0, dyn);
+        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, sine ? 1 : 0, dyn);
     }
     return hipGetLastError();
 }
