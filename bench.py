@@ -130,7 +130,7 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (the coordinate grid shards "
+        print("bench.py: this benchmark runs on one GPU; --gpus must be 1 (the coordinate grid shards "
               "trivially, but no multi-GPU path is part of it)", file=sys.stderr)
         return 2
 

@@ -46,7 +46,7 @@ extern "C" {
 typedef enum {
     DHQ_OK = 0,
     DHQ_EINVAL = -1,       /* null pointer, negative size, bad bit width, non-finite scale ... */
-    DHQ_EUNSUPPORTED = -2, /* a shape or flag this build has no kernel for */
+    DHQ_EUNSUPPORTED = -2, /* a shape or flag the library has no kernel for */
     DHQ_ENOMEM = -3,       /* host or device allocation failed */
     DHQ_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
     DHQ_ENOSCALE = -5      /* forward called before activation scales exist */
