@@ -240,6 +240,26 @@ def test_dynamic_per_layer_fused_shapes_and_ragged_rows(dims):
     m.close()
 
 
+@pytest.mark.parametrize("bits", [4, 6])
+def test_dynamic_per_layer_fused_low_bits(bits):
+    torch = _torch()
+    _say(f"dynamic per-layer fused bits {bits}")
+    wl, coords, W, b = synth.make("C1")
+    m = dhq.Model(wl.dims, wl.omega0, W, b, bits, bits)
+    net = o.quantize_net(wl.dims, wl.omega0, bits, bits, W, b)
+    exp = o.forward(net, coords, calibrate=True)
+    x = _dev(coords)
+    dyn = m.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    s_dyn = m.dynamic_scales()
+    m.set_act_scales(s_dyn)
+    sta = m.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+    assert (np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a).max() <= 1e-5
+    _gate(dyn.cpu().numpy(), exp, wl.dims, False, f"bits {bits}")
+    m.close()
+
+
 def test_dynamic_scales_follow_the_batch_and_workspace_grows():
     torch = _torch()
     wl, coords, W, b = synth.make("C2")
