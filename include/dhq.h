@@ -55,11 +55,11 @@ typedef enum {
 /* dhq_forward flags: which implementation runs.  0 picks the fused kernel when the
  * network shape has one and the layer-by-layer path otherwise. */
 #define DHQ_AUTO 0u
-#define DHQ_LAYERWISE 1u /* three kernels per layer, activations round-trip device memory */
+#define DHQ_LAYERWISE 1u /* two to four kernels per layer, activations round-trip device memory */
 #define DHQ_FUSED 2u     /* one kernel for the whole network; DHQ_EUNSUPPORTED if the shape has none */
 /* or-ed onto the above: measure every layer's activation scale on line, on this call's own
  * coordinates, instead of using the scales stored in the model (Sec. 3.3, "dynamic
- * quantization module ... between layers").  With DHQ_LAYERWISE: three kernels per layer on any
+ * quantization module ... between layers").  With DHQ_LAYERWISE: an absmax pass added to every layer, any
  * shape.  With DHQ_FUSED (and DHQ_AUTO where available): one kernel per layer that keeps the
  * layer's arithmetic in registers and passes only the transformed activations through device
  * memory; exists for input-side rotation on the shapes the whole-network kernel for hidden
