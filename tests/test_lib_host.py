@@ -112,6 +112,20 @@ def test_wide_register_map_check_catches_violations():
     b.check_wide_register_map(other)
 
 
+def test_packing_index_maps(tmp_path):
+    """The maps behind the fused kernels' offline packing (which rotated feature a lane's register holds,
+    where a feature's bias sits) are permutations and agree with the MFMA accumulator layout."""
+    import subprocess
+    from paper_2508_13478_amd import build as b
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "index_maps_check")
+    subprocess.run([b._hipcc(), "--offload-arch=gfx950", "-O1", "-w", "-I", os.path.join(root, "include"), "-I", b.CSRC,
+                    os.path.join(root, "tests", "c", "index_maps_check.hip"), "-o", exe], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "index_maps ok" in r.stdout
+
+
 def test_two_sided_int32_bound_is_enforced_before_the_device_is_touched():
     """One non-zero weight in a 512 x 512 layer rotates into 512 x 512 equal codes of +-127; with
     all activation codes at 127 the un-rotated sum reaches 127 * 127 * 512 * 512 > 2^31.  The
