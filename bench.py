@@ -157,9 +157,9 @@ def main() -> int:
     _, s_a = model.scales()
     fused = model.has_fused() and not dynamic and (args.path == "auto" or floating)
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
-    # dynamic scales: one fused kernel per layer where the library has them (input-side rotation,
-    # hidden width <= 256), the layer-by-layer kernels otherwise or with --path layerwise
-    dyn_fused = dynamic and not two_sided and args.path == "auto" and model.has_fused() and wl.dims[1] <= 256
+    # dynamic scales: one fused kernel per layer where the library has them (hidden width <= 256;
+    # two-sided: fan-out <= 4 as well), the layer-by-layer kernels otherwise or with --path layerwise
+    dyn_fused = dynamic and args.path == "auto" and model.has_fused() and wl.dims[1] <= 256
     if dynamic:
         flags = (dhq.DHQ_FUSED if dyn_fused else dhq.DHQ_LAYERWISE) | dhq.DHQ_DYNAMIC
 
@@ -248,7 +248,8 @@ def main() -> int:
         gbs = per_coord * n / (ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
                            "traffic": None,
-                           "kernel": ("dhq_fused_layer_kernel, all launches of one forward" if dyn_fused
+                           "kernel": (("dhq_fused2_layer_kernel" if two_sided else "dhq_fused_layer_kernel") +
+                                      ", all launches of one forward" if dyn_fused
                                       else "layer-by-layer path, all kernels of one forward"),
                            "algorithmic_hbm_bytes_per_launch": per_coord * n,
                            "algorithmic_ops_per_launch": ops}

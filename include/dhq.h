@@ -62,8 +62,8 @@ typedef enum {
  * quantization module ... between layers").  With DHQ_LAYERWISE: an absmax pass added to every layer, any
  * shape.  With DHQ_FUSED (and DHQ_AUTO where available): one kernel per layer that keeps the
  * layer's arithmetic in registers and passes only the transformed activations through device
- * memory; exists for input-side rotation on the shapes the whole-network kernel for hidden
- * widths 32 .. 256 covers, DHQ_EUNSUPPORTED otherwise. */
+ * memory; exists on the shapes the whole-network kernels for hidden widths 32 .. 256 cover
+ * (either rotation mode), DHQ_EUNSUPPORTED otherwise. */
 #define DHQ_DYNAMIC 4u
 
 /* dhq_quantize_weights_mode: which sides of the weight matrix are rotated. */

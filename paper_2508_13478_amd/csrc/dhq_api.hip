@@ -442,7 +442,7 @@ static int ensure_dyn_workspace(dhq_model *m, int64_t n)
     m->dyn_acc = nullptr;
     m->dyn_rows = 0;
     // the per-layer fused kernels store whole workgroup tiles
-    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (size_t)n;
+    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (m->fused2 ? dhq_fused2_dynamic_rows(n) : (size_t)n);
     const size_t act_bytes = sizeof(float) * rows * m->max_dim;
     if (hipMalloc((void **)&m->dyn_act0, act_bytes) != hipSuccess) return DHQ_ENOMEM;
     if (hipMalloc((void **)&m->dyn_act1, act_bytes) != hipSuccess) return DHQ_ENOMEM;
@@ -468,11 +468,12 @@ static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, flo
     if (rc != DHQ_OK) return rc;
     const int L = m->n_layers;
     float *partial = reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS);
-    if (per_layer_fused)
-        return dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st) ==
-                       hipSuccess
-                   ? DHQ_OK
-                   : DHQ_EHIP;
+    if (per_layer_fused) {
+        const hipError_t e =
+            m->fused2 ? dhq_fused2_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st)
+                      : dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st);
+        return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    }
     if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
     const float *cur = coords_dev;
     float *bufs[2] = {m->dyn_act0, m->dyn_act1};
@@ -500,7 +501,7 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     const uint32_t path = flags & 3u;
     const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
-    const bool dyn_fused_ok = m->fused && !m->rot_out;  // per-layer fused kernels of the dynamic mode
+    const bool dyn_fused_ok = m->fused || m->fused2;  // per-layer fused kernels of the dynamic mode
     if (dynamic && path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
     if (m->flt && (dynamic || path == DHQ_LAYERWISE)) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;

@@ -96,6 +96,154 @@ __device__ __forceinline__ void f2_gemm(const dhq_v4i *__restrict__ wA, const dh
     }
 }
 
+// A operand of the H_32 products of W: this lane supplies row c of H_32 at the contraction
+// slots 8 h + j of block kk; slot j of lane half u carries the value at location (s, u),
+// s % 16 = 8 kk + j, i.e. (after U) feature 8 ((s >> 2) & 3) + 4 (s & 1) + (s & 2) + u of its tile.
+__device__ __forceinline__ void f2_h32_operand(int c, int h, dhq_v4i (&hA)[2])
+{
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int v = 8 * kk + 2 * d;  // locations v (bit 0 clear) and v + 1
+            const int i0 = 8 * (v >> 2) + (v & 2) + h;
+            hA[kk][d] = (int)hm_h32_pair(c, i0, i0 + 4);
+        }
+    }
+}
+
+// Input layer: rotate the coordinate vector (fan-in <= 4) and quantize it; the four codes are
+// bytes 0..3 of the first operand word.
+__device__ __forceinline__ int f2_input_codes(const float *__restrict__ coords, int64_t cl, int k0, int k0p, float inv, int qmax)
+{
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (k0 == 2) {
+        const float2 xy = *reinterpret_cast<const float2 *>(coords + cl * 2);
+        v[0] = xy.x; v[1] = xy.y;
+    } else {
+        for (int k = 0; k < k0; ++k) v[k] = coords[cl * k0 + k];
+    }
+    if (k0p >= 2) {
+        float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
+        a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
+    }
+    if (k0p == 4) {
+        float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
+        a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
+    }
+    return (int)dhq_pack4(dhq_quant_bits(v[0], inv, qmax), dhq_quant_bits(v[1], inv, qmax), dhq_quant_bits(v[2], inv, qmax),
+                          dhq_quant_bits(v[3], inv, qmax));
+}
+
+// One hidden layer, G to W: codes cd -> un-normalised transform xt of the layer's activations.
+// wA: the layer's A fragments, wB: its biases in location order (both in LDS).
+template <int NT, int KB, int NCD>
+__device__ __forceinline__ void f2_hidden_layer(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
+                                                const dhq_v4i (&cd)[NCD], float c1, const dhq_v4i (&hA)[2], dhq_v16f (&xt)[NT],
+                                                int lane, int h)
+{
+    constexpr int NR = 16 * NT;
+    // G: rotated accumulators of all output tiles
+    dhq_v16i acc[NT];
+    f2_gemm<NT, KB, NCD>(wA, cd, acc, lane);
+    int z[NR];
+#pragma unroll
+    for (int T = 0; T < NT; ++T)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z[16 * T + v] = acc[T][v];
+    // U: z = H acc' in int32 (wrapping adds; the host has checked that the results fit)
+#pragma unroll
+    for (int s = 1; s < NR; s <<= 1) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            if ((i & s) == 0) {
+                const unsigned a = (unsigned)z[i], b = (unsigned)z[i | s];
+                z[i] = (int)(a + b);
+                z[i | s] = (int)(a - b);
+            }
+        }
+    }
+    float x[NR];
+    // the stage over the lane-half bit, then E: dequantize + bias + sine (biases in location order)
+#pragma unroll
+    for (int pr = 0; pr < NR / 2; ++pr) {
+        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)z[2 * pr], (unsigned)z[2 * pr + 1], false, false);
+        const int z0 = (int)(r[0] + r[1]), z1 = (int)(r[0] - r[1]);
+        const float4 bb = wB[(pr >> 1) * 2 + h];
+        const float b0 = (pr & 1) ? bb.z : bb.x, b1 = (pr & 1) ? bb.w : bb.y;
+        x[2 * pr] = dhq_sin_rev(__builtin_fmaf((float)z0, c1, b0));
+        x[2 * pr + 1] = dhq_sin_rev(__builtin_fmaf((float)z1, c1, b1));
+    }
+    // W: forward transform of the next layer's input.  The factor H_32 over the 32 features of a
+    // tile goes to the matrix unit as in dhq_fused.hip (activations split into two binary16
+    // pieces, four MFMAs per tile); the stages over the tile index follow in registers.  The
+    // MFMA's D layout is the natural accumulator order P0 again.
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+        unsigned hp[8], lp[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d) hm_split_pair(x[16 * T + 2 * d], x[16 * T + 2 * d + 1], hp[d], lp[d]);
+        dhq_v16f acc_t;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_t[v] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {  // small pieces first: lo, hi of block 0, then of block 1
+            const int blk = k >> 1;
+            dhq_v4i b;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) b[d] = (int)((k & 1) ? hp[4 * blk + d] : lp[4 * blk + d]);
+            acc_t = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(dhq_v8h, hA[blk]), __builtin_bit_cast(dhq_v8h, b),
+                                                           acc_t, 0, 0, 0);
+        }
+        xt[T] = acc_t;
+    }
+#pragma unroll
+    for (int s = 1; s < NT; s <<= 1) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            if ((T & s) == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float a = xt[T][v], b = xt[T | s][v];
+                    xt[T][v] = a + b;
+                    xt[T | s][v] = a - b;
+                }
+            }
+        }
+    }
+}
+
+// Output layer: one zero-padded tile; rows e = 0..3 of lane half 0 carry the (<= 4) rotated
+// outputs, un-rotated by two butterfly stages.  wB: the biases in plain order.
+template <int NKB>
+__device__ __forceinline__ void f2_output_layer(const dhq_v4i *__restrict__ wA, const float *__restrict__ wB,
+                                                const dhq_v4i (&cd)[NKB], float c1, float *__restrict__ out, int64_t ci, bool valid,
+                                                int m_out, int m_out_p, int lane, int h)
+{
+    dhq_v16i acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+        const dhq_v4i a = wA[kb * 64 + lane];
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
+    }
+    unsigned z[4] = {(unsigned)acc[0], (unsigned)acc[1], (unsigned)acc[2], (unsigned)acc[3]};
+    if (m_out_p >= 2) {
+        unsigned a = z[0], b = z[1]; z[0] = a + b; z[1] = a - b;
+        a = z[2]; b = z[3]; z[2] = a + b; z[3] = a - b;
+    }
+    if (m_out_p == 4) {
+        unsigned a = z[0], b = z[2]; z[0] = a + b; z[2] = a - b;
+        a = z[1]; b = z[3]; z[1] = a + b; z[3] = a - b;
+    }
+    if (valid && h == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e < m_out) out[ci * m_out + e] = __builtin_fmaf((float)(int)z[e], c1, wB[e]);
+    }
+}
+
 template <int NF>
 __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
 {
@@ -111,19 +259,8 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
     const int64_t n_tiles = (A.n + F2_TILE - 1) / F2_TILE;
     const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
 
-    // A operand of the H_32 products of W: this lane supplies row c of H_32 at the contraction
-    // slots 8 h + j of block kk; slot j of lane half u carries the value at location (s, u),
-    // s % 16 = 8 kk + j, i.e. (after U) feature 8 ((s >> 2) & 3) + 4 (s & 1) + (s & 2) + u of its tile.
     dhq_v4i hA[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int v = 8 * kk + 2 * d;  // locations v (bit 0 clear) and v + 1
-            const int i0 = 8 * (v >> 2) + (v & 2) + h;
-            hA[kk][d] = (int)hm_h32_pair(c, i0, i0 + 4);
-        }
-    }
+    f2_h32_operand(c, h, hA);
 
     int p = 0;
     if ((int64_t)blockIdx.x < n_tiles)
@@ -137,27 +274,7 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
         dhq_v4i cd[NKB];
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
-        {
-            // input layer: rotate the coordinate vector (fan-in <= 4) and quantize it
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (A.k0 == 2) {
-                const float2 xy = *reinterpret_cast<const float2 *>(A.coords + cl * 2);
-                v[0] = xy.x; v[1] = xy.y;
-            } else {
-                for (int k = 0; k < A.k0; ++k) v[k] = A.coords[cl * A.k0 + k];
-            }
-            if (A.k0p >= 2) {
-                float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
-                a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
-            }
-            if (A.k0p == 4) {
-                float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
-                a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
-            }
-            const float inv = A.layer[0].inv_in;
-            cd[0][0] = (int)dhq_pack4(dhq_quant_bits(v[0], inv, A.qmax), dhq_quant_bits(v[1], inv, A.qmax),
-                                      dhq_quant_bits(v[2], inv, A.qmax), dhq_quant_bits(v[3], inv, A.qmax));
-        }
+        cd[0][0] = f2_input_codes(A.coords, cl, A.k0, A.k0p, A.layer[0].inv_in, A.qmax);
 
         for (int l = 0; l < L - 1; ++l) {
             // weights of layer l have landed; everyone is done with the other buffer
@@ -170,79 +287,12 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const int Kb = (l == 0) ? 1 : NKB;
             const float4 *wB = reinterpret_cast<const float4 *>(lds + p * BLK + NT * Kb * 1024);
-            // G: rotated accumulators of all output tiles
-            dhq_v16i acc[NT];
-            if (l == 0)
-                f2_gemm<NT, 1, NKB>(wA, cd, acc, lane);
-            else
-                f2_gemm<NT, NKB, NKB>(wA, cd, acc, lane);
-            int z[NR];
-#pragma unroll
-            for (int T = 0; T < NT; ++T)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) z[16 * T + v] = acc[T][v];
-            // U: z = H acc' in int32 (wrapping adds; the host has checked that the results fit)
-#pragma unroll
-            for (int s = 1; s < NR; s <<= 1) {
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    if ((i & s) == 0) {
-                        const unsigned a = (unsigned)z[i], b = (unsigned)z[i | s];
-                        z[i] = (int)(a + b);
-                        z[i | s] = (int)(a - b);
-                    }
-                }
-            }
-            float x[NR];
-            const float c1 = A.layer[l].c1;
-            // the stage over the lane-half bit, then E: dequantize + bias + sine (biases in location order)
-#pragma unroll
-            for (int pr = 0; pr < NR / 2; ++pr) {
-                const auto r = __builtin_amdgcn_permlane32_swap((unsigned)z[2 * pr], (unsigned)z[2 * pr + 1], false, false);
-                const int z0 = (int)(r[0] + r[1]), z1 = (int)(r[0] - r[1]);
-                const float4 bb = wB[(pr >> 1) * 2 + h];
-                const float b0 = (pr & 1) ? bb.z : bb.x, b1 = (pr & 1) ? bb.w : bb.y;
-                x[2 * pr] = dhq_sin_rev(__builtin_fmaf((float)z0, c1, b0));
-                x[2 * pr + 1] = dhq_sin_rev(__builtin_fmaf((float)z1, c1, b1));
-            }
-            // W: forward transform of the next layer's input and its quantizer.  The factor H_32 over
-            // the 32 features of a tile goes to the matrix unit as in dhq_fused.hip (activations split
-            // into two binary16 pieces, four MFMAs per tile); the stages over the tile index follow in
-            // registers.  The MFMA's D layout is the natural accumulator order P0 again.
             dhq_v16f xt[NT];
-#pragma unroll
-            for (int T = 0; T < NT; ++T) {
-                unsigned hp[8], lp[8];
-#pragma unroll
-                for (int d = 0; d < 8; ++d) hm_split_pair(x[16 * T + 2 * d], x[16 * T + 2 * d + 1], hp[d], lp[d]);
-                dhq_v16f acc_t;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc_t[v] = 0.f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {  // small pieces first: lo, hi of block 0, then of block 1
-                    const int blk = k >> 1;
-                    dhq_v4i b;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) b[d] = (int)((k & 1) ? hp[4 * blk + d] : lp[4 * blk + d]);
-                    acc_t = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(dhq_v8h, hA[blk]),
-                                                                   __builtin_bit_cast(dhq_v8h, b), acc_t, 0, 0, 0);
-                }
-                xt[T] = acc_t;
-            }
-#pragma unroll
-            for (int s = 1; s < NT; s <<= 1) {
-#pragma unroll
-                for (int T = 0; T < NT; ++T) {
-                    if ((T & s) == 0) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float a = xt[T][v], b = xt[T | s][v];
-                            xt[T][v] = a + b;
-                            xt[T | s][v] = a - b;
-                        }
-                    }
-                }
-            }
+            if (l == 0)
+                f2_hidden_layer<NT, 1, NKB>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h);
+            else
+                f2_hidden_layer<NT, NKB, NKB>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h);
+            // the next layer's quantizer
             const float inv = A.layer[l + 1].inv_in;
 #pragma unroll
             for (int w = 0; w < NR / 4; ++w) {
@@ -254,38 +304,128 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
             p ^= 1;
         }
 
-        // output layer: one zero-padded tile; rows e = 0..3 of lane half 0 carry the (<= 4) rotated outputs
         {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             if (tile + gridDim.x < n_tiles)
                 fused_issue_copy(A.blob + A.layer[0].blob_off, lds + (p ^ 1) * BLK, (int)A.layer[0].chunks, wave, lane, F2_WAVES);
-            const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
-            const float *wB = reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024);
-            dhq_v16i acc;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0;
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const dhq_v4i a = wA[kb * 64 + lane];
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
-            }
-            unsigned z[4] = {(unsigned)acc[0], (unsigned)acc[1], (unsigned)acc[2], (unsigned)acc[3]};
-            if (A.m_out_p >= 2) {
-                unsigned a = z[0], b = z[1]; z[0] = a + b; z[1] = a - b;
-                a = z[2]; b = z[3]; z[2] = a + b; z[3] = a - b;
-            }
-            if (A.m_out_p == 4) {
-                unsigned a = z[0], b = z[2]; z[0] = a + b; z[2] = a - b;
-                a = z[1]; b = z[3]; z[1] = a + b; z[3] = a - b;
-            }
-            const float c1 = A.layer[L - 1].c1;
-            if (valid && h == 0) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (e < A.m_out) A.out[ci * A.m_out + e] = __builtin_fmaf((float)(int)z[e], c1, wB[e]);
-            }
+            f2_output_layer<NKB>(reinterpret_cast<const dhq_v4i *>(lds + p * BLK), reinterpret_cast<const float *>(lds + p * BLK + NKB * 1024),
+                                 cd, A.layer[L - 1].c1, A.out, ci, valid, A.m_out, A.m_out_p, lane, h);
             p ^= 1;
+        }
+    }
+}
+
+// With scales measured on line the network is cut at every quantizer, as in dhq_fused.hip: one
+// launch per layer folds the per-workgroup maxima of its input into the layer's constants,
+// quantizes, runs G, U, E and W of the layer and stores the transformed output x^ (fp32, in the
+// lanes' register order: [wave tile][float4 q][lane]) plus each workgroup's max |x^|.
+//   MODE 0  input layer: coordinates in, x^ out        MODE 1  hidden layer: x^ in, x^ out
+//   MODE 2  output layer: x^ in, signal values out
+struct f2l_args {
+    const float *coords;       // MODE 0
+    const float4 *xin;         // MODE 1, 2
+    float4 *xout;              // MODE 0, 1
+    float *out;                // MODE 2
+    const unsigned char *blk;  // this layer's block of the packed weights (fragments, then biases)
+    const float *partial_in;   // max |x^| of this layer's input, one float per workgroup of the launch before
+    int partial_count;
+    int kp;                    // length of this layer's rotated input
+    double c1_over_sa;         // epilogue multiplier divided by the activation scale
+    float *dyn;                // this layer's {1 / (s_a sqrt(Kp)), epilogue multiplier, s_a}: written by workgroup 0
+    float *partial;            // MODE 0, 1: max |x^| of the output per workgroup (not the buffer partial_in points to)
+    int64_t n;
+    int chunks;                // block size in KiB
+    int k0, k0p, m_out, m_out_p, qmax;
+};
+
+template <int NF, int MODE>
+__global__ __launch_bounds__(F2_THREADS) void dhq_fused2_layer_kernel(const f2l_args A)
+{
+    constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
+    constexpr int KB = (MODE == 0) ? 1 : NKB;  // k blocks of this layer's GEMM
+    constexpr int MT = (MODE == 2) ? 1 : NT;   // M tiles of this layer's GEMM
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ float red_in[F2_WAVES], red[F2_WAVES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t n_tiles = (A.n + F2_TILE - 1) / F2_TILE;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+    dhq_v4i hA[2];
+    f2_h32_operand(c, h, hA);
+    fused_issue_copy(A.blk, lds, A.chunks, wave, lane, F2_WAVES);
+    // this layer's constants from the maxima of its input
+    float inv, c1, s_a;
+    {
+        float mi = 0.f;
+        for (int i = threadIdx.x; i < A.partial_count; i += F2_THREADS) mi = fmaxf(mi, A.partial_in[i]);
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mi = fmaxf(mi, __shfl_xor(mi, m, 64));
+        if (lane == 0) red_in[wave] = mi;
+        __syncthreads();
+        mi = red_in[0];
+#pragma unroll
+        for (int w = 1; w < F2_WAVES; ++w) mi = fmaxf(mi, red_in[w]);
+        dhq_dyn_constants(mi, A.kp, A.qmax, A.c1_over_sa, inv, c1, s_a);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            A.dyn[0] = inv; A.dyn[1] = c1; A.dyn[2] = s_a;
+        }
+    }
+    const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds);
+    float mx = 0.f;
+    bool landed = false;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t ci = tile * F2_TILE + wave * 32 + c;
+        const bool valid = ci < A.n;
+        const int64_t cl = valid ? ci : A.n - 1;  // lanes past the end repeat the last coordinate: no effect on the maximum
+        const size_t slot = ((size_t)tile * F2_WAVES + wave) * (NR / 4) * 64 + lane;
+        dhq_v4i cd[NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        if constexpr (MODE == 0) {
+            cd[0][0] = f2_input_codes(A.coords, cl, A.k0, A.k0p, inv, A.qmax);
+        } else {
+#pragma unroll
+            for (int q = 0; q < NR / 4; ++q) {
+                const float4 x = A.xin[slot + (size_t)q * 64];
+                unsigned packed = 0;
+                fused_quant_byte(packed, x.x, inv, qlo, qhi, 0);
+                fused_quant_byte(packed, x.y, inv, qlo, qhi, 1);
+                fused_quant_byte(packed, x.z, inv, qlo, qhi, 2);
+                fused_quant_byte(packed, x.w, inv, qlo, qhi, 3);
+                cd[q / 4][q % 4] = (int)packed;
+            }
+        }
+        if (!landed) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // the weights are in LDS
+            landed = true;
+        }
+        if constexpr (MODE == 2) {
+            f2_output_layer<NKB>(wA, reinterpret_cast<const float *>(lds + MT * KB * 1024), cd, c1, A.out, ci, valid, A.m_out,
+                                 A.m_out_p, lane, h);
+        } else {
+            dhq_v16f xt[NT];
+            f2_hidden_layer<NT, KB, NKB>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, hA, xt, lane, h);
+#pragma unroll
+            for (int q = 0; q < NR / 4; ++q) {
+                const float4 x = make_float4(xt[q >> 2][4 * (q & 3)], xt[q >> 2][4 * (q & 3) + 1], xt[q >> 2][4 * (q & 3) + 2],
+                                             xt[q >> 2][4 * (q & 3) + 3]);
+                mx = fmaxf(fmaxf(mx, fmaxf(fabsf(x.x), fabsf(x.y))), fmaxf(fabsf(x.z), fabsf(x.w)));
+                A.xout[slot + (size_t)q * 64] = x;
+            }
+        }
+    }
+    if constexpr (MODE != 2) {
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        if (lane == 0) red[wave] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float r = red[0];
+#pragma unroll
+            for (int w = 1; w < F2_WAVES; ++w) r = fmaxf(r, red[w]);
+            A.partial[blockIdx.x] = r;
         }
     }
 }
@@ -344,6 +484,21 @@ int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan_out)
                         frag[((size_t)(T * Kb + kb) * 64 + ln) * 16 + jj] = val;
                     }
                 }
+        // the bias part of the block.  Hidden layers: location (s, u) holds true feature
+        // rot_index(s, u) after the un-rotation, and lane half u reads the biases of registers
+        // s .. s+3 as one float4 at index (s / 4) * 2 + u.  Output layer: plain order.
+        {
+            float *blk = reinterpret_cast<float *>(blob.data() + off + (size_t)Mt * Kb * 1024);
+            if (l == L - 1) {
+                for (int f = 0; f < Ly.M; ++f) blk[f] = Ly.bias_host[f];
+            } else {
+                for (int s = 0; s < nf / 2; ++s)
+                    for (int u = 0; u < 2; ++u) {
+                        const int f = rot_index(s, u);
+                        if (f < Ly.M) blk[((s >> 2) * 2 + u) * 4 + (s & 3)] = Ly.bias_rev_host[f];
+                    }
+            }
+        }
         P->args.layer[l].blob_off = (uint32_t)off;
         P->args.layer[l].chunks = (uint32_t)(bytes / 1024);
     }
@@ -383,32 +538,13 @@ void dhq_fused2_destroy(dhq_fused2_plan *P)
     delete P;
 }
 
-// Per-layer constants and the bias part of each block.  Hidden layers: location (s, u) holds
-// true feature rot_index(s, u) after the un-rotation, and lane half u reads the biases of
-// registers s .. s+3 as one float4 at index (s / 4) * 2 + u.  Output layer: plain order.
+// Per-layer constants of the static path.
 int dhq_fused2_update_scales(const dhq_model *m, dhq_fused2_plan *P)
 {
     if (!P) return DHQ_OK;
-    const int L = m->n_layers;
-    const int NT = P->nf / 32, NKB = P->nf / 32, NR = P->nf / 2;
-    for (int l = 0; l < L; ++l) {
-        const dhq_layer &Ly = m->layer[l];
-        const bool last = (l == L - 1);
+    for (int l = 0; l < m->n_layers; ++l) {
         P->args.layer[l].c1 = dhq_c1(m, l);
-        P->args.layer[l].inv_in = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
-        const int Mt = last ? 1 : NT, Kb = (l == 0) ? 1 : NKB;
-        std::vector<float> blk(256, 0.0f);
-        if (last) {
-            for (int f = 0; f < Ly.M; ++f) blk[f] = Ly.bias_host[f];
-        } else {
-            for (int s = 0; s < NR; ++s)
-                for (int u = 0; u < 2; ++u) {
-                    const int f = rot_index(s, u);
-                    if (f < Ly.M) blk[((s >> 2) * 2 + u) * 4 + (s & 3)] = Ly.bias_rev_host[f];
-                }
-        }
-        unsigned char *dst = P->blob_dev + P->args.layer[l].blob_off + (size_t)Mt * Kb * 1024;
-        if (hipMemcpy(dst, blk.data(), 1024, hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
+        P->args.layer[l].inv_in = (float)(1.0 / ((double)m->layer[l].s_a * sqrt((double)m->layer[l].Kp)));
     }
     return DHQ_OK;
 }
@@ -440,4 +576,73 @@ hipError_t dhq_fused2_launch(const dhq_fused2_plan *P, const float *coords, int6
         case 256: return fused2_launch_t<256>(P, a, grid, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+// The dynamic mode on the per-layer kernels; arguments as for dhq_fused_dynamic_launch.
+size_t dhq_fused2_dynamic_rows(int64_t n) { return (size_t)((n + F2_TILE - 1) / F2_TILE) * F2_TILE; }
+
+template <int NF, int MODE>
+static hipError_t f2l_launch_t(const f2l_args &a, unsigned grid, hipStream_t st)
+{
+    auto kern = dhq_fused2_layer_kernel<NF, MODE>;
+    const size_t lds = (size_t)a.chunks * 1024;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, F2_THREADS, lds, st>>>(a);
+    return hipGetLastError();
+}
+template <int NF>
+static hipError_t f2l_launch_mode(int mode, const f2l_args &a, unsigned grid, hipStream_t st)
+{
+    switch (mode) {
+        case 0: return f2l_launch_t<NF, 0>(a, grid, st);
+        case 1: return f2l_launch_t<NF, 1>(a, grid, st);
+        default: return f2l_launch_t<NF, 2>(a, grid, st);
+    }
+}
+
+hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                     float *partial, float *dyn, hipStream_t st)
+{
+    const dhq_fused2_plan *P = m->fused2;
+    if (!P) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    const int L = m->n_layers;
+    const int64_t tiles = (n + F2_TILE - 1) / F2_TILE;
+    const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    // the input layer's scale: max over the rotated coordinates, left as per-workgroup maxima
+    float *pbuf[2] = {partial, partial + DHQ_ABSMAX_PARTIALS};
+    int count = 0;
+    hipError_t e = dhq_launch_wht_absmax_partials(coords, n, m->layer[0].K, m->layer[0].Kp, pbuf[0], &count, st);
+    if (e != hipSuccess) return e;
+    float *bufs[2] = {ws0, ws1};
+    for (int l = 0; l < L; ++l) {
+        f2l_args a;
+        memset(&a, 0, sizeof(a));
+        a.coords = coords;
+        a.xin = reinterpret_cast<const float4 *>(bufs[(l + 1) & 1]);
+        a.xout = reinterpret_cast<float4 *>(bufs[l & 1]);
+        a.out = out;
+        a.blk = P->blob_dev + P->args.layer[l].blob_off;
+        a.chunks = (int)P->args.layer[l].chunks;
+        a.partial_in = pbuf[l & 1];
+        a.partial_count = count;
+        a.kp = m->layer[l].Kp;
+        a.c1_over_sa = dhq_c1_over_sa(m, l);
+        a.dyn = dyn + 3 * l;
+        a.partial = pbuf[(l + 1) & 1];
+        a.n = n;
+        a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.m_out_p = P->args.m_out_p; a.qmax = P->args.qmax;
+        const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
+        switch (P->nf) {
+            case 32: e = f2l_launch_mode<32>(mode, a, grid, st); break;
+            case 64: e = f2l_launch_mode<64>(mode, a, grid, st); break;
+            case 128: e = f2l_launch_mode<128>(mode, a, grid, st); break;
+            case 256: e = f2l_launch_mode<256>(mode, a, grid, st); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+        count = (int)grid;
+    }
+    return hipSuccess;
 }

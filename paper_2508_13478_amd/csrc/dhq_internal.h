@@ -150,6 +150,9 @@ int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan);
 void dhq_fused2_destroy(dhq_fused2_plan *plan);
 int dhq_fused2_update_scales(const dhq_model *m, dhq_fused2_plan *plan);
 hipError_t dhq_fused2_launch(const dhq_fused2_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
+size_t dhq_fused2_dynamic_rows(int64_t n);
+hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                     float *partial, float *dyn, hipStream_t st);
 
 // Floating-point activations (defined in dhq_float.hip): the plain SIREN on the given fp32
 // weights W[l] (dims[l+1] x dims[l]) and biases, fused over all layers.  DHQ_EUNSUPPORTED if

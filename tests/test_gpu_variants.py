@@ -260,6 +260,55 @@ def test_dynamic_per_layer_fused_low_bits(bits):
     m.close()
 
 
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_dynamic_per_layer_fused_two_sided_equals_static_fused_with_its_scales(name):
+    """The same cut for the two-sided variant: one kernel per layer that runs the two-sided fused
+    kernel's arithmetic, hence the same bits as that kernel with the measured scales."""
+    torch = _torch()
+    _say(f"dynamic per-layer fused two-sided {name}")
+    wl, coords, W, b = synth.make(name)
+    x = _dev(coords)
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH)
+    dyn = m.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    s_dyn = m.dynamic_scales()
+    auto = m.forward(x, flags=dhq.DHQ_DYNAMIC)
+    lw = m.forward(x, flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
+    s_lw = m.dynamic_scales()
+    m.set_act_scales(s_dyn)
+    sta = m.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+    assert np.array_equal(dyn.cpu().numpy(), auto.cpu().numpy())
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=True)
+    exp = o.forward(net, coords, calibrate=True)
+    rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+    _say(f"  scale rel err vs oracle max {rel.max():.2e}; vs layer-by-layer {np.abs(s_dyn / s_lw - 1).max():.2e}")
+    assert rel.max() <= 1e-5 and np.abs(s_dyn / s_lw - 1).max() <= 1e-5
+    _gate(dyn.cpu().numpy(), exp, wl.dims, False, "dynamic per-layer fused two-sided vs oracle")
+    d = np.abs(dyn.cpu().numpy() - lw.cpu().numpy()).max(axis=1)
+    assert (d > OUT_TOL).mean() <= 2 * 1e-3
+    m.close()
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 1], [4, 128, 128, 2], [1, 256, 256, 4]])
+def test_dynamic_per_layer_fused_two_sided_shapes_and_ragged_rows(dims):
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 223 + len(dims))
+    m = dhq.Model(dims, 30.0, W, b, mode=dhq.DHQ_ROTATE_BOTH)
+    net = o.quantize_net(dims, 30.0, 8, 8, W, b, two_sided=True)
+    rng = np.random.default_rng(dims[1] + 2)
+    for n in (1, 257, 3000 + 11):
+        _say(f"dynamic per-layer fused two-sided dims {dims} n={n}")
+        xs = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        exp = o.forward(net, xs, calibrate=True)
+        dyn = m.forward(_dev(xs), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+        s_dyn = m.dynamic_scales()
+        torch.cuda.synchronize()
+        assert (np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a).max() <= 1e-5
+        _gate(dyn.cpu().numpy(), exp, dims, False, f"dims {dims} n={n}")
+    m.close()
+
+
 def test_dynamic_scales_follow_the_batch_and_workspace_grows():
     torch = _torch()
     wl, coords, W, b = synth.make("C2")
@@ -303,10 +352,12 @@ def test_variant_flags_are_checked():
         with pytest.raises(dhq.DhqError) as e:
             m.forward(x, flags=flags)
         assert e.value.status == status
-    # the per-layer fused kernels of the dynamic mode exist for input-side rotation and widths <= 256
+    # the per-layer fused kernels of the dynamic mode exist for widths <= 256 (two-sided: fan-out <= 4)
     wide_dims = [2, 512, 512, 3]
     Ww, bw = synth.siren_init(wide_dims, 30.0, 3)
-    for mm in (dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_ROTATE_BOTH), dhq.Model(wide_dims, 30.0, Ww, bw)):
+    out5 = list(wl.dims[:-1]) + [5]
+    W5, b5 = synth.siren_init(out5, 30.0, 3)
+    for mm in (dhq.Model(out5, wl.omega0, W5, b5, mode=dhq.DHQ_ROTATE_BOTH), dhq.Model(wide_dims, 30.0, Ww, bw)):
         with pytest.raises(dhq.DhqError) as e:
             mm.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
         assert e.value.status == dhq.DHQ_EUNSUPPORTED
@@ -461,7 +512,8 @@ def test_full_grid_sampled_outputs_of_the_variants(mode_name):
     m.close()
 
 
-@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "w32a32"])
+@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "dynamic_fused_two_sided",
+                                     "w32a32"])
 def test_forward_replays_from_a_captured_graph(variant):
     """dhq_forward only enqueues kernels (no memset, no allocation, no synchronisation once the
     workspace exists), so a stream capture of it replays to the same bits as the eager call --
@@ -470,9 +522,11 @@ def test_forward_replays_from_a_captured_graph(variant):
     _say(f"graph replay {variant}")
     wl, coords, W, b = synth.make("C1")
     x = _dev(coords)
-    mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
+    mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "dynamic_fused_two_sided": dhq.DHQ_ROTATE_BOTH,
+            "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
     flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC,
-             "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
+             "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
+             "dynamic_fused_two_sided": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
     m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode)
     if variant != "w32a32":
         m.calibrate(x)
