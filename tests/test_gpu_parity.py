@@ -380,6 +380,49 @@ def test_forward_generic_shape_layerwise_only():
     assert e.value.status == dhq.DHQ_EUNSUPPORTED
 
 
+# Sixteen layers is the most a model may have, 512 the widest dimension.  Free-running differences
+# grow with depth (a code that differs in layer 2 perturbs every layer after it, and after fifteen
+# sine layers the perturbation has passed through fifteen more quantizers), so at this depth the
+# strict statements are the teacher-forced ones: every layer's codes within the rate, its
+# accumulators exact.  End to end: every coordinate within FLIP_BOUND, every coordinate whose codes
+# agree with the oracle's at all layers within OUT_TOL, and the typical coordinate far inside it.
+@pytest.mark.parametrize("dims", [[4] + [256] * 15 + [32], [2] + [512] * 15 + [3], [512] * 17], ids=["256x15", "512x15", "512-512x15-512"])
+def test_sixteen_layers_and_widest_dimensions(dims):
+    torch = _torch()
+    _say(f"limits: {dims[0]}-{dims[1]}x{len(dims) - 2}-{dims[-1]}")
+    W, b = synth.siren_init(dims, 30.0, 1000 + len(dims) + dims[1])
+    rng = np.random.default_rng(5)
+    coords = rng.uniform(-1, 1, size=(1500 + 7, dims[0])).astype(np.float32)
+    cs = Case(dims, coords, W, b)
+    L = len(dims) - 1
+    assert cs.model.has_fused() == (dims[0] <= 4)
+    for l in range(L):
+        assert np.array_equal(cs.model.weight_codes(l), cs.net.Wq[l]), f"weight codes of layer {l}"
+    worst = 0.0
+    for l in range(L):
+        x = coords if l == 0 else cs.dump.act[l - 1]
+        codes, acc, act = cs.model.forward_debug(_dev(x), l)
+        torch.cuda.synchronize()
+        codes, acc = codes.cpu().numpy(), acc.cpu().numpy()
+        rate, mx = code_stats(codes, cs.dump.codes[l])
+        worst = max(worst, rate)
+        assert rate <= CODE_RATE and mx <= 1, f"layer {l}"
+        assert np.array_equal(acc, o.igemm(codes, cs.net.Wq[l])), f"layer {l}"
+    _say(f"  teacher-forced: worst code mismatch rate {worst:.2e}")
+    diff = _coords_with_code_diffs(cs, coords.shape[0])
+    paths = [("layerwise", dhq.DHQ_LAYERWISE)] + ([("fused", dhq.DHQ_FUSED)] if cs.model.has_fused() else [])
+    for label, flags in paths:
+        out = cs.model.forward(_dev(coords), flags=flags)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - cs.out).max(axis=1)
+        _say(f"  {label}: max-abs err {err.max():.3e}, median {np.median(err):.3e}, {(err > OUT_TOL).sum()} of {err.size} "
+             f"beyond {OUT_TOL}; {diff.sum()} coords with a code difference somewhere")
+        assert err.max() <= FLIP_BOUND and np.median(err) <= OUT_TOL / 4
+        if flags == dhq.DHQ_LAYERWISE:
+            assert err[~diff].max() <= OUT_TOL and diff[err > OUT_TOL].all()
+    cs.model.close()
+
+
 def test_clamp_outside_calibrated_range():
     """Coordinates beyond the calibration grid drive codes into the clamp."""
     _say("clamp")

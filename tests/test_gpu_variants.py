@@ -140,6 +140,43 @@ def test_two_sided_fused_shapes_and_ragged_rows(dims):
     assert not dhq.Model(dims5, 30.0, W5, b5, mode=dhq.DHQ_ROTATE_BOTH).has_fused()
 
 
+def test_two_sided_sixteen_layers():
+    """The deepest model the library takes, two-sided: the un-rotation's int32 sums are largest here
+    relative to nothing (they do not grow with depth), but every layer's descriptor slot is used.
+    Strict statements teacher-forced per layer; end to end as in the one-sided test of the limits."""
+    torch = _torch()
+    dims = [4] + [256] * 15 + [4]
+    W, b = synth.siren_init(dims, 30.0, 1016)
+    rng = np.random.default_rng(6)
+    coords = rng.uniform(-1, 1, size=(1500 + 7, 4)).astype(np.float32)
+    cs = TwoSided(dims, coords, W, b)
+    assert cs.model.has_fused()
+    for l in range(len(dims) - 1):
+        _say(f"two-sided 16 layers: layer {l}")
+        assert np.array_equal(cs.model.weight_codes(l), cs.net.Wq[l])
+        x = coords if l == 0 else cs.dump.act[l - 1]
+        codes, z, act = cs.model.forward_debug(_dev(x), l)
+        torch.cuda.synchronize()
+        codes, z = codes.cpu().numpy(), z.cpu().numpy()
+        rate, mx = code_stats(codes, cs.dump.codes[l])
+        assert rate <= CODE_RATE and mx <= 1
+        assert np.array_equal(z, o.unrotate_acc(o.igemm(codes, cs.net.Wq[l])))
+    x = _dev(coords)
+    for label, flags in (("layerwise", dhq.DHQ_LAYERWISE), ("fused", dhq.DHQ_FUSED)):
+        out = cs.model.forward(x, flags=flags)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - cs.out).max(axis=1)
+        _say(f"  {label}: max-abs err {err.max():.3e}, median {np.median(err):.3e}, {(err > OUT_TOL).sum()} of {err.size} beyond {OUT_TOL}")
+        assert err.max() <= FLIP_BOUND and np.median(err) <= OUT_TOL / 4
+    # the per-layer kernels of the dynamic mode at this depth: same bits as the whole-network kernel with their scales
+    dyn = cs.model.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    cs.model.set_act_scales(cs.model.dynamic_scales())
+    sta = cs.model.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+    cs.model.close()
+
+
 def test_two_sided_forward_odd_shapes_ragged_rows_and_chunks():
     torch = _torch()
     dims = [3, 48, 100, 5]
