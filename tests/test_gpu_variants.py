@@ -549,6 +549,43 @@ def test_full_grid_sampled_outputs_of_the_variants(mode_name):
     m.close()
 
 
+def test_models_give_back_their_device_memory():
+    """Every kernel family's model (packed weights, workspaces, the whole-batch buffers of the dynamic
+    mode) is created, used and freed repeatedly; the device's free memory must not drift."""
+    torch = _torch()
+    rng = np.random.default_rng(3)
+    families = [([2, 64, 64, 3], dhq.DHQ_ROTATE_IN), ([2, 256, 256, 3], dhq.DHQ_ROTATE_BOTH), ([2, 512, 512, 3], dhq.DHQ_ROTATE_IN),
+                ([3, 48, 100, 5], dhq.DHQ_ROTATE_BOTH), ([2, 128, 128, 3], dhq.DHQ_W32A32), ([2, 128, 128, 3], dhq.DHQ_W8A32)]
+    nets = [(dims, mode) + synth.siren_init(dims, 30.0, 50 + i) for i, (dims, mode) in enumerate(families)]
+    xs = {k: _dev(rng.uniform(-1, 1, size=(70001, k)).astype(np.float32)) for k in (2, 3)}
+
+    def one_round():
+        for dims, mode, W, b in nets:
+            m = dhq.Model(dims, 30.0, W, b, mode=mode)
+            x = xs[dims[0]]
+            if mode in (dhq.DHQ_W32A32, dhq.DHQ_W8A32):
+                m.forward(x)
+            else:
+                m.calibrate(x)
+                m.forward(x)
+                m.forward(x, flags=dhq.DHQ_LAYERWISE)
+                m.forward(x, flags=dhq.DHQ_DYNAMIC)
+                m.forward(x, flags=dhq.DHQ_DYNAMIC | dhq.DHQ_LAYERWISE)
+            torch.cuda.synchronize()
+            m.close()
+
+    one_round()                                   # code objects loaded, torch's allocator warmed up
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    for rep in range(5):
+        _say(f"create/use/free round {rep}")
+        one_round()
+    torch.cuda.synchronize()
+    free1 = torch.cuda.mem_get_info()[0]
+    _say(f"  free device memory before {free0 >> 20} MiB, after {free1 >> 20} MiB")
+    assert free0 - free1 <= (16 << 20)            # one leaked workspace would be hundreds of MiB
+
+
 @pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "dynamic_fused_two_sided",
                                      "w32a32"])
 def test_forward_replays_from_a_captured_graph(variant):
