@@ -13,7 +13,8 @@ import pytest
 import paper_2508_13478_amd as dhq
 from oracle import dhq_oracle as o
 from paper_2508_13478_amd import synth
-from test_gpu_parity import (CODE_RATE, FLIP_BOUND, OUT_TOL, _dev, _say, _torch, code_stats, flip_frac)
+from test_gpu_parity import (CODE_RATE, FLIP_BOUND, OUT_TOL, _dev, _say, _torch, code_stats, flip_frac, int_matmul,
+                             int_unrotate)
 
 pytestmark = pytest.mark.gpu
 
@@ -93,7 +94,7 @@ def test_two_sided_layers_teacher_forced(name):
         _say(f"  code mismatch rate {rate:.2e} max {mx}")
         assert rate <= CODE_RATE and mx <= 1
         # the un-rotation is exact for the codes the library produced
-        assert np.array_equal(z, o.unrotate_acc(o.igemm(codes, cs.net.Wq[l])))
+        assert np.array_equal(z, int_unrotate(int_matmul(codes, cs.net.Wq[l])))
         same = (codes == cs.dump.codes[l][:rows]).all(axis=1)
         err = np.abs(act[same].astype(np.float64) - cs.dump.act[l][:rows][same]).max()
         _say(f"  epilogue max-abs err {err:.2e}")
@@ -160,7 +161,7 @@ def test_two_sided_sixteen_layers():
         codes, z = codes.cpu().numpy(), z.cpu().numpy()
         rate, mx = code_stats(codes, cs.dump.codes[l])
         assert rate <= CODE_RATE and mx <= 1
-        assert np.array_equal(z, o.unrotate_acc(o.igemm(codes, cs.net.Wq[l])))
+        assert np.array_equal(z, int_unrotate(int_matmul(codes, cs.net.Wq[l])))
     x = _dev(coords)
     for label, flags in (("layerwise", dhq.DHQ_LAYERWISE), ("fused", dhq.DHQ_FUSED)):
         out = cs.model.forward(x, flags=flags)
@@ -343,6 +344,49 @@ def test_dynamic_per_layer_fused_two_sided_shapes_and_ragged_rows(dims):
         torch.cuda.synchronize()
         assert (np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a).max() <= 1e-5
         _gate(dyn.cpu().numpy(), exp, dims, False, f"dims {dims} n={n}")
+    m.close()
+
+
+@pytest.mark.parametrize("mode", [dhq.DHQ_ROTATE_IN, dhq.DHQ_ROTATE_BOTH], ids=["one_sided", "two_sided"])
+def test_dynamic_whole_batch_buffers_beyond_4_gib(mode):
+    """4.2 million coordinates through a 256-wide network: each whole-batch buffer of transformed
+    activations is 4.3 GB, so byte offsets pass 2^32.  The batch is 64 copies of one block of 65 573
+    coordinates plus a ragged piece of it: its per-tensor maxima are the block's, so the oracle's
+    calibrating forward on the block gives the scales and every row's expected value.  Checked: the
+    copies come out bit-identical to the first block wherever they sit, the per-layer kernels give
+    the bits of the whole-network kernel with their scales, scales and values match the oracle's."""
+    torch = _torch()
+    dims = [2, 256, 256, 256, 3]
+    nb, copies, tail = 65536 + 37, 64, 37
+    _say(f"dynamic beyond 4 GiB, mode {mode}, n = {nb * copies + tail}")
+    W, b = synth.siren_init(dims, 30.0, 4096)
+    rng = np.random.default_rng(12)
+    block = rng.uniform(-1, 1, size=(nb, 2)).astype(np.float32)
+    net = o.quantize_net(dims, 30.0, 8, 8, W, b, two_sided=(mode == dhq.DHQ_ROTATE_BOTH))
+    exp = o.forward(net, block, calibrate=True)
+    xb = _dev(block)
+    x = torch.cat([xb] * copies + [xb[:tail]])
+    n = x.shape[0]
+    assert n * 256 * 4 > (1 << 32)
+    m = dhq.Model(dims, 30.0, W, b, mode=mode)
+    dyn = m.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    s_dyn = m.dynamic_scales()
+    lw = m.forward(x, flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
+    s_lw = m.dynamic_scales()
+    m.set_act_scales(s_dyn)
+    sta = m.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    for out, label in ((dyn, "per-layer fused"), (lw, "layer by layer")):
+        first = out[:nb]
+        for k in range(1, copies):
+            assert bool((out[k * nb:(k + 1) * nb] == first).all()), f"{label}: copy {k}"
+        assert bool((out[copies * nb:] == first[:tail]).all()), f"{label}: ragged piece"
+    assert bool((dyn == sta).all())
+    rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+    _say(f"  scale rel err vs oracle max {rel.max():.2e}; vs layer-by-layer {np.abs(s_dyn / s_lw - 1).max():.2e}")
+    assert rel.max() <= 1e-5 and np.abs(s_dyn / s_lw - 1).max() <= 1e-5
+    _gate(dyn[:nb].cpu().numpy(), exp, dims, False, "per-layer fused, first block vs oracle")
+    _gate(lw[:nb].cpu().numpy(), exp, dims, False, "layer by layer, first block vs oracle")
     m.close()
 
 
