@@ -593,6 +593,64 @@ def test_full_grid_sampled_outputs_of_the_variants(mode_name):
     m.close()
 
 
+SWEEP_WIDTHS = [1, 2, 3, 5, 8, 9, 16, 17, 31, 32, 33, 48, 64, 65, 100, 128, 129, 200, 256, 257, 300, 511, 512]
+
+
+def _sweep_case(i):
+    """Seeded random network shape, bit width, rotation mode and row count (case i of the sweep)."""
+    rng = np.random.default_rng(20250813 + i)
+    bits = int(rng.choice([4, 6, 8]))
+    mode = int(rng.choice([dhq.DHQ_ROTATE_IN, dhq.DHQ_ROTATE_BOTH]))
+    n = int(rng.choice([1, 7, 255, 257, 1000, 3001]))
+    if i >= 60:   # shapes the fused kernels take: equal power-of-two hidden widths, small fan-in and fan-out
+        L = int(rng.integers(2, 7))
+        widths = [32, 64, 128, 256] if mode == dhq.DHQ_ROTATE_BOTH else [32, 64, 128, 256, 512]   # two-sided fused: up to 256
+        dims = [int(rng.integers(1, 5))] + [int(rng.choice(widths))] * (L - 1)
+        dims.append(int(rng.integers(1, 5)) if mode == dhq.DHQ_ROTATE_BOTH else int(rng.choice([1, 2, 3, 4, 7, 32])))
+        return dims, bits, mode, n, rng
+    L = int(rng.integers(1, 6))
+    dims = [int(rng.integers(1, 5)) if rng.random() < 0.7 else int(rng.choice(SWEEP_WIDTHS))]
+    same, w = rng.random() < 0.4, int(rng.choice(SWEEP_WIDTHS))
+    dims += [w if same else int(rng.choice(SWEEP_WIDTHS)) for _ in range(L - 1)]
+    dims.append(int(rng.choice([1, 2, 3, 4, 5, 32, 33, 100])))
+    return dims, bits, mode, n, rng
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_shapes_bits_modes_and_row_counts(block):
+    """Ninety seeded random configurations (sixty of any shape: one to five layers, widths from 1 to 512
+    that are and are not powers of two or multiples of 32; thirty of the shapes the fused kernels
+    take; 4 / 6 / 8 bits, either rotation mode, row counts around the tile sizes), each through static
+    and dynamic scales on the automatically chosen and on the layer-by-layer path.  Weight codes
+    bit-identical; every coordinate none of whose codes sits at a rounding boundary within the
+    tolerance, and few of the others beyond it."""
+    from test_gpu_parity import _near_boundary
+    torch = _torch()
+    for i in range(15 * block, 15 * block + 15):
+        dims, bits, mode, n, rng = _sweep_case(i)
+        _say(f"sweep case {i}: dims {dims} bits {bits} mode {mode} n {n}")
+        W, b = synth.siren_init(dims, 30.0, 7000 + i)
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        net = o.quantize_net(dims, 30.0, bits, bits, W, b, two_sided=(mode == dhq.DHQ_ROTATE_BOTH))
+        exp, dmp = o.forward(net, x, calibrate=True, dump=True)
+        near = _near_boundary(net, dmp, bits)
+        m = dhq.Model(dims, 30.0, W, b, bits, bits, mode=mode)
+        assert m.has_fused() or i < 60
+        for l in range(len(dims) - 1):
+            assert np.array_equal(m.weight_codes(l), net.Wq[l]), f"case {i}: weight codes of layer {l}"
+        m.set_act_scales(net.s_a)
+        for flags in (dhq.DHQ_AUTO, dhq.DHQ_LAYERWISE, dhq.DHQ_DYNAMIC, dhq.DHQ_DYNAMIC | dhq.DHQ_LAYERWISE):
+            out = m.forward(_dev(x), flags=flags)
+            torch.cuda.synchronize()
+            out = out.cpu().numpy()
+            assert out.shape == exp.shape and np.isfinite(out).all()
+            err = np.abs(out.astype(np.float64) - exp).max(axis=1)
+            over = err > OUT_TOL
+            assert not (over & ~near).any(), f"case {i} flags {flags}: max-abs err {err.max():.3e}"
+            assert over.sum() <= max(2, 2 * flip_frac(dims) * n), f"case {i} flags {flags}: {over.sum()} of {n} beyond {OUT_TOL}"
+        m.close()
+
+
 def test_models_give_back_their_device_memory():
     """Every kernel family's model (packed weights, workspaces, the whole-batch buffers of the dynamic
     mode) is created, used and freed repeatedly; the device's free memory must not drift."""
