@@ -119,8 +119,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--variant", default="base", choices=["base", "two_sided", "dynamic", "two_sided_dynamic", "w8a32", "w32a32"],
                     help="base: input-side rotation, static scales (fused kernel where there is one); "
-                         "two_sided: weights rotated on both sides, un-rotation in int32 (layer-by-layer path); "
-                         "dynamic: activation scales measured on line per call (layer-by-layer path); "
+                         "two_sided: weights rotated on both sides, un-rotation in int32; "
+                         "dynamic / two_sided_dynamic: activation scales measured on line per call (one fused kernel "
+                         "per layer where there is one); "
                          "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
     ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
                     help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
