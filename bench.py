@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "89c71eca591b23cd0311c90895a7a49d19fe5fce1031b79aff26c2ee93e4917a"
-TRAFFIC_BYTES = {"C2": (2520.8 + 768.0) * 1024, "C5": (44537.9 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "ccb1aa04e4494a7a88a65231b6556f797060eb5986a261f5f1e78d1f4ad9d295"
+TRAFFIC_BYTES = {"C2": (2520.8 + 768.0) * 1024, "C5": (44538.8 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -202,7 +202,8 @@ def main() -> int:
                      "algorithmic_ops_per_launch": ops},
     }
     # Secondary view: the vector ALU, which is what actually limits this path.  Per feature and
-    # sine layer the fused kernels issue convert, fma, sine, the transform, fma, max, min.  The
+    # sine layer the fused kernels issue convert, fma, sine, the transform, fma, median, and three
+    # byte-permute/or instructions per four codes.  The
     # transform: the fused kernels give its 32-row factor to the matrix unit (two vector
     # instructions to split an activation into binary16 pieces) and keep log2(n / 32) add/sub
     # (width 512: plus one move out of the accumulation registers).
@@ -210,7 +211,7 @@ def main() -> int:
     # per second.
     import math
     nf = wl.dims[1]
-    per_feature = 3 + 2 + math.log2(nf / 32) + (1 if nf == 512 else 0) + 3
+    per_feature = 3 + 2 + math.log2(nf / 32) + (1 if nf == 512 else 0) + 2.75
     if two_sided:
         per_feature += math.log2(nf) + 0.5   # the integer un-rotation: log2(n) add/sub and half a lane swap
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n

@@ -87,27 +87,23 @@ __device__ __forceinline__ unsigned hm_h32_pair(int row, int i0, int i1)
            (((__builtin_popcount(row & i1) & 1) ? 0xBC00u : 0x3C00u) << 16);
 }
 
-// Last butterfly stage (over the lane-half bit) fused with the quantizer: registers
-// (2p, 2p+1) swap halves across the wave, one add and one sub finish the transform, and each
-// result is rounded, clamped and dropped into its byte of the packed code dword.  The final
-// clamp instruction writes that byte directly (sub-dword destination select), so packing
-// costs nothing.
-__device__ __forceinline__ void fused_quant_byte(unsigned &packed, float v, float inv, int lo, int hi, int byte)
+// The quantizer of the fused kernels for four values at once: round (magic-number add inside the
+// scaling fma), clamp (one three-operand median per value) and pack byte 0 of the four results into
+// one dword of codes, value i in byte i.  Seven instructions for four codes; clamping with max and
+// a sub-dword min that writes its byte in place takes eight.
+__device__ __forceinline__ unsigned fused_quant4(float v0, float v1, float v2, float v3, float inv, int lo, int hi)
 {
-    const float t = __builtin_fmaf(v, inv, DHQ_MAGIC_F);
-    const int b = max(__float_as_int(t), lo);
-    if (byte == 0)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else if (byte == 1)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else if (byte == 2)
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
-    else
-        asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(b), "v"(hi));
+    const float v[4] = {v0, v1, v2, v3};
+    unsigned r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int c;
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(__float_as_int(__builtin_fmaf(v[i], inv, DHQ_MAGIC_F))), "v"(lo), "v"(hi));
+        r[i] = (unsigned)c;
+    }
+    const unsigned p01 = __builtin_amdgcn_perm(r[1], r[0], 0x0c0c0400u);  // bytes r0.0, r1.0, 0, 0
+    const unsigned p23 = __builtin_amdgcn_perm(r[3], r[2], 0x04000c0cu);  // bytes 0, 0, r2.0, r3.0
+    return p01 | p23;
 }
 
 #endif

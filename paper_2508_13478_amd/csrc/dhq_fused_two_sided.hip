@@ -296,10 +296,8 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
             const float inv = A.layer[l + 1].inv_in;
 #pragma unroll
             for (int w = 0; w < NR / 4; ++w) {
-                unsigned packed = 0;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xt[w >> 2][4 * (w & 3) + b], inv, qlo, qhi, b);
-                cd[w / 4][w % 4] = (int)packed;
+                const int v = 4 * (w & 3);
+                cd[w / 4][w % 4] = (int)fused_quant4(xt[w >> 2][v], xt[w >> 2][v + 1], xt[w >> 2][v + 2], xt[w >> 2][v + 3], inv, qlo, qhi);
             }
             p ^= 1;
         }
@@ -388,12 +386,7 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_layer_kernel(const f2l_
 #pragma unroll
             for (int q = 0; q < NR / 4; ++q) {
                 const float4 x = A.xin[slot + (size_t)q * 64];
-                unsigned packed = 0;
-                fused_quant_byte(packed, x.x, inv, qlo, qhi, 0);
-                fused_quant_byte(packed, x.y, inv, qlo, qhi, 1);
-                fused_quant_byte(packed, x.z, inv, qlo, qhi, 2);
-                fused_quant_byte(packed, x.w, inv, qlo, qhi, 3);
-                cd[q / 4][q % 4] = (int)packed;
+                cd[q / 4][q % 4] = (int)fused_quant4(x.x, x.y, x.z, x.w, inv, qlo, qhi);
             }
         }
         if (!landed) {

@@ -478,10 +478,7 @@ __device__ __forceinline__ void wide_transform_quant(const dhq_v16f (&xtop)[NT -
     }
 #pragma unroll
     for (int T = 0; T < NT; ++T) {
-        unsigned packed = 0;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) fused_quant_byte(packed, xv[4 * T + b], inv, qlo, qhi, b);
-        cd[T][Q] = (int)packed;
+        cd[T][Q] = (int)fused_quant4(xv[4 * T], xv[4 * T + 1], xv[4 * T + 2], xv[4 * T + 3], inv, qlo, qhi);
     }
 }
 
