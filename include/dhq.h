@@ -57,6 +57,8 @@ typedef enum {
 #define DHQ_AUTO 0u
 #define DHQ_LAYERWISE 1u /* two to four kernels per layer, activations round-trip device memory */
 #define DHQ_FUSED 2u     /* one kernel for the whole network; DHQ_EUNSUPPORTED if the shape has none */
+/* Shapes with a whole-network kernel (DHQ_ROTATE_IN): at least two layers, fan-in <= 4, all hidden
+ * widths equal and 32 / 64 / 128 / 256 / 512, fan-out <= 32.  dhq_has_fused() tells. */
 /* or-ed onto the above: measure every layer's activation scale on line, on this call's own
  * coordinates, instead of using the scales stored in the model (Sec. 3.3, "dynamic
  * quantization module ... between layers").  With DHQ_LAYERWISE: an absmax pass added to every layer, any
