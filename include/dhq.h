@@ -117,12 +117,13 @@ int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
  *
  * mode | DHQ_W8A32 / DHQ_W32A32 (with DHQ_ROTATE_IN only) builds the comparison networks of
  * Sec. 1 / Table 2 with floating-point activations: y = W a + b, a = sin(omega0 y) in fp32 on
- * the fp32 MFMA, one fused kernel, where W is the original weight matrix (DHQ_W32A32) or
+ * the fp32 MFMA, where W is the original weight matrix (DHQ_W32A32) or
  * W~ = (s_w Wq) H_Kp / sqrt(Kp), the de-quantized weights taken back to the original basis
- * (DHQ_W8A32; bits_w applies, bits_a is ignored).  Shapes: fan-in <= 4, equal hidden widths of
- * 32 / 64 / 128 / 256, fan-out <= 32, else DHQ_EUNSUPPORTED.  Such a model has no activation
- * scales: dhq_set_act_scales, dhq_calibrate, DHQ_DYNAMIC, DHQ_LAYERWISE and the test hooks
- * return DHQ_EUNSUPPORTED; dhq_forward needs none.
+ * (DHQ_W8A32; bits_w applies, bits_a is ignored).  Any shape within the limits: with fan-in <= 4,
+ * equal hidden widths of 32 / 64 / 128 / 256 and fan-out <= 32 one fused kernel runs the whole
+ * network (DHQ_AUTO, DHQ_FUSED), every other shape (and DHQ_LAYERWISE) runs one fp32 GEMM kernel
+ * per layer.  Such a model has no activation scales: dhq_set_act_scales, dhq_calibrate,
+ * DHQ_DYNAMIC and the test hooks return DHQ_EUNSUPPORTED; dhq_forward needs none.
  */
 int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
                               const float *const *b_host, dhq_model **out);

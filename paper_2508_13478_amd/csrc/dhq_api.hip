@@ -239,7 +239,6 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
     int rc = DHQ_OK;
     // everything that can be refused is refused before the device is touched
     for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = quantize_layer_host(m, l, W_host[l], b_host[l]);
-    if (rc == DHQ_OK && precision != DHQ_W8A8 && !dhq_float_shape_ok(m->dims, L)) rc = DHQ_EUNSUPPORTED;
     if (rc == DHQ_OK && hipGetDevice(&m->device) != hipSuccess) rc = DHQ_EHIP;
     if (rc == DHQ_OK && precision != DHQ_W8A8) {
         // floating-point activations: the network runs on the original weights (W32A32) or on the
@@ -342,7 +341,8 @@ extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *W
 extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
-    return (m->fused || m->wide || m->flt || m->fused2) ? 1 : 0;
+    if (m->flt) return dhq_float_has_fused(m->flt) ? 1 : 0;
+    return (m->fused || m->wide || m->fused2) ? 1 : 0;
 }
 
 // Per-layer constant of the quantizer kernel.
@@ -503,11 +503,16 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
     const bool dyn_fused_ok = m->fused || m->fused2;  // per-layer fused kernels of the dynamic mode
     if (dynamic && path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
-    if (m->flt && (dynamic || path == DHQ_LAYERWISE)) return DHQ_EUNSUPPORTED;
+    if (m->flt && (dynamic || (path == DHQ_FUSED && !dhq_float_has_fused(m->flt)))) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    if (m->flt) return dhq_float_launch(m->flt, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    if (m->flt) {
+        const hipError_t e = (path != DHQ_LAYERWISE && dhq_float_has_fused(m->flt))
+                                 ? dhq_float_launch(m->flt, coords_dev, n, out_dev, st)
+                                 : dhq_float_launch_layerwise(m->flt, coords_dev, n, out_dev, st);
+        return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    }
     // the workspace belongs to the model and is the only thing a forward call changes in it
     if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, path != DHQ_LAYERWISE && dyn_fused_ok, st);
     if (!m->have_scales) return DHQ_ENOSCALE;

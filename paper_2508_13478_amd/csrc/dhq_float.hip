@@ -25,6 +25,10 @@
 // copy); the build checks on the compiler's assembly output that compiler-generated code never
 // touches them.  Wait states the compiler can no longer see (accumulation-register write ->
 // MFMA read, MFMA result -> vector ALU read) are covered by explicit s_nop.
+//
+// Every other shape (and DHQ_LAYERWISE on the shapes above) runs layer by layer through
+// float_layer_kernel: one fp32 MFMA GEMM with the bias + sine epilogue per layer, activations
+// in device memory between the layers, 65 536 rows at a time.
 #include <math.h>
 #include <string.h>
 
@@ -60,12 +64,25 @@ struct float_args {
     float_layer_desc layer[DHQ_MAX_LAYERS];
 };
 
+// One layer of the layer-by-layer path: weights as B fragments [M tile][k group j][lane] float4,
+// lane (c, kk) holding W[32 T + c][8 j + 4 kk + e], e = 0..3 (zero beyond M and K); bias (times
+// omega0 / 2 pi in the sine layers).
+struct float_lw_layer {
+    float *wfrag_dev = nullptr;
+    float *bias_dev = nullptr;
+    int K = 0, M = 0, NJ = 0, Mt = 0;
+};
+
 struct dhq_float_plan {
-    int nf = 0;
+    int nf = 0;              // hidden width of the fused kernel, 0 if the shape has none
     float *blob_dev = nullptr;
     size_t blob_floats = 0;
     float_args args;
     int n_cu = 0;
+    int n_layers = 0;
+    float rev = 0.f;
+    float_lw_layer lw[DHQ_MAX_LAYERS];
+    float *act[2] = {nullptr, nullptr};  // DHQ_CHUNK x widest layer, fp32
 };
 
 // ----------------------------------------------------------------------------- device code
@@ -257,6 +274,72 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
     }
 }
 
+// ---------------------------------------------------------------- layer by layer, any shape
+// out = epilogue(in W^T + b) for one layer: in n x K, out n x M, both row-major fp32.  Coordinates
+// are the MFMA row dimension (A operand), features the columns (B operand: the packed weights),
+// so the 32 lanes of a wave half store 128 contiguous bytes of one output row.  A wave takes 32
+// rows and up to FLW_TILES column tiles; k runs in groups of eight: lane (r, kk) reads the four
+// inputs 8 j + 4 kk + e of its row with one load and feeds them to four MFMAs per tile.
+#define FLW_WAVES 4
+#define FLW_TILES 4
+
+template <bool SINE>
+__global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float *__restrict__ in, int64_t n, int K, int NJ,
+                                                                     int vec, const float4 *__restrict__ wfrag, int M, int Mt,
+                                                                     const float *__restrict__ bias, float rev,
+                                                                     float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t row0 = ((int64_t)blockIdx.x * FLW_WAVES + wave) * 32;
+    if (row0 >= n) return;  // no barrier below
+    const int T0 = blockIdx.y * FLW_TILES;
+    const int nt = (Mt - T0 < FLW_TILES) ? Mt - T0 : FLW_TILES;
+    const int64_t arow = (row0 + c < n) ? row0 + c : n - 1;  // rows past the end repeat the last one and are not stored
+    const float *ap = in + arow * K;
+    dhq_v16f acc[FLW_TILES];
+#pragma unroll
+    for (int t = 0; t < FLW_TILES; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+    for (int j = 0; j < NJ; ++j) {
+        const int k0 = 8 * j + 4 * h;
+        float4 a;
+        if (vec && k0 + 3 < K) {
+            a = *reinterpret_cast<const float4 *>(ap + k0);
+        } else {
+            a.x = (k0 < K) ? ap[k0] : 0.f;
+            a.y = (k0 + 1 < K) ? ap[k0 + 1] : 0.f;
+            a.z = (k0 + 2 < K) ? ap[k0 + 2] : 0.f;
+            a.w = (k0 + 3 < K) ? ap[k0 + 3] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < FLW_TILES; ++t) {
+            if (t < nt) {
+                const float4 w = wfrag[((size_t)(T0 + t) * NJ + j) * 64 + lane];
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, w.x, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, w.y, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, w.z, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, w.w, acc[t], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < FLW_TILES; ++t) {
+        if (t < nt) {
+            const int f = 32 * (T0 + t) + c;
+            if (f < M) {
+                const float bf = bias[f];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t row = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (row < n) out[row * M + f] = SINE ? dhq_sin_rev(__builtin_fmaf(acc[t][v], rev, bf)) : acc[t][v] + bf;
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------- host code
 // Feature held by register kk of lane half h (the D layout of the 32 x 32 MFMA).
 static int flt_feature(int kk, int h) { return 32 * (kk >> 4) + 8 * ((kk >> 2) & 3) + 4 * h + (kk & 3); }
@@ -272,18 +355,43 @@ bool dhq_float_shape_ok(const int *dims, int L)
     return true;
 }
 
+static int float_create_fused(dhq_float_plan *P, const int *dims, int L, double rev, const std::vector<std::vector<float>> &W,
+                              const std::vector<std::vector<float>> &b);
+static int float_create_layerwise(dhq_float_plan *P, const int *dims, int L, double rev, const std::vector<std::vector<float>> &W,
+                                  const std::vector<std::vector<float>> &b);
+
 // W[l]: dims[l+1] x dims[l] fp32 (the weights the network is to run on), b[l]: dims[l+1].
 int dhq_float_create(const int *dims, int L, float omega0, const std::vector<std::vector<float>> &W,
                      const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan_out)
 {
     *plan_out = nullptr;
-    if (!dhq_float_shape_ok(dims, L)) return DHQ_EUNSUPPORTED;
-    const int nf = dims[1], NT = nf / 32, NR = nf / 2, CHN = NT >= 2 ? 2 : 1;
     dhq_float_plan *P = new (std::nothrow) dhq_float_plan();
     if (!P) return DHQ_ENOMEM;
-    P->nf = nf;
     memset(&P->args, 0, sizeof(P->args));
     const double rev = (double)omega0 / 6.283185307179586476925286766559;
+    P->n_layers = L;
+    P->rev = (float)rev;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) {
+        delete P;
+        return DHQ_EHIP;
+    }
+    P->n_cu = prop.multiProcessorCount;
+    int rc = float_create_layerwise(P, dims, L, rev, W, b);
+    if (rc == DHQ_OK && dhq_float_shape_ok(dims, L)) rc = float_create_fused(P, dims, L, rev, W, b);
+    if (rc != DHQ_OK) {
+        dhq_float_destroy(P);
+        return rc;
+    }
+    *plan_out = P;
+    return DHQ_OK;
+}
+
+// The packed weights and biases of the whole-network kernel.
+static int float_create_fused(dhq_float_plan *P, const int *dims, int L, double rev, const std::vector<std::vector<float>> &W,
+                              const std::vector<std::vector<float>> &b)
+{
+    const int nf = dims[1], NT = nf / 32, NR = nf / 2, CHN = NT >= 2 ? 2 : 1;
     std::vector<float> blob;
     auto bias_block = [&](int l, int tiles, bool sine) {
         // [tile][h][16]: register v of lane half h holds feature 32 T + 8 (v / 4) + 4 h + v % 4
@@ -330,28 +438,46 @@ int dhq_float_create(const int *dims, int L, float omega0, const std::vector<std
         P->args.layer[l].b_off = bias_block(l, l == L - 1 ? 1 : NT, l != L - 1);
     }
     P->blob_floats = blob.size();
-    if (hipMalloc((void **)&P->blob_dev, sizeof(float) * blob.size()) != hipSuccess) {
-        delete P;
-        return DHQ_ENOMEM;
-    }
-    if (hipMemcpy(P->blob_dev, blob.data(), sizeof(float) * blob.size(), hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipFree(P->blob_dev);
-        delete P;
-        return DHQ_EHIP;
-    }
+    if (hipMalloc((void **)&P->blob_dev, sizeof(float) * blob.size()) != hipSuccess) return DHQ_ENOMEM;
+    if (hipMemcpy(P->blob_dev, blob.data(), sizeof(float) * blob.size(), hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
     P->args.blob = P->blob_dev;
     P->args.n_layers = L;
     P->args.k0 = dims[0];
     P->args.m_out = dims[L];
     P->args.rev = (float)rev;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, device) != hipSuccess) {
-        (void)hipFree(P->blob_dev);
-        delete P;
-        return DHQ_EHIP;
+    P->nf = nf;
+    return DHQ_OK;
+}
+
+// Fragments, biases and the two activation buffers of the layer-by-layer path.
+static int float_create_layerwise(dhq_float_plan *P, const int *dims, int L, double rev, const std::vector<std::vector<float>> &W,
+                                  const std::vector<std::vector<float>> &b)
+{
+    int max_dim = 1;
+    for (int l = 0; l <= L; ++l) max_dim = dims[l] > max_dim ? dims[l] : max_dim;
+    for (int l = 0; l < L; ++l) {
+        float_lw_layer &Ly = P->lw[l];
+        Ly.K = dims[l];
+        Ly.M = dims[l + 1];
+        Ly.NJ = (Ly.K + 7) / 8;
+        Ly.Mt = (Ly.M + 31) / 32;
+        std::vector<float> frag((size_t)Ly.Mt * Ly.NJ * 64 * 4, 0.0f);
+        for (int T = 0; T < Ly.Mt; ++T)
+            for (int j = 0; j < Ly.NJ; ++j)
+                for (int ln = 0; ln < 64; ++ln)
+                    for (int e = 0; e < 4; ++e) {
+                        const int row = 32 * T + (ln & 31), k = 8 * j + 4 * (ln >> 5) + e;
+                        if (row < Ly.M && k < Ly.K) frag[(((size_t)T * Ly.NJ + j) * 64 + ln) * 4 + e] = W[l][(size_t)row * Ly.K + k];
+                    }
+        std::vector<float> bias(Ly.M);
+        for (int f = 0; f < Ly.M; ++f) bias[f] = (l != L - 1) ? (float)((double)b[l][f] * rev) : b[l][f];
+        if (hipMalloc((void **)&Ly.wfrag_dev, sizeof(float) * frag.size()) != hipSuccess) return DHQ_ENOMEM;
+        if (hipMalloc((void **)&Ly.bias_dev, sizeof(float) * bias.size()) != hipSuccess) return DHQ_ENOMEM;
+        if (hipMemcpy(Ly.wfrag_dev, frag.data(), sizeof(float) * frag.size(), hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
+        if (hipMemcpy(Ly.bias_dev, bias.data(), sizeof(float) * bias.size(), hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
     }
-    P->n_cu = prop.multiProcessorCount;
-    *plan_out = P;
+    for (int i = 0; i < 2; ++i)
+        if (hipMalloc((void **)&P->act[i], sizeof(float) * (size_t)DHQ_CHUNK * max_dim) != hipSuccess) return DHQ_ENOMEM;
     return DHQ_OK;
 }
 
@@ -359,12 +485,46 @@ void dhq_float_destroy(dhq_float_plan *P)
 {
     if (!P) return;
     if (P->blob_dev) (void)hipFree(P->blob_dev);
+    for (int l = 0; l < DHQ_MAX_LAYERS; ++l) {
+        if (P->lw[l].wfrag_dev) (void)hipFree(P->lw[l].wfrag_dev);
+        if (P->lw[l].bias_dev) (void)hipFree(P->lw[l].bias_dev);
+    }
+    for (int i = 0; i < 2; ++i)
+        if (P->act[i]) (void)hipFree(P->act[i]);
     delete P;
+}
+
+bool dhq_float_has_fused(const dhq_float_plan *P) { return P && P->nf != 0; }
+
+hipError_t dhq_float_launch_layerwise(const dhq_float_plan *P, const float *coords, int64_t n, float *out, hipStream_t st)
+{
+    if (!P) return hipErrorInvalidValue;
+    const int L = P->n_layers;
+    for (int64_t start = 0; start < n; start += DHQ_CHUNK) {
+        const int64_t rows = (n - start < DHQ_CHUNK) ? n - start : DHQ_CHUNK;
+        const float *cur = coords + start * P->lw[0].K;
+        for (int l = 0; l < L; ++l) {
+            const float_lw_layer &Ly = P->lw[l];
+            float *dst = (l == L - 1) ? out + start * Ly.M : P->act[l & 1];
+            const dim3 grid((unsigned)((rows + 32 * FLW_WAVES - 1) / (32 * FLW_WAVES)), (unsigned)((Ly.Mt + FLW_TILES - 1) / FLW_TILES));
+            // one 16-byte load per lane needs rows that start on 16-byte boundaries
+            const int vec = (Ly.K % 4 == 0 && ((uintptr_t)cur & 15) == 0) ? 1 : 0;
+            const float4 *wf = reinterpret_cast<const float4 *>(Ly.wfrag_dev);
+            if (l != L - 1)
+                float_layer_kernel<true><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NJ, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+            else
+                float_layer_kernel<false><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NJ, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            cur = dst;
+        }
+    }
+    return hipSuccess;
 }
 
 hipError_t dhq_float_launch(const dhq_float_plan *P, const float *coords, int64_t n, float *out, hipStream_t st)
 {
-    if (!P) return hipErrorInvalidValue;
+    if (!P || P->nf == 0) return hipErrorInvalidValue;
     if (n <= 0) return hipSuccess;
     float_args a = P->args;
     a.coords = coords;

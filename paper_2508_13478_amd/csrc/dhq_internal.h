@@ -155,12 +155,15 @@ hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, in
                                      float *partial, float *dyn, hipStream_t st);
 
 // Floating-point activations (defined in dhq_float.hip): the plain SIREN on the given fp32
-// weights W[l] (dims[l+1] x dims[l]) and biases, fused over all layers.  DHQ_EUNSUPPORTED if
-// the shape has no such kernel.
+// weights W[l] (dims[l+1] x dims[l]) and biases.  Every shape has the layer-by-layer path
+// (dhq_float_launch_layerwise); the shapes dhq_float_shape_ok accepts also have one kernel fused
+// over all layers (dhq_float_launch; dhq_float_has_fused tells).
 bool dhq_float_shape_ok(const int *dims, int n_layers);
 int dhq_float_create(const int *dims, int n_layers, float omega0, const std::vector<std::vector<float>> &W,
                      const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan);
 void dhq_float_destroy(dhq_float_plan *plan);
 hipError_t dhq_float_launch(const dhq_float_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
+bool dhq_float_has_fused(const dhq_float_plan *plan);
+hipError_t dhq_float_launch_layerwise(const dhq_float_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
 #endif

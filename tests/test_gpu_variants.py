@@ -487,6 +487,58 @@ def test_w32a32_shapes_and_ragged_rows(dims):
         assert np.abs(out.cpu().numpy().astype(np.float64) - exp).max() <= FLOAT_TOL
 
 
+FLOAT_TOL_WIDE = 4e-6   # the same arithmetic with up to 512 terms per sum and up to sixteen layers (measured 1e-6)
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 48, 100, 5], [2, 512, 512, 512, 3], [512, 512, 512], [1, 1, 1], [7, 9, 300, 33, 2],
+                                  [4] + [256] * 15 + [32], [2, 64, 1], [129, 5]])
+def test_w32a32_layer_by_layer_any_shape(dims):
+    """The layer-by-layer fp32 path: every shape the library accepts (widths that are no multiple of 8 or
+    32, one to sixteen layers, 512 on every side), ragged rows, more rows than one workspace chunk; on
+    the shapes that also have the whole-network kernel the two paths are compared as well."""
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 199 + len(dims) + dims[0])
+    m = dhq.Model(dims, 30.0, W, b, mode=dhq.DHQ_W32A32)
+    rng = np.random.default_rng(dims[0] + 3)
+    for n in (1, 129, 5000 + 17, 70001):
+        if n == 70001 and max(dims) > 128:
+            continue                                            # the oracle would take too long
+        _say(f"W32A32 layer by layer dims {dims[:3]}.. ({len(dims) - 1} layers) n={n}")
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        exp, _ = o.mlp_float(dims, 30.0, W, b, x)
+        out = m.forward(_dev(x), flags=dhq.DHQ_LAYERWISE)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max()
+        _say(f"  max-abs err {err:.2e} (|out| max {np.abs(exp).max():.2f})")
+        # a 512-wide input layer with the input layer's initialisation drives the sine argument to tens of
+        # revolutions, where one fp32 unit in the last place is already 4e-6 revolutions
+        tol = FLOAT_TOL_WIDE if dims[0] <= 8 else 5e-5
+        assert out.shape == exp.shape and err <= tol
+        auto = m.forward(_dev(x))
+        torch.cuda.synchronize()
+        if m.has_fused():
+            assert np.abs(auto.cpu().numpy() - out.cpu().numpy()).max() <= 2 * FLOAT_TOL_WIDE
+        else:
+            assert np.array_equal(auto.cpu().numpy(), out.cpu().numpy())
+    m.close()
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_w8a32_layer_by_layer_odd_shape(bits):
+    torch = _torch()
+    dims = [3, 48, 100, 5]
+    _say(f"W8A32 layer by layer bits {bits}")
+    W, b = synth.siren_init(dims, 30.0, 4242)
+    rng = np.random.default_rng(bits)
+    x = rng.uniform(-1, 1, size=(3001, 3)).astype(np.float32)
+    exp, _, _ = o.mlp_w8a32(dims, 30.0, bits, W, b, x)
+    m = dhq.Model(dims, 30.0, W, b, bits, bits, mode=dhq.DHQ_W8A32)
+    out = m.forward(_dev(x))
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - exp).max() <= FLOAT_TOL_WIDE
+    m.close()
+
+
 @pytest.mark.parametrize("bits", [4, 6, 8])
 def test_w8a32_forward(bits):
     torch = _torch()
@@ -513,16 +565,20 @@ def test_float_modes_refuse_what_they_do_not_have():
     m = dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W32A32)
     x = _dev(coords[:64])
     for call in (lambda: m.calibrate(x), lambda: m.set_act_scales(np.ones(4, np.float32)),
-                 lambda: m.forward(x, flags=dhq.DHQ_LAYERWISE), lambda: m.forward(x, flags=dhq.DHQ_DYNAMIC),
+                 lambda: m.forward(x, flags=dhq.DHQ_DYNAMIC), lambda: m.forward(x, flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC),
                  lambda: m.weight_codes(0), lambda: m.forward_debug(x, 0), lambda: m.dynamic_scales()):
         with pytest.raises(dhq.DhqError) as e:
             call()
         assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    # shapes without a whole-network fp32 kernel run layer by layer and refuse DHQ_FUSED
     for dims in ([2, 512, 512, 3], [2, 48, 48, 3], [2, 64, 128, 3], [5, 64, 64, 3]):
         Wd, bd = synth.siren_init(dims, 30.0, 5)
+        md = dhq.Model(dims, 30.0, Wd, bd, mode=dhq.DHQ_W8A32)
+        assert not md.has_fused()
         with pytest.raises(dhq.DhqError) as e:
-            dhq.Model(dims, 30.0, Wd, bd, mode=dhq.DHQ_W8A32)
+            md.forward(_dev(np.zeros((8, dims[0]), np.float32)), flags=dhq.DHQ_FUSED)
         assert e.value.status == dhq.DHQ_EUNSUPPORTED
+        md.close()
     with pytest.raises(dhq.DhqError) as e:
         dhq.Model(wl.dims, wl.omega0, W, b, mode=dhq.DHQ_W8A32 | dhq.DHQ_ROTATE_BOTH)
     assert e.value.status == dhq.DHQ_EUNSUPPORTED
