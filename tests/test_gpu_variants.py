@@ -713,7 +713,8 @@ def test_models_give_back_their_device_memory():
     torch = _torch()
     rng = np.random.default_rng(3)
     families = [([2, 64, 64, 3], dhq.DHQ_ROTATE_IN), ([2, 256, 256, 3], dhq.DHQ_ROTATE_BOTH), ([2, 512, 512, 3], dhq.DHQ_ROTATE_IN),
-                ([3, 48, 100, 5], dhq.DHQ_ROTATE_BOTH), ([2, 128, 128, 3], dhq.DHQ_W32A32), ([2, 128, 128, 3], dhq.DHQ_W8A32)]
+                ([3, 48, 100, 5], dhq.DHQ_ROTATE_BOTH), ([2, 128, 128, 3], dhq.DHQ_W32A32), ([2, 128, 128, 3], dhq.DHQ_W8A32),
+                ([3, 48, 100, 5], dhq.DHQ_W32A32)]
     nets = [(dims, mode) + synth.siren_init(dims, 30.0, 50 + i) for i, (dims, mode) in enumerate(families)]
     xs = {k: _dev(rng.uniform(-1, 1, size=(70001, k)).astype(np.float32)) for k in (2, 3)}
 
@@ -723,6 +724,7 @@ def test_models_give_back_their_device_memory():
             x = xs[dims[0]]
             if mode in (dhq.DHQ_W32A32, dhq.DHQ_W8A32):
                 m.forward(x)
+                m.forward(x, flags=dhq.DHQ_LAYERWISE)
             else:
                 m.calibrate(x)
                 m.forward(x)
@@ -745,7 +747,7 @@ def test_models_give_back_their_device_memory():
 
 
 @pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "dynamic_fused_two_sided",
-                                     "w32a32"])
+                                     "w32a32", "w32a32_layerwise"])
 def test_forward_replays_from_a_captured_graph(variant):
     """dhq_forward only enqueues kernels (no memset, no allocation, no synchronisation once the
     workspace exists), so a stream capture of it replays to the same bits as the eager call --
@@ -755,12 +757,13 @@ def test_forward_replays_from_a_captured_graph(variant):
     wl, coords, W, b = synth.make("C1")
     x = _dev(coords)
     mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "dynamic_fused_two_sided": dhq.DHQ_ROTATE_BOTH,
-            "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
+            "w32a32": dhq.DHQ_W32A32, "w32a32_layerwise": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
     flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC,
              "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
-             "dynamic_fused_two_sided": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
+             "dynamic_fused_two_sided": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
+             "w32a32_layerwise": dhq.DHQ_LAYERWISE}.get(variant, dhq.DHQ_AUTO)
     m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode)
-    if variant != "w32a32":
+    if not variant.startswith("w32a32"):
         m.calibrate(x)
     out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
     eager = m.forward(x, flags=flags).clone()                # also grows the dynamic workspace before capture
