@@ -64,13 +64,13 @@ struct float_args {
     float_layer_desc layer[DHQ_MAX_LAYERS];
 };
 
-// One layer of the layer-by-layer path: weights as B fragments [M tile][k group j][lane] float4,
-// lane (c, kk) holding W[32 T + c][8 j + 4 kk + e], e = 0..3 (zero beyond M and K); bias (times
-// omega0 / 2 pi in the sine layers).
+// One layer of the layer-by-layer path: weights as B fragments [M tile][k group J][quarter q][lane]
+// float4, lane (c, kk) holding W[32 T + c][32 J + 16 kk + 4 q + e], e = 0..3 (zero beyond M and K);
+// bias (times omega0 / 2 pi in the sine layers).
 struct float_lw_layer {
     float *wfrag_dev = nullptr;
     float *bias_dev = nullptr;
-    int K = 0, M = 0, NJ = 0, Mt = 0;
+    int K = 0, M = 0, NG = 0, Mt = 0;
 };
 
 struct dhq_float_plan {
@@ -278,13 +278,14 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
 // out = epilogue(in W^T + b) for one layer: in n x K, out n x M, both row-major fp32.  Coordinates
 // are the MFMA row dimension (A operand), features the columns (B operand: the packed weights),
 // so the 32 lanes of a wave half store 128 contiguous bytes of one output row.  A wave takes 32
-// rows and up to FLW_TILES column tiles; k runs in groups of eight: lane (r, kk) reads the four
-// inputs 8 j + 4 kk + e of its row with one load and feeds them to four MFMAs per tile.
+// rows and up to FLW_TILES column tiles; k runs in groups of 32: lane (r, kk) reads the sixteen
+// inputs 32 J + 16 kk + i of its row (64 contiguous bytes, so that a row's cache line is fetched
+// once) and feeds them to sixteen MFMAs per tile, MFMA i taking k = 32 J + i and 32 J + 16 + i.
 #define FLW_WAVES 4
 #define FLW_TILES 4
 
 template <bool SINE>
-__global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float *__restrict__ in, int64_t n, int K, int NJ,
+__global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float *__restrict__ in, int64_t n, int K, int NG,
                                                                      int vec, const float4 *__restrict__ wfrag, int M, int Mt,
                                                                      const float *__restrict__ bias, float rev,
                                                                      float *__restrict__ out)
@@ -302,27 +303,54 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
     for (int t = 0; t < FLW_TILES; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-    for (int j = 0; j < NJ; ++j) {
-        const int k0 = 8 * j + 4 * h;
-        float4 a;
-        if (vec && k0 + 3 < K) {
-            a = *reinterpret_cast<const float4 *>(ap + k0);
-        } else {
-            a.x = (k0 < K) ? ap[k0] : 0.f;
-            a.y = (k0 + 1 < K) ? ap[k0 + 1] : 0.f;
-            a.z = (k0 + 2 < K) ? ap[k0 + 2] : 0.f;
-            a.w = (k0 + 3 < K) ? ap[k0 + 3] : 0.f;
-        }
+    // this lane's sixteen inputs of k group J (zero beyond K): 64 contiguous bytes of its row
+    auto load_a = [&](int J, float4 (&a)[4]) {
 #pragma unroll
-        for (int t = 0; t < FLW_TILES; ++t) {
-            if (t < nt) {
-                const float4 w = wfrag[((size_t)(T0 + t) * NJ + j) * 64 + lane];
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, w.x, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, w.y, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, w.z, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, w.w, acc[t], 0, 0, 0);
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = 32 * J + 16 * h + 4 * q;
+            if (vec && k0 + 3 < K) {
+                a[q] = *reinterpret_cast<const float4 *>(ap + k0);
+            } else {
+                a[q].x = (k0 < K) ? ap[k0] : 0.f;
+                a[q].y = (k0 + 1 < K) ? ap[k0 + 1] : 0.f;
+                a[q].z = (k0 + 2 < K) ? ap[k0 + 2] : 0.f;
+                a[q].w = (k0 + 3 < K) ? ap[k0 + 3] : 0.f;
             }
         }
+    };
+    // tiles past the layer's last one re-read the last one's weights; their results are dropped
+    const float4 *wp[FLW_TILES];
+#pragma unroll
+    for (int t = 0; t < FLW_TILES; ++t) wp[t] = wfrag + (size_t)(T0 + (t < nt ? t : nt - 1)) * NG * 4 * 64 + lane;
+    float4 a[4], w[FLW_TILES];
+    load_a(0, a);
+#pragma unroll
+    for (int t = 0; t < FLW_TILES; ++t) w[t] = wp[t][0];
+    for (int J = 0; J < NG; ++J) {
+        // the next operands are fetched while the current MFMAs run (inputs one group of 32 k ahead, weights
+        // one quarter group ahead); consecutive MFMAs go to different accumulators
+        const int Jn = (J + 1 < NG) ? J + 1 : J;
+        float4 an[4];
+        load_a(Jn, an);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int nxt = (q < 3) ? 4 * J + q + 1 : 4 * Jn;
+            float4 wn[FLW_TILES];
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) wn[t] = wp[t][(size_t)nxt * 64];
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, w[t].x, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].y, w[t].y, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].z, w[t].z, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].w, w[t].w, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < FLW_TILES; ++t) w[t] = wn[t];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a[q] = an[q];
     }
 #pragma unroll
     for (int t = 0; t < FLW_TILES; ++t) {
@@ -459,16 +487,18 @@ static int float_create_layerwise(dhq_float_plan *P, const int *dims, int L, dou
         float_lw_layer &Ly = P->lw[l];
         Ly.K = dims[l];
         Ly.M = dims[l + 1];
-        Ly.NJ = (Ly.K + 7) / 8;
+        Ly.NG = (Ly.K + 31) / 32;
         Ly.Mt = (Ly.M + 31) / 32;
-        std::vector<float> frag((size_t)Ly.Mt * Ly.NJ * 64 * 4, 0.0f);
+        std::vector<float> frag((size_t)Ly.Mt * Ly.NG * 4 * 64 * 4, 0.0f);
         for (int T = 0; T < Ly.Mt; ++T)
-            for (int j = 0; j < Ly.NJ; ++j)
-                for (int ln = 0; ln < 64; ++ln)
-                    for (int e = 0; e < 4; ++e) {
-                        const int row = 32 * T + (ln & 31), k = 8 * j + 4 * (ln >> 5) + e;
-                        if (row < Ly.M && k < Ly.K) frag[(((size_t)T * Ly.NJ + j) * 64 + ln) * 4 + e] = W[l][(size_t)row * Ly.K + k];
-                    }
+            for (int J = 0; J < Ly.NG; ++J)
+                for (int q = 0; q < 4; ++q)
+                    for (int ln = 0; ln < 64; ++ln)
+                        for (int e = 0; e < 4; ++e) {
+                            const int row = 32 * T + (ln & 31), k = 32 * J + 16 * (ln >> 5) + 4 * q + e;
+                            if (row < Ly.M && k < Ly.K)
+                                frag[((((size_t)T * Ly.NG + J) * 4 + q) * 64 + ln) * 4 + e] = W[l][(size_t)row * Ly.K + k];
+                        }
         std::vector<float> bias(Ly.M);
         for (int f = 0; f < Ly.M; ++f) bias[f] = (l != L - 1) ? (float)((double)b[l][f] * rev) : b[l][f];
         if (hipMalloc((void **)&Ly.wfrag_dev, sizeof(float) * frag.size()) != hipSuccess) return DHQ_ENOMEM;
@@ -511,9 +541,9 @@ hipError_t dhq_float_launch_layerwise(const dhq_float_plan *P, const float *coor
             const int vec = (Ly.K % 4 == 0 && ((uintptr_t)cur & 15) == 0) ? 1 : 0;
             const float4 *wf = reinterpret_cast<const float4 *>(Ly.wfrag_dev);
             if (l != L - 1)
-                float_layer_kernel<true><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NJ, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+                float_layer_kernel<true><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
             else
-                float_layer_kernel<false><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NJ, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+                float_layer_kernel<false><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             cur = dst;
