@@ -18,6 +18,8 @@
  *     paragraph) with the round() and bit width b of Eq. 1 (Sec. 2.2)
  *   - MAC array with adder tree, quantization module between
  *     layers, sine after every layer but the last ............... Sec. 3.3
+ *   - wavelet activation of the second evaluated architecture ... Sec. 4.1, Table 1
+ *     (formula from the publication the paper cites for it; see dhqo_activation)
  *
  * Readings taken where the paper is silent (all listed in the design notes):
  * rotation over the input-feature dimension of both operands (it cancels in
@@ -35,6 +37,9 @@
  * integer un-rotation against an int64 matrix product with scipy's Hadamard
  * matrix, fan-out 1 against the one-sided path (bitwise), reconstruction
  * error bound of the de-rotated quantized weights.
+ * Wavelet activation: the real part of numpy's complex exponential, the
+ * zero-spread case against the sine network with shifted biases, evenness,
+ * zeros and envelope.
  * Parity unpinned: absolute image quality (Table 1) -- it needs the paper's
  * images and trained weights.
  */
@@ -220,12 +225,35 @@ int dhqo_igemm(const int8_t *q, const int8_t *w, int64_t N, int M, int Kp, int32
 }
 
 /*
+ * Activation functions (argument y = the layer's pre-activation, fp64).
+ *   DHQO_ACT_NONE   y                                   the output layer (Sec. 3.3)
+ *   DHQO_ACT_SINE   sin(omega0 y)                       SIREN (Sec. 3.1, 3.3)
+ *   DHQO_ACT_GABOR  cos(omega0 y) exp(-(s0 y)^2)        wavelet activation: the real part of
+ *                   the complex Gabor wavelet exp(j omega0 y - |s0 y|^2) of the WIRE
+ *                   architecture that Sec. 4.1 / Table 1 evaluate.  Reading: the paper names
+ *                   WIRE and cites its publication but prints neither the activation nor the
+ *                   layer structure; the activation is taken from that publication, and the
+ *                   network is kept real-valued (real weights, real part of the wavelet), so
+ *                   that every other step of the quantized path is unchanged.
+ */
+#define DHQO_ACT_NONE 0
+#define DHQO_ACT_SINE 1
+#define DHQO_ACT_GABOR 2
+
+double dhqo_activation(double y, int act, double omega0, double s0)
+{
+    if (act == DHQO_ACT_SINE) return sin(omega0 * y);
+    if (act == DHQO_ACT_GABOR) return cos(omega0 * y) * exp(-(s0 * y) * (s0 * y));
+    return y;
+}
+
+/*
  * Dequantize, add bias and (except in the output layer) apply the sine
- * (Sec. 3.3): y = acc * (s_a * s_w) + b;  a = sin(omega0 * y), rounded once
- * to fp32;  the output layer returns (float) y.
+ * or the wavelet (Sec. 3.3): y = acc * (s_a * s_w) + b;  a = activation(y),
+ * rounded once to fp32;  the output layer (act = DHQO_ACT_NONE) returns (float) y.
  */
 int dhqo_epilogue(const int32_t *acc, int64_t N, int M, float s_a, float s_w,
-                  const float *b, int apply_sine, float omega0, float *out)
+                  const float *b, int act, float omega0, float s0, float *out)
 {
     if (!acc || !b || !out) return DHQO_EINVAL;
     const double sc = (double)s_a * (double)s_w;
@@ -233,7 +261,7 @@ int dhqo_epilogue(const int32_t *acc, int64_t N, int M, float s_a, float s_w,
     for (int64_t i = 0; i < N; ++i)
         for (int j = 0; j < M; ++j) {
             double y = (double)acc[i * M + j] * sc + (double)b[j];
-            out[i * M + j] = apply_sine ? (float)sin((double)omega0 * y) : (float)y;
+            out[i * M + j] = (float)dhqo_activation(y, act, (double)omega0, (double)s0);
         }
     return DHQO_OK;
 }
@@ -272,8 +300,8 @@ int dhqo_quantize_weights(const float *W, int M, int K, int bits, int8_t *Wq, fl
  * Optional dumps (may be NULL): rot N x Kp fp64, codes N x Kp, acc N x M.
  */
 int dhqo_layer(const float *a_in, int64_t N, int K, int M, const int8_t *Wq, float s_w,
-               const float *bias, float *s_a, int calibrate, int bits_a, int apply_sine,
-               float omega0, float *out, double *dump_rot, int8_t *dump_codes,
+               const float *bias, float *s_a, int calibrate, int bits_a, int act,
+               float omega0, float s0, float *out, double *dump_rot, int8_t *dump_codes,
                int32_t *dump_acc)
 {
     if (!a_in || !Wq || !bias || !s_a || !out || N < 0) return DHQO_EINVAL;
@@ -292,7 +320,7 @@ int dhqo_layer(const float *a_in, int64_t N, int K, int M, const int8_t *Wq, flo
     if (rc) goto done;
     rc = dhqo_igemm(codes, Wq, N, M, Kp, acc);
     if (rc) goto done;
-    rc = dhqo_epilogue(acc, N, M, *s_a, s_w, bias, apply_sine, omega0, out);
+    rc = dhqo_epilogue(acc, N, M, *s_a, s_w, bias, act, omega0, s0, out);
 done:
     free(ad);
     if (!dump_rot) free(rot);
@@ -306,11 +334,11 @@ done:
  * dims[l+1] x next_pow2(dims[l]); bias[l] has dims[l+1] entries.
  * s_a has n_layers entries: read when calibrate == 0, written when
  * calibrate != 0 (each layer's scale is then measured on the input that the
- * quantized layers before it produced).  The sine follows every layer except
+ * quantized layers before it produced).  The activation `act` (sine or wavelet) follows every layer except
  * the last.  Optional per-layer dumps: arrays of n_layers pointers, each
  * either NULL or a buffer of the size given in dhqo_layer.
  */
-int dhqo_forward(int n_layers, const int32_t *dims, float omega0, int bits_a,
+int dhqo_forward(int n_layers, const int32_t *dims, int act, float omega0, float s0, int bits_a,
                  const int8_t *const *Wq, const float *s_w, const float *const *bias,
                  float *s_a, int calibrate, const float *coords, int64_t N, float *out,
                  double *const *dump_rot, int8_t *const *dump_codes,
@@ -327,7 +355,7 @@ int dhqo_forward(int n_layers, const int32_t *dims, float omega0, int bits_a,
         float *dst = last ? out : (float *)malloc(sizeof(float) * (size_t)(N * M + 1));
         if (!dst) { rc = DHQO_ENOMEM; break; }
         rc = dhqo_layer(cur, N, K, M, Wq[l], s_w[l], bias[l], &s_a[l], calibrate, bits_a,
-                        !last, omega0, dst, dump_rot ? dump_rot[l] : NULL,
+                        last ? DHQO_ACT_NONE : act, omega0, s0, dst, dump_rot ? dump_rot[l] : NULL,
                         dump_codes ? dump_codes[l] : NULL, dump_acc ? dump_acc[l] : NULL);
         if (rc == DHQO_OK && dump_act && dump_act[l])
             memcpy(dump_act[l], dst, sizeof(float) * (size_t)(N * M));
@@ -411,8 +439,8 @@ int dhqo_unrotate_acc(const int32_t *acc, int64_t N, int Mp, int32_t *z)
  * y[j] = z[j] * (s_a s_w / sqrt(Mp)) + b[j] for j < M.
  */
 int dhqo_layer_two_sided(const float *a_in, int64_t N, int K, int M, const int8_t *Wq, float s_w,
-                         const float *bias, float *s_a, int calibrate, int bits_a, int apply_sine,
-                         float omega0, float *out, double *dump_rot, int8_t *dump_codes,
+                         const float *bias, float *s_a, int calibrate, int bits_a, int act,
+                         float omega0, float s0, float *out, double *dump_rot, int8_t *dump_codes,
                          int32_t *dump_acc, int32_t *dump_unrot)
 {
     if (!a_in || !Wq || !bias || !s_a || !out || N < 0) return DHQO_EINVAL;
@@ -440,7 +468,7 @@ int dhqo_layer_two_sided(const float *a_in, int64_t N, int K, int M, const int8_
         for (int64_t i = 0; i < N; ++i)
             for (int j = 0; j < M; ++j) {
                 double y = (double)z[i * Mp + j] * sc + (double)bias[j];
-                out[i * M + j] = apply_sine ? (float)sin((double)omega0 * y) : (float)y;
+                out[i * M + j] = (float)dhqo_activation(y, act, (double)omega0, (double)s0);
             }
     }
 done:
@@ -453,7 +481,7 @@ done:
 }
 
 /* Whole quantized forward, two-sided; arguments as dhqo_forward (Wq[l] is Mp x Kp). */
-int dhqo_forward_two_sided(int n_layers, const int32_t *dims, float omega0, int bits_a,
+int dhqo_forward_two_sided(int n_layers, const int32_t *dims, int act, float omega0, float s0, int bits_a,
                            const int8_t *const *Wq, const float *s_w, const float *const *bias,
                            float *s_a, int calibrate, const float *coords, int64_t N, float *out,
                            double *const *dump_rot, int8_t *const *dump_codes,
@@ -470,7 +498,7 @@ int dhqo_forward_two_sided(int n_layers, const int32_t *dims, float omega0, int 
         float *dst = last ? out : (float *)malloc(sizeof(float) * (size_t)(N * M + 1));
         if (!dst) { rc = DHQO_ENOMEM; break; }
         rc = dhqo_layer_two_sided(cur, N, K, M, Wq[l], s_w[l], bias[l], &s_a[l], calibrate, bits_a,
-                                  !last, omega0, dst, dump_rot ? dump_rot[l] : NULL,
+                                  last ? DHQO_ACT_NONE : act, omega0, s0, dst, dump_rot ? dump_rot[l] : NULL,
                                   dump_codes ? dump_codes[l] : NULL, dump_acc ? dump_acc[l] : NULL, NULL);
         if (rc == DHQO_OK && dump_act && dump_act[l])
             memcpy(dump_act[l], dst, sizeof(float) * (size_t)(N * M));
@@ -512,9 +540,9 @@ int dhqo_dequantize_weights(const int8_t *Wq, float s_w, int M, int K, float *Wt
 /*
  * Float reference: the plain MLP, neither rotated nor quantized, in fp64
  * (out64) and, if out32 is not NULL, a second pass in fp32 arithmetic.
- * y = W a + b per layer, sine after all but the last.
+ * y = W a + b per layer, the activation (sine or wavelet) after all but the last.
  */
-int dhqo_mlp_float(int n_layers, const int32_t *dims, float omega0, const float *const *W,
+int dhqo_mlp_float(int n_layers, const int32_t *dims, int act, float omega0, float s0, const float *const *W,
                    const float *const *bias, const float *coords, int64_t N, double *out64,
                    float *out32)
 {
@@ -549,8 +577,11 @@ int dhqo_mlp_float(int n_layers, const int32_t *dims, float omega0, const float 
                         }
                         s += (double)bias[l][j];
                         sf += bias[l][j];
-                        y[j] = last ? s : sin((double)omega0 * s);
-                        yf[j] = last ? sf : sinf(omega0 * sf);
+                        y[j] = last ? s : dhqo_activation(s, act, (double)omega0, (double)s0);
+                        if (last) yf[j] = sf;
+                        else if (act == DHQO_ACT_GABOR) yf[j] = cosf(omega0 * sf) * expf(-(s0 * sf) * (s0 * sf));
+                        else if (act == DHQO_ACT_SINE) yf[j] = sinf(omega0 * sf);
+                        else yf[j] = sf;
                     }
                     memcpy(a, y, sizeof(double) * (size_t)M);
                     memcpy(af, yf, sizeof(float) * (size_t)M);

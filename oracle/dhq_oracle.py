@@ -61,21 +61,23 @@ def _declare(L: C.CDLL) -> None:
     L.dhqo_dequantize.argtypes = [_i8p, C.c_int64, C.c_float, _dp]
     L.dhqo_dequantize.restype = None
     L.dhqo_igemm.argtypes = [_i8p, _i8p, C.c_int64, C.c_int, C.c_int, _i32p]
+    L.dhqo_activation.argtypes = [C.c_double, C.c_int, C.c_double, C.c_double]
+    L.dhqo_activation.restype = C.c_double
     L.dhqo_epilogue.argtypes = [_i32p, C.c_int64, C.c_int, C.c_float, C.c_float, _fp, C.c_int,
-                                C.c_float, _fp]
+                                C.c_float, C.c_float, _fp]
     L.dhqo_quantize_weights.argtypes = [_fp, C.c_int, C.c_int, C.c_int, _i8p, _fp, _dp]
     L.dhqo_layer.argtypes = [_fp, C.c_int64, C.c_int, C.c_int, _i8p, C.c_float, _fp, _fp, C.c_int,
-                             C.c_int, C.c_int, C.c_float, _fp, _dp, _i8p, _i32p]
-    L.dhqo_forward.argtypes = [C.c_int, _i32p, C.c_float, C.c_int, C.POINTER(_i8p), _fp,
+                             C.c_int, C.c_int, C.c_float, C.c_float, _fp, _dp, _i8p, _i32p]
+    L.dhqo_forward.argtypes = [C.c_int, _i32p, C.c_int, C.c_float, C.c_float, C.c_int, C.POINTER(_i8p), _fp,
                                C.POINTER(_fp), _fp, C.c_int, _fp, C.c_int64, _fp,
                                C.POINTER(_dp), C.POINTER(_i8p), C.POINTER(_i32p), C.POINTER(_fp)]
     L.dhqo_quantize_weights_two_sided.argtypes = [_fp, C.c_int, C.c_int, C.c_int, _i8p, _fp, _dp]
     L.dhqo_unrotate_acc.argtypes = [_i32p, C.c_int64, C.c_int, _i32p]
     L.dhqo_layer_two_sided.argtypes = [_fp, C.c_int64, C.c_int, C.c_int, _i8p, C.c_float, _fp, _fp, C.c_int,
-                                       C.c_int, C.c_int, C.c_float, _fp, _dp, _i8p, _i32p, _i32p]
+                                       C.c_int, C.c_int, C.c_float, C.c_float, _fp, _dp, _i8p, _i32p, _i32p]
     L.dhqo_forward_two_sided.argtypes = L.dhqo_forward.argtypes
     L.dhqo_dequantize_weights.argtypes = [_i8p, C.c_float, C.c_int, C.c_int, _fp]
-    L.dhqo_mlp_float.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp), _fp,
+    L.dhqo_mlp_float.argtypes = [C.c_int, _i32p, C.c_int, C.c_float, C.c_float, C.POINTER(_fp), C.POINTER(_fp), _fp,
                                  C.c_int64, _dp, _fp]
     L.dhqo_mlp_rotated_f64.argtypes = [C.c_int, _i32p, C.c_float, C.POINTER(_fp), C.POINTER(_fp),
                                        _fp, C.c_int64, _dp]
@@ -159,14 +161,34 @@ def igemm(q: np.ndarray, w: np.ndarray) -> np.ndarray:
     return acc
 
 
+ACT_NONE, ACT_SINE, ACT_GABOR = 0, 1, 2
+
+
+def _act(apply_act: bool, gabor_s0: Optional[float]):
+    """(activation code, spread) of a layer: none for the output layer, else the sine, or the
+    wavelet cos(omega0 y) exp(-(s0 y)^2) when a spread s0 is given."""
+    if not apply_act:
+        return ACT_NONE, 0.0
+    return (ACT_SINE, 0.0) if gabor_s0 is None else (ACT_GABOR, float(gabor_s0))
+
+
+def activation(y: np.ndarray, omega0: float, gabor_s0: Optional[float] = None) -> np.ndarray:
+    """Elementwise activation in fp64: sin(omega0 y), or the wavelet if gabor_s0 is given."""
+    act, s0 = _act(True, gabor_s0)
+    y = np.asarray(y, dtype=np.float64)
+    f = lib().dhqo_activation
+    return np.array([f(float(v), act, float(omega0), s0) for v in y.ravel()]).reshape(y.shape)
+
+
 def epilogue(acc: np.ndarray, s_a: float, s_w: float, b: np.ndarray, apply_sine: bool,
-             omega0: float) -> np.ndarray:
+             omega0: float, gabor_s0: Optional[float] = None) -> np.ndarray:
     acc = _c(acc, np.int32)
     b = _c(b, np.float32)
     N, M = acc.shape
     out = np.empty((N, M), dtype=np.float32)
     _check(lib().dhqo_epilogue(_ptr(acc, _i32p), N, M, C.c_float(s_a), C.c_float(s_w),
-                               _ptr(b, _fp), int(apply_sine), C.c_float(omega0), _ptr(out, _fp)),
+                               _ptr(b, _fp), _act(apply_sine, gabor_s0)[0], C.c_float(omega0),
+                               C.c_float(_act(apply_sine, gabor_s0)[1]), _ptr(out, _fp)),
            "epilogue")
     return out
 
@@ -222,6 +244,7 @@ class QuantizedNet:
     bias: List[np.ndarray]
     s_a: Optional[np.ndarray] = None
     two_sided: bool = False
+    gabor_s0: Optional[float] = None  # None: sine layers; a number: wavelet layers with that spread
 
 
 @dataclass
@@ -233,7 +256,8 @@ class ForwardDump:
 
 
 def quantize_net(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int,
-                 W: Sequence[np.ndarray], bias: Sequence[np.ndarray], two_sided: bool = False) -> QuantizedNet:
+                 W: Sequence[np.ndarray], bias: Sequence[np.ndarray], two_sided: bool = False,
+                 gabor_s0: Optional[float] = None) -> QuantizedNet:
     Wq, s_w = [], []
     for Wl in W:
         q, s = (quantize_weights_two_sided if two_sided else quantize_weights)(Wl, bits_w)
@@ -241,7 +265,7 @@ def quantize_net(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int,
         s_w.append(s)
     return QuantizedNet(list(dims), float(omega0), bits_w, bits_a, Wq,
                         np.asarray(s_w, dtype=np.float32),
-                        [_c(b, np.float32) for b in bias], None, two_sided)
+                        [_c(b, np.float32) for b in bias], None, two_sided, gabor_s0)
 
 
 def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump: bool = False):
@@ -276,7 +300,8 @@ def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump
         acc_p = (_i32p * L)(*[_ptr(a, _i32p) for a in d.acc])
         act_p = (_fp * L)(*[_ptr(a, _fp) for a in d.act])
     fwd = lib().dhqo_forward_two_sided if net.two_sided else lib().dhqo_forward
-    rc = fwd(L, _ptr(dimsa, _i32p), C.c_float(net.omega0), net.bits_a, Wq_p,
+    act, s0 = _act(True, net.gabor_s0)
+    rc = fwd(L, _ptr(dimsa, _i32p), act, C.c_float(net.omega0), C.c_float(s0), net.bits_a, Wq_p,
             _ptr(net.s_w, _fp), b_p, _ptr(s_a, _fp), int(calibrate),
             _ptr(coords, _fp), N, _ptr(out, _fp), rot_p, cod_p, acc_p, act_p)
     _check(rc, "forward")
@@ -286,7 +311,7 @@ def forward(net: QuantizedNet, coords: np.ndarray, calibrate: bool = False, dump
 
 
 def layer(a_in: np.ndarray, Wq: np.ndarray, s_w: float, bias: np.ndarray, s_a: Optional[float],
-          bits_a: int, apply_sine: bool, omega0: float):
+          bits_a: int, apply_sine: bool, omega0: float, gabor_s0: Optional[float] = None):
     """One quantized layer. s_a=None measures the scale on this input.
     Returns dict(rot, codes, acc, act, s_a)."""
     a_in = _c(a_in, np.float32)
@@ -301,14 +326,16 @@ def layer(a_in: np.ndarray, Wq: np.ndarray, s_w: float, bias: np.ndarray, s_a: O
     out = np.empty((N, M), dtype=np.float32)
     s = C.c_float(0.0 if s_a is None else s_a)
     rc = lib().dhqo_layer(_ptr(a_in, _fp), N, K, M, _ptr(Wq, _i8p), C.c_float(s_w), _ptr(bias, _fp),
-                          C.byref(s), int(s_a is None), bits_a, int(apply_sine), C.c_float(omega0),
+                          C.byref(s), int(s_a is None), bits_a, _act(apply_sine, gabor_s0)[0], C.c_float(omega0),
+                          C.c_float(_act(apply_sine, gabor_s0)[1]),
                           _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p))
     _check(rc, "layer")
     return dict(rot=rot, codes=codes, acc=acc, act=out, s_a=np.float32(s.value))
 
 
 def layer_two_sided(a_in: np.ndarray, M: int, Wq: np.ndarray, s_w: float, bias: np.ndarray,
-                    s_a: Optional[float], bits_a: int, apply_sine: bool, omega0: float):
+                    s_a: Optional[float], bits_a: int, apply_sine: bool, omega0: float,
+                    gabor_s0: Optional[float] = None):
     """One two-sided layer (Wq is Mp x Kp, M outputs kept). s_a=None measures the scale.
     Returns dict(rot, codes, acc [N x Mp, rotated], unrot [N x Mp], act [N x M], s_a)."""
     a_in = _c(a_in, np.float32)
@@ -324,8 +351,8 @@ def layer_two_sided(a_in: np.ndarray, M: int, Wq: np.ndarray, s_w: float, bias: 
     out = np.empty((N, M), dtype=np.float32)
     s = C.c_float(0.0 if s_a is None else s_a)
     rc = lib().dhqo_layer_two_sided(_ptr(a_in, _fp), N, K, M, _ptr(Wq, _i8p), C.c_float(s_w), _ptr(bias, _fp),
-                                    C.byref(s), int(s_a is None), bits_a, int(apply_sine), C.c_float(omega0),
-                                    _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p),
+                                    C.byref(s), int(s_a is None), bits_a, _act(apply_sine, gabor_s0)[0],
+                                    C.c_float(omega0), C.c_float(_act(apply_sine, gabor_s0)[1]), _ptr(out, _fp), _ptr(rot, _dp), _ptr(codes, _i8p), _ptr(acc, _i32p),
                                     _ptr(unrot, _i32p))
     _check(rc, "layer_two_sided")
     return dict(rot=rot, codes=codes, acc=acc, unrot=unrot, act=out, s_a=np.float32(s.value))
@@ -342,18 +369,19 @@ def dequantize_weights(Wq: np.ndarray, s_w: float, K: int) -> np.ndarray:
 
 
 def mlp_w8a32(dims: Sequence[int], omega0: float, bits_w: int, W: Sequence[np.ndarray],
-              bias: Sequence[np.ndarray], coords: np.ndarray):
+              bias: Sequence[np.ndarray], coords: np.ndarray, gabor_s0: Optional[float] = None):
     """Weight-only quantization: the plain MLP on the de-quantized weights. Returns (out_fp64, out_fp32, W~)."""
     Wt = []
     for l, Wl in enumerate(W):
         q, s = quantize_weights(Wl, bits_w)
         Wt.append(dequantize_weights(q, s, dims[l]))
-    o64, o32 = mlp_float(dims, omega0, Wt, bias, coords)
+    o64, o32 = mlp_float(dims, omega0, Wt, bias, coords, gabor_s0=gabor_s0)
     return o64, o32, Wt
 
 
 def mlp_float(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],
-              bias: Sequence[np.ndarray], coords: np.ndarray, want_f32: bool = True):
+              bias: Sequence[np.ndarray], coords: np.ndarray, want_f32: bool = True,
+              gabor_s0: Optional[float] = None):
     """Plain un-rotated, un-quantized MLP: returns (out_fp64, out_fp32 or None)."""
     L = len(dims) - 1
     Wc = [_c(w, np.float32) for w in W]
@@ -365,7 +393,8 @@ def mlp_float(dims: Sequence[int], omega0: float, W: Sequence[np.ndarray],
     o32 = np.empty((N, dims[-1]), dtype=np.float32) if want_f32 else None
     W_p = (_fp * L)(*[_ptr(w, _fp) for w in Wc])
     b_p = (_fp * L)(*[_ptr(b, _fp) for b in bc])
-    _check(lib().dhqo_mlp_float(L, _ptr(dimsa, _i32p), C.c_float(omega0), W_p, b_p,
+    act, s0 = _act(True, gabor_s0)
+    _check(lib().dhqo_mlp_float(L, _ptr(dimsa, _i32p), act, C.c_float(omega0), C.c_float(s0), W_p, b_p,
                                 _ptr(coords, _fp), N, _ptr(o64, _dp), _ptr(o32, _fp)), "mlp_float")
     return o64, o32
 

@@ -488,3 +488,96 @@ def test_w8a32_error_shrinks_with_bits_and_stays_below_w8a8():
     net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
     w8a8 = o.forward(net, coords, calibrate=True)
     assert errs[2] < float(np.sqrt(np.mean((w8a8 - ref) ** 2)))
+
+
+# ------------------------------------------------- wavelet activation (Sec. 4.1, Table 1: WIRE)
+S0 = 10.0  # spread of the Gaussian envelope used by the wavelet tests
+
+
+def test_wavelet_is_real_part_of_complex_gabor():
+    """cos(w y) exp(-(s y)^2) against the complex exponential exp(j w y - |s y|^2) evaluated by numpy."""
+    y = np.linspace(-0.4, 0.4, 2001)
+    ref = np.real(np.exp(1j * 30.0 * y - np.abs(S0 * y) ** 2))
+    assert np.abs(o.activation(y, 30.0, S0) - ref).max() <= 1e-15
+    assert np.abs(o.activation(y, 7.5, 0.5) - np.real(np.exp((1j * 7.5 - 0.25 * y) * y))).max() <= 1e-15
+
+
+def test_wavelet_closed_form_facts():
+    y = np.linspace(-0.5, 0.5, 1001)
+    g = o.activation(y, 30.0, S0)
+    assert o.activation(np.zeros(1), 30.0, S0)[0] == 1.0                       # peak at the origin
+    assert np.array_equal(g, o.activation(-y, 30.0, S0))                       # even
+    assert (np.abs(g) <= np.exp(-(S0 * y) ** 2) + 1e-16).all()                 # inside the Gaussian envelope
+    zeros = (np.arange(-4, 4) + 0.5) * math.pi / 30.0                          # cos(w y) = 0
+    assert np.abs(o.activation(zeros, 30.0, S0)).max() <= 1e-15
+    k = np.arange(-3, 4) * 2.0 * math.pi / 30.0                                # cos(w y) = 1: the envelope itself
+    assert np.abs(o.activation(k, 30.0, S0) - np.exp(-(S0 * k) ** 2)).max() <= 1e-15
+    assert np.abs(o.activation(y, 30.0, 0.0) - np.cos(30.0 * y)).max() <= 1e-15  # no envelope: a cosine
+    # the sine path did not change: sin from the same entry point
+    assert np.abs(o.activation(y, 30.0) - np.sin(30.0 * y)).max() <= 1e-15
+
+
+def test_wavelet_zero_spread_is_the_sine_network_with_shifted_biases():
+    """cos(w y) = sin(w (y + pi / 2w)): with s0 = 0 a wavelet layer is a sine layer whose biases
+    are shifted by a quarter period -- ties the wavelet path to the already pinned sine path."""
+    wl, coords, W, b = synth.make("C1")
+    shift = np.float64(math.pi / (2.0 * wl.omega0))
+    b_shift = [bl.astype(np.float64) + (shift if l < len(b) - 1 else 0.0) for l, bl in enumerate(b)]
+    # plain fp64 network
+    w64, _ = o.mlp_float(wl.dims, wl.omega0, W, b, coords[::5], want_f32=False, gabor_s0=0.0)
+    s64, _ = o.mlp_float(wl.dims, wl.omega0, W, [x.astype(np.float32) for x in b_shift], coords[::5], want_f32=False)
+    assert np.abs(w64 - s64).max() <= 1e-4      # the shifted biases are rounded to fp32
+    # one quantized layer, teacher-forced: same codes and accumulators, activations equal up to that rounding
+    Wq, sw = o.quantize_weights(W[1], 8)
+    rng = np.random.default_rng(5)
+    a_in = rng.uniform(-1, 1, size=(257, wl.dims[1])).astype(np.float32)
+    lw = o.layer(a_in, Wq, sw, b[1], None, 8, True, wl.omega0, gabor_s0=0.0)
+    ls = o.layer(a_in, Wq, sw, b_shift[1].astype(np.float32), None, 8, True, wl.omega0)
+    assert np.array_equal(lw["codes"], ls["codes"]) and np.array_equal(lw["acc"], ls["acc"])
+    assert np.abs(lw["act"] - ls["act"]).max() <= 5e-6
+    # and the two-sided layer
+    Wq2, sw2 = o.quantize_weights_two_sided(W[1], 8)
+    lw2 = o.layer_two_sided(a_in, wl.dims[2], Wq2, sw2, b[1], None, 8, True, wl.omega0, gabor_s0=0.0)
+    ls2 = o.layer_two_sided(a_in, wl.dims[2], Wq2, sw2, b_shift[1].astype(np.float32), None, 8, True, wl.omega0)
+    assert np.array_equal(lw2["unrot"], ls2["unrot"]) and np.abs(lw2["act"] - ls2["act"]).max() <= 5e-6
+
+
+@pytest.mark.parametrize("two_sided", [False, True])
+def test_wavelet_forward_is_composition_of_steps(two_sided):
+    """The quantized wavelet forward, layer by layer from its own dumped integers: numpy's dequantization and
+    the complex-exponential form of the wavelet give the dumped activations, which are the next layer's input."""
+    wl, coords, W, b = synth.make("C1")
+    coords = coords[::9]
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two_sided, gabor_s0=S0)
+    out, d = o.forward(net, coords, calibrate=True, dump=True)
+    L = len(wl.dims) - 1
+    a = coords.astype(np.float32)
+    for l in range(L):
+        one = (o.layer_two_sided(a, wl.dims[l + 1], net.Wq[l], net.s_w[l], b[l], float(net.s_a[l]), 8, l < L - 1,
+                                 wl.omega0, gabor_s0=S0) if two_sided else
+               o.layer(a, net.Wq[l], net.s_w[l], b[l], float(net.s_a[l]), 8, l < L - 1, wl.omega0, gabor_s0=S0))
+        assert np.array_equal(one["codes"], d.codes[l]) and np.array_equal(one["acc"], d.acc[l])
+        M = wl.dims[l + 1]
+        z = (o.unrotate_acc(d.acc[l])[:, :M] if two_sided else d.acc[l]).astype(np.float64)
+        sc = float(net.s_a[l]) * float(net.s_w[l]) / (math.sqrt(d.acc[l].shape[1]) if two_sided else 1.0)
+        y = z * sc + b[l].astype(np.float64)
+        ref = np.real(np.exp(1j * wl.omega0 * y - (S0 * y) ** 2)) if l < L - 1 else y
+        assert np.abs(ref - d.act[l]).max() <= 1e-7      # one fp32 rounding of a value in [-1, 1]
+        a = d.act[l]
+    assert np.array_equal(a, out)
+
+
+def test_wavelet_quantized_network_tracks_the_float_one():
+    """Error of the quantized wavelet network against the plain one falls with the bit width, and the
+    weight-only network is closer than the fully quantized one (the ordering of Fig. 2)."""
+    wl, coords, W, b = synth.make("C1")
+    coords = coords[::3]
+    ref, r32 = o.mlp_float(wl.dims, wl.omega0, W, b, coords, gabor_s0=S0)
+    assert np.abs(ref - r32).max() <= 1e-4 and np.abs(ref).max() > 0.05
+    errs = []
+    for bits in (4, 6, 8):
+        net = o.quantize_net(wl.dims, wl.omega0, bits, bits, W, b, gabor_s0=S0)
+        errs.append(np.sqrt(np.mean((o.forward(net, coords, calibrate=True) - ref) ** 2)))
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 0.05
+    w8a32, _, _ = o.mlp_w8a32(wl.dims, wl.omega0, 8, W, b, coords, gabor_s0=S0)
+    assert np.sqrt(np.mean((w8a32 - ref) ** 2)) < errs[2]
