@@ -10,7 +10,8 @@
  *     q   = clamp(rne(x^ / s_a[l]), -qmax, qmax)  the "standard quantizer", Sec. 3.2
  *     acc = q * Wq[l]^T   (int8 x int8 -> int32)  MAC array + adder tree, Sec. 3.3
  *     y   = acc * (s_a[l] * s_w[l]) + b[l]
- *     a_l = sin(omega0 * y)   (all layers but the last; the last returns y)
+ *     a_l = sin(omega0 * y)   (all layers but the last; the last returns y;
+ *                              dhq_quantize_weights_wavelet: a wavelet instead of the sine)
  *
  * with Wq[l] = clamp(rne((pad(W[l]) * H_Kp / sqrt(Kp)) / s_w[l])) produced once,
  * offline, by dhq_quantize_weights, and qmax = 2^(bits-1) - 1.  The rotation is
@@ -127,6 +128,21 @@ int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
  */
 int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
                               const float *const *b_host, dhq_model **out);
+
+/*
+ * The same offline step for a network with wavelet activations, the second architecture the
+ * paper evaluates (WIRE: Sec. 4.1, Table 1): every layer but the last is followed by
+ *     a = cos(omega0 y) exp(-(s0 y)^2)
+ * instead of sin(omega0 y) -- the real part of the complex Gabor wavelet exp(j omega0 y - |s0 y|^2)
+ * of the publication the paper cites for WIRE (the paper itself does not print the activation;
+ * layers stay real-valued, so rotation, quantizer, integer GEMM and dequantization are those of
+ * the sine network).  `mode` as in dhq_quantize_weights_mode (both rotation modes, all three
+ * precisions); s0 >= 0 is the spread of the Gaussian envelope (finite; 0 leaves a plain cosine);
+ * omega0 must not be 0.  Such a model runs layer by layer: DHQ_FUSED returns DHQ_EUNSUPPORTED
+ * (also with DHQ_DYNAMIC), dhq_has_fused 0; everything else behaves as for a sine model.
+ */
+int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float s0, const float *const *W_host,
+                                 const float *const *b_host, dhq_model **out);
 
 /* Static per-layer activation scales s_a (host, n_layers entries, each finite and > 0). */
 int dhq_set_act_scales(dhq_model *m, const float *s_a_host);

@@ -23,7 +23,7 @@ DHQ_ROTATE_IN, DHQ_ROTATE_BOTH = 0, 1
 DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 
 # every symbol include/dhq.h declares
-EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
+EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
            "dhq_get_weight_codes", "dhq_forward", "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
            "dhq_free", "dhq_strerror", "dhq_version")
 
@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.dhq_quantize_weights.argtypes = [C.POINTER(dhq_net_desc), _fpp, _fpp, C.POINTER(C.c_void_p)]
         L.dhq_quantize_weights_mode.argtypes = [C.POINTER(dhq_net_desc), C.c_uint32, _fpp, _fpp, C.POINTER(C.c_void_p)]
+        L.dhq_quantize_weights_wavelet.argtypes = [C.POINTER(dhq_net_desc), C.c_uint32, C.c_float, _fpp, _fpp,
+                                                   C.POINTER(C.c_void_p)]
         L.dhq_get_dynamic_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_void_p]
         L.dhq_set_act_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dhq_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
@@ -113,6 +115,16 @@ def dhq_quantize_weights(dims: Sequence[int], omega0: float, bits_w: int, bits_a
 
 def dhq_quantize_weights_mode(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int, mode: int,
                               W: Sequence[np.ndarray], b: Sequence[np.ndarray]) -> int:
+    return _quantize(dims, omega0, bits_w, bits_a, mode, None, W, b)
+
+
+def dhq_quantize_weights_wavelet(dims: Sequence[int], omega0: float, bits_w: int, bits_a: int, mode: int, s0: float,
+                                 W: Sequence[np.ndarray], b: Sequence[np.ndarray]) -> int:
+    """A network whose hidden layers end in the wavelet cos(omega0 y) exp(-(s0 y)^2)."""
+    return _quantize(dims, omega0, bits_w, bits_a, mode, float(s0), W, b)
+
+
+def _quantize(dims, omega0, bits_w, bits_a, mode, s0, W, b) -> int:
     L = len(dims) - 1
     dims_a = (C.c_int32 * (L + 1))(*[int(d) for d in dims])
     desc = dhq_net_desc(L, dims_a, float(omega0), int(bits_w), int(bits_a))
@@ -124,7 +136,11 @@ def dhq_quantize_weights_mode(dims: Sequence[int], omega0: float, bits_w: int, b
     Wp = (C.POINTER(C.c_float) * L)(*[w.ctypes.data_as(C.POINTER(C.c_float)) for w in Wc])
     bp = (C.POINTER(C.c_float) * L)(*[x.ctypes.data_as(C.POINTER(C.c_float)) for x in bc])
     h = C.c_void_p()
-    _ok(lib().dhq_quantize_weights_mode(C.byref(desc), int(mode), Wp, bp, C.byref(h)), "dhq_quantize_weights_mode")
+    if s0 is None:
+        _ok(lib().dhq_quantize_weights_mode(C.byref(desc), int(mode), Wp, bp, C.byref(h)), "dhq_quantize_weights_mode")
+    else:
+        _ok(lib().dhq_quantize_weights_wavelet(C.byref(desc), int(mode), C.c_float(s0), Wp, bp, C.byref(h)),
+            "dhq_quantize_weights_wavelet")
     return h.value
 
 
@@ -190,11 +206,11 @@ class Model:
     """Owns a dhq_model handle; methods forward to the functions above."""
 
     def __init__(self, dims: Sequence[int], omega0: float, W, b, bits_w: int = 8, bits_a: int = 8,
-                 mode: int = DHQ_ROTATE_IN):
+                 mode: int = DHQ_ROTATE_IN, wavelet_s0: Optional[float] = None):
         self.dims: List[int] = [int(d) for d in dims]
         self.n_layers = len(self.dims) - 1
         self.mode = int(mode)
-        self.handle = dhq_quantize_weights_mode(self.dims, omega0, bits_w, bits_a, mode, W, b)
+        self.handle = _quantize(self.dims, omega0, bits_w, bits_a, mode, wavelet_s0, W, b)
 
     def close(self) -> None:
         if getattr(self, "handle", None):

@@ -205,8 +205,9 @@ static int upload_layer(dhq_layer &Ly)
     return rc;
 }
 
-extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
-                                         const float *const *b_host, dhq_model **out)
+// The offline step behind every dhq_quantize_weights* entry point; act_kind follows every layer but the last.
+static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, float wavelet_s0, const float *const *W_host,
+                        const float *const *b_host, dhq_model **out)
 {
     if (!desc || !W_host || !b_host || !out || !desc->dims) return DHQ_EINVAL;
     *out = nullptr;
@@ -231,6 +232,8 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
     m->n_layers = L;
     for (int l = 0; l <= L; ++l) m->dims[l] = desc->dims[l];
     m->omega0 = desc->omega0;
+    m->act_kind = act_kind;
+    m->wavelet_s0 = wavelet_s0;
     m->bits_w = desc->bits_w;
     m->bits_a = desc->bits_a;
     m->qmax_a = (1 << (desc->bits_a - 1)) - 1;
@@ -260,7 +263,7 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
                 for (int k = 0; k < Ly.K; ++k) Wf[l][(size_t)r * Ly.K + k] = (float)(row[k] * inv);
             }
         }
-        rc = dhq_float_create(m->dims, L, m->omega0, Wf, bf, m->device, &m->flt);
+        rc = dhq_float_create(m->dims, L, m->omega0, dhq_hidden_act(m), Wf, bf, m->device, &m->flt);
         if (rc != DHQ_OK) {
             dhq_free(m);
             return rc;
@@ -283,9 +286,11 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
         // dhq_get_dynamic_scales before any dynamic forward reports zeros
         if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
     }
-    if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
-    if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
-    if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
+    // the whole-network kernels are built for the sine; a wavelet network runs layer by layer
+    const bool sine = (m->act_kind == DHQ_ACT_KIND_SINE);
+    if (rc == DHQ_OK && sine && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
+    if (rc == DHQ_OK && sine && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
+    if (rc == DHQ_OK && sine && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
         return rc;
@@ -294,10 +299,25 @@ extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode
     return DHQ_OK;
 }
 
+extern "C" int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const float *const *W_host,
+                                         const float *const *b_host, dhq_model **out)
+{
+    return create_model(desc, mode, DHQ_ACT_KIND_SINE, 0.f, W_host, b_host, out);
+}
+
 extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
                                     const float *const *b_host, dhq_model **out)
 {
-    return dhq_quantize_weights_mode(desc, DHQ_ROTATE_IN, W_host, b_host, out);
+    return create_model(desc, DHQ_ROTATE_IN, DHQ_ACT_KIND_SINE, 0.f, W_host, b_host, out);
+}
+
+extern "C" int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float s0, const float *const *W_host,
+                                            const float *const *b_host, dhq_model **out)
+{
+    if (!isfinite(s0) || s0 < 0.0f) return DHQ_EINVAL;
+    // the sine and cosine take omega0 y / 2 pi; the envelope's argument is recovered from it
+    if (desc && !(fabsf(desc->omega0) > 0.0f)) return DHQ_EINVAL;
+    return create_model(desc, mode, DHQ_ACT_KIND_WAVELET, s0, W_host, b_host, out);
 }
 
 static int update_fused_scales(dhq_model *m)
@@ -365,10 +385,10 @@ static hipError_t gemm_epilogue(const dhq_model *m, int l, const int8_t *codes, 
     const bool last = (l == m->n_layers - 1);
     const float c1 = dyn ? 0.0f : dhq_c1(m, l);
     const float *bias = last ? Ly.bias_dev : Ly.bias_rev_dev;
-    if (!m->rot_out) return dhq_launch_gemm(Ly, codes, rows, nullptr, dst, c1, bias, !last, dyn, st);
-    hipError_t e = dhq_launch_gemm(Ly, codes, rows, acc_ws, nullptr, 0.0f, nullptr, false, nullptr, st);
+    if (!m->rot_out) return dhq_launch_gemm(Ly, codes, rows, nullptr, dst, c1, bias, dhq_layer_act(m, l), dyn, st);
+    hipError_t e = dhq_launch_gemm(Ly, codes, rows, acc_ws, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st);
     if (e != hipSuccess) return e;
-    return dhq_launch_unrotate(acc_ws, rows, Ly.Mp, Ly.M, c1, bias, !last, dyn, nullptr, dst, st);
+    return dhq_launch_unrotate(acc_ws, rows, Ly.Mp, Ly.M, c1, bias, dhq_layer_act(m, l), dyn, nullptr, dst, st);
 }
 
 // Runs layers [0, upto) of the layer-by-layer path on `rows` coordinates with the model's static
@@ -563,15 +583,15 @@ extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_
     if (!acc_dev && !act_dev) return DHQ_OK;
     if (m->rot_out) {
         // rotated accumulators into the workspace, then un-rotated ones and the activation out
-        if (dhq_launch_gemm(Ly, codes, n, m->acc_ws, nullptr, 0.0f, nullptr, false, nullptr, st) != hipSuccess) return DHQ_EHIP;
-        return dhq_launch_unrotate(m->acc_ws, n, Ly.Mp, Ly.M, dhq_c1(m, layer), bias, !last, nullptr, acc_dev, act_dev, st) == hipSuccess
+        if (dhq_launch_gemm(Ly, codes, n, m->acc_ws, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st) != hipSuccess) return DHQ_EHIP;
+        return dhq_launch_unrotate(m->acc_ws, n, Ly.Mp, Ly.M, dhq_c1(m, layer), bias, dhq_layer_act(m, layer), nullptr, acc_dev, act_dev, st) == hipSuccess
                    ? DHQ_OK
                    : DHQ_EHIP;
     }
     // the int32 accumulators go through the workspace when the caller does not want them
     int32_t *acc = acc_dev ? acc_dev : reinterpret_cast<int32_t *>(m->act0);
-    if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, false, nullptr, st) != hipSuccess) return DHQ_EHIP;
-    if (act_dev && dhq_launch_epilogue(acc, n, Ly.M, dhq_c1(m, layer), bias, !last, act_dev, st) != hipSuccess) return DHQ_EHIP;
+    if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st) != hipSuccess) return DHQ_EHIP;
+    if (act_dev && dhq_launch_epilogue(acc, n, Ly.M, dhq_c1(m, layer), bias, dhq_layer_act(m, layer), act_dev, st) != hipSuccess) return DHQ_EHIP;
     return DHQ_OK;
 }
 
@@ -582,7 +602,7 @@ extern "C" int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *code
     if (m->flt) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!codes_dev || !acc_dev) return DHQ_EINVAL;
-    return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, false, nullptr, (hipStream_t)stream) == hipSuccess
+    return dhq_launch_gemm(m->layer[layer], codes_dev, n, acc_dev, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, (hipStream_t)stream) == hipSuccess
                ? DHQ_OK
                : DHQ_EHIP;
 }

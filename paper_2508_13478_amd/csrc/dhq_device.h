@@ -39,12 +39,36 @@ __device__ __forceinline__ float dhq_sin_rev(float t)
     return __builtin_amdgcn_sinf(t);
 }
 
-// Dequantize + bias (+ sine), Sec. 3.3.  For sine layers c1 and bias are pre-multiplied by
-// omega0 / (2 pi) on the host, so the fused multiply-add yields the argument in revolutions.
-__device__ __forceinline__ float dhq_epilogue(int acc, float c1, float bias, bool sine)
+// What follows a layer's affine part: nothing (the output layer), the sine of Sec. 3.3, or the
+// wavelet cos(omega0 y) exp(-(s0 y)^2) (the real part of the complex Gabor wavelet of the WIRE
+// architecture, Sec. 4.1).  c2 = 2 pi s0 sqrt(log2 e) / omega0 turns the argument in revolutions
+// into the square root of the envelope's base-2 exponent.
+#define DHQ_ACT_KIND_NONE 0
+#define DHQ_ACT_KIND_SINE 1
+#define DHQ_ACT_KIND_WAVELET 2
+struct dhq_act {
+    int kind;
+    float c2;
+};
+
+// The activation on an argument t = omega0 y / (2 pi) in revolutions (the hardware sine and
+// cosine take revolutions; the hardware exponential is base 2).
+__device__ __forceinline__ float dhq_activate_rev(float t, dhq_act act)
+{
+    if (act.kind == DHQ_ACT_KIND_WAVELET) {
+        const float g = t * act.c2;
+        return __builtin_amdgcn_cosf(t) * __builtin_amdgcn_exp2f(-(g * g));
+    }
+    return dhq_sin_rev(t);
+}
+
+// Dequantize + bias (+ activation), Sec. 3.3.  For layers with an activation c1 and bias are
+// pre-multiplied by omega0 / (2 pi) on the host, so the fused multiply-add yields the argument in
+// revolutions.
+__device__ __forceinline__ float dhq_epilogue(int acc, float c1, float bias, dhq_act act)
 {
     float y = __builtin_fmaf((float)acc, c1, bias);
-    return sine ? dhq_sin_rev(y) : y;
+    return act.kind == DHQ_ACT_KIND_NONE ? y : dhq_activate_rev(y, act);
 }
 
 // From max |un-normalised x^| of a layer input to the constants of the dynamic mode, in the same

@@ -81,6 +81,7 @@ struct dhq_float_plan {
     int n_cu = 0;
     int n_layers = 0;
     float rev = 0.f;
+    dhq_act actf = {DHQ_ACT_KIND_SINE, 0.f};  // what follows every layer but the last
     float_lw_layer lw[DHQ_MAX_LAYERS];
     float *act[2] = {nullptr, nullptr};  // DHQ_CHUNK x widest layer, fp32
 };
@@ -284,10 +285,10 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
 #define FLW_WAVES 4
 #define FLW_TILES 4
 
-template <bool SINE>
+template <int ACT>
 __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float *__restrict__ in, int64_t n, int K, int NG,
                                                                      int vec, const float4 *__restrict__ wfrag, int M, int Mt,
-                                                                     const float *__restrict__ bias, float rev,
+                                                                     const float *__restrict__ bias, float rev, float c2,
                                                                      float *__restrict__ out)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -361,7 +362,9 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int64_t row = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (row < n) out[row * M + f] = SINE ? dhq_sin_rev(__builtin_fmaf(acc[t][v], rev, bf)) : acc[t][v] + bf;
+                    if (row < n)
+                        out[row * M + f] = ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev(__builtin_fmaf(acc[t][v], rev, bf), dhq_act{ACT, c2})
+                                                                    : acc[t][v] + bf;
                 }
             }
         }
@@ -389,7 +392,8 @@ static int float_create_layerwise(dhq_float_plan *P, const int *dims, int L, dou
                                   const std::vector<std::vector<float>> &b);
 
 // W[l]: dims[l+1] x dims[l] fp32 (the weights the network is to run on), b[l]: dims[l+1].
-int dhq_float_create(const int *dims, int L, float omega0, const std::vector<std::vector<float>> &W,
+// `act` follows every layer but the last; the kernel fused over all layers exists for the sine only.
+int dhq_float_create(const int *dims, int L, float omega0, dhq_act act, const std::vector<std::vector<float>> &W,
                      const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan_out)
 {
     *plan_out = nullptr;
@@ -399,6 +403,7 @@ int dhq_float_create(const int *dims, int L, float omega0, const std::vector<std
     const double rev = (double)omega0 / 6.283185307179586476925286766559;
     P->n_layers = L;
     P->rev = (float)rev;
+    P->actf = act;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) {
         delete P;
@@ -406,7 +411,7 @@ int dhq_float_create(const int *dims, int L, float omega0, const std::vector<std
     }
     P->n_cu = prop.multiProcessorCount;
     int rc = float_create_layerwise(P, dims, L, rev, W, b);
-    if (rc == DHQ_OK && dhq_float_shape_ok(dims, L)) rc = float_create_fused(P, dims, L, rev, W, b);
+    if (rc == DHQ_OK && act.kind == DHQ_ACT_KIND_SINE && dhq_float_shape_ok(dims, L)) rc = float_create_fused(P, dims, L, rev, W, b);
     if (rc != DHQ_OK) {
         dhq_float_destroy(P);
         return rc;
@@ -540,10 +545,12 @@ hipError_t dhq_float_launch_layerwise(const dhq_float_plan *P, const float *coor
             // one 16-byte load per lane needs rows that start on 16-byte boundaries
             const int vec = (Ly.K % 4 == 0 && ((uintptr_t)cur & 15) == 0) ? 1 : 0;
             const float4 *wf = reinterpret_cast<const float4 *>(Ly.wfrag_dev);
-            if (l != L - 1)
-                float_layer_kernel<true><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+            if (l == L - 1)
+                float_layer_kernel<DHQ_ACT_KIND_NONE><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, 0.f, dst);
+            else if (P->actf.kind == DHQ_ACT_KIND_WAVELET)
+                float_layer_kernel<DHQ_ACT_KIND_WAVELET><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, P->actf.c2, dst);
             else
-                float_layer_kernel<false><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
+                float_layer_kernel<DHQ_ACT_KIND_SINE><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, 0.f, dst);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             cur = dst;

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "dhq.h"
+#include "dhq_device.h"
 
 #define DHQ_MAX_LAYERS 16
 #define DHQ_MAX_DIM 512
@@ -42,6 +43,8 @@ struct dhq_model {
     int n_layers = 0;
     int dims[DHQ_MAX_LAYERS + 1] = {0};
     float omega0 = 0.f;
+    int act_kind = DHQ_ACT_KIND_SINE;  // what follows every layer but the last: sine or wavelet
+    float wavelet_s0 = 0.f;            // spread of the wavelet's Gaussian envelope
     int bits_w = 8, bits_a = 8;
     int qmax_a = 127;
     bool have_scales = false;
@@ -87,14 +90,14 @@ hipError_t dhq_launch_wht_absmax(const float *in, int64_t n, int K, int Kp, unsi
 
 // acc = codes * Wq^T.  Exactly one of acc_out / act_out is written:
 //   acc_out  n x Mg int32
-//   act_out  n x Mg fp32 = sine ? sin(2 pi (acc * c1 + bias[f])) : acc * c1 + bias[f]
+//   act_out  n x Mg fp32 = activation(acc * c1 + bias[f]) (sine or wavelet of an argument in revolutions, or none)
 // If dyn != nullptr, c1 is read from dyn[1] on the device.
 hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                           float *act_out, float c1, const float *bias, bool sine, const float *dyn, hipStream_t st);
+                           float *act_out, float c1, const float *bias, dhq_act act, const float *dyn, hipStream_t st);
 
 // Two-sided variant: z = acc H_Mp (int32, n x Mp) and act[:, f < M] = epilogue(z, c1, bias).
 // Either output may be null.  If dyn != nullptr, c1 is read from dyn[1].
-hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
+hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, dhq_act act,
                                const float *dyn, int32_t *z_out, float *act_out, hipStream_t st);
 
 // The first of the two launches of dhq_launch_wht_absmax only: partial[0 .. *count) holds the
@@ -114,11 +117,25 @@ static inline double dhq_c1_over_sa(const dhq_model *m, int l)
     if (m->rot_out) c = c / sqrt((double)Ly.Mp);
     return c;
 }
+// The activation after every layer but the last, and after layer l, as the kernels take it.
+static inline dhq_act dhq_hidden_act(const dhq_model *m)
+{
+    dhq_act a;
+    a.kind = m->act_kind;
+    a.c2 = (a.kind == DHQ_ACT_KIND_WAVELET)
+               ? (float)(6.283185307179586476925286766559 * (double)m->wavelet_s0 * sqrt(1.4426950408889634074) / (double)m->omega0)
+               : 0.f;
+    return a;
+}
+static inline dhq_act dhq_layer_act(const dhq_model *m, int l)
+{
+    return (l == m->n_layers - 1) ? dhq_act{DHQ_ACT_KIND_NONE, 0.f} : dhq_hidden_act(m);
+}
 static inline float dhq_c1(const dhq_model *m, int l) { return (float)((double)m->layer[l].s_a * dhq_c1_over_sa(m, l)); }
 
-// act = epilogue(acc) elementwise, same formula as above.
+// act_out = epilogue(acc) elementwise, same formula as above.
 hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, const float *bias,
-                               bool sine, float *act, hipStream_t st);
+                               dhq_act act, float *act_out, hipStream_t st);
 
 // ---- fused path (defined in dhq_fused.hip) -------------------------------------------------
 // Builds the packed weights for the whole-network kernel if the shape is supported.
@@ -154,12 +171,12 @@ size_t dhq_fused2_dynamic_rows(int64_t n);
 hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
                                      float *partial, float *dyn, hipStream_t st);
 
-// Floating-point activations (defined in dhq_float.hip): the plain SIREN on the given fp32
+// Floating-point activations (defined in dhq_float.hip): the plain network (sine, or the wavelet `act`) on the given fp32
 // weights W[l] (dims[l+1] x dims[l]) and biases.  Every shape has the layer-by-layer path
 // (dhq_float_launch_layerwise); the shapes dhq_float_shape_ok accepts also have one kernel fused
 // over all layers (dhq_float_launch; dhq_float_has_fused tells).
 bool dhq_float_shape_ok(const int *dims, int n_layers);
-int dhq_float_create(const int *dims, int n_layers, float omega0, const std::vector<std::vector<float>> &W,
+int dhq_float_create(const int *dims, int n_layers, float omega0, dhq_act act, const std::vector<std::vector<float>> &W,
                      const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan);
 void dhq_float_destroy(dhq_float_plan *plan);
 hipError_t dhq_float_launch(const dhq_float_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int
                                                            const int8_t *__restrict__ wfrag, int M, int Mt,
                                                            int32_t *__restrict__ acc_out,
                                                            float *__restrict__ act_out, float c1,
-                                                           const float *__restrict__ bias, int sine,
+                                                           const float *__restrict__ bias, dhq_act act,
                                                            const float *__restrict__ dyn)
 {
     if (ACT && dyn) c1 = dyn[1];
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int
             const int64_t r = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (r >= n) continue;
             if (ACT)
-                act_out[r * M + f] = dhq_epilogue(acc[v], c1, bf, sine != 0);
+                act_out[r * M + f] = dhq_epilogue(acc[v], c1, bf, act);
             else
                 acc_out[r * M + f] = acc[v];
         }
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restri
                                                           const int8_t *__restrict__ wq, int M,
                                                           int32_t *__restrict__ acc_out,
                                                           float *__restrict__ act_out, float c1,
-                                                          const float *__restrict__ bias, int sine,
+                                                          const float *__restrict__ bias, dhq_act act,
                                                           const float *__restrict__ dyn)
 {
     if (ACT && dyn) c1 = dyn[1];
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restri
             if (ACT) {
                 float o[VEC];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) o[e] = dhq_epilogue(acc[e], c1, bv[e], sine != 0);
+                for (int e = 0; e < VEC; ++e) o[e] = dhq_epilogue(acc[e], c1, bv[e], act);
                 if constexpr (VEC == 4)
                     *reinterpret_cast<float4 *>(act_out + row * M + f0) = make_float4(o[0], o[1], o[2], o[3]);
                 else
@@ -451,33 +451,32 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restri
 
 template <bool ACT, int VEC>
 static void launch_gemm_narrow_kp(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out, float *act_out,
-                                  float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
+                                  float c1, const float *bias, dhq_act act, const float *dyn, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((n + 4 * NARROW_ROWS - 1) / (4 * NARROW_ROWS));
     const dim3 block(64, 4);
-    const int s = sine ? 1 : 0;
     if (L.Kp == 2)
-        gemm_narrow_kernel<ACT, VEC, 2><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
+        gemm_narrow_kernel<ACT, VEC, 2><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, act, dyn);
     else if (L.Kp == 4)
-        gemm_narrow_kernel<ACT, VEC, 4><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
+        gemm_narrow_kernel<ACT, VEC, 4><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, act, dyn);
     else
-        gemm_narrow_kernel<ACT, VEC, 0><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, s, dyn);
+        gemm_narrow_kernel<ACT, VEC, 0><<<blocks, block, 0, st>>>(codes, n, L.Kp, L.wq_dev, L.Mg, acc_out, act_out, c1, bias, act, dyn);
 }
 
 template <bool ACT>
 static hipError_t launch_gemm_narrow(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out, float *act_out,
-                                     float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
+                                     float c1, const float *bias, dhq_act act, const float *dyn, hipStream_t st)
 {
     if ((L.Mg & 3) == 0)
-        launch_gemm_narrow_kp<ACT, 4>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        launch_gemm_narrow_kp<ACT, 4>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
     else
-        launch_gemm_narrow_kp<ACT, 1>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        launch_gemm_narrow_kp<ACT, 1>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
     return hipGetLastError();
 }
 
 template <int NKB>
 static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                                   float *act_out, float c1, const float *bias, bool sine, const float *dyn,
+                                   float *act_out, float c1, const float *bias, dhq_act act, const float *dyn,
                                    hipStream_t st)
 {
     dim3 grid((unsigned)((n + 32 * GEMM_WAVES - 1) / (32 * GEMM_WAVES)), (unsigned)((L.Mt + 3) / 4));
@@ -488,52 +487,52 @@ static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int6
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, sine ? 1 : 0, dyn);
+        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, act, dyn);
     } else {
         auto kern = gemm_i8_mfma_kernel<NKB, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, sine ? 1 : 0, dyn);
+        kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, act, dyn);
     }
     return hipGetLastError();
 }
 
 hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, int32_t *acc_out,
-                           float *act_out, float c1, const float *bias, bool sine, const float *dyn, hipStream_t st)
+                           float *act_out, float c1, const float *bias, dhq_act act, const float *dyn, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     if ((acc_out == nullptr) == (act_out == nullptr)) return hipErrorInvalidValue;
     if (L.Kp < 32)
-        return act_out ? launch_gemm_narrow<true>(L, codes, n, nullptr, act_out, c1, bias, sine, dyn, st)
-                       : launch_gemm_narrow<false>(L, codes, n, acc_out, nullptr, c1, bias, sine, dyn, st);
+        return act_out ? launch_gemm_narrow<true>(L, codes, n, nullptr, act_out, c1, bias, act, dyn, st)
+                       : launch_gemm_narrow<false>(L, codes, n, acc_out, nullptr, c1, bias, act, dyn, st);
     switch (L.Kp / 32) {
-        case 1: return launch_gemm_mfma<1>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
-        case 2: return launch_gemm_mfma<2>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
-        case 4: return launch_gemm_mfma<4>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
-        case 8: return launch_gemm_mfma<8>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
-        case 16: return launch_gemm_mfma<16>(L, codes, n, acc_out, act_out, c1, bias, sine, dyn, st);
+        case 1: return launch_gemm_mfma<1>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
+        case 2: return launch_gemm_mfma<2>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
+        case 4: return launch_gemm_mfma<4>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
+        case 8: return launch_gemm_mfma<8>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
+        case 16: return launch_gemm_mfma<16>(L, codes, n, acc_out, act_out, c1, bias, act, dyn, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 // -------------------------------------------------------------------------------- epilogue
 __global__ __launch_bounds__(256) void epilogue_kernel(const int32_t *__restrict__ acc, int64_t total, int M,
-                                                       float c1, const float *__restrict__ bias, int sine,
-                                                       float *__restrict__ act)
+                                                       float c1, const float *__restrict__ bias, dhq_act act,
+                                                       float *__restrict__ act_out)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    act[idx] = dhq_epilogue(acc[idx], c1, bias[idx % M], sine != 0);
+    act_out[idx] = dhq_epilogue(acc[idx], c1, bias[idx % M], act);
 }
 
-hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, const float *bias, bool sine,
-                               float *act, hipStream_t st)
+hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, const float *bias, dhq_act act,
+                               float *act_out, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     const int64_t total = n * M;
-    epilogue_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(acc, total, M, c1, bias, sine ? 1 : 0, act);
+    epilogue_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(acc, total, M, c1, bias, act, act_out);
     return hipGetLastError();
 }
 
@@ -546,7 +545,7 @@ hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, c
 // Intermediate sums may wrap; the host has checked that the final ones fit.
 template <int MP>
 __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *__restrict__ acc, int64_t n, int M,
-                                                                float c1, const float *__restrict__ bias, int sine,
+                                                                float c1, const float *__restrict__ bias, dhq_act act,
                                                                 const float *__restrict__ dyn,
                                                                 int32_t *__restrict__ z_out,
                                                                 float *__restrict__ act_out)
@@ -580,12 +579,12 @@ __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *_
             if (act_out && f < M) {
                 if ((M & 3) == 0) {
                     *reinterpret_cast<float4 *>(act_out + row * M + f) =
-                        make_float4(dhq_epilogue(v[4 * g], c1, bias[f], sine != 0), dhq_epilogue(v[4 * g + 1], c1, bias[f + 1], sine != 0),
-                                    dhq_epilogue(v[4 * g + 2], c1, bias[f + 2], sine != 0), dhq_epilogue(v[4 * g + 3], c1, bias[f + 3], sine != 0));
+                        make_float4(dhq_epilogue(v[4 * g], c1, bias[f], act), dhq_epilogue(v[4 * g + 1], c1, bias[f + 1], act),
+                                    dhq_epilogue(v[4 * g + 2], c1, bias[f + 2], act), dhq_epilogue(v[4 * g + 3], c1, bias[f + 3], act));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (f + e < M) act_out[row * M + f + e] = dhq_epilogue(v[4 * g + e], c1, bias[f + e], sine != 0);
+                        if (f + e < M) act_out[row * M + f + e] = dhq_epilogue(v[4 * g + e], c1, bias[f + e], act);
                 }
             }
         }
@@ -594,37 +593,37 @@ __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *_
         for (int e = 0; e < EPL; ++e) {
             const int f = S::index(t, e);
             if (z_out) z_out[row * MP + f] = v[e];
-            if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], sine != 0);
+            if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], act);
         }
     }
 }
 
 template <int MP>
-static hipError_t launch_unrotate(const int32_t *acc, int64_t n, int M, float c1, const float *bias, bool sine,
+static hipError_t launch_unrotate(const int32_t *acc, int64_t n, int M, float c1, const float *bias, dhq_act act,
                                   const float *dyn, int32_t *z_out, float *act_out, hipStream_t st)
 {
     constexpr int LPR = wht_shape<MP>::LPR;
     const int64_t threads = n * LPR;
-    unrotate_epilogue_kernel<MP><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(acc, n, M, c1, bias, sine ? 1 : 0, dyn,
+    unrotate_epilogue_kernel<MP><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(acc, n, M, c1, bias, act, dyn,
                                                                                    z_out, act_out);
     return hipGetLastError();
 }
 
-hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, bool sine,
+hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, dhq_act act,
                                const float *dyn, int32_t *z_out, float *act_out, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     switch (Mp) {
-        case 1: return launch_unrotate<1>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 2: return launch_unrotate<2>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 4: return launch_unrotate<4>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 8: return launch_unrotate<8>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 16: return launch_unrotate<16>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 32: return launch_unrotate<32>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 64: return launch_unrotate<64>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 128: return launch_unrotate<128>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 256: return launch_unrotate<256>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
-        case 512: return launch_unrotate<512>(acc, n, M, c1, bias, sine, dyn, z_out, act_out, st);
+        case 1: return launch_unrotate<1>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 2: return launch_unrotate<2>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 4: return launch_unrotate<4>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 8: return launch_unrotate<8>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 16: return launch_unrotate<16>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 32: return launch_unrotate<32>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 64: return launch_unrotate<64>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 128: return launch_unrotate<128>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 256: return launch_unrotate<256>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        case 512: return launch_unrotate<512>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
         default: return hipErrorInvalidValue;
     }
 }

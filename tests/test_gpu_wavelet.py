@@ -1,0 +1,191 @@
+"""GPU parity of networks with the wavelet activation cos(omega0 y) exp(-(s0 y)^2) (the second
+architecture the paper evaluates, Sec. 4.1 / Table 1) against the CPU oracle.
+
+Everything but the activation is the sine network's path, so the gates are the same: weight codes
+and integer stages bit-exact, codes <= 0.1 % off by <= 1 LSB when teacher-forced, epilogue within
+2e-5, final values within 2e-3 (free-running rule of test_gpu_parity.py), fp32 networks within 4e-6.
+"""
+import numpy as np
+import pytest
+
+import paper_2508_13478_amd as dhq
+from oracle import dhq_oracle as o
+from paper_2508_13478_amd import synth
+from test_gpu_parity import (CODE_RATE, OUT_TOL, _check_forward, _dev, _say, _torch, code_stats, int_matmul,
+                             int_unrotate)
+
+pytestmark = pytest.mark.gpu
+
+S0 = 10.0   # spread of the Gaussian envelope; 2.0 gives denser hidden activations
+
+
+class WaveletCase:
+    def __init__(self, dims, coords, W, b, s0, two_sided=False, bits=8, omega0=30.0):
+        self.dims, self.coords, self.s0, self.two_sided = list(dims), coords, s0, two_sided
+        self.net = o.quantize_net(dims, omega0, bits, bits, W, b, two_sided=two_sided, gabor_s0=s0)
+        self.out, self.dump = o.forward(self.net, coords, calibrate=True, dump=True)
+        mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
+        self.model = dhq.Model(dims, omega0, W, b, bits, bits, mode=mode, wavelet_s0=s0)
+        self.model.set_act_scales(self.net.s_a)
+
+
+_cache = {}
+
+
+def wavelet(name, s0=S0, two_sided=False, bits=8):
+    key = (name, s0, two_sided, bits)
+    if key not in _cache:
+        wl, coords, W, b = synth.make(name)
+        _cache[key] = WaveletCase(wl.dims, coords, W, b, s0, two_sided, bits)
+    return _cache[key]
+
+
+@pytest.mark.parametrize("two_sided", [False, True], ids=["one_sided", "two_sided"])
+@pytest.mark.parametrize("name,s0", [("C1", S0), ("C1", 2.0), ("C2", S0)])
+def test_wavelet_layers_teacher_forced(name, s0, two_sided):
+    torch = _torch()
+    cs = wavelet(name, s0, two_sided)
+    sw, sa = cs.model.scales()
+    assert np.array_equal(sw, cs.net.s_w) and np.array_equal(sa, cs.net.s_a)
+    rows = min(cs.coords.shape[0], 20000 + 13)
+    for l in range(len(cs.dims) - 1):
+        _say(f"wavelet layer {name} s0={s0} two_sided={two_sided} layer {l}")
+        assert np.array_equal(cs.model.weight_codes(l), cs.net.Wq[l])
+        x = cs.coords[:rows] if l == 0 else cs.dump.act[l - 1][:rows]
+        codes, acc, act = cs.model.forward_debug(_dev(x), l)
+        torch.cuda.synchronize()
+        codes, acc, act = codes.cpu().numpy(), acc.cpu().numpy(), act.cpu().numpy()
+        rate, mx = code_stats(codes, cs.dump.codes[l][:rows])
+        assert rate <= CODE_RATE and mx <= 1
+        prod = int_matmul(codes, cs.net.Wq[l])
+        assert np.array_equal(acc, int_unrotate(prod) if two_sided else prod)
+        same = (codes == cs.dump.codes[l][:rows]).all(axis=1)
+        exp = cs.dump.act[l][:rows][same]
+        err = np.abs(act[same].astype(np.float64) - exp).max()
+        _say(f"  code mismatch rate {rate:.2e}; epilogue max-abs err {err:.2e} (|act| max {np.abs(exp).max():.3f}, "
+             f"mean {np.abs(exp).mean():.3f})")
+        assert act.shape[1] == cs.dims[l + 1] and err <= 2e-5
+
+
+@pytest.mark.parametrize("two_sided", [False, True], ids=["one_sided", "two_sided"])
+@pytest.mark.parametrize("name,s0", [("C1", S0), ("C1", 2.0), ("C2", S0)])
+def test_wavelet_forward(name, s0, two_sided):
+    torch = _torch()
+    _say(f"wavelet forward {name} s0={s0} two_sided={two_sided}")
+    cs = wavelet(name, s0, two_sided)
+    out = _check_forward(cs, dhq.DHQ_LAYERWISE, "wavelet layer-by-layer", strict=(name == "C1"))
+    assert np.abs(cs.out).max() > 0.02                     # the network's output is not degenerate
+    # no whole-network kernel for this activation: the automatic choice is the layer-by-layer path
+    assert not cs.model.has_fused()
+    auto = cs.model.forward(_dev(cs.coords))
+    torch.cuda.synchronize()
+    assert np.array_equal(auto.cpu().numpy(), out)
+    with pytest.raises(dhq.DhqError) as e:
+        cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
+    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    with pytest.raises(dhq.DhqError) as e:
+        cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    # the sine network on the same weights is a different function
+    sine = dhq.Model(cs.dims, 30.0, *synth.make(name)[2:], mode=cs.model.mode)
+    sine.set_act_scales(cs.net.s_a)
+    other = sine.forward(_dev(cs.coords), flags=dhq.DHQ_LAYERWISE)
+    torch.cuda.synchronize()
+    assert np.abs(other.cpu().numpy() - out).max() > 0.01
+    sine.close()
+
+
+@pytest.mark.parametrize("bits", [4, 6])
+def test_wavelet_low_bits(bits):
+    _say(f"wavelet forward C1 {bits} bits")
+    _check_forward(wavelet("C1", 2.0, False, bits), dhq.DHQ_LAYERWISE, f"wavelet {bits} bits", strict=False)
+
+
+@pytest.mark.parametrize("name,two_sided", [("C1", False), ("C2", True), ("C3", False)])
+def test_wavelet_dynamic_equals_calibrate_then_static(name, two_sided):
+    torch = _torch()
+    _say(f"wavelet dynamic {name} two_sided={two_sided}")
+    wl, coords, W, b = synth.make(name)
+    if name == "C3":
+        coords = coords[:70000 + 11]                      # more than one workspace chunk, ragged
+    x = _dev(coords)
+    mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode, wavelet_s0=S0)
+    dyn = m.forward(x, flags=dhq.DHQ_DYNAMIC)             # automatic choice: layer by layer
+    s_dyn = m.dynamic_scales()
+    m.calibrate(x)
+    _, s_cal = m.scales()
+    sta = m.forward(x, flags=dhq.DHQ_LAYERWISE)
+    torch.cuda.synchronize()
+    assert np.array_equal(s_dyn, s_cal) and np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two_sided, gabor_s0=S0)
+    exp = o.forward(net, coords, calibrate=True)
+    rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+    err = np.abs(dyn.cpu().numpy().astype(np.float64) - exp).max(axis=1)
+    _say(f"  scale rel err max {rel.max():.2e}; {(err > OUT_TOL).sum()} of {err.size} coords beyond {OUT_TOL}, max {err.max():.2e}")
+    assert rel.max() <= 1e-5
+    assert (err > OUT_TOL).mean() <= 3e-3 and err.max() <= 2e-2
+    m.close()
+
+
+@pytest.mark.parametrize("dims", [[2, 64, 64, 64, 3], [3, 48, 100, 5], [2, 256, 256, 256, 1], [7, 9, 300, 33, 2], [2, 512, 512, 3]])
+@pytest.mark.parametrize("precision", ["w32a32", "w8a32"])
+def test_wavelet_float_networks(dims, precision):
+    """fp32-activation wavelet networks (the W32A32 and W8A32 rows of Table 2), layer by layer."""
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 977 + len(dims) + dims[1])
+    rng = np.random.default_rng(dims[1])
+    mode = dhq.DHQ_W32A32 if precision == "w32a32" else dhq.DHQ_W8A32
+    m = dhq.Model(dims, 30.0, W, b, mode=mode, wavelet_s0=2.0)
+    assert not m.has_fused()
+    for n in (1, 4000 + 19, 66000):
+        if n == 66000 and max(dims) > 128:
+            continue
+        _say(f"wavelet {precision} dims {dims} n={n}")
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        if precision == "w32a32":
+            exp, _ = o.mlp_float(dims, 30.0, W, b, x, gabor_s0=2.0)
+        else:
+            exp, _, _ = o.mlp_w8a32(dims, 30.0, 8, W, b, x, gabor_s0=2.0)
+        out = m.forward(_dev(x))
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max()
+        _say(f"  max-abs err {err:.2e} (|out| max {np.abs(exp).max():.2f})")
+        assert out.shape == exp.shape and err <= 4e-6
+    m.close()
+
+
+def test_wavelet_one_channel_output_and_zero_spread():
+    """A grayscale-style network (one output channel); with s0 = 0 the wavelet is a cosine, i.e. the sine
+    network with its hidden biases moved by a quarter period."""
+    torch = _torch()
+    dims = [2, 64, 64, 1]
+    W, b = synth.siren_init(dims, 30.0, 4242)
+    coords = synth.grid_coords(96)
+    x = _dev(coords)
+    _say("wavelet one output channel, s0 = 0 against shifted sine")
+    m = dhq.Model(dims, 30.0, W, b, wavelet_s0=0.0)
+    m.calibrate(x)
+    out = m.forward(x)
+    shift = np.pi / 60.0
+    b2 = [(bl.astype(np.float64) + (shift if l < 2 else 0.0)).astype(np.float32) for l, bl in enumerate(b)]
+    s = dhq.Model(dims, 30.0, W, b2)
+    s.set_act_scales(m.scales()[1])
+    ref = s.forward(x, flags=dhq.DHQ_LAYERWISE)
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy() - ref.cpu().numpy()).max(axis=1)
+    _say(f"  {(err > OUT_TOL).sum()} of {err.size} beyond {OUT_TOL}; median {np.median(err):.2e}")
+    assert out.shape == (96 * 96, 1) and (err > OUT_TOL).mean() <= 3e-3 and np.median(err) <= 1e-5
+    m.close()
+    s.close()
+
+
+def test_wavelet_arguments_are_checked():
+    wl, _, W, b = synth.make("C1")
+    for bad in (-1.0, float("nan"), float("inf")):
+        with pytest.raises(dhq.DhqError) as e:
+            dhq.Model(wl.dims, wl.omega0, W, b, wavelet_s0=bad)
+        assert e.value.status == dhq.DHQ_EINVAL
+    with pytest.raises(dhq.DhqError) as e:
+        dhq.Model(wl.dims, 0.0, W, b, wavelet_s0=1.0)
+    assert e.value.status == dhq.DHQ_EINVAL
