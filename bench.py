@@ -60,7 +60,7 @@ def time_forward(model, x, out, flags, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def cpu_baseline(name, max_coords, two_sided=False):
+def cpu_baseline(name, max_coords, two_sided=False, wavelet_s0=None):
     """The CPU oracle's quantized forward (static scales) timed on a bounded sample."""
     import numpy as np
     from oracle import dhq_oracle as o
@@ -68,7 +68,7 @@ def cpu_baseline(name, max_coords, two_sided=False):
     wl, coords, W, b = synth.make(name)
     stride = max(1, -(-coords.shape[0] // max_coords))
     sample = coords[::stride]
-    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two_sided)
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, two_sided=two_sided, gabor_s0=wavelet_s0)
     o.forward(net, sample, calibrate=True)   # the oracle's own scales (untimed); nothing from the GPU goes into it
     # repeat the sample until about ten seconds of oracle time have been spent
     runs, t0 = 0, time.perf_counter()
@@ -88,7 +88,7 @@ def cpu_baseline(name, max_coords, two_sided=False):
                       f"calibration excluded)"}
 
 
-def cpu_baseline_float(name, max_coords):
+def cpu_baseline_float(name, max_coords, wavelet_s0=None):
     """The CPU oracle's plain fp64/fp32 MLP timed on a bounded sample."""
     from oracle import dhq_oracle as o
     from paper_2508_13478_amd import synth
@@ -97,7 +97,7 @@ def cpu_baseline_float(name, max_coords):
     sample = coords[::stride]
     runs, t0 = 0, time.perf_counter()
     while True:
-        o.mlp_float(wl.dims, wl.omega0, W, b, sample)
+        o.mlp_float(wl.dims, wl.omega0, W, b, sample, gabor_s0=wavelet_s0)
         runs += 1
         dt = time.perf_counter() - t0
         if dt >= 10.0 or runs >= 50:
@@ -123,6 +123,10 @@ def main() -> int:
                          "dynamic / two_sided_dynamic: activation scales measured on line per call (one fused kernel "
                          "per layer where there is one); "
                          "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
+    ap.add_argument("--activation", default="sine", choices=["sine", "wavelet"],
+                    help="sine: the SIREN of the workload; wavelet: the same shapes and weights with the activation "
+                         "cos(omega0 y) exp(-(s0 y)^2) of the second architecture the paper evaluates (runs layer by layer)")
+    ap.add_argument("--wavelet-s0", type=float, default=10.0, help="spread of the wavelet's Gaussian envelope")
     ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
                     help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -150,7 +154,8 @@ def main() -> int:
     mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
     if floating:
         mode = dhq.DHQ_W8A32 if args.variant == "w8a32" else dhq.DHQ_W32A32
-    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode)
+    s0 = args.wavelet_s0 if args.activation == "wavelet" else None
+    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode, wavelet_s0=s0)
     x = torch.from_numpy(coords).to("cuda")
     out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
     if not floating:
@@ -263,7 +268,7 @@ def main() -> int:
         # the paper's W32A32-versus-W8A8 comparison (Table 2) on this GPU: the plain fp32 network through
         # the library's own fp32 kernels (one fused kernel up to width 256, layer by layer beyond), and how
         # far the quantized output is from it
-        ref_model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=dhq.DHQ_W32A32)
+        ref_model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=dhq.DHQ_W32A32, wavelet_s0=s0)
         ref_out = torch.empty_like(out)
         ms_f, _ = time_forward(ref_model, x, ref_out, dhq.DHQ_AUTO, max(10, args.steps // 20), 5)
         dhq.dhq_forward(model.handle, x, out, torch.cuda.current_stream(), flags)
@@ -275,6 +280,10 @@ def main() -> int:
         res["speedup_vs_w32a32"] = ms_f / ms
         res["psnr_vs_w32a32_db"] = 10.0 * math.log10(peak * peak / mse) if mse > 0 else float("inf")
         ref_model.close()
+    if s0 is not None:
+        res["config"]["workload"] = res["config"]["workload"].replace("SIREN", f"wavelet MLP (s0={s0:g})")
+        res["config"]["activation"] = "wavelet"
+        res["metric"] = res["metric"].replace("SIREN", "wavelet-MLP")
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -282,8 +291,8 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = (cpu_baseline_float(args.workload, args.cpu_coords) if floating else
-                               cpu_baseline(args.workload, args.cpu_coords, two_sided))
+        res["cpu_baseline"] = (cpu_baseline_float(args.workload, args.cpu_coords, s0) if floating else
+                               cpu_baseline(args.workload, args.cpu_coords, two_sided, s0))
     print(json.dumps(res))
     return 0
 

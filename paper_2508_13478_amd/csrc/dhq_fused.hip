@@ -58,6 +58,7 @@ struct fused_args {
     int k0, k0p;   // fan-in of the first layer and its power-of-two padding (<= 4)
     int m_out;     // fan-out of the output layer (<= 32)
     int qmax;
+    float c2;      // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     fused_layer_desc layer[DHQ_MAX_LAYERS];
 };
 
@@ -135,10 +136,11 @@ struct hm_sched {
 // One layer's GEMM with the dequantize + bias + sine epilogue, the split into binary16 pieces and
 // the H_32 products, software-pipelined by hand according to hm_sched.  On return xt[T][v]
 // holds, for this lane's coordinate, row 8 (v / 4) + 4 h + v % 4 of H_32 * (activations of tile T).
-template <int NT, int KB, int NCD>
+// ACTK: the activation (sine, or the wavelet with envelope constant c2).
+template <int NT, int KB, int NCD, int ACTK = DHQ_ACT_KIND_SINE>
 __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
                                                    const dhq_v4i (&cd)[NCD], float c1, dhq_v16f (&xt)[NT],
-                                                   const dhq_v4i (&hA)[2], int lane, int h)
+                                                   const dhq_v4i (&hA)[2], int lane, int h, float c2 = 0.f)
 {
     constexpr hm_sched<NT, KB> S{};
     constexpr int LAST = S.last;
@@ -201,8 +203,8 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
                 const int v = S.drain_pos[g] * EPS + j;
                 const float4 bb = bq[Td % 3][v >> 2];
                 const float bias0 = (v & 2) ? bb.z : bb.x, bias1 = (v & 2) ? bb.w : bb.y;
-                const float a0 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0));
-                const float a1 = dhq_sin_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1));
+                const float a0 = dhq_activate_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0), dhq_act{ACTK, c2});
+                const float a1 = dhq_activate_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1), dhq_act{ACTK, c2});
                 hm_split_pair(a0, a1, hp[Td & 1][v >> 1], lp[Td & 1][v >> 1]);
             }
         }
@@ -303,7 +305,7 @@ __device__ __forceinline__ void fused_output_layer(const dhq_v4i *__restrict__ w
     }
 }
 
-template <int NF>
+template <int NF, int ACTK>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_args A)
 {
     constexpr int NT = NF / 32;   // M tiles of a hidden layer
@@ -346,11 +348,11 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_kernel(const fused_ar
             const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds + p * BLK);
             const float c1 = A.layer[l].c1;
             if (l == 0)
-                fused_gemm_sine_hm<NT, 1, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, xt,
-                                               hA, lane, h);
+                fused_gemm_sine_hm<NT, 1, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * 1024), cd, c1, xt,
+                                                     hA, lane, h, A.c2);
             else
-                fused_gemm_sine_hm<NT, NKB, NKB>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
-                                                 c1, xt, hA, lane, h);
+                fused_gemm_sine_hm<NT, NKB, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + p * BLK + NT * NKB * 1024), cd,
+                                                       c1, xt, hA, lane, h, A.c2);
             // The two waves of a SIMD overlap well while both feed the matrix unit or both
             // do vector work, but a wave in its vector phase starves the MFMA chain of the
             // other; keep the phases aligned across the workgroup.
@@ -602,14 +604,20 @@ int dhq_fused_update_scales(const dhq_model *m, dhq_fused_plan *P)
     return DHQ_OK;
 }
 
-template <int NF>
-static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, unsigned grid, hipStream_t st)
+template <int NF, int ACTK>
+static hipError_t fused_launch_act(const dhq_fused_plan *P, const fused_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused_kernel<NF>;
+    auto kern = dhq_fused_kernel<NF, ACTK>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
     if (e != hipSuccess) return e;
     kern<<<grid, FUSED_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+template <int NF>
+static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, int act_kind, unsigned grid, hipStream_t st)
+{
+    return act_kind == DHQ_ACT_KIND_WAVELET ? fused_launch_act<NF, DHQ_ACT_KIND_WAVELET>(P, a, grid, st)
+                                            : fused_launch_act<NF, DHQ_ACT_KIND_SINE>(P, a, grid, st);
 }
 
 hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, float *out, hipStream_t st)
@@ -621,13 +629,14 @@ hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, 
     a.coords = coords;
     a.out = out;
     a.n = n;
+    a.c2 = dhq_hidden_act(m).c2;
     const int64_t tiles = (n + FUSED_TILE - 1) / FUSED_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
     switch (P->nf) {
-        case 32: return fused_launch_t<32>(P, a, grid, st);
-        case 64: return fused_launch_t<64>(P, a, grid, st);
-        case 128: return fused_launch_t<128>(P, a, grid, st);
-        case 256: return fused_launch_t<256>(P, a, grid, st);
+        case 32: return fused_launch_t<32>(P, a, m->act_kind, grid, st);
+        case 64: return fused_launch_t<64>(P, a, m->act_kind, grid, st);
+        case 128: return fused_launch_t<128>(P, a, m->act_kind, grid, st);
+        case 256: return fused_launch_t<256>(P, a, m->act_kind, grid, st);
         default: return hipErrorInvalidValue;
     }
 }

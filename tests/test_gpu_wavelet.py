@@ -11,7 +11,7 @@ import pytest
 import paper_2508_13478_amd as dhq
 from oracle import dhq_oracle as o
 from paper_2508_13478_amd import synth
-from test_gpu_parity import (CODE_RATE, OUT_TOL, _check_forward, _dev, _say, _torch, code_stats, int_matmul,
+from test_gpu_parity import (CODE_RATE, OUT_TOL, _check_forward, _dev, _say, _torch, code_stats, flip_frac, int_matmul,
                              int_unrotate)
 
 pytestmark = pytest.mark.gpu
@@ -75,14 +75,25 @@ def test_wavelet_forward(name, s0, two_sided):
     cs = wavelet(name, s0, two_sided)
     out = _check_forward(cs, dhq.DHQ_LAYERWISE, "wavelet layer-by-layer", strict=(name == "C1"))
     assert np.abs(cs.out).max() > 0.02                     # the network's output is not degenerate
-    # no whole-network kernel for this activation: the automatic choice is the layer-by-layer path
-    assert not cs.model.has_fused()
-    auto = cs.model.forward(_dev(cs.coords))
-    torch.cuda.synchronize()
-    assert np.array_equal(auto.cpu().numpy(), out)
-    with pytest.raises(dhq.DhqError) as e:
-        cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
-    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    if two_sided:
+        # no whole-network kernel for the two-sided wavelet network: the automatic choice is the layer-by-layer path
+        assert not cs.model.has_fused()
+        auto = cs.model.forward(_dev(cs.coords))
+        torch.cuda.synchronize()
+        assert np.array_equal(auto.cpu().numpy(), out)
+        with pytest.raises(dhq.DhqError) as e:
+            cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
+        assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    else:
+        # input-side rotation, hidden width <= 256: the whole-network kernel, which is also the automatic choice
+        assert cs.model.has_fused()
+        fu = _check_forward(cs, dhq.DHQ_FUSED, "wavelet fused", strict=(name == "C1"))
+        auto = cs.model.forward(_dev(cs.coords))
+        torch.cuda.synchronize()
+        assert np.array_equal(auto.cpu().numpy(), fu)
+        d = np.abs(fu - out).max(axis=1)
+        _say(f"  fused vs layer-by-layer: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
+        assert (d > OUT_TOL).mean() <= flip_frac(cs.dims)
     with pytest.raises(dhq.DhqError) as e:
         cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
     assert e.value.status == dhq.DHQ_EUNSUPPORTED
@@ -98,7 +109,40 @@ def test_wavelet_forward(name, s0, two_sided):
 @pytest.mark.parametrize("bits", [4, 6])
 def test_wavelet_low_bits(bits):
     _say(f"wavelet forward C1 {bits} bits")
-    _check_forward(wavelet("C1", 2.0, False, bits), dhq.DHQ_LAYERWISE, f"wavelet {bits} bits", strict=False)
+    cs = wavelet("C1", 2.0, False, bits)
+    _check_forward(cs, dhq.DHQ_LAYERWISE, f"wavelet {bits} bits", strict=False)
+    _check_forward(cs, dhq.DHQ_FUSED, f"wavelet {bits} bits fused", strict=False)
+
+
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 5], [4, 128, 128, 2], [1, 256, 256, 256, 32], [2, 512, 512, 3]])
+def test_wavelet_fused_shapes_and_ragged_rows(dims):
+    """Every hidden width the whole-network kernel has, ragged row counts over several workgroup passes; a
+    512-wide wavelet network has no such kernel and runs layer by layer."""
+    torch = _torch()
+    W, b = synth.siren_init(dims, 30.0, 31 + dims[1])
+    rng = np.random.default_rng(dims[1])
+    for n, s0 in ((1, 2.0), (255, S0), (70000 + 3, 2.0)):
+        if n > 70000 and dims[1] > 128:
+            n = 9000 + 7                                   # keeps the oracle's share short
+        _say(f"wavelet fused dims {dims} n={n} s0={s0}")
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        net = o.quantize_net(dims, 30.0, 8, 8, W, b, gabor_s0=s0)
+        exp = o.forward(net, x, calibrate=True)
+        m = dhq.Model(dims, 30.0, W, b, wavelet_s0=s0)
+        m.set_act_scales(net.s_a)
+        assert m.has_fused() == (dims[1] <= 256)
+        out = m.forward(_dev(x))
+        lw = m.forward(_dev(x), flags=dhq.DHQ_LAYERWISE)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max(axis=1)
+        d = np.abs(out.cpu().numpy() - lw.cpu().numpy()).max(axis=1)
+        _say(f"  {(err > OUT_TOL).sum()} of {n} coords beyond {OUT_TOL}, max {err.max():.2e}, median {np.median(err):.1e}; "
+             f"against layer by layer: {(d > OUT_TOL).sum()} beyond")
+        assert (err > OUT_TOL).mean() <= max(3e-3, 1.0 / n)      # a code on a rounding boundary may move a coordinate
+        assert err.max() <= 2e-2 and np.median(err) <= 1e-5
+        if dims[1] > 256:
+            assert np.array_equal(out.cpu().numpy(), lw.cpu().numpy())
+        m.close()
 
 
 @pytest.mark.parametrize("name,two_sided", [("C1", False), ("C2", True), ("C3", False)])
@@ -137,7 +181,7 @@ def test_wavelet_float_networks(dims, precision):
     rng = np.random.default_rng(dims[1])
     mode = dhq.DHQ_W32A32 if precision == "w32a32" else dhq.DHQ_W8A32
     m = dhq.Model(dims, 30.0, W, b, mode=mode, wavelet_s0=2.0)
-    assert not m.has_fused()
+    assert not m.has_fused()                                # fp32 wavelet networks run one kernel per layer
     for n in (1, 4000 + 19, 66000):
         if n == 66000 and max(dims) > 128:
             continue
