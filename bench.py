@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "ccb1aa04e4494a7a88a65231b6556f797060eb5986a261f5f1e78d1f4ad9d295"
-TRAFFIC_BYTES = {"C2": (2520.8 + 768.0) * 1024, "C5": (44538.8 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "946f4d25dde46c3129ffa4bff14b6e3f70fdbfdb665568f3d856c6f73de0457d"
+TRAFFIC_BYTES = {"C2": (2524.5 + 768.0) * 1024, "C5": (44538.8 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -197,11 +197,12 @@ def main() -> int:
         # layer shapes
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": tops / INT8_MFMA_PEAK_TOPS,
-                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and kernel_sources_sha256() == TRAFFIC_SHA256
+                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and s0 is None and kernel_sources_sha256() == TRAFFIC_SHA256
                                  else None),
                      "traffic_unit": "bytes per launch (HBM, measured)",
                      "kernel": ((f"dhq_fused2_kernel<{wl.dims[1]}>" if two_sided else
-                                 "dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else f"dhq_fused_kernel<{wl.dims[1]}>")
+                                 "dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else
+                                 f"dhq_fused_kernel<{wl.dims[1]}, {2 if s0 is not None else 1}>")
                                 if fused else "layerwise kernels"),
                      "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
                      "algorithmic_ops_per_launch": ops},
