@@ -286,12 +286,11 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
         // dhq_get_dynamic_scales before any dynamic forward reports zeros
         if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
     }
-    // a wavelet network has the whole-network kernel for hidden widths up to 256 (input-side rotation, static
-    // scales) and runs layer by layer otherwise
+    // a wavelet network has the fused kernels for hidden widths up to 256 and runs layer by layer at width 512
     const bool sine = (m->act_kind == DHQ_ACT_KIND_SINE);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && sine && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
-    if (rc == DHQ_OK && sine && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
+    if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
         return rc;
@@ -522,8 +521,7 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     const uint32_t path = flags & 3u;
     const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
-    // per-layer fused kernels of the dynamic mode (sine networks)
-    const bool dyn_fused_ok = (m->fused || m->fused2) && m->act_kind == DHQ_ACT_KIND_SINE;
+    const bool dyn_fused_ok = m->fused || m->fused2;  // per-layer fused kernels of the dynamic mode
     if (dynamic && path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
     if (m->flt && (dynamic || (path == DHQ_FUSED && !dhq_float_has_fused(m->flt)))) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;

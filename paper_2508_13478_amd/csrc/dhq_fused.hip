@@ -403,9 +403,11 @@ struct fusedl_args {
     int64_t n;
     int chunks;                // block size in KiB
     int k0, k0p, m_out, qmax;
+    float c2;                  // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
 };
 
-template <int NF, int MODE>
+// ACTK: the activation after the layer (MODE 0, 1).
+template <int NF, int MODE, int ACTK>
 __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fusedl_args A)
 {
     constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
@@ -467,7 +469,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fu
                                     lane, h);
         } else {
             dhq_v16f xt[NT];
-            fused_gemm_sine_hm<NT, KB, NKB>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, xt, hA, lane, h);
+            fused_gemm_sine_hm<NT, KB, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, xt, hA, lane, h,
+                                                  A.c2);
             fused_tile_stages<NT>(xt);
 #pragma unroll
             for (int q = 0; q < NR / 4; ++q) {
@@ -648,10 +651,10 @@ hipError_t dhq_fused_launch(const dhq_model *m, const float *coords, int64_t n, 
 // dyn: three floats per layer.
 size_t dhq_fused_dynamic_rows(int64_t n) { return (size_t)((n + FUSED_TILE - 1) / FUSED_TILE) * FUSED_TILE; }
 
-template <int NF, int MODE>
+template <int NF, int MODE, int ACTK>
 static hipError_t fusedl_launch_t(const fusedl_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused_layer_kernel<NF, MODE>;
+    auto kern = dhq_fused_layer_kernel<NF, MODE, ACTK>;
     const size_t lds = (size_t)a.chunks * 1024;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -659,12 +662,13 @@ static hipError_t fusedl_launch_t(const fusedl_args &a, unsigned grid, hipStream
     return hipGetLastError();
 }
 template <int NF>
-static hipError_t fusedl_launch_mode(int mode, const fusedl_args &a, unsigned grid, hipStream_t st)
+static hipError_t fusedl_launch_mode(int mode, int act_kind, const fusedl_args &a, unsigned grid, hipStream_t st)
 {
+    const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
     switch (mode) {
-        case 0: return fusedl_launch_t<NF, 0>(a, grid, st);
-        case 1: return fusedl_launch_t<NF, 1>(a, grid, st);
-        default: return fusedl_launch_t<NF, 2>(a, grid, st);
+        case 0: return wav ? fusedl_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET>(a, grid, st) : fusedl_launch_t<NF, 0, DHQ_ACT_KIND_SINE>(a, grid, st);
+        case 1: return wav ? fusedl_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET>(a, grid, st) : fusedl_launch_t<NF, 1, DHQ_ACT_KIND_SINE>(a, grid, st);
+        default: return fusedl_launch_t<NF, 2, DHQ_ACT_KIND_NONE>(a, grid, st);  // the output layer has no activation
     }
 }
 
@@ -700,12 +704,13 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
         a.partial = pbuf[(l + 1) & 1];
         a.n = n;
         a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.qmax = P->args.qmax;
+        a.c2 = dhq_hidden_act(m).c2;
         const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
         switch (P->nf) {
-            case 32: e = fusedl_launch_mode<32>(mode, a, grid, st); break;
-            case 64: e = fusedl_launch_mode<64>(mode, a, grid, st); break;
-            case 128: e = fusedl_launch_mode<128>(mode, a, grid, st); break;
-            case 256: e = fusedl_launch_mode<256>(mode, a, grid, st); break;
+            case 32: e = fusedl_launch_mode<32>(mode, m->act_kind, a, grid, st); break;
+            case 64: e = fusedl_launch_mode<64>(mode, m->act_kind, a, grid, st); break;
+            case 128: e = fusedl_launch_mode<128>(mode, m->act_kind, a, grid, st); break;
+            case 256: e = fusedl_launch_mode<256>(mode, m->act_kind, a, grid, st); break;
             default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;

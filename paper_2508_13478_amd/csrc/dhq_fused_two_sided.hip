@@ -54,11 +54,13 @@ struct f2_args {
     int k0, k0p;
     int m_out, m_out_p;  // fan-out of the output layer and its power-of-two padding (<= 4)
     int qmax;
+    float c2;            // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     f2_layer_desc layer[DHQ_MAX_LAYERS];
 };
 
 struct dhq_fused2_plan {
     int nf = 0;
+    int act_kind = DHQ_ACT_KIND_SINE;  // the activation after every layer but the last
     unsigned char *blob_dev = nullptr;
     size_t blob_bytes = 0;
     f2_args args;
@@ -137,10 +139,11 @@ __device__ __forceinline__ int f2_input_codes(const float *__restrict__ coords, 
 
 // One hidden layer, G to W: codes cd -> un-normalised transform xt of the layer's activations.
 // wA: the layer's A fragments, wB: its biases in location order (both in LDS).
-template <int NT, int KB, int NCD>
+// ACTK: the activation (sine, or the wavelet with envelope constant c2).
+template <int NT, int KB, int NCD, int ACTK>
 __device__ __forceinline__ void f2_hidden_layer(const dhq_v4i *__restrict__ wA, const float4 *__restrict__ wB,
                                                 const dhq_v4i (&cd)[NCD], float c1, const dhq_v4i (&hA)[2], dhq_v16f (&xt)[NT],
-                                                int lane, int h)
+                                                int lane, int h, float c2)
 {
     constexpr int NR = 16 * NT;
     // G: rotated accumulators of all output tiles
@@ -171,8 +174,8 @@ __device__ __forceinline__ void f2_hidden_layer(const dhq_v4i *__restrict__ wA, 
         const int z0 = (int)(r[0] + r[1]), z1 = (int)(r[0] - r[1]);
         const float4 bb = wB[(pr >> 1) * 2 + h];
         const float b0 = (pr & 1) ? bb.z : bb.x, b1 = (pr & 1) ? bb.w : bb.y;
-        x[2 * pr] = dhq_sin_rev(__builtin_fmaf((float)z0, c1, b0));
-        x[2 * pr + 1] = dhq_sin_rev(__builtin_fmaf((float)z1, c1, b1));
+        x[2 * pr] = dhq_activate_rev(__builtin_fmaf((float)z0, c1, b0), dhq_act{ACTK, c2});
+        x[2 * pr + 1] = dhq_activate_rev(__builtin_fmaf((float)z1, c1, b1), dhq_act{ACTK, c2});
     }
     // W: forward transform of the next layer's input.  The factor H_32 over the 32 features of a
     // tile goes to the matrix unit as in dhq_fused.hip (activations split into two binary16
@@ -244,7 +247,7 @@ __device__ __forceinline__ void f2_output_layer(const dhq_v4i *__restrict__ wA, 
     }
 }
 
-template <int NF>
+template <int NF, int ACTK>
 __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
 {
     constexpr int NT = NF / 32;
@@ -289,9 +292,9 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_kernel(const f2_args A)
             const float4 *wB = reinterpret_cast<const float4 *>(lds + p * BLK + NT * Kb * 1024);
             dhq_v16f xt[NT];
             if (l == 0)
-                f2_hidden_layer<NT, 1, NKB>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h);
+                f2_hidden_layer<NT, 1, NKB, ACTK>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h, A.c2);
             else
-                f2_hidden_layer<NT, NKB, NKB>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h);
+                f2_hidden_layer<NT, NKB, NKB, ACTK>(wA, wB, cd, A.layer[l].c1, hA, xt, lane, h, A.c2);
             // the next layer's quantizer
             const float inv = A.layer[l + 1].inv_in;
 #pragma unroll
@@ -335,9 +338,11 @@ struct f2l_args {
     int64_t n;
     int chunks;                // block size in KiB
     int k0, k0p, m_out, m_out_p, qmax;
+    float c2;                  // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
 };
 
-template <int NF, int MODE>
+// ACTK: the activation after the layer (MODE 0, 1).
+template <int NF, int MODE, int ACTK>
 __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_layer_kernel(const f2l_args A)
 {
     constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_layer_kernel(const f2l_
                                  A.m_out_p, lane, h);
         } else {
             dhq_v16f xt[NT];
-            f2_hidden_layer<NT, KB, NKB>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, hA, xt, lane, h);
+            f2_hidden_layer<NT, KB, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + MT * KB * 1024), cd, c1, hA, xt, lane, h, A.c2);
 #pragma unroll
             for (int q = 0; q < NR / 4; ++q) {
                 const float4 x = make_float4(xt[q >> 2][4 * (q & 3)], xt[q >> 2][4 * (q & 3) + 1], xt[q >> 2][4 * (q & 3) + 2],
@@ -512,6 +517,8 @@ int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan_out)
     P->args.m_out = m->dims[L];
     P->args.m_out_p = m->layer[L - 1].Mp;
     P->args.qmax = m->qmax_a;
+    P->args.c2 = dhq_hidden_act(m).c2;
+    P->act_kind = m->act_kind;
     P->lds_bytes = (size_t)2 * (NT * NKB + 1) * 1024;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
@@ -542,14 +549,20 @@ int dhq_fused2_update_scales(const dhq_model *m, dhq_fused2_plan *P)
     return DHQ_OK;
 }
 
-template <int NF>
-static hipError_t fused2_launch_t(const dhq_fused2_plan *P, const f2_args &a, unsigned grid, hipStream_t st)
+template <int NF, int ACTK>
+static hipError_t fused2_launch_act(const dhq_fused2_plan *P, const f2_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused2_kernel<NF>;
+    auto kern = dhq_fused2_kernel<NF, ACTK>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
     if (e != hipSuccess) return e;
     kern<<<grid, F2_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+template <int NF>
+static hipError_t fused2_launch_t(const dhq_fused2_plan *P, const f2_args &a, unsigned grid, hipStream_t st)
+{
+    return P->act_kind == DHQ_ACT_KIND_WAVELET ? fused2_launch_act<NF, DHQ_ACT_KIND_WAVELET>(P, a, grid, st)
+                                               : fused2_launch_act<NF, DHQ_ACT_KIND_SINE>(P, a, grid, st);
 }
 
 hipError_t dhq_fused2_launch(const dhq_fused2_plan *P, const float *coords, int64_t n, float *out, hipStream_t st)
@@ -574,10 +587,10 @@ hipError_t dhq_fused2_launch(const dhq_fused2_plan *P, const float *coords, int6
 // The dynamic mode on the per-layer kernels; arguments as for dhq_fused_dynamic_launch.
 size_t dhq_fused2_dynamic_rows(int64_t n) { return (size_t)((n + F2_TILE - 1) / F2_TILE) * F2_TILE; }
 
-template <int NF, int MODE>
+template <int NF, int MODE, int ACTK>
 static hipError_t f2l_launch_t(const f2l_args &a, unsigned grid, hipStream_t st)
 {
-    auto kern = dhq_fused2_layer_kernel<NF, MODE>;
+    auto kern = dhq_fused2_layer_kernel<NF, MODE, ACTK>;
     const size_t lds = (size_t)a.chunks * 1024;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -585,12 +598,13 @@ static hipError_t f2l_launch_t(const f2l_args &a, unsigned grid, hipStream_t st)
     return hipGetLastError();
 }
 template <int NF>
-static hipError_t f2l_launch_mode(int mode, const f2l_args &a, unsigned grid, hipStream_t st)
+static hipError_t f2l_launch_mode(int mode, int act_kind, const f2l_args &a, unsigned grid, hipStream_t st)
 {
+    const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
     switch (mode) {
-        case 0: return f2l_launch_t<NF, 0>(a, grid, st);
-        case 1: return f2l_launch_t<NF, 1>(a, grid, st);
-        default: return f2l_launch_t<NF, 2>(a, grid, st);
+        case 0: return wav ? f2l_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET>(a, grid, st) : f2l_launch_t<NF, 0, DHQ_ACT_KIND_SINE>(a, grid, st);
+        case 1: return wav ? f2l_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET>(a, grid, st) : f2l_launch_t<NF, 1, DHQ_ACT_KIND_SINE>(a, grid, st);
+        default: return f2l_launch_t<NF, 2, DHQ_ACT_KIND_NONE>(a, grid, st);  // the output layer has no activation
     }
 }
 
@@ -626,12 +640,13 @@ hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, in
         a.partial = pbuf[(l + 1) & 1];
         a.n = n;
         a.k0 = P->args.k0; a.k0p = P->args.k0p; a.m_out = P->args.m_out; a.m_out_p = P->args.m_out_p; a.qmax = P->args.qmax;
+        a.c2 = P->args.c2;
         const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
         switch (P->nf) {
-            case 32: e = f2l_launch_mode<32>(mode, a, grid, st); break;
-            case 64: e = f2l_launch_mode<64>(mode, a, grid, st); break;
-            case 128: e = f2l_launch_mode<128>(mode, a, grid, st); break;
-            case 256: e = f2l_launch_mode<256>(mode, a, grid, st); break;
+            case 32: e = f2l_launch_mode<32>(mode, m->act_kind, a, grid, st); break;
+            case 64: e = f2l_launch_mode<64>(mode, m->act_kind, a, grid, st); break;
+            case 128: e = f2l_launch_mode<128>(mode, m->act_kind, a, grid, st); break;
+            case 256: e = f2l_launch_mode<256>(mode, m->act_kind, a, grid, st); break;
             default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;

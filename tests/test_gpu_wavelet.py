@@ -75,28 +75,15 @@ def test_wavelet_forward(name, s0, two_sided):
     cs = wavelet(name, s0, two_sided)
     out = _check_forward(cs, dhq.DHQ_LAYERWISE, "wavelet layer-by-layer", strict=(name == "C1"))
     assert np.abs(cs.out).max() > 0.02                     # the network's output is not degenerate
-    if two_sided:
-        # no whole-network kernel for the two-sided wavelet network: the automatic choice is the layer-by-layer path
-        assert not cs.model.has_fused()
-        auto = cs.model.forward(_dev(cs.coords))
-        torch.cuda.synchronize()
-        assert np.array_equal(auto.cpu().numpy(), out)
-        with pytest.raises(dhq.DhqError) as e:
-            cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
-        assert e.value.status == dhq.DHQ_EUNSUPPORTED
-    else:
-        # input-side rotation, hidden width <= 256: the whole-network kernel, which is also the automatic choice
-        assert cs.model.has_fused()
-        fu = _check_forward(cs, dhq.DHQ_FUSED, "wavelet fused", strict=(name == "C1"))
-        auto = cs.model.forward(_dev(cs.coords))
-        torch.cuda.synchronize()
-        assert np.array_equal(auto.cpu().numpy(), fu)
-        d = np.abs(fu - out).max(axis=1)
-        _say(f"  fused vs layer-by-layer: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
-        assert (d > OUT_TOL).mean() <= flip_frac(cs.dims)
-    with pytest.raises(dhq.DhqError) as e:
-        cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
-    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    # hidden width <= 256: the whole-network kernel (either rotation mode), which is also the automatic choice
+    assert cs.model.has_fused()
+    fu = _check_forward(cs, dhq.DHQ_FUSED, "wavelet fused", strict=(name == "C1"))
+    auto = cs.model.forward(_dev(cs.coords))
+    torch.cuda.synchronize()
+    assert np.array_equal(auto.cpu().numpy(), fu)
+    d = np.abs(fu - out).max(axis=1)
+    _say(f"  fused vs layer-by-layer: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
+    assert (d > OUT_TOL).mean() <= flip_frac(cs.dims)
     # the sine network on the same weights is a different function
     sine = dhq.Model(cs.dims, 30.0, *synth.make(name)[2:], mode=cs.model.mode)
     sine.set_act_scales(cs.net.s_a)
@@ -114,21 +101,24 @@ def test_wavelet_low_bits(bits):
     _check_forward(cs, dhq.DHQ_FUSED, f"wavelet {bits} bits fused", strict=False)
 
 
-@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 5], [4, 128, 128, 2], [1, 256, 256, 256, 32], [2, 512, 512, 3]])
-def test_wavelet_fused_shapes_and_ragged_rows(dims):
-    """Every hidden width the whole-network kernel has, ragged row counts over several workgroup passes; a
-    512-wide wavelet network has no such kernel and runs layer by layer."""
+@pytest.mark.parametrize("two_sided", [False, True], ids=["one_sided", "two_sided"])
+@pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 4], [4, 128, 128, 2], [1, 256, 256, 256, 1], [2, 512, 512, 3]])
+def test_wavelet_fused_shapes_and_ragged_rows(dims, two_sided):
+    """Every hidden width the fused kernels have, ragged row counts over several workgroup passes, static scales
+    (whole-network kernel) and on-line scales (one kernel per layer); a 512-wide wavelet network has no fused
+    kernel and runs layer by layer."""
     torch = _torch()
     W, b = synth.siren_init(dims, 30.0, 31 + dims[1])
     rng = np.random.default_rng(dims[1])
+    mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
     for n, s0 in ((1, 2.0), (255, S0), (70000 + 3, 2.0)):
         if n > 70000 and dims[1] > 128:
             n = 9000 + 7                                   # keeps the oracle's share short
-        _say(f"wavelet fused dims {dims} n={n} s0={s0}")
+        _say(f"wavelet fused dims {dims} two_sided={two_sided} n={n} s0={s0}")
         x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
-        net = o.quantize_net(dims, 30.0, 8, 8, W, b, gabor_s0=s0)
+        net = o.quantize_net(dims, 30.0, 8, 8, W, b, two_sided=two_sided, gabor_s0=s0)
         exp = o.forward(net, x, calibrate=True)
-        m = dhq.Model(dims, 30.0, W, b, wavelet_s0=s0)
+        m = dhq.Model(dims, 30.0, W, b, mode=mode, wavelet_s0=s0)
         m.set_act_scales(net.s_a)
         assert m.has_fused() == (dims[1] <= 256)
         out = m.forward(_dev(x))
@@ -142,6 +132,23 @@ def test_wavelet_fused_shapes_and_ragged_rows(dims):
         assert err.max() <= 2e-2 and np.median(err) <= 1e-5
         if dims[1] > 256:
             assert np.array_equal(out.cpu().numpy(), lw.cpu().numpy())
+            with pytest.raises(dhq.DhqError) as e:
+                m.forward(_dev(x), flags=dhq.DHQ_FUSED)
+            assert e.value.status == dhq.DHQ_EUNSUPPORTED
+            with pytest.raises(dhq.DhqError) as e:
+                m.forward(_dev(x), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+            assert e.value.status == dhq.DHQ_EUNSUPPORTED
+        else:
+            # on-line scales on one fused kernel per layer: the bits of a static fused forward with the scales it measured
+            dyn = m.forward(_dev(x), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+            s_dyn = m.dynamic_scales()
+            m.set_act_scales(s_dyn)
+            sta = m.forward(_dev(x), flags=dhq.DHQ_FUSED)
+            torch.cuda.synchronize()
+            assert np.array_equal(dyn.cpu().numpy(), sta.cpu().numpy())
+            rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+            _say(f"  on-line scales: rel err max {rel.max():.2e}")
+            assert rel.max() <= 1e-5
         m.close()
 
 
@@ -155,7 +162,7 @@ def test_wavelet_dynamic_equals_calibrate_then_static(name, two_sided):
     x = _dev(coords)
     mode = dhq.DHQ_ROTATE_BOTH if two_sided else dhq.DHQ_ROTATE_IN
     m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode, wavelet_s0=S0)
-    dyn = m.forward(x, flags=dhq.DHQ_DYNAMIC)             # automatic choice: layer by layer
+    dyn = m.forward(x, flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
     s_dyn = m.dynamic_scales()
     m.calibrate(x)
     _, s_cal = m.scales()
@@ -233,3 +240,74 @@ def test_wavelet_arguments_are_checked():
     with pytest.raises(dhq.DhqError) as e:
         dhq.Model(wl.dims, 0.0, W, b, wavelet_s0=1.0)
     assert e.value.status == dhq.DHQ_EINVAL
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_wavelet_random_shapes_bits_modes_and_row_counts(block):
+    """Thirty of the seeded random configurations of the sine sweep (every third: any shape, and shapes the fused
+    kernels take; 4 / 6 / 8 bits, either rotation mode, row counts around the tile sizes) as wavelet networks with
+    a seeded spread, through static and on-line scales on the automatic and the layer-by-layer path."""
+    from test_gpu_parity import _near_boundary
+    from test_gpu_variants import _sweep_case
+    torch = _torch()
+    for i in range(45 * block, 45 * block + 45, 3):
+        dims, bits, mode, n, rng = _sweep_case(i)
+        s0 = float(rng.choice([0.5, 2.0, 10.0]))
+        _say(f"wavelet sweep case {i}: dims {dims} bits {bits} mode {mode} n {n} s0 {s0}")
+        W, b = synth.siren_init(dims, 30.0, 7000 + i)
+        x = rng.uniform(-1, 1, size=(n, dims[0])).astype(np.float32)
+        net = o.quantize_net(dims, 30.0, bits, bits, W, b, two_sided=(mode == dhq.DHQ_ROTATE_BOTH), gabor_s0=s0)
+        exp, dmp = o.forward(net, x, calibrate=True, dump=True)
+        near = _near_boundary(net, dmp, bits)
+        m = dhq.Model(dims, 30.0, W, b, bits, bits, mode=mode, wavelet_s0=s0)
+        if i >= 60:
+            assert m.has_fused() == (dims[1] <= 256)          # a 512-wide wavelet network runs layer by layer
+        for l in range(len(dims) - 1):
+            assert np.array_equal(m.weight_codes(l), net.Wq[l]), f"case {i}: weight codes of layer {l}"
+        m.set_act_scales(net.s_a)
+        for flags in (dhq.DHQ_AUTO, dhq.DHQ_LAYERWISE, dhq.DHQ_DYNAMIC, dhq.DHQ_DYNAMIC | dhq.DHQ_LAYERWISE):
+            out = m.forward(_dev(x), flags=flags)
+            torch.cuda.synchronize()
+            out = out.cpu().numpy()
+            assert out.shape == exp.shape and np.isfinite(out).all()
+            err = np.abs(out.astype(np.float64) - exp).max(axis=1)
+            over = err > OUT_TOL
+            assert not (over & ~near).any(), f"case {i} flags {flags}: max-abs err {err.max():.3e}"
+            assert over.sum() <= max(2, 2 * flip_frac(dims) * n), f"case {i} flags {flags}: {over.sum()} of {n} beyond {OUT_TOL}"
+        m.close()
+
+
+@pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic_fused", "dynamic_fused_two_sided", "w32a32"])
+def test_wavelet_forward_replays_from_a_captured_graph(variant):
+    """As for the sine network: a stream capture of dhq_forward replays to the bits of the eager call, several
+    times, with eager work on the same model in between."""
+    torch = _torch()
+    _say(f"wavelet graph replay {variant}")
+    wl, coords, W, b = synth.make("C1")
+    x = _dev(coords)
+    mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "dynamic_fused_two_sided": dhq.DHQ_ROTATE_BOTH,
+            "w32a32": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
+    flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
+             "dynamic_fused_two_sided": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC}.get(variant, dhq.DHQ_AUTO)
+    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode, wavelet_s0=S0)
+    if variant != "w32a32":
+        m.calibrate(x)
+    out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
+    eager = m.forward(x, flags=flags).clone()                # also grows the dynamic workspace before capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            dhq.dhq_forward(m.handle, x, out, s, flags)
+    torch.cuda.current_stream().wait_stream(s)
+    for rep in range(3):
+        out.zero_()
+        scratch = m.forward(x[: 100 + rep], flags=flags)     # eager work on the same model in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), eager.cpu().numpy()), f"replay {rep}"
+        assert bool(torch.isfinite(scratch).all())
+    m.close()
