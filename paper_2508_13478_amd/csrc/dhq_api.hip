@@ -286,10 +286,8 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
         // dhq_get_dynamic_scales before any dynamic forward reports zeros
         if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
     }
-    // a wavelet network has the fused kernels for hidden widths up to 256 and runs layer by layer at width 512
-    const bool sine = (m->act_kind == DHQ_ACT_KIND_SINE);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
-    if (rc == DHQ_OK && sine && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
+    if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
     if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);

@@ -44,6 +44,7 @@ struct wide_args {
     int m_out;
     int qmax;
     int n_chunks;                       // weight chunks per coordinate pass
+    float c2;                           // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     float c1[DHQ_MAX_LAYERS];           // sine layers: s_a s_w omega0 / (2 pi); output layer: s_a s_w
     float inv_in[DHQ_MAX_LAYERS];       // 1 / (s_a sqrt(Kp))
     uint32_t chunk_off[WIDE_MAX_CHUNKS];  // byte offset of each chunk in the blob
@@ -52,6 +53,7 @@ struct wide_args {
 
 struct dhq_wide_plan {
     int nf = 0;
+    int act_kind = DHQ_ACT_KIND_SINE;  // the activation after every layer but the last
     unsigned char *blob_dev = nullptr;
     size_t blob_bytes = 0;
     wide_args args;
@@ -256,7 +258,8 @@ __device__ __forceinline__ float wide_comp(const float4 &v, int i) { return i ==
 //                         16 accumulators of tile g and splits them
 // Biases are read from LDS a few steps before use; those of tile T sit in the bias block
 // of the chunk that is resident while T is drained (see the host-side packing).
-template <int NT, int KB, int NCD>
+// ACTK: the activation after the layer (sine, or the wavelet with envelope constant c2).
+template <int NT, int KB, int NCD, int ACTK>
 struct wide_gemm_ctx {
     static constexpr int PF = (NT * KB >= 4) ? 4 : (NT * KB >= 2 ? 2 : 1);
     wide_stream &S;
@@ -265,7 +268,7 @@ struct wide_gemm_ctx {
     const dhq_v4i (&hA)[2];                      // H_32 as an MFMA A operand, two k blocks
     const unsigned char *bufs[2];
     int cc;
-    float c1;
+    float c1, c2;
     int h;
     dhq_v4i fr[PF + 1];
     float4 bq[2];
@@ -283,8 +286,8 @@ struct wide_gemm_ctx {
 };
 
 // input layer (one chunk, bias block [tile][g][h][e]): the biases of tile T
-template <int NT, int KB, int NCD, int CHM>
-__device__ __forceinline__ void wide_load_bias0(wide_gemm_ctx<NT, KB, NCD> &C, int T)
+template <int NT, int KB, int NCD, int CHM, int ACTK>
+__device__ __forceinline__ void wide_load_bias0(wide_gemm_ctx<NT, KB, NCD, ACTK> &C, int T)
 {
 #pragma unroll
     for (int gg = 0; gg < 4; ++gg)
@@ -292,8 +295,8 @@ __device__ __forceinline__ void wide_load_bias0(wide_gemm_ctx<NT, KB, NCD> &C, i
 }
 
 // H_32 product K of tile T from the pieces in hp / lp [T & 1].
-template <int NT, int KB, int NCD, int T, int K>
-__device__ __forceinline__ void wide_h32_step(wide_gemm_ctx<NT, KB, NCD> &C)
+template <int NT, int KB, int NCD, int T, int K, int ACTK>
+__device__ __forceinline__ void wide_h32_step(wide_gemm_ctx<NT, KB, NCD, ACTK> &C)
 {
     constexpr int blk = K >> 1;
     dhq_v4i b;
@@ -314,14 +317,14 @@ __device__ __forceinline__ void wide_h32_step(wide_gemm_ctx<NT, KB, NCD> &C)
     }
 }
 
-template <int NT, int KB, int CH, int NCD, int G>
-__device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
+template <int NT, int KB, int CH, int NCD, int G, int ACTK>
+__device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD, ACTK> &C)
 {
     constexpr int NM = NT * KB;
     constexpr int CHM = CH * KB;  // MFMAs per chunk
     constexpr int NC = NT / CH;
     constexpr int NE = NT * 16;   // accumulators per lane and layer
-    constexpr int PF = wide_gemm_ctx<NT, KB, NCD>::PF;
+    constexpr int PF = wide_gemm_ctx<NT, KB, NCD, ACTK>::PF;
     if constexpr (G < NM) {
         constexpr int pf = G + PF;
         if constexpr (pf < NM) {
@@ -357,7 +360,7 @@ __device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
 #pragma unroll
             for (int v = 0; v < 16; ++v) x[v] = __builtin_fmaf(x[v], C.c1, wide_comp(C.bq0[v >> 2], v & 3));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) x[v] = dhq_sin_rev(x[v]);
+            for (int v = 0; v < 16; ++v) x[v] = dhq_activate_rev(x[v], dhq_act{ACTK, C.c2});
 #pragma unroll
             for (int d = 0; d < 8; ++d) hm_split_pair(x[2 * d], x[2 * d + 1], C.hp[G & 1][d], C.lp[G & 1][d]);
         }
@@ -391,7 +394,7 @@ __device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
             if constexpr (e2 >= 3 && pm < NE / 2)
                 hm_remainders(C.ar[(e2 - 3) & 3], C.ar[(e2 - 2) & 3], C.hp[(pm / 8) & 1][pm % 8], C.er[0], C.er[1]);
         }
-        if constexpr (e2 >= 0 && e2 < NE) C.ar[e2 & 3] = dhq_sin_rev(C.ey);
+        if constexpr (e2 >= 0 && e2 < NE) C.ar[e2 & 3] = dhq_activate_rev(C.ey, dhq_act{ACTK, C.c2});
         if constexpr (e1 >= 0 && e1 < NE) C.ey = __builtin_fmaf(C.ex, C.c1, wide_comp(C.bq[(e1 / 4) & 1], e1 % 4));
         if constexpr (e0 >= 0 && e0 < NE) C.ex = (float)C.acc[(e0 / 16) & 1][e0 % 16];
         if constexpr (e0 + 4 >= 0 && (e0 + 4) % 4 == 0 && e0 + 4 < NE) {
@@ -406,8 +409,8 @@ __device__ __forceinline__ void wide_gemm_step(wide_gemm_ctx<NT, KB, NCD> &C)
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int NT, int KB, int CH, int NCD, int... Gs>
-__device__ __forceinline__ void wide_gemm_steps(wide_gemm_ctx<NT, KB, NCD> &C, std::integer_sequence<int, Gs...>)
+template <int NT, int KB, int CH, int NCD, int ACTK, int... Gs>
+__device__ __forceinline__ void wide_gemm_steps(wide_gemm_ctx<NT, KB, NCD, ACTK> &C, std::integer_sequence<int, Gs...>)
 {
     (wide_gemm_step<NT, KB, CH, NCD, Gs>(C), ...);
 }
@@ -418,18 +421,19 @@ __device__ __forceinline__ void wide_copy_prologue(const wide_stream &S, std::in
 }
 
 // cc is the running chunk count on entry and is advanced by the chunks consumed.
-template <int NT, int KB, int CH, int NCD>
-__device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1, const dhq_v4i (&cd)[NCD],
+template <int NT, int KB, int CH, int NCD, int ACTK>
+__device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1, float c2, const dhq_v4i (&cd)[NCD],
                                                dhq_v16f (&xtop)[NT - WIDE_AGPR_TILES], const dhq_v4i (&hA)[2], int h)
 {
     constexpr int NM = NT * KB;
-    constexpr int PF = wide_gemm_ctx<NT, KB, NCD>::PF;
+    constexpr int PF = wide_gemm_ctx<NT, KB, NCD, ACTK>::PF;
     // last step with work: the fourth H_32 product of the last tile (e2 - 11 = 16 (NT - 1) + 9)
     constexpr int NSTEPS = (KB == 1) ? NT + 1 : 16 * (NT - 1) + 9 + 11 + 2 + KB + 1;
     static_assert(CH * KB >= PF, "a chunk must be longer than the prefetch distance");
-    wide_gemm_ctx<NT, KB, NCD> C(S, cd, xtop, hA);
+    wide_gemm_ctx<NT, KB, NCD, ACTK> C(S, cd, xtop, hA);
     C.cc = cc;
     C.c1 = c1;
+    C.c2 = c2;
     C.h = h;
     C.ex = C.ey = 0.f;
     wide_enter_chunk(S, cc);
@@ -440,7 +444,7 @@ __device__ __forceinline__ void wide_gemm_sine(wide_stream &S, int &cc, float c1
         if (m < NM) C.fr[m % (PF + 1)] = reinterpret_cast<const dhq_v4i *>(C.bufs[0])[m * 64 + S.lane];
     if constexpr (KB == 1) wide_load_bias0<NT, KB, NCD, CH * KB>(C, 0);
     wide_copy_prologue<KB, CH * KB, PF, NT / CH>(S, std::make_integer_sequence<int, PF>{});
-    wide_gemm_steps<NT, KB, CH, NCD>(C, std::make_integer_sequence<int, NSTEPS>{});
+    wide_gemm_steps<NT, KB, CH, NCD, ACTK>(C, std::make_integer_sequence<int, NSTEPS>{});
     cc += NT / CH;
 }
 
@@ -482,7 +486,7 @@ __device__ __forceinline__ void wide_transform_quant(const dhq_v16f (&xtop)[NT -
     }
 }
 
-template <int NF>
+template <int NF, int ACTK>
 __global__ __launch_bounds__(WIDE_THREADS) __attribute__((amdgpu_num_vgpr(256 + WIDE_AGPR_COMPILER)))
 void dhq_fused_wide_kernel(const wide_args A)
 {
@@ -568,7 +572,7 @@ void dhq_fused_wide_kernel(const wide_args A)
         }
 
         dhq_v16f xtop[NT - WIDE_AGPR_TILES];
-        wide_gemm_sine<NT, 1, NT, NKB>(S, cc, A.c1[0], cd, xtop, hA, h);
+        wide_gemm_sine<NT, 1, NT, NKB, ACTK>(S, cc, A.c1[0], A.c2, cd, xtop, hA, h);
         for (int l = 1;; ++l) {
             // finish the transform of the output of layer l-1 and quantize it: the input of layer l
             const float inv = A.inv_in[l];
@@ -577,7 +581,7 @@ void dhq_fused_wide_kernel(const wide_args A)
             wide_transform_quant<NT, NKB, 2>(xtop, cd, inv, qlo, qhi);
             wide_transform_quant<NT, NKB, 3>(xtop, cd, inv, qlo, qhi);
             if (l == L - 1) break;
-            wide_gemm_sine<NT, NKB, WIDE_CH, NKB>(S, cc, A.c1[l], cd, xtop, hA, h);
+            wide_gemm_sine<NT, NKB, WIDE_CH, NKB, ACTK>(S, cc, A.c1[l], A.c2, cd, xtop, hA, h);
         }
 
         // output layer: one zero-padded M tile, no sine; meanwhile the next pass's first chunk
@@ -699,6 +703,8 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
     P->args.k0p = m->layer[0].Kp;
     P->args.m_out = m->dims[L];
     P->args.qmax = m->qmax_a;
+    P->args.c2 = dhq_hidden_act(m).c2;
+    P->act_kind = m->act_kind;
     P->lds_bytes = (size_t)2 * (WIDE_CH * NKB + 1) * 1024;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
@@ -755,7 +761,8 @@ hipError_t dhq_wide_launch(const dhq_wide_plan *P, const float *coords, int64_t 
     a.n = n;
     const int64_t tiles = (n + WIDE_TILE - 1) / WIDE_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
-    auto kern = dhq_fused_wide_kernel<512>;
+    auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_wide_kernel<512, DHQ_ACT_KIND_WAVELET>
+                                                      : dhq_fused_wide_kernel<512, DHQ_ACT_KIND_SINE>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
     if (e != hipSuccess) return e;
     kern<<<grid, WIDE_THREADS, P->lds_bytes, st>>>(a);

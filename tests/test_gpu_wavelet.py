@@ -104,9 +104,8 @@ def test_wavelet_low_bits(bits):
 @pytest.mark.parametrize("two_sided", [False, True], ids=["one_sided", "two_sided"])
 @pytest.mark.parametrize("dims", [[2, 32, 32, 3], [3, 64, 64, 64, 4], [4, 128, 128, 2], [1, 256, 256, 256, 1], [2, 512, 512, 3]])
 def test_wavelet_fused_shapes_and_ragged_rows(dims, two_sided):
-    """Every hidden width the fused kernels have, ragged row counts over several workgroup passes, static scales
-    (whole-network kernel) and on-line scales (one kernel per layer); a 512-wide wavelet network has no fused
-    kernel and runs layer by layer."""
+    """Every hidden width the fused kernels have (512: input-side rotation only), ragged row counts over several
+    workgroup passes, static scales (whole-network kernel) and on-line scales (one kernel per layer, up to 256)."""
     torch = _torch()
     W, b = synth.siren_init(dims, 30.0, 31 + dims[1])
     rng = np.random.default_rng(dims[1])
@@ -120,7 +119,7 @@ def test_wavelet_fused_shapes_and_ragged_rows(dims, two_sided):
         exp = o.forward(net, x, calibrate=True)
         m = dhq.Model(dims, 30.0, W, b, mode=mode, wavelet_s0=s0)
         m.set_act_scales(net.s_a)
-        assert m.has_fused() == (dims[1] <= 256)
+        assert m.has_fused() == (dims[1] <= 256 or not two_sided)
         out = m.forward(_dev(x))
         lw = m.forward(_dev(x), flags=dhq.DHQ_LAYERWISE)
         torch.cuda.synchronize()
@@ -131,10 +130,13 @@ def test_wavelet_fused_shapes_and_ragged_rows(dims, two_sided):
         assert (err > OUT_TOL).mean() <= max(3e-3, 1.0 / n)      # a code on a rounding boundary may move a coordinate
         assert err.max() <= 2e-2 and np.median(err) <= 1e-5
         if dims[1] > 256:
-            assert np.array_equal(out.cpu().numpy(), lw.cpu().numpy())
-            with pytest.raises(dhq.DhqError) as e:
-                m.forward(_dev(x), flags=dhq.DHQ_FUSED)
-            assert e.value.status == dhq.DHQ_EUNSUPPORTED
+            # width 512: the whole-network kernel for input-side rotation, nothing fused for the two-sided model,
+            # and no per-layer fused kernels for on-line scales
+            if two_sided:
+                assert np.array_equal(out.cpu().numpy(), lw.cpu().numpy())
+                with pytest.raises(dhq.DhqError) as e:
+                    m.forward(_dev(x), flags=dhq.DHQ_FUSED)
+                assert e.value.status == dhq.DHQ_EUNSUPPORTED
             with pytest.raises(dhq.DhqError) as e:
                 m.forward(_dev(x), flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
             assert e.value.status == dhq.DHQ_EUNSUPPORTED
@@ -260,8 +262,7 @@ def test_wavelet_random_shapes_bits_modes_and_row_counts(block):
         exp, dmp = o.forward(net, x, calibrate=True, dump=True)
         near = _near_boundary(net, dmp, bits)
         m = dhq.Model(dims, 30.0, W, b, bits, bits, mode=mode, wavelet_s0=s0)
-        if i >= 60:
-            assert m.has_fused() == (dims[1] <= 256)          # a 512-wide wavelet network runs layer by layer
+        assert m.has_fused() or i < 60
         for l in range(len(dims) - 1):
             assert np.array_equal(m.weight_codes(l), net.Wq[l]), f"case {i}: weight codes of layer {l}"
         m.set_act_scales(net.s_a)
@@ -311,3 +312,39 @@ def test_wavelet_forward_replays_from_a_captured_graph(variant):
         assert np.array_equal(out.cpu().numpy(), eager.cpu().numpy()), f"replay {rep}"
         assert bool(torch.isfinite(scratch).all())
     m.close()
+
+
+def test_wavelet_full_grid_sampled_outputs_width_512():
+    """The 512-wide network on its full 2048 x 2048 grid through the whole-network kernel, as the benchmark
+    launches it: the oracle calibrates on a strided sub-grid and is compared on sampled coordinates."""
+    from test_gpu_parity import BOUNDARY_EPS, FLIP_BOUND, _near_boundary
+    torch = _torch()
+    _say("wavelet full grid C5")
+    wl, coords, W, b = synth.make("C5")
+    n = coords.shape[0]
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b, gabor_s0=S0)
+    o.forward(net, coords[:: n // 8192], calibrate=True)
+    model = dhq.Model(wl.dims, wl.omega0, W, b, wavelet_s0=S0)
+    model.set_act_scales(net.s_a)
+    assert model.has_fused()
+    out = model.forward(_dev(coords), flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(23)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 3000), np.arange(0, 200), np.arange(n - 200, n)]))
+    got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    exp, dmp = o.forward(net, coords[idx], dump=True)
+    err = np.abs(got.astype(np.float64) - exp).max(axis=1)
+    over = err > OUT_TOL
+    near = _near_boundary(net, dmp, 8)
+    _say(f"  {idx.size} sampled coords: max-abs err {err.max():.3e}, median {np.median(err):.1e}, {over.sum()} beyond {OUT_TOL}; "
+         f"{near.sum()} have a code within {BOUNDARY_EPS} of a rounding boundary (|out| max {np.abs(exp).max():.3f})")
+    assert err.max() <= FLIP_BOUND and not (over & ~near).any()
+    assert over.sum() <= max(3, 2 * flip_frac(wl.dims) * idx.size)
+    assert bool(torch.isfinite(out).all())
+    lw = model.forward(_dev(coords[idx]), flags=dhq.DHQ_LAYERWISE)
+    sub = model.forward(_dev(coords[idx]), flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(sub.cpu().numpy(), got)
+    d = np.abs(lw.cpu().numpy() - got).max(axis=1)
+    assert (d > OUT_TOL).sum() <= max(3, 2 * flip_frac(wl.dims) * idx.size)
+    model.close()
