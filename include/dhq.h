@@ -138,10 +138,8 @@ int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const flo
  * layers stay real-valued, so rotation, quantizer, integer GEMM and dequantization are those of
  * the sine network).  `mode` as in dhq_quantize_weights_mode (both rotation modes, all three
  * precisions); s0 >= 0 is the spread of the Gaussian envelope (finite; 0 leaves a plain cosine);
- * omega0 must not be 0.  A W8A8 model has the fused kernels of a sine model (whole network, and one
- * kernel per layer with DHQ_DYNAMIC; either rotation mode) on the same shapes; the fp32-activation
- * wavelet models run layer by layer (DHQ_FUSED is then DHQ_EUNSUPPORTED, dhq_has_fused 0).
- * Everything else behaves as for a sine model.
+ * omega0 must not be 0.  Such a model has the fused kernels of a sine model on the same shapes
+ * and behaves like one in every other respect.
  */
 int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float s0, const float *const *W_host,
                                  const float *const *b_host, dhq_model **out);

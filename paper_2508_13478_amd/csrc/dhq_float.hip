@@ -61,6 +61,7 @@ struct float_args {
     int k0;          // fan-in of the input layer (<= 4)
     int m_out;       // fan-out of the output layer (<= 32)
     float rev;       // omega0 / (2 pi): the sine takes revolutions
+    float c2;        // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     float_layer_desc layer[DHQ_MAX_LAYERS];
 };
 
@@ -150,9 +151,10 @@ __device__ __forceinline__ void flt_group(const float4 *__restrict__ wl, float4 
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int NF, int CHN, int P, int... Qs>
+// ACTK: the activation (sine, or the wavelet with envelope constant c2).
+template <int NF, int CHN, int ACTK, int P, int... Qs>
 __device__ __forceinline__ void flt_pair(const float4 *__restrict__ wl, const float4 *__restrict__ bl,
-                                         float4 (&ring)[FLT_AHEAD * CHN], float rev, float (&y)[NF / 2],
+                                         float4 (&ring)[FLT_AHEAD * CHN], float rev, float c2, float (&y)[NF / 2],
                                          std::integer_sequence<int, Qs...>)
 {
     constexpr int NQ = NF / 8;
@@ -171,13 +173,13 @@ __device__ __forceinline__ void flt_pair(const float4 *__restrict__ wl, const fl
         for (int v = 0; v < 16; ++v) {
             const float4 bb = bq[j][v >> 2];
             const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
-            y[16 * (P * CHN + j) + v] = dhq_sin_rev(__builtin_fmaf(acc[j][v], rev, bias));
+            y[16 * (P * CHN + j) + v] = dhq_activate_rev(__builtin_fmaf(acc[j][v], rev, bias), dhq_act{ACTK, c2});
         }
     }
 }
 
-template <int NF, int CHN, int... Ps>
-__device__ __forceinline__ void flt_hidden_layer(const float4 *__restrict__ wl, const float4 *__restrict__ bl, float rev,
+template <int NF, int CHN, int ACTK, int... Ps>
+__device__ __forceinline__ void flt_hidden_layer(const float4 *__restrict__ wl, const float4 *__restrict__ bl, float rev, float c2,
                                                  float (&y)[NF / 2], std::integer_sequence<int, Ps...>)
 {
     constexpr int NQ = NF / 8;
@@ -189,7 +191,7 @@ __device__ __forceinline__ void flt_hidden_layer(const float4 *__restrict__ wl, 
 #pragma unroll
             for (int j = 0; j < CHN; ++j) ring[g * CHN + j] = wl[(g * CHN + j) * 64];
         }
-    (flt_pair<NF, CHN, Ps>(wl, bl, ring, rev, y, std::make_integer_sequence<int, NQ>{}), ...);
+    (flt_pair<NF, CHN, ACTK, Ps>(wl, bl, ring, rev, c2, y, std::make_integer_sequence<int, NQ>{}), ...);
 }
 
 template <int NF, int... Qs>
@@ -202,7 +204,7 @@ __device__ __forceinline__ void flt_out_layer(const float4 *__restrict__ wl, dhq
      ...);
 }
 
-template <int NF>
+template <int NF, int ACTK>
 __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args A)
 {
     constexpr int NT = NF / 32;
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
                 for (int v = 0; v < 16; ++v) {
                     const float4 bb = bq[v >> 2];
                     const float bias = (v & 3) == 0 ? bb.x : (v & 3) == 1 ? bb.y : (v & 3) == 2 ? bb.z : bb.w;
-                    y[16 * T + v] = dhq_sin_rev(__builtin_fmaf(acc[v], A.rev, bias));
+                    y[16 * T + v] = dhq_activate_rev(__builtin_fmaf(acc[v], A.rev, bias), dhq_act{ACTK, A.c2});
                 }
             }
         }
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
             flt_x_store(y, std::make_integer_sequence<int, NR>{});
             const float4 *wl = reinterpret_cast<const float4 *>(A.blob + A.layer[l].w_off) + lane;
             const float4 *bl = reinterpret_cast<const float4 *>(A.blob + A.layer[l].b_off) + h * 4;
-            flt_hidden_layer<NF, CHN>(wl, bl, A.rev, y, std::make_integer_sequence<int, NT / CHN>{});
+            flt_hidden_layer<NF, CHN, ACTK>(wl, bl, A.rev, A.c2, y, std::make_integer_sequence<int, NT / CHN>{});
         }
         {
             // output layer: one zero-padded tile, no sine
@@ -392,7 +394,7 @@ static int float_create_layerwise(dhq_float_plan *P, const int *dims, int L, dou
                                   const std::vector<std::vector<float>> &b);
 
 // W[l]: dims[l+1] x dims[l] fp32 (the weights the network is to run on), b[l]: dims[l+1].
-// `act` follows every layer but the last; the kernel fused over all layers exists for the sine only.
+// `act` follows every layer but the last.
 int dhq_float_create(const int *dims, int L, float omega0, dhq_act act, const std::vector<std::vector<float>> &W,
                      const std::vector<std::vector<float>> &b, int device, dhq_float_plan **plan_out)
 {
@@ -411,7 +413,7 @@ int dhq_float_create(const int *dims, int L, float omega0, dhq_act act, const st
     }
     P->n_cu = prop.multiProcessorCount;
     int rc = float_create_layerwise(P, dims, L, rev, W, b);
-    if (rc == DHQ_OK && act.kind == DHQ_ACT_KIND_SINE && dhq_float_shape_ok(dims, L)) rc = float_create_fused(P, dims, L, rev, W, b);
+    if (rc == DHQ_OK && dhq_float_shape_ok(dims, L)) rc = float_create_fused(P, dims, L, rev, W, b);
     if (rc != DHQ_OK) {
         dhq_float_destroy(P);
         return rc;
@@ -478,6 +480,7 @@ static int float_create_fused(dhq_float_plan *P, const int *dims, int L, double 
     P->args.k0 = dims[0];
     P->args.m_out = dims[L];
     P->args.rev = (float)rev;
+    P->args.c2 = P->actf.c2;
     P->nf = nf;
     return DHQ_OK;
 }
@@ -569,11 +572,24 @@ hipError_t dhq_float_launch(const dhq_float_plan *P, const float *coords, int64_
     a.n = n;
     const int64_t tiles = (n + FLT_TILE - 1) / FLT_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    const bool wav = (P->actf.kind == DHQ_ACT_KIND_WAVELET);
     switch (P->nf) {
-        case 32: dhq_float_kernel<32><<<grid, FLT_THREADS, 0, st>>>(a); break;
-        case 64: dhq_float_kernel<64><<<grid, FLT_THREADS, 0, st>>>(a); break;
-        case 128: dhq_float_kernel<128><<<grid, FLT_THREADS, 0, st>>>(a); break;
-        case 256: dhq_float_kernel<256><<<grid, FLT_THREADS, 0, st>>>(a); break;
+        case 32:
+            if (wav) dhq_float_kernel<32, DHQ_ACT_KIND_WAVELET><<<grid, FLT_THREADS, 0, st>>>(a);
+            else dhq_float_kernel<32, DHQ_ACT_KIND_SINE><<<grid, FLT_THREADS, 0, st>>>(a);
+            break;
+        case 64:
+            if (wav) dhq_float_kernel<64, DHQ_ACT_KIND_WAVELET><<<grid, FLT_THREADS, 0, st>>>(a);
+            else dhq_float_kernel<64, DHQ_ACT_KIND_SINE><<<grid, FLT_THREADS, 0, st>>>(a);
+            break;
+        case 128:
+            if (wav) dhq_float_kernel<128, DHQ_ACT_KIND_WAVELET><<<grid, FLT_THREADS, 0, st>>>(a);
+            else dhq_float_kernel<128, DHQ_ACT_KIND_SINE><<<grid, FLT_THREADS, 0, st>>>(a);
+            break;
+        case 256:
+            if (wav) dhq_float_kernel<256, DHQ_ACT_KIND_WAVELET><<<grid, FLT_THREADS, 0, st>>>(a);
+            else dhq_float_kernel<256, DHQ_ACT_KIND_SINE><<<grid, FLT_THREADS, 0, st>>>(a);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -190,7 +190,8 @@ def test_wavelet_float_networks(dims, precision):
     rng = np.random.default_rng(dims[1])
     mode = dhq.DHQ_W32A32 if precision == "w32a32" else dhq.DHQ_W8A32
     m = dhq.Model(dims, 30.0, W, b, mode=mode, wavelet_s0=2.0)
-    assert not m.has_fused()                                # fp32 wavelet networks run one kernel per layer
+    # equal hidden widths of 32 .. 256, fan-in <= 4: one kernel for the whole network; otherwise one per layer
+    assert m.has_fused() == (len(set(dims[1:-1])) == 1 and dims[1] in (32, 64, 128, 256) and dims[0] <= 4)
     for n in (1, 4000 + 19, 66000):
         if n == 66000 and max(dims) > 128:
             continue
@@ -201,10 +202,14 @@ def test_wavelet_float_networks(dims, precision):
         else:
             exp, _, _ = o.mlp_w8a32(dims, 30.0, 8, W, b, x, gabor_s0=2.0)
         out = m.forward(_dev(x))
+        lw = m.forward(_dev(x), flags=dhq.DHQ_LAYERWISE)
         torch.cuda.synchronize()
         err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max()
-        _say(f"  max-abs err {err:.2e} (|out| max {np.abs(exp).max():.2f})")
-        assert out.shape == exp.shape and err <= 4e-6
+        err_lw = np.abs(lw.cpu().numpy().astype(np.float64) - exp).max()
+        _say(f"  max-abs err {err:.2e}, layer by layer {err_lw:.2e} (|out| max {np.abs(exp).max():.2f})")
+        assert out.shape == exp.shape and err <= 4e-6 and err_lw <= 4e-6
+        if not m.has_fused():
+            assert np.array_equal(out.cpu().numpy(), lw.cpu().numpy())
     m.close()
 
 
