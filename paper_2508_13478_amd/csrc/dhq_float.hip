@@ -295,7 +295,8 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
-    const int64_t row0 = ((int64_t)blockIdx.x * FLW_WAVES + wave) * 32;
+    // wave-uniform, so that the row part of every store address is scalar arithmetic
+    const int64_t row0 = ((int64_t)blockIdx.x * FLW_WAVES + __builtin_amdgcn_readfirstlane(wave)) * 32;
     if (row0 >= n) return;  // no barrier below
     const int T0 = blockIdx.y * FLW_TILES;
     const int nt = (Mt - T0 < FLW_TILES) ? Mt - T0 : FLW_TILES;
@@ -355,18 +356,29 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
 #pragma unroll
         for (int q = 0; q < 4; ++q) a[q] = an[q];
     }
+    // accumulator v of a lane: row row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (T0 + t) + c; a store address is a
+    // scalar base (row, tile) plus the lane's constant offset; whole 32-row blocks skip the row checks
+    const int nrows = (n - row0 < 32) ? (int)(n - row0) : 32;
+    const bool full = (nrows == 32);
+    const unsigned loff = (unsigned)(4 * h * M + c);
+    auto epi = [&](float a, float bf) {
+        return ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev(__builtin_fmaf(a, rev, bf), dhq_act{ACT, c2}) : a + bf;
+    };
 #pragma unroll
     for (int t = 0; t < FLW_TILES; ++t) {
         if (t < nt) {
             const int f = 32 * (T0 + t) + c;
             if (f < M) {
                 const float bf = bias[f];
+                float *tile_out = out + (size_t)row0 * M + (size_t)(T0 + t) * 32;  // wave-uniform
+                if (full) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t row = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (row < n)
-                        out[row * M + f] = ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev(__builtin_fmaf(acc[t][v], rev, bf), dhq_act{ACT, c2})
-                                                                    : acc[t][v] + bf;
+                    for (int v = 0; v < 16; ++v)
+                        (tile_out + (size_t)(8 * (v >> 2) + (v & 3)) * M)[loff] = epi(acc[t][v], bf);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (8 * (v >> 2) + (v & 3) + 4 * h < nrows) (tile_out + (size_t)(8 * (v >> 2) + (v & 3)) * M)[loff] = epi(acc[t][v], bf);
                 }
             }
         }

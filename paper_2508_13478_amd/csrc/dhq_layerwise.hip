@@ -327,6 +327,44 @@ hipError_t dhq_launch_wht_absmax_partials(const float *in, int64_t n, int K, int
 // they are stored in device memory) and read back conflict-free with one 16-byte LDS load
 // per lane.  Codes are read straight from device memory.
 #define GEMM_WAVES 8  // waves per workgroup: 32 coordinates each, sharing the staged weight fragments
+
+// The tiles of one wave, one after the other: a tile's epilogue and stores follow its MFMAs directly, so
+// the stores of one tile travel while the next one is multiplied.  Accumulator v of a lane: coordinate
+// row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (tile0 + t) + c.  KIND: the activation of the epilogue, or
+// -1 for the raw accumulators; FULL: all 32 rows exist.
+template <int NKB, bool FULL, int KIND>
+__device__ __forceinline__ void gemm_tiles(const dhq_v4i *lds, const dhq_v4i (&b)[NKB], int tile0, int ntile, int M, int64_t row0,
+                                           int nrows, int lane, int32_t *__restrict__ acc_out, float *__restrict__ act_out,
+                                           float c1, const float *__restrict__ bias, float c2)
+{
+    const int c = lane & 31, h = lane >> 5;
+    const unsigned loff = (unsigned)(4 * h * M + c);  // this lane's place within a tile's 32 x M block of the output
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        if (t >= ntile) break;
+        dhq_v16i acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            const dhq_v4i w = lds[(t * NKB + kb) * 64 + lane];
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kb], w, acc, 0, 0, 0);
+        }
+        const int f = (tile0 + t) * 32 + c;
+        if (f >= M) continue;
+        const size_t tile_off = (size_t)row0 * M + (size_t)(tile0 + t) * 32;  // wave-uniform
+        const float bf = (KIND >= 0) ? bias[f] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 8 * (v >> 2) + (v & 3);  // row within the block, less the lane half's 4 h
+            if (!FULL && rl + 4 * h >= nrows) continue;
+            if constexpr (KIND >= 0)
+                (act_out + tile_off + (size_t)rl * M)[loff] = dhq_epilogue(acc[v], c1, bf, dhq_act{KIND, c2});
+            else
+                (acc_out + tile_off + (size_t)rl * M)[loff] = acc[v];
+        }
+    }
+}
 template <int NKB, bool ACT>
 __global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int8_t *__restrict__ codes, int64_t n,
                                                            const int8_t *__restrict__ wfrag, int M, int Mt,
@@ -359,33 +397,23 @@ __global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int
     }
     __syncthreads();
 
-    // tile after tile: a tile's epilogue and stores follow its MFMAs directly, so the stores of one
-    // tile travel while the next one is multiplied
-    // accumulator v of this lane: coordinate row0 + 8 (v / 4) + 4 h + v % 4, feature 32 (tile0 + t) + c
-    const int64_t row0 = (int64_t)blockIdx.x * (32 * GEMM_WAVES) + wave * 32;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        if (t >= ntile) break;
-        dhq_v16i acc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0;
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
-            const dhq_v4i w = lds[(t * NKB + kb) * 64 + lane];
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kb], w, acc, 0, 0, 0);
-        }
-        const int f = (tile0 + t) * 32 + c;
-        if (f >= M) continue;
-        const float bf = ACT ? bias[f] : 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t r = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (r >= n) continue;
-            if (ACT)
-                act_out[r * M + f] = dhq_epilogue(acc[v], c1, bf, act);
-            else
-                acc_out[r * M + f] = acc[v];
-        }
+    // The 32 rows of a wave start at a wave-uniform row, so every store address is a scalar base (row and tile)
+    // plus one 32-bit lane offset that never changes; whole 32-row blocks skip the row checks, and the
+    // activation is chosen once per wave, not once per value.
+    const int64_t row0 = (int64_t)blockIdx.x * (32 * GEMM_WAVES) + __builtin_amdgcn_readfirstlane(wave) * 32;
+    if (row0 >= n) return;  // no barrier below
+    const int nrows = (n - row0 < 32) ? (int)(n - row0) : 32;
+    const int kind = ACT ? act.kind : -1;
+    if (nrows == 32) {
+        if (kind == DHQ_ACT_KIND_SINE) gemm_tiles<NKB, true, DHQ_ACT_KIND_SINE>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else if (kind == DHQ_ACT_KIND_WAVELET) gemm_tiles<NKB, true, DHQ_ACT_KIND_WAVELET>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else if (kind == DHQ_ACT_KIND_NONE) gemm_tiles<NKB, true, DHQ_ACT_KIND_NONE>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else gemm_tiles<NKB, true, -1>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+    } else {
+        if (kind == DHQ_ACT_KIND_SINE) gemm_tiles<NKB, false, DHQ_ACT_KIND_SINE>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else if (kind == DHQ_ACT_KIND_WAVELET) gemm_tiles<NKB, false, DHQ_ACT_KIND_WAVELET>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else if (kind == DHQ_ACT_KIND_NONE) gemm_tiles<NKB, false, DHQ_ACT_KIND_NONE>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
+        else gemm_tiles<NKB, false, -1>(lds, b, tile0, ntile, M, row0, nrows, lane, acc_out, act_out, c1, bias, act.c2);
     }
 }
 
@@ -395,14 +423,16 @@ __global__ __launch_bounds__(64 * GEMM_WAVES) void gemm_i8_mfma_kernel(const int
 // weights of its VEC consecutive features (4 when the row length allows 16-byte stores) in
 // registers and walks over NARROW_ROWS coordinates.  KP = 0 takes the fan-in at run time.
 #define NARROW_ROWS 8
-template <bool ACT, int VEC, int KP>
-__global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restrict__ codes, int64_t n, int Kp_rt,
+// KIND: the activation, fixed at compile time so that the epilogue has no branch per value.
+template <bool ACT, int VEC, int KP, int KIND>
+__device__ __forceinline__ void gemm_narrow_body(const int8_t *__restrict__ codes, int64_t n, int Kp_rt,
                                                           const int8_t *__restrict__ wq, int M,
                                                           int32_t *__restrict__ acc_out,
                                                           float *__restrict__ act_out, float c1,
-                                                          const float *__restrict__ bias, dhq_act act,
+                                                          const float *__restrict__ bias, float c2,
                                                           const float *__restrict__ dyn)
 {
+    const dhq_act act{KIND, c2};
     if (ACT && dyn) c1 = dyn[1];
     const int Kp = KP ? KP : Kp_rt;
     constexpr int KMAX = KP ? KP : 16;
@@ -447,6 +477,19 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restri
             }
         }
     }
+}
+
+template <bool ACT, int VEC, int KP>
+__global__ __launch_bounds__(256) void gemm_narrow_kernel(const int8_t *__restrict__ codes, int64_t n, int Kp_rt,
+                                                          const int8_t *__restrict__ wq, int M,
+                                                          int32_t *__restrict__ acc_out,
+                                                          float *__restrict__ act_out, float c1,
+                                                          const float *__restrict__ bias, dhq_act act,
+                                                          const float *__restrict__ dyn)
+{
+    if (act.kind == DHQ_ACT_KIND_SINE) gemm_narrow_body<ACT, VEC, KP, DHQ_ACT_KIND_SINE>(codes, n, Kp_rt, wq, M, acc_out, act_out, c1, bias, act.c2, dyn);
+    else if (act.kind == DHQ_ACT_KIND_WAVELET) gemm_narrow_body<ACT, VEC, KP, DHQ_ACT_KIND_WAVELET>(codes, n, Kp_rt, wq, M, acc_out, act_out, c1, bias, act.c2, dyn);
+    else gemm_narrow_body<ACT, VEC, KP, DHQ_ACT_KIND_NONE>(codes, n, Kp_rt, wq, M, acc_out, act_out, c1, bias, act.c2, dyn);
 }
 
 template <bool ACT, int VEC>
@@ -543,13 +586,13 @@ hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, c
 // c1 carries), then y = z c1 + bias (and the sine) for the first M features.  Same lane
 // layout and the same butterfly network as the forward transform (wht_shape, wht_butterflies).
 // Intermediate sums may wrap; the host has checked that the final ones fit.
-template <int MP>
-__global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *__restrict__ acc, int64_t n, int M,
-                                                                float c1, const float *__restrict__ bias, dhq_act act,
-                                                                const float *__restrict__ dyn,
-                                                                int32_t *__restrict__ z_out,
-                                                                float *__restrict__ act_out)
+// KIND: the activation, fixed at compile time so that the epilogue has no branch per value.
+template <int MP, int KIND>
+__device__ __forceinline__ void unrotate_epilogue_body(const int32_t *__restrict__ acc, int64_t n, int M, float c1,
+                                                       const float *__restrict__ bias, float c2, const float *__restrict__ dyn,
+                                                       int32_t *__restrict__ z_out, float *__restrict__ act_out)
 {
+    const dhq_act act{KIND, c2};
     if (dyn) c1 = dyn[1];
     constexpr int EPL = wht_shape<MP>::EPL;
     constexpr int LPR = wht_shape<MP>::LPR;
@@ -596,6 +639,18 @@ __global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *_
             if (act_out && f < M) act_out[row * M + f] = dhq_epilogue(v[e], c1, bias[f], act);
         }
     }
+}
+
+template <int MP>
+__global__ __launch_bounds__(256) void unrotate_epilogue_kernel(const int32_t *__restrict__ acc, int64_t n, int M,
+                                                                float c1, const float *__restrict__ bias, dhq_act act,
+                                                                const float *__restrict__ dyn,
+                                                                int32_t *__restrict__ z_out,
+                                                                float *__restrict__ act_out)
+{
+    if (act.kind == DHQ_ACT_KIND_SINE) unrotate_epilogue_body<MP, DHQ_ACT_KIND_SINE>(acc, n, M, c1, bias, act.c2, dyn, z_out, act_out);
+    else if (act.kind == DHQ_ACT_KIND_WAVELET) unrotate_epilogue_body<MP, DHQ_ACT_KIND_WAVELET>(acc, n, M, c1, bias, act.c2, dyn, z_out, act_out);
+    else unrotate_epilogue_body<MP, DHQ_ACT_KIND_NONE>(acc, n, M, c1, bias, act.c2, dyn, z_out, act_out);
 }
 
 template <int MP>
