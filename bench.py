@@ -29,8 +29,8 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "946f4d25dde46c3129ffa4bff14b6e3f70fdbfdb665568f3d856c6f73de0457d"
-TRAFFIC_BYTES = {"C2": (2524.5 + 768.0) * 1024, "C5": (44538.8 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "606abad06a56a5e1be04ae723d0bf922c1e99e0cacb73e58a6bc8573eb22b452"
+TRAFFIC_BYTES = {"C2": (2524.8 + 768.0) * 1024, "C5": (44537.6 + 49152.0) * 1024}
 
 
 def kernel_sources_sha256():
@@ -201,7 +201,7 @@ def main() -> int:
                                  else None),
                      "traffic_unit": "bytes per launch (HBM, measured)",
                      "kernel": ((f"dhq_fused2_kernel<{wl.dims[1]}>" if two_sided else
-                                 "dhq_fused_wide_kernel<512>" if wl.dims[1] == 512 else
+                                 f"dhq_fused_wide_kernel<512, {2 if s0 is not None else 1}>" if wl.dims[1] == 512 else
                                  f"dhq_fused_kernel<{wl.dims[1]}, {2 if s0 is not None else 1}>")
                                 if fused else "layerwise kernels"),
                      "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
