@@ -287,7 +287,8 @@ __global__ __launch_bounds__(FLT_THREADS) void dhq_float_kernel(const float_args
 #define FLW_WAVES 4
 #define FLW_TILES 4
 
-template <int ACT>
+// NTT: column tiles per wave (NTT, or all of a layer with fewer: its few tiles then cost no more than their own MFMAs).
+template <int ACT, int NTT>
 __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float *__restrict__ in, int64_t n, int K, int NG,
                                                                      int vec, const float4 *__restrict__ wfrag, int M, int Mt,
                                                                      const float *__restrict__ bias, float rev, float c2,
@@ -298,13 +299,13 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
     // wave-uniform, so that the row part of every store address is scalar arithmetic
     const int64_t row0 = ((int64_t)blockIdx.x * FLW_WAVES + __builtin_amdgcn_readfirstlane(wave)) * 32;
     if (row0 >= n) return;  // no barrier below
-    const int T0 = blockIdx.y * FLW_TILES;
-    const int nt = (Mt - T0 < FLW_TILES) ? Mt - T0 : FLW_TILES;
+    const int T0 = blockIdx.y * NTT;
+    const int nt = (Mt - T0 < NTT) ? Mt - T0 : NTT;
     const int64_t arow = (row0 + c < n) ? row0 + c : n - 1;  // rows past the end repeat the last one and are not stored
     const float *ap = in + arow * K;
-    dhq_v16f acc[FLW_TILES];
+    dhq_v16f acc[NTT];
 #pragma unroll
-    for (int t = 0; t < FLW_TILES; ++t)
+    for (int t = 0; t < NTT; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
     // this lane's sixteen inputs of k group J (zero beyond K): 64 contiguous bytes of its row
@@ -323,13 +324,13 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
         }
     };
     // tiles past the layer's last one re-read the last one's weights; their results are dropped
-    const float4 *wp[FLW_TILES];
+    const float4 *wp[NTT];
 #pragma unroll
-    for (int t = 0; t < FLW_TILES; ++t) wp[t] = wfrag + (size_t)(T0 + (t < nt ? t : nt - 1)) * NG * 4 * 64 + lane;
-    float4 a[4], w[FLW_TILES];
+    for (int t = 0; t < NTT; ++t) wp[t] = wfrag + (size_t)(T0 + (t < nt ? t : nt - 1)) * NG * 4 * 64 + lane;
+    float4 a[4], w[NTT];
     load_a(0, a);
 #pragma unroll
-    for (int t = 0; t < FLW_TILES; ++t) w[t] = wp[t][0];
+    for (int t = 0; t < NTT; ++t) w[t] = wp[t][0];
     for (int J = 0; J < NG; ++J) {
         // the next operands are fetched while the current MFMAs run (inputs one group of 32 k ahead, weights
         // one quarter group ahead); consecutive MFMAs go to different accumulators
@@ -339,19 +340,19 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int nxt = (q < 3) ? 4 * J + q + 1 : 4 * Jn;
-            float4 wn[FLW_TILES];
+            float4 wn[NTT];
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) wn[t] = wp[t][(size_t)nxt * 64];
+            for (int t = 0; t < NTT; ++t) wn[t] = wp[t][(size_t)nxt * 64];
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, w[t].x, acc[t], 0, 0, 0);
+            for (int t = 0; t < NTT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, w[t].x, acc[t], 0, 0, 0);
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].y, w[t].y, acc[t], 0, 0, 0);
+            for (int t = 0; t < NTT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].y, w[t].y, acc[t], 0, 0, 0);
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].z, w[t].z, acc[t], 0, 0, 0);
+            for (int t = 0; t < NTT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].z, w[t].z, acc[t], 0, 0, 0);
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].w, w[t].w, acc[t], 0, 0, 0);
+            for (int t = 0; t < NTT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].w, w[t].w, acc[t], 0, 0, 0);
 #pragma unroll
-            for (int t = 0; t < FLW_TILES; ++t) w[t] = wn[t];
+            for (int t = 0; t < NTT; ++t) w[t] = wn[t];
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) a[q] = an[q];
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
         return ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev(__builtin_fmaf(a, rev, bf), dhq_act{ACT, c2}) : a + bf;
     };
 #pragma unroll
-    for (int t = 0; t < FLW_TILES; ++t) {
+    for (int t = 0; t < NTT; ++t) {
         if (t < nt) {
             const int f = 32 * (T0 + t) + c;
             if (f < M) {
@@ -546,6 +547,25 @@ void dhq_float_destroy(dhq_float_plan *P)
 
 bool dhq_float_has_fused(const dhq_float_plan *P) { return P && P->nf != 0; }
 
+template <int ACT>
+static void float_layer_launch_act(int ntt, float c2, dim3 grid, hipStream_t st, const float *in, int64_t n, int K, int NG, int vec,
+                                   const float4 *wf, int M, int Mt, const float *bias, float rev, float *out)
+{
+    switch (ntt) {
+        case 1: float_layer_kernel<ACT, 1><<<grid, 64 * FLW_WAVES, 0, st>>>(in, n, K, NG, vec, wf, M, Mt, bias, rev, c2, out); break;
+        case 2: float_layer_kernel<ACT, 2><<<grid, 64 * FLW_WAVES, 0, st>>>(in, n, K, NG, vec, wf, M, Mt, bias, rev, c2, out); break;
+        case 3: float_layer_kernel<ACT, 3><<<grid, 64 * FLW_WAVES, 0, st>>>(in, n, K, NG, vec, wf, M, Mt, bias, rev, c2, out); break;
+        default: float_layer_kernel<ACT, FLW_TILES><<<grid, 64 * FLW_WAVES, 0, st>>>(in, n, K, NG, vec, wf, M, Mt, bias, rev, c2, out); break;
+    }
+}
+static void float_layer_launch(int ntt, dhq_act act, dim3 grid, hipStream_t st, const float *in, int64_t n, int K, int NG, int vec,
+                               const float4 *wf, int M, int Mt, const float *bias, float rev, float *out)
+{
+    if (act.kind == DHQ_ACT_KIND_SINE) float_layer_launch_act<DHQ_ACT_KIND_SINE>(ntt, 0.f, grid, st, in, n, K, NG, vec, wf, M, Mt, bias, rev, out);
+    else if (act.kind == DHQ_ACT_KIND_WAVELET) float_layer_launch_act<DHQ_ACT_KIND_WAVELET>(ntt, act.c2, grid, st, in, n, K, NG, vec, wf, M, Mt, bias, rev, out);
+    else float_layer_launch_act<DHQ_ACT_KIND_NONE>(ntt, 0.f, grid, st, in, n, K, NG, vec, wf, M, Mt, bias, rev, out);
+}
+
 hipError_t dhq_float_launch_layerwise(const dhq_float_plan *P, const float *coords, int64_t n, float *out, hipStream_t st)
 {
     if (!P) return hipErrorInvalidValue;
@@ -556,16 +576,13 @@ hipError_t dhq_float_launch_layerwise(const dhq_float_plan *P, const float *coor
         for (int l = 0; l < L; ++l) {
             const float_lw_layer &Ly = P->lw[l];
             float *dst = (l == L - 1) ? out + start * Ly.M : P->act[l & 1];
-            const dim3 grid((unsigned)((rows + 32 * FLW_WAVES - 1) / (32 * FLW_WAVES)), (unsigned)((Ly.Mt + FLW_TILES - 1) / FLW_TILES));
+            const int ntt = Ly.Mt < FLW_TILES ? Ly.Mt : FLW_TILES;  // column tiles per wave
+            const dim3 grid((unsigned)((rows + 32 * FLW_WAVES - 1) / (32 * FLW_WAVES)), (unsigned)((Ly.Mt + ntt - 1) / ntt));
             // one 16-byte load per lane needs rows that start on 16-byte boundaries
             const int vec = (Ly.K % 4 == 0 && ((uintptr_t)cur & 15) == 0) ? 1 : 0;
             const float4 *wf = reinterpret_cast<const float4 *>(Ly.wfrag_dev);
-            if (l == L - 1)
-                float_layer_kernel<DHQ_ACT_KIND_NONE><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, 0.f, dst);
-            else if (P->actf.kind == DHQ_ACT_KIND_WAVELET)
-                float_layer_kernel<DHQ_ACT_KIND_WAVELET><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, P->actf.c2, dst);
-            else
-                float_layer_kernel<DHQ_ACT_KIND_SINE><<<grid, 64 * FLW_WAVES, 0, st>>>(cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, 0.f, dst);
+            const dhq_act act = (l == L - 1) ? dhq_act{DHQ_ACT_KIND_NONE, 0.f} : P->actf;
+            float_layer_launch(ntt, act, grid, st, cur, rows, Ly.K, Ly.NG, vec, wf, Ly.M, Ly.Mt, Ly.bias_dev, P->rev, dst);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             cur = dst;
