@@ -34,8 +34,17 @@ int main(void)
     dims[1] = 4;
     CHECK(dhq_quantize_weights_mode(&d, 7u, W, B, &m) == DHQ_EINVAL);
     CHECK(dhq_quantize_weights_mode(&d, DHQ_ROTATE_BOTH | DHQ_W8A32, W, B, &m) == DHQ_EUNSUPPORTED);
+    /* wavelet networks: the spread and omega0 are checked on the host */
+    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, -1.0f, W, B, &m) == DHQ_EINVAL);
+    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, 1.0f / 0.0f, W, B, &m) == DHQ_EINVAL);
+    CHECK(dhq_quantize_weights_wavelet(NULL, DHQ_ROTATE_IN, 10.0f, W, B, &m) == DHQ_EINVAL);
+    CHECK(dhq_quantize_weights_wavelet(&d, 7u, 10.0f, W, B, &m) == DHQ_EINVAL);
+    d.omega0 = 0.0f;
+    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, 10.0f, W, B, &m) == DHQ_EINVAL);
+    d.omega0 = 30.0f;
     w0[3] = 1.0f / 0.0f;
     CHECK(dhq_quantize_weights(&d, W, B, &m) == DHQ_EINVAL);
+    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, 10.0f, W, B, &m) == DHQ_EINVAL);
 
     CHECK(dhq_forward(NULL, NULL, 0, NULL, NULL, DHQ_AUTO) == DHQ_EINVAL);
     CHECK(dhq_set_act_scales(NULL, NULL) == DHQ_EINVAL);
