@@ -312,6 +312,7 @@ extern "C" int dhq_quantize_weights(const dhq_net_desc *desc, const float *const
 extern "C" int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float s0, const float *const *W_host,
                                             const float *const *b_host, dhq_model **out)
 {
+    if (out) *out = nullptr;
     if (!isfinite(s0) || s0 < 0.0f) return DHQ_EINVAL;
     // the sine and cosine take omega0 y / 2 pi; the envelope's argument is recovered from it
     if (desc && !(fabsf(desc->omega0) > 0.0f)) return DHQ_EINVAL;

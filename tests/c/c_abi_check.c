@@ -35,7 +35,8 @@ int main(void)
     CHECK(dhq_quantize_weights_mode(&d, 7u, W, B, &m) == DHQ_EINVAL);
     CHECK(dhq_quantize_weights_mode(&d, DHQ_ROTATE_BOTH | DHQ_W8A32, W, B, &m) == DHQ_EUNSUPPORTED);
     /* wavelet networks: the spread and omega0 are checked on the host */
-    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, -1.0f, W, B, &m) == DHQ_EINVAL);
+    m = (dhq_model *)0x1;
+    CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, -1.0f, W, B, &m) == DHQ_EINVAL && m == NULL);
     CHECK(dhq_quantize_weights_wavelet(&d, DHQ_ROTATE_IN, 1.0f / 0.0f, W, B, &m) == DHQ_EINVAL);
     CHECK(dhq_quantize_weights_wavelet(NULL, DHQ_ROTATE_IN, 10.0f, W, B, &m) == DHQ_EINVAL);
     CHECK(dhq_quantize_weights_wavelet(&d, 7u, 10.0f, W, B, &m) == DHQ_EINVAL);
