@@ -493,7 +493,6 @@ static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, flo
                       : dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st);
         return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
     }
-    if (dhq_launch_clear_words(m->dyn_absmax, DHQ_MAX_LAYERS, st) != hipSuccess) return DHQ_EHIP;
     const float *cur = coords_dev;
     float *bufs[2] = {m->dyn_act0, m->dyn_act1};
     int which = 0;
@@ -501,10 +500,11 @@ static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, flo
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == L - 1);
         float *dyn = m->dyn_params + 3 * l;
-        if (dhq_launch_wht_absmax(cur, n, Ly.K, Ly.Kp, m->dyn_absmax + l, partial, m->qmax_a, dhq_c1_over_sa(m, l), dyn, st) !=
-            hipSuccess)
-            return DHQ_EHIP;
-        if (dhq_launch_wht_quant(cur, n, Ly.K, Ly.Kp, 0.0f, m->qmax_a, m->dyn_codes, dyn, st) != hipSuccess) return DHQ_EHIP;
+        // pass 1 leaves one maximum of |x^| per workgroup; pass 2 folds them, quantizes and stores the constants
+        int count = 0;
+        if (dhq_launch_wht_absmax_partials(cur, n, Ly.K, Ly.Kp, partial, &count, st) != hipSuccess) return DHQ_EHIP;
+        const dhq_wht_fold fold = {partial, count, dhq_c1_over_sa(m, l), dyn};
+        if (dhq_launch_wht_quant(cur, n, Ly.K, Ly.Kp, 0.0f, m->qmax_a, m->dyn_codes, &fold, st) != hipSuccess) return DHQ_EHIP;
         float *dst = last ? out_dev : bufs[which];
         if (gemm_epilogue(m, l, m->dyn_codes, n, m->dyn_acc, dyn, dst, st) != hipSuccess) return DHQ_EHIP;
         cur = dst;

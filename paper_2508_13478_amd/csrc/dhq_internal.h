@@ -75,9 +75,17 @@ struct dhq_model {
 // ---- launchers (defined in dhq_layerwise.hip) --------------------------------------------
 // Rotate rows over K (zero-padded to Kp) and quantize: codes = clamp(rne(x^ * inv)).
 // inv = 1 / (s_a * sqrt(Kp)) because the butterflies run un-normalised.
-// If dyn != nullptr, inv is read from dyn[0] on the device.
-hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float inv, int qmax,
-                                int8_t *codes, const float *dyn, hipStream_t st);
+// Dynamic mode (fold != nullptr): inv is ignored; the kernel folds the `count` per-workgroup maxima that
+// dhq_launch_wht_absmax_partials left in `partial` into max |x^| and derives the layer's constants from it,
+// and stores dyn_out[0..2] = {1 / (s_a sqrt(Kp)), s_a * c1_over_sa, s_a} for the kernels that follow.
+struct dhq_wht_fold {
+    const float *partial;
+    int count;
+    double c1_over_sa;
+    float *dyn_out;
+};
+hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float inv, int qmax, int8_t *codes,
+                                const dhq_wht_fold *fold, hipStream_t st);
 
 // The same rotation, reduced to max |un-normalised x^| over all rows: *absmax_bits (float bits;
 // cleared by the caller before the first of several calls that are to accumulate) is raised to

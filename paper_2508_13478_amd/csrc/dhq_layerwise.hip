@@ -9,8 +9,9 @@
 //   epilogue    dequantize + bias + sine from stored accumulators
 //   unrotate    two-sided variant (Eq. 4-5 with both factors): multiplies the rotated
 //               accumulators by H over the output features, exactly in int32, then the epilogue
-//   dyn_scale   on-line per-tensor scale (the dynamic quantization module of Sec. 3.3): turns
-//               the absmax word of a layer input into the constants the next kernels read
+//   dyn_scale   on-line per-tensor scale (the dynamic quantization module of Sec. 3.3): the per-workgroup
+//               maxima of a layer input become the constants the kernels read -- folded by the quantizing
+//               kernel itself in a forward pass, by a one-workgroup kernel during calibration
 //
 // Activations travel through device memory between these kernels; the fused whole-network
 // kernel lives in dhq_fused.hip.
@@ -143,9 +144,31 @@ template <int KP>
 __global__ __launch_bounds__(256) void wht_quant_kernel(const float *__restrict__ in, int64_t n,
                                                         int K, float inv, int qmax,
                                                         int8_t *__restrict__ codes,
-                                                        const float *__restrict__ dyn)
+                                                        const float *__restrict__ fold_partial, int fold_count,
+                                                        double c1_over_sa, float *__restrict__ dyn_out)
 {
-    if (dyn) inv = dyn[0];  // scale measured on the device (dynamic mode)
+    if (fold_partial) {
+        // dynamic mode: the scale is measured on the device.  Every workgroup folds the per-workgroup maxima
+        // the absmax pass left (a few KiB from L2: cheaper than a one-workgroup launch in between) and turns
+        // the maximum into the layer's constants; workgroup 0 also stores them for the kernels that follow.
+        __shared__ float red[5];
+        float mx = 0.0f;
+        for (int i = threadIdx.x; i < fold_count; i += 256) mx = fmaxf(mx, fold_partial[i]);
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float c1, s_a;
+            dhq_dyn_constants(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])), KP, qmax, c1_over_sa, inv, c1, s_a);
+            red[4] = inv;
+            if (blockIdx.x == 0) {
+                dyn_out[0] = inv; dyn_out[1] = c1; dyn_out[2] = s_a;
+            }
+        }
+        __syncthreads();
+        inv = red[4];
+    }
     constexpr int EPL = wht_shape<KP>::EPL;
     constexpr int LPR = wht_shape<KP>::LPR;
     const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -233,12 +256,13 @@ __global__ __launch_bounds__(256) void absmax_finish_kernel(const float *__restr
 
 template <int KP>
 static hipError_t launch_wht(const float *in, int64_t n, int K, float inv, int qmax, int8_t *codes,
-                             const float *dyn, hipStream_t st)
+                             const dhq_wht_fold *fold, hipStream_t st)
 {
     constexpr int LPR = wht_shape<KP>::LPR;
     const int64_t threads = n * LPR;
     const unsigned blocks = (unsigned)((threads + 255) / 256);
-    wht_quant_kernel<KP><<<blocks, 256, 0, st>>>(in, n, K, inv, qmax, codes, dyn);
+    wht_quant_kernel<KP><<<blocks, 256, 0, st>>>(in, n, K, inv, qmax, codes, fold ? fold->partial : nullptr, fold ? fold->count : 0,
+                                                 fold ? fold->c1_over_sa : 0.0, fold ? fold->dyn_out : nullptr);
     return hipGetLastError();
 }
 
@@ -261,20 +285,21 @@ static hipError_t launch_absmax(const float *in, int64_t n, int K, unsigned *abs
 }
 
 hipError_t dhq_launch_wht_quant(const float *in, int64_t n, int K, int Kp, float inv, int qmax,
-                                int8_t *codes, const float *dyn, hipStream_t st)
+                                int8_t *codes, const dhq_wht_fold *fold, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
+    if (fold && (!fold->partial || !fold->dyn_out || fold->count < 1 || fold->count > DHQ_ABSMAX_PARTIALS)) return hipErrorInvalidValue;
     switch (Kp) {
-        case 1: return launch_wht<1>(in, n, K, inv, qmax, codes, dyn, st);
-        case 2: return launch_wht<2>(in, n, K, inv, qmax, codes, dyn, st);
-        case 4: return launch_wht<4>(in, n, K, inv, qmax, codes, dyn, st);
-        case 8: return launch_wht<8>(in, n, K, inv, qmax, codes, dyn, st);
-        case 16: return launch_wht<16>(in, n, K, inv, qmax, codes, dyn, st);
-        case 32: return launch_wht<32>(in, n, K, inv, qmax, codes, dyn, st);
-        case 64: return launch_wht<64>(in, n, K, inv, qmax, codes, dyn, st);
-        case 128: return launch_wht<128>(in, n, K, inv, qmax, codes, dyn, st);
-        case 256: return launch_wht<256>(in, n, K, inv, qmax, codes, dyn, st);
-        case 512: return launch_wht<512>(in, n, K, inv, qmax, codes, dyn, st);
+        case 1: return launch_wht<1>(in, n, K, inv, qmax, codes, fold, st);
+        case 2: return launch_wht<2>(in, n, K, inv, qmax, codes, fold, st);
+        case 4: return launch_wht<4>(in, n, K, inv, qmax, codes, fold, st);
+        case 8: return launch_wht<8>(in, n, K, inv, qmax, codes, fold, st);
+        case 16: return launch_wht<16>(in, n, K, inv, qmax, codes, fold, st);
+        case 32: return launch_wht<32>(in, n, K, inv, qmax, codes, fold, st);
+        case 64: return launch_wht<64>(in, n, K, inv, qmax, codes, fold, st);
+        case 128: return launch_wht<128>(in, n, K, inv, qmax, codes, fold, st);
+        case 256: return launch_wht<256>(in, n, K, inv, qmax, codes, fold, st);
+        case 512: return launch_wht<512>(in, n, K, inv, qmax, codes, fold, st);
         default: return hipErrorInvalidValue;
     }
 }
