@@ -581,3 +581,16 @@ def test_wavelet_quantized_network_tracks_the_float_one():
     assert errs[0] > errs[1] > errs[2] and errs[2] < 0.05
     w8a32, _, _ = o.mlp_w8a32(wl.dims, wl.omega0, 8, W, b, coords, gabor_s0=S0)
     assert np.sqrt(np.mean((w8a32 - ref) ** 2)) < errs[2]
+
+
+def test_wavelet_matches_complex_form_for_random_parameters():
+    """Seeded random frequencies, spreads and arguments: the oracle's activation is the real part of the complex
+    Gabor wavelet, is bounded by 1 and is even."""
+    rng = np.random.default_rng(2508)
+    for _ in range(40):
+        w0, s0 = float(rng.uniform(0.5, 60.0)), float(rng.uniform(0.0, 20.0))
+        y = rng.uniform(-1.5, 1.5, size=64)
+        g = o.activation(y, w0, s0)
+        ref = np.real(np.exp(1j * w0 * y - np.abs(s0 * y) ** 2))
+        assert np.abs(g - ref).max() <= 2e-15 and np.abs(g).max() <= 1.0
+        assert np.array_equal(g, o.activation(-y, w0, s0))
