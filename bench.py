@@ -3,9 +3,10 @@
 
 A step is one pass of the whole hot path (coordinates in, signal values out: rotation,
 quantizer, int8 GEMM, dequantize + bias + sine for every layer) over one synthetic coordinate
-grid that is already resident in device memory.  The workload is the C2 configuration
-(SIREN 2 -> 256 x 4 hidden -> 3 on a 256 x 256 grid); other configurations can be selected with
---workload.  Prints ONE JSON line.
+grid that is already resident in device memory.  The workload is the largest configuration,
+C5 (SIREN 2 -> 512 x 6 hidden -> 3 on a 2048 x 2048 grid); other configurations can be selected
+with --workload, and the default run also times C2, C3 and C4 and reports them under
+"other_workloads".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -114,9 +115,11 @@ def cpu_baseline_float(name, max_coords, wavelet_s0=None):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C5")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the extra timings of C2, C3 and C4 that the default run adds to its line")
     ap.add_argument("--variant", default="base", choices=["base", "two_sided", "dynamic", "two_sided_dynamic", "w8a32", "w32a32"],
                     help="base: input-side rotation, static scales (fused kernel where there is one); "
                          "two_sided: weights rotated on both sides, un-rotation in int32; "
@@ -125,12 +128,12 @@ def main() -> int:
                          "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
     ap.add_argument("--activation", default="sine", choices=["sine", "wavelet"],
                     help="sine: the SIREN of the workload; wavelet: the same shapes and weights with the activation "
-                         "cos(omega0 y) exp(-(s0 y)^2) of the second architecture the paper evaluates (runs layer by layer)")
+                         "cos(omega0 y) exp(-(s0 y)^2) of the second architecture the paper evaluates (same fused kernels)")
     ap.add_argument("--wavelet-s0", type=float, default=10.0, help="spread of the wavelet's Gaussian envelope")
     ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
                     help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-coords", type=int, default=131072, help="cap of the CPU-baseline sample")
+    ap.add_argument("--cpu-coords", type=int, default=32768, help="cap of the CPU-baseline sample")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -199,7 +202,8 @@ def main() -> int:
                      "frac": tops / INT8_MFMA_PEAK_TOPS,
                      "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and s0 is None and kernel_sources_sha256() == TRAFFIC_SHA256
                                  else None),
-                     "traffic_unit": "bytes per launch (HBM, measured)",
+                     "traffic_unit": "HBM bytes per launch, stored from the rocprofv3 --pmc runs summarised in "
+                                     "profiles/dhq_fused_hbm_traffic_pmc.md (null when the kernel sources have changed since)",
                      "kernel": ((f"dhq_fused2_kernel<{wl.dims[1]}>" if two_sided else
                                  f"dhq_fused_wide_kernel<512, {2 if s0 is not None else 1}>" if wl.dims[1] == 512 else
                                  f"dhq_fused_kernel<{wl.dims[1]}, {2 if s0 is not None else 1}>")
@@ -281,6 +285,23 @@ def main() -> int:
         res["speedup_vs_w32a32"] = ms_f / ms
         res["psnr_vs_w32a32_db"] = 10.0 * math.log10(peak * peak / mse) if mse > 0 else float("inf")
         ref_model.close()
+    if args.workload == "C5" and args.variant == "base" and s0 is None and args.path == "auto" and not args.no_other_workloads:
+        # the smaller configurations on the same kernels, for the record (not the headline)
+        others = {}
+        for name, steps in (("C2", 400), ("C3", 100), ("C4", 40)):
+            wl2, coords2, W2, b2 = synth.make(name)
+            m2 = dhq.Model(wl2.dims, wl2.omega0, W2, b2, 8, 8)
+            x2 = torch.from_numpy(coords2).to("cuda")
+            out2 = torch.empty((x2.shape[0], wl2.dims[-1]), dtype=torch.float32, device="cuda")
+            m2.calibrate(x2)
+            ms2, _ = time_forward(m2, x2, out2, dhq.DHQ_FUSED, steps, 10)
+            tops2 = wl2.int8_ops_per_coord() * x2.shape[0] / (ms2 * 1e-3) / 1e12
+            others[name] = {"ms_per_step": ms2, "coords_per_s": x2.shape[0] / (ms2 * 1e-3), "int8_tops": tops2,
+                            "frac_int8_mfma_peak": tops2 / INT8_MFMA_PEAK_TOPS, "steps": steps, "coords": x2.shape[0],
+                            "dims": list(wl2.dims)}
+            m2.close()
+            del x2, out2
+        res["other_workloads"] = others
     if s0 is not None:
         res["config"]["workload"] = res["config"]["workload"].replace("SIREN", f"wavelet MLP (s0={s0:g})")
         res["config"]["activation"] = "wavelet"

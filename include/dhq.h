@@ -30,8 +30,8 @@
  *     can be replayed as a HIP graph; with DHQ_DYNAMIC make one eager call of at least the
  *     captured size first, so that the workspace does not grow during capture.
  *   - A model owns device buffers (quantized weights, biases, a workspace for the
- *     layer-by-layer path).  Calls that use the same model concurrently from
- *     several streams or threads are not supported.
+ *     layer-by-layer path) which its forward calls write: use one stream per model.  Calls
+ *     that use the same model concurrently from several streams or threads race.
  *   - Limits: 1 <= n_layers <= 16, every dims[] entry in [1, 512], bits in
  *     {4, 6, 8}.  Anything else is DHQ_EUNSUPPORTED / DHQ_EINVAL.
  */
@@ -144,7 +144,14 @@ int dhq_quantize_weights_mode(const dhq_net_desc *desc, uint32_t mode, const flo
 int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float s0, const float *const *W_host,
                                  const float *const *b_host, dhq_model **out);
 
-/* Static per-layer activation scales s_a (host, n_layers entries, each finite and > 0). */
+/*
+ * Static per-layer activation scales for the quantization module between layers (Sec. 3.3; the
+ * per-tensor scale of the "standard quantizer" of Sec. 3.2, Eq. 1's step size with zero-point 0):
+ * s_a_host is a host array of n_layers entries, each finite and > 0; entry l divides the rotated
+ * input of layer l.  Copied into the model; replaces any scales set or calibrated before.
+ * Returns DHQ_EUNSUPPORTED, and leaves the model's scales as they were, if with these scales the
+ * argument of a layer's sine could leave the range of the hardware sine (see dhq_forward).
+ */
 int dhq_set_act_scales(dhq_model *m, const float *s_a_host);
 
 /*
@@ -157,12 +164,15 @@ int dhq_set_act_scales(dhq_model *m, const float *s_a_host);
  */
 int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, void *stream);
 
-/* Copies the scales out (either pointer may be NULL): host arrays of n_layers floats.
+/* Copies out the per-tensor scales of Sec. 3.2's quantizer (either pointer may be NULL): host
+ * arrays of n_layers floats -- s_w[l] = max|W^[l]| / qmax of the rotated weights (Eq. 4-5 on the
+ * input side), s_a[l] the activation scale of layer l's rotated input (Sec. 3.3).
  * s_a_host is filled with zeros if no activation scales are set yet. */
 int dhq_get_scales(const dhq_model *m, float *s_w_host, float *s_a_host);
 
-/* Copies layer l's quantized, rotated weights out: host, dims[l+1] x Kp int8, row-major
- * (Mp x Kp for a DHQ_ROTATE_BOTH model). */
+/* Copies out layer l's weights after the transform of Eq. 4-5 and the quantizer of Sec. 3.2
+ * (what the MAC array of Sec. 3.3 multiplies with): host, dims[l+1] x Kp int8, row-major, column k
+ * = rotated input feature k (Mp x Kp for a DHQ_ROTATE_BOTH model). */
 int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
 
 /*
@@ -178,12 +188,33 @@ int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
  * coordinates followed by a static DHQ_LAYERWISE forward gives; DHQ_DYNAMIC | DHQ_FUSED gives
  * exactly what a static DHQ_FUSED forward with the scales it measured gives (the two transform
  * the activations with differently rounded fp32 arithmetic, so their scales can differ in the
- * last place).  Dynamic mode keeps all n rows of a layer in device memory: the model's
- * workspace grows to n rows on the first such call (an allocation, and a device
- * synchronisation, whenever n exceeds every earlier dynamic call).
+ * last place).  Dynamic mode keeps all n rows of a layer in device memory: unless
+ * dhq_reserve_dynamic has provided for n rows, the model's workspace grows to n rows in this call
+ * (an allocation, and a device synchronisation, whenever n exceeds every earlier dynamic call and
+ * reservation); this is the only case in which dhq_forward changes the model or does anything but
+ * enqueue kernels.
+ *
+ * Domain of the sine: the hardware sine takes its argument in revolutions and is defined up to
+ * 256 of them.  With static scales dhq_set_act_scales / dhq_calibrate check that no layer's
+ * argument omega0 y / 2 pi can exceed that (bound: qmax_a c max_j sum_k |Wq[j][k]| + max_j |b_j|
+ * omega0 / 2 pi with c = s_a s_w omega0 / 2 pi; for layers whose inputs lie in [-1, 1] also the
+ * norm bound below, whichever is smaller) and refuse the scales otherwise.  With DHQ_DYNAMIC the
+ * scales are not known in advance: every layer after the first is covered by a bound that needs
+ * none (its inputs lie in [-1, 1], so |y_j| <= sqrt(K) (1 + sqrt(Kp) / (2 qmax_a)) s_w ||Wq[j]||_2 + |b_j|),
+ * checked when the model is created, and DHQ_DYNAMIC returns DHQ_EUNSUPPORTED for a model that fails
+ * it; for the first layer the caller keeps |omega0 (W x + b)| / 2 pi of its coordinates below 256.
  */
 int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev,
                 void *stream, uint32_t flags);
+
+/*
+ * Sizes the whole-batch buffers of DHQ_DYNAMIC forwards for up to n rows now (allocates, and
+ * synchronises the device if they have to grow), so that later dhq_forward(... | DHQ_DYNAMIC)
+ * calls with at most n rows only enqueue kernels.  Not needed for static-scale forwards, which
+ * never allocate.  (Sec. 3.3's dynamic quantization module needs a layer's whole input before it
+ * can emit a code; these buffers hold it.)
+ */
+int dhq_reserve_dynamic(dhq_model *m, int64_t n);
 
 /* The scales s_a (host, n_layers floats) that the last DHQ_DYNAMIC forward on this model
  * measured (zeros if there has been none).  Synchronises `stream` (pass the stream that forward ran on). */
@@ -209,7 +240,9 @@ int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_t n, int32_
 int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int64_t n,
                 int32_t *acc_dev, void *stream);
 
-/* 1 if DHQ_FUSED can run this model's shape, else 0 (negative status on error). */
+/* 1 if DHQ_FUSED can run this model's shape -- the whole pipeline of Sec. 3.3 (input layer, linear
+ * layers with the quantization module between them, output layer) in one kernel -- else 0
+ * (negative status on error). */
 int dhq_has_fused(const dhq_model *m);
 
 void dhq_free(dhq_model *m);

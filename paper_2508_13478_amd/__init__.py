@@ -16,7 +16,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdhq.so")
 
-DHQ_OK, DHQ_EINVAL, DHQ_EUNSUPPORTED, DHQ_ENOMEM, DHQ_EHIP, DHQ_ENOSCALE = 0, -1, -2, -3, -4, -5
+DHQ_OK, DHQ_EINVAL, DHQ_EUNSUPPORTED, DHQ_ENOMEM, DHQ_EHIP, DHQ_ENOSCALE, DHQ_ETOOBIG = 0, -1, -2, -3, -4, -5, -6
 DHQ_AUTO, DHQ_LAYERWISE, DHQ_FUSED = 0, 1, 2
 DHQ_DYNAMIC = 4
 DHQ_ROTATE_IN, DHQ_ROTATE_BOTH = 0, 1
@@ -24,7 +24,8 @@ DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 
 # every symbol include/dhq.h declares
 EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
-           "dhq_get_weight_codes", "dhq_forward", "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
+           "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic",
+           "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
            "dhq_free", "dhq_strerror", "dhq_version")
 
 
@@ -67,6 +68,7 @@ def lib() -> C.CDLL:
         L.dhq_get_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.dhq_get_weight_codes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int8)]
         L.dhq_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.dhq_reserve_dynamic.argtypes = [C.c_void_p, C.c_int64]
         L.dhq_forward_debug.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p]
         L.dhq_gemm_i8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -178,6 +180,10 @@ def dhq_forward(model: int, coords, out, stream=None, flags: int = DHQ_AUTO) -> 
     """coords: (n, dims[0]) fp32 device tensor; out: (n, dims[-1]) fp32 device tensor."""
     _ok(lib().dhq_forward(model, _dptr(coords), coords.shape[0], _dptr(out), _stream_ptr(stream), flags),
         "dhq_forward")
+
+
+def dhq_reserve_dynamic(model: int, n: int) -> None:
+    _ok(lib().dhq_reserve_dynamic(model, int(n)), "dhq_reserve_dynamic")
 
 
 def dhq_forward_debug(model: int, x, layer: int, codes=None, acc=None, act=None, stream=None) -> None:

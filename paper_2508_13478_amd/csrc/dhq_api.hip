@@ -15,7 +15,39 @@
 
 #include "dhq_internal.h"
 
-#define DHQ_VERSION_NUM 100
+#define DHQ_VERSION_NUM 200
+#define DHQ_SINE_MAX_REV 256.0  // the hardware sine and cosine are defined up to this many revolutions
+
+// What dhq_lds_limit_once has already set: (kernel, device) -> bytes.  A fixed table searched
+// linearly (the library has a few dozen kernel instances); when it is full the attribute is
+// simply set again on every call.  Entries are only ever added, by whole-word stores, so
+// concurrent callers at worst set an attribute twice.
+#define DHQ_LDS_TABLE 256
+static struct { const void *kern; int device; int bytes; } lds_table[DHQ_LDS_TABLE];
+static int lds_table_used = 0;
+
+hipError_t dhq_lds_limit_once_impl(const void *kern, size_t bytes, int device)
+{
+    const int used = lds_table_used;
+    int slot = -1;
+    for (int i = 0; i < used; ++i)
+        if (lds_table[i].kern == kern && lds_table[i].device == device) {
+            if ((size_t)lds_table[i].bytes >= bytes) return hipSuccess;
+            slot = i;
+            break;
+        }
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    if (slot < 0 && used < DHQ_LDS_TABLE) {
+        slot = used;
+        lds_table[slot].kern = kern;
+        lds_table[slot].device = device;
+        lds_table[slot].bytes = 0;
+        lds_table_used = used + 1;
+    }
+    if (slot >= 0) lds_table[slot].bytes = (int)bytes;
+    return hipSuccess;
+}
 
 static int next_pow2(int k)
 {
@@ -155,23 +187,37 @@ static int quantize_layer_host(dhq_model *m, int l, const float *W, const float 
         if (q < -qmax_w) q = -qmax_w;
         Ly.wq_host[i] = (int8_t)q;
     }
-    if (m->rot_out) {
-        // The un-rotation z = acc' H_Mp runs in int32.  z[j] = sum_k q[k] U[j][k] with U = H_Mp Wq, so
-        // |z[j]| <= qmax_a sum_k |U[j][k]|: refuse weights for which that bound leaves int32.
-        std::vector<int64_t> U(Ly.wq_host.begin(), Ly.wq_host.end());
+    // U = the integer matrix whose product with the codes is what the epilogue scales: Wq itself, or
+    // in the two-sided variant H_Mp Wq (the un-rotation z = acc' H_Mp runs in int32 and
+    // z[j] = sum_k q[k] U[j][k]).
+    std::vector<int64_t> U(Ly.wq_host.begin(), Ly.wq_host.end());
+    if (m->rot_out)
         for (int k = 0; k < Kp; ++k) fwht_strided(U.data() + k, Mg, (size_t)Kp);
-        for (int j = 0; j < Mg; ++j) {
-            int64_t sum = 0;
-            for (int k = 0; k < Kp; ++k) sum += U[(size_t)j * Kp + k] < 0 ? -U[(size_t)j * Kp + k] : U[(size_t)j * Kp + k];
-            if (sum * (int64_t)m->qmax_a > (int64_t)INT32_MAX) return DHQ_EUNSUPPORTED;
+    Ly.sum_abs_max = 0;
+    Ly.norm2_max = 0.0;
+    for (int j = 0; j < Mg; ++j) {
+        int64_t sum = 0;
+        double sq = 0.0;
+        for (int k = 0; k < Kp; ++k) {
+            const int64_t u = U[(size_t)j * Kp + k];
+            sum += u < 0 ? -u : u;
+            sq += (double)u * (double)u;
+        }
+        // |z[j]| <= qmax_a sum_k |U[j][k]|: refuse weights for which that bound leaves int32
+        if (m->rot_out && sum * (int64_t)m->qmax_a > (int64_t)INT32_MAX) return DHQ_EUNSUPPORTED;
+        if (j < M) {  // padded outputs are dropped before the activation
+            if (sum > Ly.sum_abs_max) Ly.sum_abs_max = sum;
+            if (sqrt(sq) > Ly.norm2_max) Ly.norm2_max = sqrt(sq);
         }
     }
     const double two_pi = 6.283185307179586476925286766559;
     Ly.bias_host.assign(b, b + M);
     Ly.bias_rev_host.resize(M);
+    Ly.bias_rev_abs_max = 0.0;
     for (int j = 0; j < M; ++j) {
         if (!isfinite(b[j])) return DHQ_EINVAL;
         Ly.bias_rev_host[j] = (float)((double)b[j] * (double)m->omega0 / two_pi);
+        if (fabs((double)Ly.bias_rev_host[j]) > Ly.bias_rev_abs_max) Ly.bias_rev_abs_max = fabs((double)Ly.bias_rev_host[j]);
     }
     if (M > m->max_dim) m->max_dim = M;
     if (K > m->max_dim) m->max_dim = K;
@@ -203,6 +249,41 @@ static int upload_layer(dhq_layer &Ly)
     if (rc == DHQ_OK) rc = upload(&Ly.bias_dev, Ly.bias_host.data(), (size_t)Ly.M);
     if (rc == DHQ_OK) rc = upload(&Ly.bias_rev_dev, Ly.bias_rev_host.data(), (size_t)Ly.M);
     return rc;
+}
+
+// The hardware sine and cosine take revolutions and are defined for |t| <= 256.  The layer-by-layer
+// kernels reduce the argument first (they are bound by memory traffic, the extra instruction is
+// free); the whole-network kernels, which are bound by vector instruction issue, do not, and run
+// only when the argument provably stays in range.  Upper bounds of
+// |t| = |acc c1 + b omega0 / 2 pi| of layer l (one that ends in an activation):
+//   by magnitudes: |acc| <= qmax_a max_j sum_k |U[j][k]|;
+//   by norms, for layers whose inputs lie in [-1, 1] (every layer after the first): the rotation is
+//   orthonormal, so ||x^|| <= sqrt(K); rounding adds at most s_a sqrt(Kp) / 2 to the norm of the
+//   de-quantized codes and clamping only shortens it, hence s_a |acc| <= (sqrt(K) + s_a sqrt(Kp) / 2) ||U[j]||.
+static double sine_arg_bound(const dhq_model *m, int l, double s_a)
+{
+    const dhq_layer &Ly = m->layer[l];
+    const double c_over = dhq_c1_over_sa(m, l);
+    double bound = s_a * c_over * (double)m->qmax_a * (double)Ly.sum_abs_max;
+    if (l >= 1) {
+        const double by_norm = c_over * (sqrt((double)Ly.K) + s_a * sqrt((double)Ly.Kp) / 2.0) * Ly.norm2_max;
+        if (by_norm < bound) bound = by_norm;
+    }
+    return bound + Ly.bias_rev_abs_max;
+}
+// Static scales: every layer with an activation.
+static bool sine_range_ok_static(const dhq_model *m)
+{
+    for (int l = 0; l < m->n_layers - 1; ++l)
+        if (!(sine_arg_bound(m, l, (double)m->layer[l].s_a) <= DHQ_SINE_MAX_REV)) return false;
+    return true;
+}
+// Scales measured on line: s_a = max|x^| / qmax_a <= sqrt(K) / qmax_a for the layers after the first.
+static bool sine_range_ok_dynamic(const dhq_model *m)
+{
+    for (int l = 1; l < m->n_layers - 1; ++l)
+        if (!(sine_arg_bound(m, l, sqrt((double)m->layer[l].K) / (double)m->qmax_a) <= DHQ_SINE_MAX_REV)) return false;
+    return true;
 }
 
 // The offline step behind every dhq_quantize_weights* entry point; act_kind follows every layer but the last.
@@ -242,6 +323,7 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
     int rc = DHQ_OK;
     // everything that can be refused is refused before the device is touched
     for (int l = 0; l < L && rc == DHQ_OK; ++l) rc = quantize_layer_host(m, l, W_host[l], b_host[l]);
+    if (rc == DHQ_OK) m->dyn_sine_ok = sine_range_ok_dynamic(m);
     if (rc == DHQ_OK && hipGetDevice(&m->device) != hipSuccess) rc = DHQ_EHIP;
     if (rc == DHQ_OK && precision != DHQ_W8A8) {
         // floating-point activations: the network runs on the original weights (W32A32) or on the
@@ -261,6 +343,17 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
                 for (int k = 0; k < Ly.Kp; ++k) row[k] = (double)Ly.wq_host[(size_t)r * Ly.Kp + k] * (double)Ly.s_w;
                 fwht_f64(row.data(), Ly.Kp);
                 for (int k = 0; k < Ly.K; ++k) Wf[l][(size_t)r * Ly.K + k] = (float)(row[k] * inv);
+            }
+        }
+        // the sine's argument in revolutions, layers after the first (inputs in [-1, 1]):
+        // |t_j| <= (sum_k |W[j][k]| + |b_j|) omega0 / 2 pi; beyond the hardware sine's range only the
+        // layer-by-layer kernels (which reduce the argument) may run
+        for (int l = 1; l < L - 1; ++l) {
+            const dhq_layer &Ly = m->layer[l];
+            for (int r = 0; r < Ly.M; ++r) {
+                double sum = fabs((double)bf[l][r]);
+                for (int k = 0; k < Ly.K; ++k) sum += fabs((double)Wf[l][(size_t)r * Ly.K + k]);
+                if (!(sum * fabs((double)m->omega0) / 6.283185307179586476925286766559 <= DHQ_SINE_MAX_REV)) m->fused_sine_ok = false;
             }
         }
         rc = dhq_float_create(m->dims, L, m->omega0, dhq_hidden_act(m), Wf, bf, m->device, &m->flt);
@@ -321,6 +414,7 @@ extern "C" int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t m
 
 static int update_fused_scales(dhq_model *m)
 {
+    m->fused_sine_ok = sine_range_ok_static(m);
     int rc = dhq_fused_update_scales(m, m->fused);
     if (rc == DHQ_OK) rc = dhq_wide_update_scales(m, m->wide);
     if (rc == DHQ_OK) rc = dhq_fused2_update_scales(m, m->fused2);
@@ -360,8 +454,8 @@ extern "C" int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *W
 extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
-    if (m->flt) return dhq_float_has_fused(m->flt) ? 1 : 0;
-    return (m->fused || m->wide || m->fused2) ? 1 : 0;
+    if (m->flt) return (dhq_float_has_fused(m->flt) && m->fused_sine_ok) ? 1 : 0;
+    return ((m->fused || m->wide || m->fused2) && (!m->have_scales || m->fused_sine_ok)) ? 1 : 0;
 }
 
 // Per-layer constant of the quantizer kernel.
@@ -447,7 +541,33 @@ extern "C" int dhq_calibrate(dhq_model *m, const float *coords_dev, int64_t n, v
     return update_fused_scales(m);
 }
 
-// Whole-batch buffers of the dynamic mode, grown when a call brings more rows than any before.
+// Buffers a dynamic forward works in: whole-batch activations (transformed activations for the
+// per-layer fused kernels), codes, the two-sided variant's rotated accumulators, two sets of
+// per-workgroup maxima, and the per-layer constants {quantizer multiplier, epilogue multiplier, s_a}.
+struct dyn_ws {
+    float *act0, *act1;
+    int8_t *codes;
+    int32_t *acc;
+    float *partial;  // 2 x DHQ_ABSMAX_PARTIALS floats
+    float *params;   // DHQ_MAX_LAYERS x 3
+};
+
+// Bytes of each whole-batch buffer for n rows.
+struct dyn_sizes {
+    size_t act, codes, acc;
+};
+static dyn_sizes dyn_buffer_sizes(const dhq_model *m, int64_t n)
+{
+    // the per-layer fused kernels store whole workgroup tiles
+    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (m->fused2 ? dhq_fused2_dynamic_rows(n) : (size_t)n);
+    dyn_sizes z;
+    z.act = sizeof(float) * rows * m->max_dim;
+    z.codes = (size_t)n * m->max_kp;
+    z.acc = m->rot_out ? sizeof(int32_t) * (size_t)n * m->max_mg : 0;
+    return z;
+}
+
+// Whole-batch buffers of the dynamic mode in the model, grown when a call brings more rows than any before.
 static int ensure_dyn_workspace(dhq_model *m, int64_t n)
 {
     if (n <= m->dyn_rows) return DHQ_OK;
@@ -460,15 +580,20 @@ static int ensure_dyn_workspace(dhq_model *m, int64_t n)
     m->dyn_codes = nullptr;
     m->dyn_acc = nullptr;
     m->dyn_rows = 0;
-    // the per-layer fused kernels store whole workgroup tiles
-    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (m->fused2 ? dhq_fused2_dynamic_rows(n) : (size_t)n);
-    const size_t act_bytes = sizeof(float) * rows * m->max_dim;
-    if (hipMalloc((void **)&m->dyn_act0, act_bytes) != hipSuccess) return DHQ_ENOMEM;
-    if (hipMalloc((void **)&m->dyn_act1, act_bytes) != hipSuccess) return DHQ_ENOMEM;
-    if (hipMalloc((void **)&m->dyn_codes, (size_t)n * m->max_kp) != hipSuccess) return DHQ_ENOMEM;
-    if (m->rot_out && hipMalloc((void **)&m->dyn_acc, sizeof(int32_t) * (size_t)n * m->max_mg) != hipSuccess) return DHQ_ENOMEM;
+    const dyn_sizes z = dyn_buffer_sizes(m, n);
+    if (hipMalloc((void **)&m->dyn_act0, z.act) != hipSuccess) return DHQ_ENOMEM;
+    if (hipMalloc((void **)&m->dyn_act1, z.act) != hipSuccess) return DHQ_ENOMEM;
+    if (hipMalloc((void **)&m->dyn_codes, z.codes) != hipSuccess) return DHQ_ENOMEM;
+    if (z.acc && hipMalloc((void **)&m->dyn_acc, z.acc) != hipSuccess) return DHQ_ENOMEM;
     m->dyn_rows = n;
     return DHQ_OK;
+}
+
+extern "C" int dhq_reserve_dynamic(dhq_model *m, int64_t n)
+{
+    if (!m || n < 0) return DHQ_EINVAL;
+    if (m->flt) return DHQ_EUNSUPPORTED;
+    return ensure_dyn_workspace(m, n);
 }
 
 // The dynamic quantization module between layers (Sec. 3.3) taken literally: every layer first
@@ -479,37 +604,46 @@ static int ensure_dyn_workspace(dhq_model *m, int64_t n)
 // Two realisations: layer by layer (absmax pass, quantizer, GEMM: three launches per layer, any
 // shape), or -- where the whole-network fused kernel exists -- one launch per layer that keeps
 // the layer's arithmetic in registers and passes only the transformed activations through
-// device memory (dhq_fused_dynamic_launch).
-static int forward_dynamic(dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, bool per_layer_fused,
-                           hipStream_t st)
+// device memory (dhq_fused_dynamic_launch).  Enqueues kernels only.
+static int forward_dynamic(const dhq_model *m, const dyn_ws &ws, const float *coords_dev, int64_t n, float *out_dev,
+                           bool per_layer_fused, hipStream_t st)
 {
-    int rc = ensure_dyn_workspace(m, n);
-    if (rc != DHQ_OK) return rc;
     const int L = m->n_layers;
-    float *partial = reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS);
     if (per_layer_fused) {
         const hipError_t e =
-            m->fused2 ? dhq_fused2_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st)
-                      : dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, m->dyn_act0, m->dyn_act1, partial, m->dyn_params, st);
+            m->fused2 ? dhq_fused2_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st)
+                      : dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st);
         return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
     }
     const float *cur = coords_dev;
-    float *bufs[2] = {m->dyn_act0, m->dyn_act1};
+    float *bufs[2] = {ws.act0, ws.act1};
     int which = 0;
     for (int l = 0; l < L; ++l) {
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == L - 1);
-        float *dyn = m->dyn_params + 3 * l;
+        float *dyn = ws.params + 3 * l;
         // pass 1 leaves one maximum of |x^| per workgroup; pass 2 folds them, quantizes and stores the constants
         int count = 0;
-        if (dhq_launch_wht_absmax_partials(cur, n, Ly.K, Ly.Kp, partial, &count, st) != hipSuccess) return DHQ_EHIP;
-        const dhq_wht_fold fold = {partial, count, dhq_c1_over_sa(m, l), dyn};
-        if (dhq_launch_wht_quant(cur, n, Ly.K, Ly.Kp, 0.0f, m->qmax_a, m->dyn_codes, &fold, st) != hipSuccess) return DHQ_EHIP;
+        if (dhq_launch_wht_absmax_partials(cur, n, Ly.K, Ly.Kp, ws.partial, &count, st) != hipSuccess) return DHQ_EHIP;
+        const dhq_wht_fold fold = {ws.partial, count, dhq_c1_over_sa(m, l), dyn};
+        if (dhq_launch_wht_quant(cur, n, Ly.K, Ly.Kp, 0.0f, m->qmax_a, ws.codes, &fold, st) != hipSuccess) return DHQ_EHIP;
         float *dst = last ? out_dev : bufs[which];
-        if (gemm_epilogue(m, l, m->dyn_codes, n, m->dyn_acc, dyn, dst, st) != hipSuccess) return DHQ_EHIP;
+        if (gemm_epilogue(m, l, ws.codes, n, ws.acc, dyn, dst, st) != hipSuccess) return DHQ_EHIP;
         cur = dst;
         which ^= 1;
     }
+    return DHQ_OK;
+}
+
+// Argument checks shared by the two entry points that run a dynamic forward.
+static int check_dynamic_call(const dhq_model *m, int64_t n, uint32_t path, bool *per_layer_fused)
+{
+    if (!m || n < 0) return DHQ_EINVAL;
+    if (path == 3u) return DHQ_EINVAL;
+    const bool dyn_fused_ok = (m->fused || m->fused2) && m->dyn_sine_ok;  // per-layer fused kernels of the dynamic mode
+    if (m->flt) return DHQ_EUNSUPPORTED;
+    if (path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
+    *per_layer_fused = path != DHQ_LAYERWISE && dyn_fused_ok;
     return DHQ_OK;
 }
 
@@ -520,28 +654,44 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     const uint32_t path = flags & 3u;
     const bool dynamic = (flags & DHQ_DYNAMIC) != 0;
     if ((flags & ~(3u | DHQ_DYNAMIC)) != 0 || path == 3u) return DHQ_EINVAL;
-    const bool dyn_fused_ok = m->fused || m->fused2;  // per-layer fused kernels of the dynamic mode
-    if (dynamic && path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
-    if (m->flt && (dynamic || (path == DHQ_FUSED && !dhq_float_has_fused(m->flt)))) return DHQ_EUNSUPPORTED;
-    if (n == 0) return DHQ_OK;
-    if (!coords_dev || !out_dev) return DHQ_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     if (m->flt) {
-        const hipError_t e = (path != DHQ_LAYERWISE && dhq_float_has_fused(m->flt))
-                                 ? dhq_float_launch(m->flt, coords_dev, n, out_dev, st)
-                                 : dhq_float_launch_layerwise(m->flt, coords_dev, n, out_dev, st);
+        // the whole-network fp32 kernel runs only where the sine's argument provably stays in range
+        const bool fused_ok = dhq_float_has_fused(m->flt) && m->fused_sine_ok;
+        if (dynamic || (path == DHQ_FUSED && !fused_ok)) return DHQ_EUNSUPPORTED;
+        if (n == 0) return DHQ_OK;
+        if (!coords_dev || !out_dev) return DHQ_EINVAL;
+        const hipError_t e = (path != DHQ_LAYERWISE && fused_ok) ? dhq_float_launch(m->flt, coords_dev, n, out_dev, st)
+                                                                 : dhq_float_launch_layerwise(m->flt, coords_dev, n, out_dev, st);
         return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
     }
-    // the workspace belongs to the model and is the only thing a forward call changes in it
-    if (dynamic) return forward_dynamic(const_cast<dhq_model *>(m), coords_dev, n, out_dev, path != DHQ_LAYERWISE && dyn_fused_ok, st);
+    if (dynamic) {
+        bool per_layer_fused = false;
+        int rc = check_dynamic_call(m, n, path, &per_layer_fused);
+        if (rc != DHQ_OK) return rc;
+        if (n == 0) return DHQ_OK;
+        if (!coords_dev || !out_dev) return DHQ_EINVAL;
+        // The whole-batch buffers are the one thing a forward call may change in the model: they grow
+        // here when this call brings more rows than dhq_reserve_dynamic or any earlier call provided for.
+        rc = ensure_dyn_workspace(const_cast<dhq_model *>(m), n);
+        if (rc != DHQ_OK) return rc;
+        const dyn_ws ws = {m->dyn_act0, m->dyn_act1, m->dyn_codes, m->dyn_acc,
+                           reinterpret_cast<float *>(m->dyn_absmax + DHQ_MAX_LAYERS), m->dyn_params};
+        return forward_dynamic(m, ws, coords_dev, n, out_dev, per_layer_fused, st);
+    }
+    // static scales; a whole-network kernel runs only where the sine's argument provably stays in range
+    const bool fused_ok = (m->fused || m->wide || m->fused2) && m->fused_sine_ok;
+    if (path == DHQ_FUSED && !(m->fused || m->wide || m->fused2)) return DHQ_EUNSUPPORTED;
+    if (n == 0) return DHQ_OK;
+    if (!coords_dev || !out_dev) return DHQ_EINVAL;
     if (!m->have_scales) return DHQ_ENOSCALE;
-    if (path == DHQ_FUSED && !m->fused && !m->wide && !m->fused2) return DHQ_EUNSUPPORTED;
-    if (path != DHQ_LAYERWISE && m->fused2)
-        return dhq_fused2_launch(m->fused2, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
-    if (path != DHQ_LAYERWISE && m->fused)
-        return dhq_fused_launch(m, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
-    if (path != DHQ_LAYERWISE && m->wide)
-        return dhq_wide_launch(m->wide, coords_dev, n, out_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    if (path == DHQ_FUSED && !fused_ok) return DHQ_EUNSUPPORTED;
+    if (path != DHQ_LAYERWISE && fused_ok) {
+        const hipError_t e = m->fused2 ? dhq_fused2_launch(m->fused2, coords_dev, n, out_dev, st)
+                             : m->fused ? dhq_fused_launch(m, coords_dev, n, out_dev, st)
+                                        : dhq_wide_launch(m->wide, coords_dev, n, out_dev, st);
+        return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
+    }
     const int K0 = m->dims[0], Mo = m->dims[m->n_layers];
     for (int64_t off = 0; off < n; off += DHQ_CHUNK) {
         const int64_t rows = (n - off) < DHQ_CHUNK ? (n - off) : DHQ_CHUNK;

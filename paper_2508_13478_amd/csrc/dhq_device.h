@@ -33,7 +33,7 @@ __device__ __forceinline__ unsigned dhq_pack4(int a, int b, int c, int d)
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// sin(2 pi t): the hardware sine takes its argument in revolutions (valid for |t| <= 256).
+// sin(2 pi t): the hardware sine takes its argument in revolutions (defined for |t| <= 256).
 __device__ __forceinline__ float dhq_sin_rev(float t)
 {
     return __builtin_amdgcn_sinf(t);
@@ -62,13 +62,27 @@ __device__ __forceinline__ float dhq_activate_rev(float t, dhq_act act)
     return dhq_sin_rev(t);
 }
 
+// The same for any finite argument: the hardware sine and cosine are defined up to 256
+// revolutions, so the fractional part is taken first (one more instruction; the kernels that
+// are bound by memory traffic use this form, the whole-network kernels the one above on
+// arguments the host has bounded).  The wavelet's envelope needs the whole argument.
+__device__ __forceinline__ float dhq_activate_rev_any(float t, dhq_act act)
+{
+    const float f = __builtin_amdgcn_fractf(t);
+    if (act.kind == DHQ_ACT_KIND_WAVELET) {
+        const float g = t * act.c2;
+        return __builtin_amdgcn_cosf(f) * __builtin_amdgcn_exp2f(-(g * g));
+    }
+    return __builtin_amdgcn_sinf(f);
+}
+
 // Dequantize + bias (+ activation), Sec. 3.3.  For layers with an activation c1 and bias are
 // pre-multiplied by omega0 / (2 pi) on the host, so the fused multiply-add yields the argument in
 // revolutions.
 __device__ __forceinline__ float dhq_epilogue(int acc, float c1, float bias, dhq_act act)
 {
     float y = __builtin_fmaf((float)acc, c1, bias);
-    return act.kind == DHQ_ACT_KIND_NONE ? y : dhq_activate_rev(y, act);
+    return act.kind == DHQ_ACT_KIND_NONE ? y : dhq_activate_rev_any(y, act);
 }
 
 // From max |un-normalised x^| of a layer input to the constants of the dynamic mode, in the same

@@ -363,7 +363,7 @@ __global__ __launch_bounds__(64 * FLW_WAVES) void float_layer_kernel(const float
     const bool full = (nrows == 32);
     const unsigned loff = (unsigned)(4 * h * M + c);
     auto epi = [&](float a, float bf) {
-        return ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev(__builtin_fmaf(a, rev, bf), dhq_act{ACT, c2}) : a + bf;
+        return ACT != DHQ_ACT_KIND_NONE ? dhq_activate_rev_any(__builtin_fmaf(a, rev, bf), dhq_act{ACT, c2}) : a + bf;
     };
 #pragma unroll
     for (int t = 0; t < NTT; ++t) {

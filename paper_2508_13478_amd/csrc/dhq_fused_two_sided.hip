@@ -66,6 +66,7 @@ struct dhq_fused2_plan {
     f2_args args;
     size_t lds_bytes = 0;
     int n_cu = 0;
+    int device = 0;
 };
 
 // ----------------------------------------------------------------------------- device code
@@ -527,6 +528,7 @@ int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan_out)
         return DHQ_EHIP;
     }
     P->n_cu = prop.multiProcessorCount;
+    P->device = m->device;
     *plan_out = P;
     return DHQ_OK;
 }
@@ -553,7 +555,7 @@ template <int NF, int ACTK>
 static hipError_t fused2_launch_act(const dhq_fused2_plan *P, const f2_args &a, unsigned grid, hipStream_t st)
 {
     auto kern = dhq_fused2_kernel<NF, ACTK>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
+    hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
     if (e != hipSuccess) return e;
     kern<<<grid, F2_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();
@@ -588,23 +590,23 @@ hipError_t dhq_fused2_launch(const dhq_fused2_plan *P, const float *coords, int6
 size_t dhq_fused2_dynamic_rows(int64_t n) { return (size_t)((n + F2_TILE - 1) / F2_TILE) * F2_TILE; }
 
 template <int NF, int MODE, int ACTK>
-static hipError_t f2l_launch_t(const f2l_args &a, unsigned grid, hipStream_t st)
+static hipError_t f2l_launch_t(const f2l_args &a, unsigned grid, int device, hipStream_t st)
 {
     auto kern = dhq_fused2_layer_kernel<NF, MODE, ACTK>;
     const size_t lds = (size_t)a.chunks * 1024;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = dhq_lds_limit_once(kern, lds, device);
     if (e != hipSuccess) return e;
     kern<<<grid, F2_THREADS, lds, st>>>(a);
     return hipGetLastError();
 }
 template <int NF>
-static hipError_t f2l_launch_mode(int mode, int act_kind, const f2l_args &a, unsigned grid, hipStream_t st)
+static hipError_t f2l_launch_mode(int mode, int act_kind, const f2l_args &a, unsigned grid, int device, hipStream_t st)
 {
     const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
     switch (mode) {
-        case 0: return wav ? f2l_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET>(a, grid, st) : f2l_launch_t<NF, 0, DHQ_ACT_KIND_SINE>(a, grid, st);
-        case 1: return wav ? f2l_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET>(a, grid, st) : f2l_launch_t<NF, 1, DHQ_ACT_KIND_SINE>(a, grid, st);
-        default: return f2l_launch_t<NF, 2, DHQ_ACT_KIND_NONE>(a, grid, st);  // the output layer has no activation
+        case 0: return wav ? f2l_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : f2l_launch_t<NF, 0, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+        case 1: return wav ? f2l_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : f2l_launch_t<NF, 1, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+        default: return f2l_launch_t<NF, 2, DHQ_ACT_KIND_NONE>(a, grid, device, st);  // the output layer has no activation
     }
 }
 
@@ -643,10 +645,10 @@ hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, in
         a.c2 = P->args.c2;
         const int mode = (l == 0) ? 0 : (l == L - 1 ? 2 : 1);
         switch (P->nf) {
-            case 32: e = f2l_launch_mode<32>(mode, m->act_kind, a, grid, st); break;
-            case 64: e = f2l_launch_mode<64>(mode, m->act_kind, a, grid, st); break;
-            case 128: e = f2l_launch_mode<128>(mode, m->act_kind, a, grid, st); break;
-            case 256: e = f2l_launch_mode<256>(mode, m->act_kind, a, grid, st); break;
+            case 32: e = f2l_launch_mode<32>(mode, m->act_kind, a, grid, P->device, st); break;
+            case 64: e = f2l_launch_mode<64>(mode, m->act_kind, a, grid, P->device, st); break;
+            case 128: e = f2l_launch_mode<128>(mode, m->act_kind, a, grid, P->device, st); break;
+            case 256: e = f2l_launch_mode<256>(mode, m->act_kind, a, grid, P->device, st); break;
             default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;

@@ -59,10 +59,7 @@ struct dhq_wide_plan {
     wide_args args;
     size_t lds_bytes = 0;
     int n_cu = 0;
-    // per layer and tile: byte offsets of the tile's 32 biases in the blob.  A hidden layer's
-    // chunk also carries the biases of the tile before its first one (that tile's
-    // accumulators are drained while this chunk is resident), hence up to two places.
-    std::vector<uint32_t> bias_off, bias_off_dup;
+    int device = 0;
 };
 
 // ----------------------------------------------------------------------------- device code
@@ -640,8 +637,10 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
     if (!P) return DHQ_ENOMEM;
     P->nf = nf;
     memset(&P->args, 0, sizeof(P->args));
-    P->bias_off.assign((size_t)L * NT, 0);
-    P->bias_off_dup.assign((size_t)L * NT, 0);
+    // per layer and tile: byte offsets of the tile's 32 biases in the blob.  A hidden layer's
+    // chunk also carries the biases of the tile before its first one (that tile's
+    // accumulators are drained while this chunk is resident), hence up to two places.
+    std::vector<uint32_t> bias_off((size_t)L * NT, 0), bias_off_dup((size_t)L * NT, 0);
 
     std::vector<unsigned char> blob;
     int n_chunks = 0;
@@ -661,8 +660,8 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
             int8_t *frag = reinterpret_cast<int8_t *>(blob.data() + off);
             for (int tl = 0; tl < ch; ++tl) {
                 const int T = T0 + tl;
-                P->bias_off[(size_t)l * NT + T] = (uint32_t)(off + frag_bytes + (size_t)(hidden ? tl + 1 : tl) * 128);
-                if (hidden && tl == 0 && T > 0) P->bias_off_dup[(size_t)l * NT + T - 1] = (uint32_t)(off + frag_bytes);
+                bias_off[(size_t)l * NT + T] = (uint32_t)(off + frag_bytes + (size_t)(hidden ? tl + 1 : tl) * 128);
+                if (hidden && tl == 0 && T > 0) bias_off_dup[(size_t)l * NT + T - 1] = (uint32_t)(off + frag_bytes);
                 for (int kb = 0; kb < Kb; ++kb)
                     for (int ln = 0; ln < 64; ++ln) {
                         const int row = 32 * T + (ln & 31), u = ln >> 5;
@@ -687,6 +686,24 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
     P->args.n_chunks = n_chunks;
     // the in-kernel copy always fetches 65 KiB from a chunk's start (see wide_copy_load)
     blob.resize(blob.size() + (size_t)(WIDE_CH * NKB + 1) * 1024, 0);
+    // the biases (they do not depend on the activation scales): [g][h][e] within a tile, in
+    // revolutions for the layers that end in an activation
+    for (int l = 0; l < L; ++l) {
+        const dhq_layer &Ly = m->layer[l];
+        const bool last = (l == L - 1);
+        const std::vector<float> &src = last ? Ly.bias_host : Ly.bias_rev_host;
+        const int Mt = last ? 1 : NT;
+        for (int T = 0; T < Mt; ++T) {
+            float blk[32] = {0};
+            for (int i = 0; i < 32; ++i) {
+                const int f = 32 * T + i;
+                if (f < Ly.M) blk[bias_slot(i)] = src[f];
+            }
+            memcpy(blob.data() + bias_off[(size_t)l * NT + T], blk, sizeof(blk));
+            const uint32_t dup = bias_off_dup[(size_t)l * NT + T];
+            if (dup) memcpy(blob.data() + dup, blk, sizeof(blk));
+        }
+    }
     P->blob_bytes = blob.size();
     if (hipMalloc((void **)&P->blob_dev, P->blob_bytes) != hipSuccess) {
         delete P;
@@ -713,6 +730,7 @@ int dhq_wide_create(const dhq_model *m, dhq_wide_plan **plan_out)
         return DHQ_EHIP;
     }
     P->n_cu = prop.multiProcessorCount;
+    P->device = m->device;
     *plan_out = P;
     return DHQ_OK;
 }
@@ -728,25 +746,10 @@ int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *P)
 {
     if (!P) return DHQ_OK;
     const int L = m->n_layers;
-    const int NT = P->nf / 32;
     for (int l = 0; l < L; ++l) {
         const dhq_layer &Ly = m->layer[l];
-        const bool last = (l == L - 1);
         P->args.c1[l] = dhq_c1(m, l);
         P->args.inv_in[l] = (float)(1.0 / ((double)Ly.s_a * sqrt((double)Ly.Kp)));
-        const std::vector<float> &src = last ? Ly.bias_host : Ly.bias_rev_host;
-        const int Mt = last ? 1 : NT;
-        for (int T = 0; T < Mt; ++T) {
-            float blk[32] = {0};
-            for (int i = 0; i < 32; ++i) {
-                const int f = 32 * T + i;
-                if (f < Ly.M) blk[bias_slot(i)] = src[f];
-            }
-            if (hipMemcpy(P->blob_dev + P->bias_off[(size_t)l * NT + T], blk, sizeof(blk), hipMemcpyHostToDevice) != hipSuccess)
-                return DHQ_EHIP;
-            const uint32_t dup = P->bias_off_dup[(size_t)l * NT + T];
-            if (dup && hipMemcpy(P->blob_dev + dup, blk, sizeof(blk), hipMemcpyHostToDevice) != hipSuccess) return DHQ_EHIP;
-        }
     }
     return DHQ_OK;
 }
@@ -763,7 +766,7 @@ hipError_t dhq_wide_launch(const dhq_wide_plan *P, const float *coords, int64_t 
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
     auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_wide_kernel<512, DHQ_ACT_KIND_WAVELET>
                                                       : dhq_fused_wide_kernel<512, DHQ_ACT_KIND_SINE>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P->lds_bytes);
+    hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
     if (e != hipSuccess) return e;
     kern<<<grid, WIDE_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();

@@ -14,6 +14,7 @@
 #define DHQ_MAX_LAYERS 16
 #define DHQ_MAX_DIM 512
 #define DHQ_CHUNK 65536  // rows per pass of the layer-by-layer path (workspace size)
+#define DHQ_MAX_DEVICES 64
 
 // One linear layer as the kernels see it.
 struct dhq_layer {
@@ -32,6 +33,11 @@ struct dhq_layer {
     std::vector<int8_t> wq_host;  // copy of the codes for dhq_get_weight_codes
     std::vector<float> bias_host;      // M
     std::vector<float> bias_rev_host;  // M
+    // for the range check of the sine's argument: over the outputs j < M of the integer matrix U the
+    // epilogue's input is a product with (Wq, or H_Mp Wq when two-sided)
+    int64_t sum_abs_max = 0;        // max_j sum_k |U[j][k]|
+    double norm2_max = 0.0;         // max_j ||U[j]||_2
+    double bias_rev_abs_max = 0.0;  // max_j |bias_rev[j]|
 };
 
 struct dhq_fused_plan;  // defined in dhq_fused.hip
@@ -49,6 +55,8 @@ struct dhq_model {
     int qmax_a = 127;
     bool have_scales = false;
     bool rot_out = false;  // two-sided variant: weights also rotated over the output features
+    bool fused_sine_ok = true;  // with the current static scales (or fp32 weights) no sine argument can leave the hardware's range
+    bool dyn_sine_ok = true;  // scales measured on line cannot push a sine argument out of the hardware's range
     uint32_t precision = 0;  // DHQ_W8A8 / DHQ_W8A32 / DHQ_W32A32
     dhq_layer layer[DHQ_MAX_LAYERS];
     // workspace of the layer-by-layer path: two activation buffers, one code buffer
@@ -71,6 +79,16 @@ struct dhq_model {
     dhq_fused2_plan *fused2 = nullptr;  // two-sided variant, hidden width 32..256, fan-out <= 4
     int device = 0;
 };
+
+// Raises a kernel's dynamic-LDS limit to `bytes` on `device`, once: the library remembers what it
+// has already asked for per kernel and device, so after a kernel's first launch on a device the
+// launch path makes no runtime call besides the launch itself (defined in dhq_api.hip).
+hipError_t dhq_lds_limit_once_impl(const void *kern, size_t bytes, int device);
+template <typename Kern>
+static inline hipError_t dhq_lds_limit_once(Kern kern, size_t bytes, int device)
+{
+    return dhq_lds_limit_once_impl((const void *)kern, bytes, device);
+}
 
 // ---- launchers (defined in dhq_layerwise.hip) --------------------------------------------
 // Rotate rows over K (zero-padded to Kp) and quantize: codes = clamp(rne(x^ * inv)).

@@ -549,17 +549,19 @@ static hipError_t launch_gemm_mfma(const dhq_layer &L, const int8_t *codes, int6
 {
     dim3 grid((unsigned)((n + 32 * GEMM_WAVES - 1) / (32 * GEMM_WAVES)), (unsigned)((L.Mt + 3) / 4));
     const size_t lds = (size_t)(L.Mt < 4 ? L.Mt : 4) * NKB * 1024;
+    int device = -1;
+    if (lds > 48 * 1024 && hipGetDevice(&device) != hipSuccess) return hipErrorInvalidDevice;
     if (act_out) {
         auto kern = gemm_i8_mfma_kernel<NKB, true>;
         if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = dhq_lds_limit_once(kern, lds, device);
             if (e != hipSuccess) return e;
         }
         kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, nullptr, act_out, c1, bias, act, dyn);
     } else {
         auto kern = gemm_i8_mfma_kernel<NKB, false>;
         if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = dhq_lds_limit_once(kern, lds, device);
             if (e != hipSuccess) return e;
         }
         kern<<<grid, 64 * GEMM_WAVES, lds, st>>>(codes, n, L.wfrag_dev, L.Mg, L.Mt, acc_out, nullptr, c1, bias, act, dyn);
