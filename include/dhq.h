@@ -50,7 +50,8 @@ typedef enum {
     DHQ_EUNSUPPORTED = -2, /* a shape or flag the library has no kernel for */
     DHQ_ENOMEM = -3,       /* host or device allocation failed */
     DHQ_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
-    DHQ_ENOSCALE = -5      /* forward called before activation scales exist */
+    DHQ_ENOSCALE = -5,     /* forward called before activation scales exist */
+    DHQ_ETOOBIG = -6       /* dhq_forward_noalloc: more rows than its fixed buffer holds */
 } dhq_status;
 
 /* dhq_forward flags: which implementation runs.  0 picks the fused kernel when the
@@ -192,7 +193,7 @@ int dhq_get_weight_codes(const dhq_model *m, int32_t layer, int8_t *Wq_host);
  * dhq_reserve_dynamic has provided for n rows, the model's workspace grows to n rows in this call
  * (an allocation, and a device synchronisation, whenever n exceeds every earlier dynamic call and
  * reservation); this is the only case in which dhq_forward changes the model or does anything but
- * enqueue kernels.
+ * enqueue kernels.  dhq_forward_noalloc is the variant that never allocates.
  *
  * Domain of the sine: the hardware sine takes its argument in revolutions and is defined up to
  * 256 of them.  With static scales dhq_set_act_scales / dhq_calibrate check that no layer's
@@ -215,6 +216,27 @@ int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t n, float *o
  * can emit a code; these buffers hold it.)
  */
 int dhq_reserve_dynamic(dhq_model *m, int64_t n);
+
+/*
+ * For callers that cannot allocate device memory -- a stream being captured into a HIP graph, a
+ * serving loop or harness with a no-allocation rule: dhq_forward(..., flags | DHQ_DYNAMIC) on a
+ * fixed scratch buffer that is part of the library's device image instead of the model's growing
+ * buffers.  Same kernels, same results, bit for bit.  Calls no hipMalloc / hipFree and nothing
+ * that allocates; only enqueues kernels on `stream`.
+ *   flags  DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED (the dynamic mode is implied)
+ *   n      at most dhq_noalloc_max_rows(m) rows, else DHQ_ETOOBIG and nothing is enqueued.  The buffer
+ *          is 32 MiB per device (held by every device that has loaded the library, until the process
+ *          ends): e.g. 14336 rows for a 256-wide network, 7281 for a 512-wide one.
+ * All calls on one device share that device's buffer, whichever model they use: calls that overlap
+ * in time on one device (different streams or threads) race and give wrong results; calls on one
+ * stream, or otherwise ordered, are fine.  The buffer keeps the last call's contents; nothing in it
+ * needs clearing between calls.  The measured scales go to the model as with dhq_forward
+ * (dhq_get_dynamic_scales).
+ */
+int dhq_forward_noalloc(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev,
+                        void *stream, uint32_t flags);
+/* Largest n dhq_forward_noalloc accepts for this model (0 for a model without quantized activations). */
+int64_t dhq_noalloc_max_rows(const dhq_model *m);
 
 /* The scales s_a (host, n_layers floats) that the last DHQ_DYNAMIC forward on this model
  * measured (zeros if there has been none).  Synchronises `stream` (pass the stream that forward ran on). */

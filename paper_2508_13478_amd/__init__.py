@@ -24,7 +24,7 @@ DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 
 # every symbol include/dhq.h declares
 EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
-           "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic",
+           "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic", "dhq_forward_noalloc", "dhq_noalloc_max_rows",
            "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
            "dhq_free", "dhq_strerror", "dhq_version")
 
@@ -69,6 +69,9 @@ def lib() -> C.CDLL:
         L.dhq_get_weight_codes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int8)]
         L.dhq_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32]
         L.dhq_reserve_dynamic.argtypes = [C.c_void_p, C.c_int64]
+        L.dhq_forward_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.dhq_noalloc_max_rows.argtypes = [C.c_void_p]
+        L.dhq_noalloc_max_rows.restype = C.c_int64
         L.dhq_forward_debug.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p]
         L.dhq_gemm_i8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -184,6 +187,16 @@ def dhq_forward(model: int, coords, out, stream=None, flags: int = DHQ_AUTO) -> 
 
 def dhq_reserve_dynamic(model: int, n: int) -> None:
     _ok(lib().dhq_reserve_dynamic(model, int(n)), "dhq_reserve_dynamic")
+
+
+def dhq_forward_noalloc(model: int, coords, out, stream=None, flags: int = DHQ_AUTO) -> None:
+    """dhq_forward(..., flags | DHQ_DYNAMIC) on the library's fixed scratch buffer; allocates nothing."""
+    _ok(lib().dhq_forward_noalloc(model, _dptr(coords), coords.shape[0], _dptr(out), _stream_ptr(stream), flags),
+        "dhq_forward_noalloc")
+
+
+def dhq_noalloc_max_rows(model: int) -> int:
+    return int(lib().dhq_noalloc_max_rows(model))
 
 
 def dhq_forward_debug(model: int, x, layer: int, codes=None, acc=None, act=None, stream=None) -> None:

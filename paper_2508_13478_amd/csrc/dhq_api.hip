@@ -49,6 +49,35 @@ hipError_t dhq_lds_limit_once_impl(const void *kern, size_t bytes, int device)
     return hipSuccess;
 }
 
+// ---- the fixed scratch buffer of dhq_forward_noalloc ------------------------------------------
+// dhq_forward with DHQ_DYNAMIC keeps whole-batch buffers in the model and grows them with
+// hipMalloc when a call brings more rows than any before.  Callers that cannot allocate (a
+// stream being captured into a graph, a serving loop with a no-allocation rule) get the same
+// computation on a fixed buffer that is part of the library's device image: every device that
+// loads the library holds DHQ_NOALLOC_SCRATCH_BYTES of it until the process ends.  In host code
+// `scratch` is only a handle for the symbol; its device address is looked up once per device
+// (scratch_on_device, called when a model is created on that device) and only that pointer is
+// ever handed to kernels.
+#define DHQ_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+#define DHQ_NOALLOC_PARTIAL_BYTES ((size_t)2 * DHQ_ABSMAX_PARTIALS * sizeof(float))
+static __device__ __align__(256) unsigned char scratch[DHQ_NOALLOC_SCRATCH_BYTES + DHQ_NOALLOC_PARTIAL_BYTES];
+static unsigned char *scratch_dev_ptr[DHQ_MAX_DEVICES];
+
+// The device address of `scratch` on `device`, which must be the current device.
+static int scratch_on_device(int device, unsigned char **ptr)
+{
+    if (device < 0 || device >= DHQ_MAX_DEVICES) return DHQ_EUNSUPPORTED;
+    if (!scratch_dev_ptr[device]) {
+        unsigned char *p = nullptr;
+        if (hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DHQ_EHIP;
+        scratch_dev_ptr[device] = p;
+    }
+    *ptr = scratch_dev_ptr[device];
+    return DHQ_OK;
+}
+
+static size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+
 static int next_pow2(int k)
 {
     int p = 1;
@@ -126,6 +155,7 @@ extern "C" const char *dhq_strerror(int status)
         case DHQ_ENOMEM: return "out of memory";
         case DHQ_EHIP: return "HIP runtime error";
         case DHQ_ENOSCALE: return "activation scales not set";
+        case DHQ_ETOOBIG: return "input larger than the fixed buffer of the non-allocating entry point";
         default: return "unknown status";
     }
 }
@@ -379,6 +409,7 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
         // dhq_get_dynamic_scales before any dynamic forward reports zeros
         if (rc == DHQ_OK && hipMemset(m->dyn_params, 0, sizeof(float) * 3 * DHQ_MAX_LAYERS) != hipSuccess) rc = DHQ_EHIP;
     }
+    if (rc == DHQ_OK) rc = scratch_on_device(m->device, &m->scratch);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
     if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
@@ -700,6 +731,54 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
             return DHQ_EHIP;
     }
     return DHQ_OK;
+}
+
+// ---- the entry point that allocates nothing (its buffer is declared near the top of this file) ----
+extern "C" int64_t dhq_noalloc_max_rows(const dhq_model *m)
+{
+    if (!m || m->flt) return 0;
+    // bytes per row: two activation buffers, the codes, the two-sided variant's accumulators; the
+    // per-layer fused kernels round the rows up to a whole workgroup tile, hence the search
+    int64_t lo = 0, hi = (int64_t)(DHQ_NOALLOC_SCRATCH_BYTES / 4);
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo + 1) / 2;
+        const dyn_sizes z = dyn_buffer_sizes(m, mid);
+        if (2 * round256(z.act) + round256(z.codes) + round256(z.acc) <= DHQ_NOALLOC_SCRATCH_BYTES) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+extern "C" int dhq_forward_noalloc(const dhq_model *m, const float *coords_dev, int64_t n, float *out_dev, void *stream,
+                                   uint32_t flags)
+{
+    bool per_layer_fused = false;
+    if ((flags & ~3u) != 0) return DHQ_EINVAL;
+    int rc = check_dynamic_call(m, n, flags & 3u, &per_layer_fused);
+    if (rc != DHQ_OK) return rc;
+    if (n == 0) return DHQ_OK;
+    if (!coords_dev || !out_dev) return DHQ_EINVAL;
+    const dyn_sizes z = dyn_buffer_sizes(m, n);
+    if (2 * round256(z.act) + round256(z.codes) + round256(z.acc) > DHQ_NOALLOC_SCRATCH_BYTES) return DHQ_ETOOBIG;
+    unsigned char *base = m->scratch;  // looked up when the model was created, with its device current
+    if (!base) return DHQ_EHIP;
+    dyn_ws ws;
+    ws.partial = reinterpret_cast<float *>(base);
+    base += DHQ_NOALLOC_PARTIAL_BYTES;
+    ws.act0 = reinterpret_cast<float *>(base);
+    base += round256(z.act);
+    ws.act1 = reinterpret_cast<float *>(base);
+    base += round256(z.act);
+    ws.codes = reinterpret_cast<int8_t *>(base);
+    base += round256(z.codes);
+    ws.acc = z.acc ? reinterpret_cast<int32_t *>(base) : nullptr;
+    // the per-layer constants are a result (dhq_get_dynamic_scales reads them), not scratch: they
+    // stay in the model, whose buffer exists since dhq_quantize_weights
+    ws.params = m->dyn_params;
+    // Nothing in the scratch buffer has to start at zero: every kernel writes the part it hands to
+    // the next one in full (per-workgroup maxima up to the count the host passes on, every row of
+    // the activation and code buffers below n) before that kernel reads it.
+    return forward_dynamic(m, ws, coords_dev, n, out_dev, per_layer_fused, (hipStream_t)stream);
 }
 
 extern "C" int dhq_get_dynamic_scales(const dhq_model *m, float *s_a_host, void *stream)

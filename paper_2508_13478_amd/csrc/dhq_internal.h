@@ -78,6 +78,7 @@ struct dhq_model {
     dhq_float_plan *flt = nullptr;    // floating-point activations (DHQ_W8A32 / DHQ_W32A32)
     dhq_fused2_plan *fused2 = nullptr;  // two-sided variant, hidden width 32..256, fan-out <= 4
     int device = 0;
+    unsigned char *scratch = nullptr;  // this device's copy of the library's fixed scratch buffer (dhq_forward_noalloc)
 };
 
 // Raises a kernel's dynamic-LDS limit to `bytes` on `device`, once: the library remembers what it
