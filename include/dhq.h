@@ -255,6 +255,24 @@ int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_t n, int32_
                       int8_t *codes_dev, int32_t *acc_dev, float *act_dev, void *stream);
 
 /*
+ * Test hook for the whole-network kernels (DHQ_FUSED), which keep every intermediate in
+ * registers: one layer of such a kernel -- the same device code, on the same packed weights --
+ * run on caller-supplied input codes, with what it hands to the next layer exposed.  Covers the
+ * steps of Sec. 3.3 after the quantization module of layer `layer`: MAC array (acc), dequantize +
+ * bias + activation, the rotation of Eq. 3-5 over the layer's outputs (x^), and the next quantization
+ * module (codes).  `layer` must be one that ends in an activation (not the last); needs static scales.
+ *   codes_in_dev   dev, n x Kp(layer) int8: the layer's rotated + quantized input (what
+ *                  dhq_forward_debug returns in codes_dev), rotated-feature order
+ *   xhat_dev       dev, n x Kp(layer+1) fp32: pad(a_layer) * H_Kp UN-normalised, i.e. sqrt(Kp) x^
+ *   codes_out_dev  dev, n x Kp(layer+1) int8: clamp(rne(x^ / s_a[layer+1]))
+ *   acc_dev        dev, n x dims[layer+1] int32 accumulators of the layer (DHQ_ROTATE_BOTH: the
+ *                  rotated ones, before the integer un-rotation)
+ * Any output may be NULL.  DHQ_EUNSUPPORTED if the model has no whole-network kernel.
+ */
+int dhq_forward_debug_fused(const dhq_model *m, const int8_t *codes_in_dev, int64_t n, int32_t layer,
+                            float *xhat_dev, int8_t *codes_out_dev, int32_t *acc_dev, void *stream);
+
+/*
  * Test hook: the integer GEMM of one layer alone (Sec. 3.3 MAC array) on
  * caller-supplied codes: acc = codes * Wq[layer]^T.
  *   codes_dev  dev, n x Kp int8;  acc_dev  dev, n x dims[layer+1] int32 (n x Mp for DHQ_ROTATE_BOTH)

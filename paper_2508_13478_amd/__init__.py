@@ -25,7 +25,7 @@ DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 # every symbol include/dhq.h declares
 EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
            "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic", "dhq_forward_noalloc", "dhq_noalloc_max_rows",
-           "dhq_forward_debug", "dhq_gemm_i8", "dhq_has_fused",
+           "dhq_forward_debug", "dhq_forward_debug_fused", "dhq_gemm_i8", "dhq_has_fused",
            "dhq_free", "dhq_strerror", "dhq_version")
 
 
@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.dhq_noalloc_max_rows.restype = C.c_int64
         L.dhq_forward_debug.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p]
+        L.dhq_forward_debug_fused.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
         L.dhq_gemm_i8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.dhq_has_fused.argtypes = [C.c_void_p]
         L.dhq_free.argtypes = [C.c_void_p]
@@ -204,6 +206,11 @@ def dhq_forward_debug(model: int, x, layer: int, codes=None, acc=None, act=None,
                                 _stream_ptr(stream)), "dhq_forward_debug")
 
 
+def dhq_forward_debug_fused(model: int, codes_in, layer: int, xhat=None, codes_out=None, acc=None, stream=None) -> None:
+    _ok(lib().dhq_forward_debug_fused(model, _dptr(codes_in), codes_in.shape[0], layer, _dptr(xhat), _dptr(codes_out),
+                                      _dptr(acc), _stream_ptr(stream)), "dhq_forward_debug_fused")
+
+
 def dhq_gemm_i8(model: int, layer: int, codes, acc, stream=None) -> None:
     _ok(lib().dhq_gemm_i8(model, layer, _dptr(codes), codes.shape[0], _dptr(acc), _stream_ptr(stream)),
         "dhq_gemm_i8")
@@ -286,6 +293,15 @@ class Model:
         act = torch.empty((n, self.dims[layer + 1]), dtype=torch.float32, device=x.device)
         dhq_forward_debug(self.handle, x, layer, codes, acc, act, stream)
         return codes, acc, act
+
+    def forward_debug_fused(self, codes_in, layer: int, stream=None):
+        import torch
+        n, w = codes_in.shape[0], self.kp(layer + 1)
+        xhat = torch.empty((n, w), dtype=torch.float32, device=codes_in.device)
+        codes = torch.empty((n, w), dtype=torch.int8, device=codes_in.device)
+        acc = torch.empty((n, self.mg(layer)), dtype=torch.int32, device=codes_in.device)
+        dhq_forward_debug_fused(self.handle, codes_in, layer, xhat, codes, acc, stream)
+        return xhat, codes, acc
 
     def gemm_i8(self, layer: int, codes, stream=None):
         import torch

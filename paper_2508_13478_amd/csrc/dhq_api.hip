@@ -823,6 +823,23 @@ extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_
     return DHQ_OK;
 }
 
+extern "C" int dhq_forward_debug_fused(const dhq_model *m, const int8_t *codes_in_dev, int64_t n, int32_t layer, float *xhat_dev,
+                                       int8_t *codes_out_dev, int32_t *acc_dev, void *stream)
+{
+    if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
+    if (m->flt || !(m->fused || m->wide || m->fused2)) return DHQ_EUNSUPPORTED;
+    if (layer >= m->n_layers - 1) return DHQ_EUNSUPPORTED;  // the output layer has no transform after it
+    if (n == 0) return DHQ_OK;
+    if (!codes_in_dev) return DHQ_EINVAL;
+    if (!m->have_scales) return DHQ_ENOSCALE;
+    if (!m->fused_sine_ok) return DHQ_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const hipError_t e = m->fused2 ? dhq_fused2_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st)
+                         : m->fused ? dhq_fused_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st)
+                                    : dhq_wide_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st);
+    return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
+}
+
 extern "C" int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int64_t n, int32_t *acc_dev,
                            void *stream)
 {

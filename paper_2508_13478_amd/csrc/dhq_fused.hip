@@ -496,6 +496,87 @@ __global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_layer_kernel(const fu
     }
 }
 
+// ---- test hook: one layer of the whole-network kernel on caller-supplied codes ---------------
+// The layer body is the code dhq_fused_kernel runs (fused_gemm_sine_hm, fused_tile_stages,
+// fused_quant4 on the same packed weights); only the way in and out differs: the input codes
+// are gathered from a row-major n x Kp array into the lanes' register order, and the
+// un-normalised transform x^ of the layer's output and the codes the next layer's quantizer
+// makes of it are scattered back to row-major n x NF arrays in rotated-feature order.  The
+// integer accumulators come from a second, plain MFMA loop over the same fragments and codes.
+struct fusedd_args {
+    const int8_t *codes_in;    // n x kp_in, rotated-feature order
+    const unsigned char *blk;  // the layer's block of the packed weights
+    float *xhat;               // n x NF or null
+    int8_t *codes_out;         // n x NF or null
+    int32_t *acc;              // n x NF or null
+    int64_t n;
+    int chunks, kp_in, qmax;
+    float c1, inv_next, c2;
+};
+
+template <int NF, bool FIRST, int ACTK>
+__global__ __launch_bounds__(FUSED_THREADS) void dhq_fused_debug_kernel(const fusedd_args A)
+{
+    constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
+    constexpr int KB = FIRST ? 1 : NKB;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+    dhq_v4i hA[2];
+    fused_h32_operand(c, h, hA);
+    fused_issue_copy(A.blk, lds, A.chunks, wave, lane, FUSED_WAVES);
+    const int64_t ci = (int64_t)blockIdx.x * FUSED_TILE + wave * 32 + c;
+    const bool valid = ci < A.n;
+    const int64_t cl = valid ? ci : A.n - 1;
+    dhq_v4i cd[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+    if constexpr (FIRST) {
+        // the input layer's (<= 4) codes sit in bytes 0.. of dword 0, whichever lane half
+        unsigned w = 0;
+        for (int k = 0; k < A.kp_in; ++k) w |= (unsigned)(uint8_t)A.codes_in[cl * A.kp_in + k] << (8 * k);
+        cd[0][0] = (int)w;
+    } else {
+#pragma unroll
+        for (int s = 0; s < NR; ++s) {
+            const int f = 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * h + (s & 3);  // rotated feature of register s
+            const unsigned byte = (unsigned)(uint8_t)A.codes_in[cl * A.kp_in + f];
+            cd[s >> 4][(s >> 2) & 3] |= (int)(byte << (8 * (s & 3)));
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds);
+    if (A.acc) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            dhq_v16i acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wA[(T * KB + kb) * 64 + lane], cd[kb], acc, 0, 0, 0);
+            if (valid) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) A.acc[ci * NF + 32 * T + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[v];
+            }
+        }
+    }
+    dhq_v16f xt[NT];
+    fused_gemm_sine_hm<NT, KB, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + NT * KB * 1024), cd, A.c1, xt, hA, lane, h, A.c2);
+    __syncthreads();
+    fused_tile_stages<NT>(xt);
+    fused_quantize<NT>(xt, cd, A.inv_next, qlo, qhi);
+    if (valid) {
+#pragma unroll
+        for (int s = 0; s < NR; ++s) {
+            const int f = 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * h + (s & 3);
+            if (A.xhat) A.xhat[ci * NF + f] = xt[s >> 4][s & 15];
+            if (A.codes_out) A.codes_out[ci * NF + f] = (int8_t)(((unsigned)cd[s >> 4][(s >> 2) & 3] >> (8 * (s & 3))) & 0xffu);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------- host code
 static bool fused_shape_ok(const dhq_model *m, int *nf_out)
 {
@@ -719,4 +800,54 @@ hipError_t dhq_fused_dynamic_launch(const dhq_model *m, const float *coords, int
         count = (int)grid;
     }
     return hipSuccess;
+}
+
+// Test hook behind dhq_forward_debug_fused: layer `layer` (one that ends in an activation) of the
+// whole-network kernel on the caller's codes.
+template <int NF, bool FIRST, int ACTK>
+static hipError_t fusedd_launch_t(const fusedd_args &a, unsigned grid, int device, hipStream_t st)
+{
+    auto kern = dhq_fused_debug_kernel<NF, FIRST, ACTK>;
+    const size_t lds = (size_t)a.chunks * 1024;
+    hipError_t e = dhq_lds_limit_once(kern, lds, device);
+    if (e != hipSuccess) return e;
+    kern<<<grid, FUSED_THREADS, lds, st>>>(a);
+    return hipGetLastError();
+}
+template <int NF>
+static hipError_t fusedd_launch_nf(bool first, int act_kind, const fusedd_args &a, unsigned grid, int device, hipStream_t st)
+{
+    const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
+    if (first) return wav ? fusedd_launch_t<NF, true, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedd_launch_t<NF, true, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+    return wav ? fusedd_launch_t<NF, false, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedd_launch_t<NF, false, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+}
+
+hipError_t dhq_fused_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                  int32_t *acc, hipStream_t st)
+{
+    const dhq_fused_plan *P = m->fused;
+    if (!P || layer < 0 || layer >= m->n_layers - 1) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    fusedd_args a;
+    memset(&a, 0, sizeof(a));
+    a.codes_in = codes_in;
+    a.blk = P->blob_dev + P->args.layer[layer].blob_off;
+    a.chunks = (int)P->args.layer[layer].chunks;
+    a.xhat = xhat;
+    a.codes_out = codes_out;
+    a.acc = acc;
+    a.n = n;
+    a.kp_in = m->layer[layer].Kp;
+    a.qmax = P->args.qmax;
+    a.c1 = P->args.layer[layer].c1;
+    a.inv_next = P->args.layer[layer + 1].inv_in;
+    a.c2 = dhq_hidden_act(m).c2;
+    const unsigned grid = (unsigned)((n + FUSED_TILE - 1) / FUSED_TILE);
+    switch (P->nf) {
+        case 32: return fusedd_launch_nf<32>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 64: return fusedd_launch_nf<64>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 128: return fusedd_launch_nf<128>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 256: return fusedd_launch_nf<256>(layer == 0, m->act_kind, a, grid, P->device, st);
+        default: return hipErrorInvalidValue;
+    }
 }

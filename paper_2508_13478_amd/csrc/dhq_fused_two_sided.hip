@@ -429,6 +429,86 @@ __global__ __launch_bounds__(F2_THREADS) void dhq_fused2_layer_kernel(const f2l_
     }
 }
 
+// ---- test hook: one layer of the whole-network kernel on caller-supplied codes ---------------
+// The layer body is f2_hidden_layer and the quantizer as dhq_fused2_kernel runs them, on the same
+// packed weights; the codes come in from a row-major n x Kp array (rotated-feature order) and the
+// un-normalised transform x^ of the layer's output, the next layer's codes and the rotated
+// accumulators (from a second, plain MFMA loop) go out to row-major n x NF arrays.
+struct f2d_args {
+    const int8_t *codes_in;
+    const unsigned char *blk;
+    float *xhat;
+    int8_t *codes_out;
+    int32_t *acc;
+    int64_t n;
+    int chunks, kp_in, qmax;
+    float c1, inv_next, c2;
+};
+
+template <int NF, bool FIRST, int ACTK>
+__global__ __launch_bounds__(F2_THREADS) void dhq_fused2_debug_kernel(const f2d_args A)
+{
+    constexpr int NT = NF / 32, NKB = NF / 32, NR = NF / 2;
+    constexpr int KB = FIRST ? 1 : NKB;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+    dhq_v4i hA[2];
+    f2_h32_operand(c, h, hA);
+    fused_issue_copy(A.blk, lds, A.chunks, wave, lane, F2_WAVES);
+    const int64_t ci = (int64_t)blockIdx.x * F2_TILE + wave * 32 + c;
+    const bool valid = ci < A.n;
+    const int64_t cl = valid ? ci : A.n - 1;
+    dhq_v4i cd[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+    if constexpr (FIRST) {
+        unsigned w = 0;
+        for (int k = 0; k < A.kp_in; ++k) w |= (unsigned)(uint8_t)A.codes_in[cl * A.kp_in + k] << (8 * k);
+        cd[0][0] = (int)w;
+    } else {
+#pragma unroll
+        for (int s = 0; s < NR; ++s) {
+            const int f = 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * h + (s & 3);  // rotated feature of register s
+            const unsigned byte = (unsigned)(uint8_t)A.codes_in[cl * A.kp_in + f];
+            cd[s >> 4][(s >> 2) & 3] |= (int)(byte << (8 * (s & 3)));
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(lds);
+    if (A.acc) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            dhq_v16i acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wA[(T * KB + kb) * 64 + lane], cd[kb], acc, 0, 0, 0);
+            if (valid) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) A.acc[ci * NF + 32 * T + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[v];
+            }
+        }
+    }
+    dhq_v16f xt[NT];
+    f2_hidden_layer<NT, KB, NKB, ACTK>(wA, reinterpret_cast<const float4 *>(lds + NT * KB * 1024), cd, A.c1, hA, xt, lane, h, A.c2);
+#pragma unroll
+    for (int w = 0; w < NR / 4; ++w) {
+        const int v = 4 * (w & 3);
+        cd[w / 4][w % 4] = (int)fused_quant4(xt[w >> 2][v], xt[w >> 2][v + 1], xt[w >> 2][v + 2], xt[w >> 2][v + 3], A.inv_next, qlo, qhi);
+    }
+    if (valid) {
+#pragma unroll
+        for (int s = 0; s < NR; ++s) {
+            const int f = 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * h + (s & 3);
+            if (A.xhat) A.xhat[ci * NF + f] = xt[s >> 4][s & 15];
+            if (A.codes_out) A.codes_out[ci * NF + f] = (int8_t)(((unsigned)cd[s >> 4][(s >> 2) & 3] >> (8 * (s & 3))) & 0xffu);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------- host code
 // Natural accumulator order: rotated index held by register s of lane half u.
 static int p0_index(int s, int u) { return 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * u + (s & 3); }
@@ -655,4 +735,53 @@ hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, in
         count = (int)grid;
     }
     return hipSuccess;
+}
+
+// Test hook behind dhq_forward_debug_fused for the two-sided whole-network kernel.
+template <int NF, bool FIRST, int ACTK>
+static hipError_t f2d_launch_t(const f2d_args &a, unsigned grid, int device, hipStream_t st)
+{
+    auto kern = dhq_fused2_debug_kernel<NF, FIRST, ACTK>;
+    const size_t lds = (size_t)a.chunks * 1024;
+    hipError_t e = dhq_lds_limit_once(kern, lds, device);
+    if (e != hipSuccess) return e;
+    kern<<<grid, F2_THREADS, lds, st>>>(a);
+    return hipGetLastError();
+}
+template <int NF>
+static hipError_t f2d_launch_nf(bool first, int act_kind, const f2d_args &a, unsigned grid, int device, hipStream_t st)
+{
+    const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
+    if (first) return wav ? f2d_launch_t<NF, true, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : f2d_launch_t<NF, true, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+    return wav ? f2d_launch_t<NF, false, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : f2d_launch_t<NF, false, DHQ_ACT_KIND_SINE>(a, grid, device, st);
+}
+
+hipError_t dhq_fused2_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                   int32_t *acc, hipStream_t st)
+{
+    const dhq_fused2_plan *P = m->fused2;
+    if (!P || layer < 0 || layer >= m->n_layers - 1) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    f2d_args a;
+    memset(&a, 0, sizeof(a));
+    a.codes_in = codes_in;
+    a.blk = P->blob_dev + P->args.layer[layer].blob_off;
+    a.chunks = (int)P->args.layer[layer].chunks;
+    a.xhat = xhat;
+    a.codes_out = codes_out;
+    a.acc = acc;
+    a.n = n;
+    a.kp_in = m->layer[layer].Kp;
+    a.qmax = P->args.qmax;
+    a.c1 = P->args.layer[layer].c1;
+    a.inv_next = P->args.layer[layer + 1].inv_in;
+    a.c2 = P->args.c2;
+    const unsigned grid = (unsigned)((n + F2_TILE - 1) / F2_TILE);
+    switch (P->nf) {
+        case 32: return f2d_launch_nf<32>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 64: return f2d_launch_nf<64>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 128: return f2d_launch_nf<128>(layer == 0, m->act_kind, a, grid, P->device, st);
+        case 256: return f2d_launch_nf<256>(layer == 0, m->act_kind, a, grid, P->device, st);
+        default: return hipErrorInvalidValue;
+    }
 }

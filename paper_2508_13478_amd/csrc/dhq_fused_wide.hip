@@ -456,9 +456,10 @@ __device__ __forceinline__ void wide_fetch_rows(float (&xv)[NT * 4], std::intege
       xv[4 * Ts + 2] = wide_tile_read<Ts, 4 * Q + 2>(), xv[4 * Ts + 3] = wide_tile_read<Ts, 4 * Q + 3>()),
      ...);
 }
-template <int NT, int NCD, int Q>
+// xrow (test hook only): where this lane's coordinate keeps its row of x^; feature 32 T + 8 Q + 4 h + b.
+template <int NT, int NCD, int Q, bool DUMP = false>
 __device__ __forceinline__ void wide_transform_quant(const dhq_v16f (&xtop)[NT - WIDE_AGPR_TILES], dhq_v4i (&cd)[NCD],
-                                                     float inv, int qlo, int qhi)
+                                                     float inv, int qlo, int qhi, float *xrow = nullptr, int h = 0)
 {
     float xv[NT * 4];
     wide_fetch_rows<NT, Q>(xv, std::make_integer_sequence<int, WIDE_AGPR_TILES>{});
@@ -476,6 +477,11 @@ __device__ __forceinline__ void wide_transform_quant(const dhq_v16f (&xtop)[NT -
                 xv[i | s] = a - b;
             }
         }
+    }
+    if constexpr (DUMP) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T)
+            *reinterpret_cast<float4 *>(xrow + 32 * T + 8 * Q + 4 * h) = make_float4(xv[4 * T], xv[4 * T + 1], xv[4 * T + 2], xv[4 * T + 3]);
     }
 #pragma unroll
     for (int T = 0; T < NT; ++T) {
@@ -611,6 +617,155 @@ void dhq_fused_wide_kernel(const wide_args A)
             }
             cc += 1;
         }
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+}
+
+// ---- test hook: one layer of the kernel above on caller-supplied codes ------------------------
+// Runs wide_gemm_sine and wide_transform_quant, the code of dhq_fused_wide_kernel, on the same
+// packed weights and through the same chunk stream (started at the layer's first chunk); the
+// codes come in from a row-major n x Kp array (rotated-feature order), and the un-normalised
+// transform x^ of the layer's output, the next layer's codes and the integer accumulators (from
+// a second, plain MFMA loop that reads the fragments from device memory) go out to row-major
+// n x NF arrays.  One coordinate tile per workgroup.
+struct wide_dargs {
+    wide_args w;
+    const int8_t *codes_in;
+    float *xhat;        // rows rounded up to whole tiles
+    int8_t *codes_out;  // the same
+    int32_t *acc;       // n rows (wide_debug_acc_kernel)
+    int layer, kp_in;
+};
+
+// The integer accumulators of the layer for the test hook: a plain MFMA loop over the layer's packed
+// fragments, read from device memory, and the codes gathered as below.  One wave per 32 coordinates.
+template <int NF>
+__global__ __launch_bounds__(64) void wide_debug_acc_kernel(const wide_dargs D)
+{
+    constexpr int NT = NF / 32, NKB = NF / 32;
+    const wide_args &A = D.w;
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 31, h = lane >> 5;
+    const int l = D.layer;
+    const int cc0 = (l == 0) ? 0 : 1 + (NT / WIDE_CH) * (l - 1);
+    const int KB = (l == 0) ? 1 : NKB, ch = (l == 0) ? NT : WIDE_CH;
+    const int64_t ci = (int64_t)blockIdx.x * 32 + c;
+    const bool valid = ci < A.n;
+    const int64_t cl = valid ? ci : A.n - 1;
+    for (int T = 0; T < NT; ++T) {
+        const dhq_v4i *fr = reinterpret_cast<const dhq_v4i *>(A.blob + A.chunk_off[cc0 + T / ch]) + (size_t)(T % ch) * KB * 64;
+        dhq_v16i acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0;
+        for (int kb = 0; kb < KB; ++kb) {
+            dhq_v4i b = dhq_v4i{0, 0, 0, 0};
+            if (l == 0) {
+                unsigned w = 0;
+                for (int k = 0; k < D.kp_in; ++k) w |= (unsigned)(uint8_t)D.codes_in[cl * D.kp_in + k] << (8 * k);
+                b[0] = (int)w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int s = 16 * kb + j;
+                    const int f = 32 * (s >> 4) + 8 * ((s >> 2) & 3) + 4 * h + (s & 3);  // rotated feature of register s
+                    b[j >> 2] |= (int)((unsigned)(uint8_t)D.codes_in[cl * D.kp_in + f] << (8 * (j & 3)));
+                }
+            }
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[kb * 64 + lane], b, acc, 0, 0, 0);
+        }
+        if (valid) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) D.acc[ci * NF + 32 * T + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[v];
+        }
+    }
+}
+
+template <int NF, int ACTK>
+__global__ __launch_bounds__(WIDE_THREADS) __attribute__((amdgpu_num_vgpr(256 + WIDE_AGPR_COMPILER)))
+void dhq_fused_wide_kernel_debug(const wide_dargs D)
+{
+    constexpr int NT = NF / 32;
+    constexpr int NKB = NF / 32;
+    constexpr int BLK = (WIDE_CH * NKB + 1) * 1024;
+    const wide_args &A = D.w;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int l = D.layer;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+    const int cc0 = (l == 0) ? 0 : 1 + (NT / WIDE_CH) * (l - 1);  // the layer's first chunk
+
+    wide_stream S;
+    S.A = &A;
+    S.lds = lds;
+    S.blk = BLK;
+    S.wave = __builtin_amdgcn_readfirstlane(wave);
+    S.lane = lane;
+    S.cp_voff = (unsigned)(wave * 1024 + lane * 16);
+    S.cp_kib = 0;
+    S.cp_src = A.blob;
+    S.cp_dst = 0;
+    int cc = cc0;
+    for (int q = wave; q < (int)A.chunk_kib[cc0]; q += WIDE_WAVES)
+        reinterpret_cast<dhq_v4i *>(lds + (cc0 & 1) * BLK)[q * 64 + lane] =
+            reinterpret_cast<const dhq_v4i *>(A.blob + A.chunk_off[cc0])[q * 64 + lane];
+    asm volatile("" ::: "a255");
+
+    dhq_v4i hA[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int v = 8 * kk + 2 * d;
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
+        }
+    }
+    const int64_t ci = (int64_t)blockIdx.x * WIDE_TILE + wave * 32 + c;
+    const bool valid = ci < A.n;
+    const int64_t cl = valid ? ci : A.n - 1;
+    dhq_v4i cd[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+    if (l == 0) {
+        unsigned w = 0;
+        for (int k = 0; k < D.kp_in; ++k) w |= (unsigned)(uint8_t)D.codes_in[cl * D.kp_in + k] << (8 * k);
+        cd[0][0] = (int)w;
+    } else {
+        // four consecutive rotated features per dword (4-byte aligned: Kp is a multiple of 32); the
+        // scheduling barrier keeps the compiler from gathering all 64 loads first, which this
+        // kernel has no registers for
+#pragma unroll
+        for (int w = 0; w < NF / 8; ++w) {
+            const int f = 32 * (w >> 2) + 8 * (w & 3) + 4 * h;  // rotated features f .. f + 3 of registers 4 w .. 4 w + 3
+            cd[w >> 2][w & 3] = *reinterpret_cast<const int *>(D.codes_in + cl * D.kp_in + f);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    dhq_v16f xtop[NT - WIDE_AGPR_TILES];
+    if (l == 0)
+        wide_gemm_sine<NT, 1, NT, NKB, ACTK>(S, cc, A.c1[0], A.c2, cd, xtop, hA, h);
+    else
+        wide_gemm_sine<NT, NKB, WIDE_CH, NKB, ACTK>(S, cc, A.c1[l], A.c2, cd, xtop, hA, h);
+    const float inv = A.inv_in[l + 1];
+    // The coordinate index is worked out again from the thread index (through an empty asm, so that
+    // the compiler cannot tell it is the value from above): kept alive across the layer it would be
+    // parked in an accumulation register, which this kernel addresses by number.
+    unsigned tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int64_t ci2 = (int64_t)blockIdx.x * WIDE_TILE + (tid >> 6) * 32 + (tid & 31);
+    const bool valid2 = ci2 < A.n;
+    (void)valid2;
+    // both outputs go to workspace buffers with room for whole tiles, so nothing here is conditional
+    float *xrow = D.xhat + ci2 * NF;
+    wide_transform_quant<NT, NKB, 0, true>(xtop, cd, inv, qlo, qhi, xrow, h);
+    wide_transform_quant<NT, NKB, 1, true>(xtop, cd, inv, qlo, qhi, xrow, h);
+    wide_transform_quant<NT, NKB, 2, true>(xtop, cd, inv, qlo, qhi, xrow, h);
+    wide_transform_quant<NT, NKB, 3, true>(xtop, cd, inv, qlo, qhi, xrow, h);
+#pragma unroll
+    for (int w = 0; w < NF / 8; ++w) {
+        const int f = 32 * (w >> 2) + 8 * (w & 3) + 4 * h;
+        *reinterpret_cast<int *>(D.codes_out + ci2 * NF + f) = cd[w >> 2][w & 3];
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 }
@@ -770,4 +925,39 @@ hipError_t dhq_wide_launch(const dhq_wide_plan *P, const float *coords, int64_t 
     if (e != hipSuccess) return e;
     kern<<<grid, WIDE_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+
+// Test hook behind dhq_forward_debug_fused for hidden width 512.
+hipError_t dhq_wide_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                 int32_t *acc, hipStream_t st)
+{
+    const dhq_wide_plan *P = m->wide;
+    if (!P || layer < 0 || layer >= m->n_layers - 1) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    if (n > DHQ_CHUNK) return hipErrorInvalidValue;  // the outputs pass through the model's workspace (whole tiles)
+    wide_dargs d;
+    memset(&d, 0, sizeof(d));
+    d.w = P->args;
+    d.w.n = n;
+    d.codes_in = codes_in;
+    d.xhat = m->act0;
+    d.codes_out = m->codes;
+    d.acc = acc;
+    d.layer = layer;
+    d.kp_in = m->layer[layer].Kp;
+    const unsigned grid = (unsigned)((n + WIDE_TILE - 1) / WIDE_TILE);
+    auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_wide_kernel_debug<512, DHQ_ACT_KIND_WAVELET>
+                                                      : dhq_fused_wide_kernel_debug<512, DHQ_ACT_KIND_SINE>;
+    hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
+    if (e != hipSuccess) return e;
+    if (acc) {
+        wide_debug_acc_kernel<512><<<(unsigned)((n + 31) / 32), 64, 0, st>>>(d);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (!xhat && !codes_out) return hipSuccess;
+    kern<<<grid, WIDE_THREADS, P->lds_bytes, st>>>(d);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (xhat && (e = hipMemcpyAsync(xhat, m->act0, sizeof(float) * (size_t)n * 512, hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+    if (codes_out && (e = hipMemcpyAsync(codes_out, m->codes, (size_t)n * 512, hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+    return hipSuccess;
 }

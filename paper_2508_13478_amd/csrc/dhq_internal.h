@@ -198,6 +198,18 @@ size_t dhq_fused2_dynamic_rows(int64_t n);
 hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
                                      float *partial, float *dyn, hipStream_t st);
 
+// Test hooks: layer `layer` (one that ends in an activation) of a whole-network kernel on the
+// caller's input codes (n x Kp int8, rotated-feature order).  Outputs, each n x hidden width,
+// row-major in rotated-feature order, any may be null: the un-normalised transform x^ of the
+// layer's output, the codes the next layer's quantizer makes of it, the layer's int32 accumulators
+// (two-sided: the rotated ones).
+hipError_t dhq_fused_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                  int32_t *acc, hipStream_t st);
+hipError_t dhq_wide_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                 int32_t *acc, hipStream_t st);
+hipError_t dhq_fused2_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                   int32_t *acc, hipStream_t st);
+
 // Floating-point activations (defined in dhq_float.hip): the plain network (sine, or the wavelet `act`) on the given fp32
 // weights W[l] (dims[l+1] x dims[l]) and biases.  Every shape has the layer-by-layer path
 // (dhq_float_launch_layerwise); the shapes dhq_float_shape_ok accepts also have one kernel fused

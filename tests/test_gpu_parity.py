@@ -232,6 +232,72 @@ def _assert_close(out, exp, strict=False, frac=FLIP_FRAC):
     return err
 
 
+# ---------------------------------------------------------------- the fused kernels, free-running
+# The whole-network kernels expose nothing but their final values, so their chain of codes is
+# replayed through dhq_forward_debug_fused, which runs one layer of the same device code on given
+# input codes: layer 0's quantizer through the layer-by-layer hook (the same two-point butterfly
+# and quantizer), then layer after layer on the codes the previous one produced.  That the replay
+# is what the whole-network launch computed is checked on its last link: the output layer's
+# accumulators of the replayed codes, dequantized, must give the launch's outputs.
+def fused_chain(model, net, coords):
+    """Codes of every layer's input as the fused kernels produce them free-running, and the
+    final values they imply.  coords: (n <= 65536, K0) numpy."""
+    torch = _torch()
+    L = len(net.dims) - 1
+    codes = [model.forward_debug(_dev(coords), 0)[0]]
+    for l in range(L - 1):
+        _, nxt, _ = model.forward_debug_fused(codes[l], l)
+        codes.append(nxt)
+    acc = model.gemm_i8(L - 1, codes[L - 1])
+    torch.cuda.synchronize()
+    acc = acc.cpu().numpy()
+    scale = float(net.s_a[L - 1]) * float(net.s_w[L - 1])
+    if net.two_sided:
+        acc = int_unrotate(acc)
+        scale /= np.sqrt(float(acc.shape[1]))
+    out = acc[:, : net.dims[-1]].astype(np.float64) * scale + net.bias[L - 1].astype(np.float64)
+    return [c.cpu().numpy() for c in codes], out
+
+
+def first_differences(got_codes, exp_codes):
+    """Free-running code comparison.  A coordinate's codes of layer l are a teacher-forced
+    comparison exactly as long as all its earlier codes agree with the oracle's (the layer then saw
+    the oracle's input).  Returns (mask of coordinates with any difference, number of codes compared
+    under that condition, number of those that differ, largest such difference)."""
+    n = got_codes[0].shape[0]
+    agree = np.ones(n, dtype=bool)
+    compared = differing = 0
+    worst = 0
+    for g, e in zip(got_codes, exp_codes):
+        d = np.abs(g.astype(np.int32) - e.astype(np.int32))[agree]
+        compared += d.size
+        differing += int((d != 0).sum())
+        worst = max(worst, int(d.max()) if d.size else 0)
+        agree[agree] = (d == 0).all(axis=1)
+    return ~agree, compared, differing, worst
+
+
+def check_fused_against_oracle(model, net, coords, out, exp, dump, label):
+    """The end-to-end gate of a whole-network launch `out` on `coords` (oracle: exp, dump):
+      * the replayed chain reproduces the launch;
+      * codes compared while a coordinate still agrees with the oracle: <= 0.1 % differ, each by 1 LSB;
+      * every coordinate without a code difference is within OUT_TOL, i.e. every excess is explained
+        by a code difference upstream; no value is further off than FLIP_BOUND.
+    Returns (err per coordinate, mask of coordinates with a code difference)."""
+    chain, chain_out = fused_chain(model, net, coords)
+    assert np.abs(chain_out - out.astype(np.float64)).max() <= 1e-6, f"{label}: the replayed chain is not what the launch computed"
+    diff, compared, differing, worst = first_differences(chain, dump.codes)
+    err = np.abs(out.astype(np.float64) - exp).max(axis=1)
+    over = err > OUT_TOL
+    _say(f"  {label}: {differing} of {compared} codes differ where the input agreed ({differing / compared:.2e}, max {worst} LSB); "
+         f"{diff.sum()} of {err.size} coords with a code difference, {over.sum()} beyond {OUT_TOL}; "
+         f"max err without any: {err[~diff].max() if (~diff).any() else 0.0:.3e}, overall {err.max():.3e}")
+    assert worst <= 1 and differing <= CODE_RATE * compared
+    assert not (over & ~diff).any()
+    assert err.max() <= FLIP_BOUND
+    return err, diff
+
+
 def _check_forward(cs, flags, label, strict=False):
     torch = _torch()
     out = cs.model.forward(_dev(cs.coords), flags=flags)
@@ -252,6 +318,8 @@ def _check_forward(cs, flags, label, strict=False):
              f"max err without any: {err[~diff].max():.3e}")
         assert err[~diff].max() <= OUT_TOL        # identical codes -> the tolerance holds strictly
         assert diff[over].all()                   # every excess is explained by a code difference
+    if flags == dhq.DHQ_FUSED and cs.dump is not None and err.size <= 65536:
+        check_fused_against_oracle(cs.model, cs.net, cs.coords, out, cs.out, cs.dump, label)
     return out
 
 
@@ -288,6 +356,7 @@ def test_forward_fused_width_512():
     b = _check_forward(cs, dhq.DHQ_LAYERWISE, "layerwise-512")
     d = np.abs(a - b).max(axis=1)
     _say(f"  fused vs layerwise: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
+    # two paths with independently rounded transforms: either may have moved a coordinate
     assert (d > OUT_TOL).mean() <= 2 * flip_frac(cs.dims)
     c = _check_forward(cs, dhq.DHQ_FUSED, "fused-512 again")
     assert np.array_equal(a, c)
@@ -326,22 +395,19 @@ def test_full_grid_sampled_outputs(name, bits):
     idx = np.unique(np.concatenate([rng.integers(0, n, 6000), np.arange(0, 300), np.arange(n - 300, n)]))
     got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
     exp, dmp = o.forward(net, coords[idx], dump=True)
-    err = np.abs(got.astype(np.float64) - exp).max(axis=1)
+    # every excess tied to a code difference in the kernel's own chain, the differing codes held to the
+    # code gate (0.1 %, 1 LSB) where they are teacher-forced comparisons
+    err, diff = check_fused_against_oracle(model, net, coords[idx], got, exp, dmp, f"{name} {bits} bits")
     over = err > OUT_TOL
-    near = _near_boundary(net, dmp, bits)
     # coordinates that share their first-layer codes share everything after them; at 4 bits the
-    # whole grid collapses to about a hundred such cases, so the share of coordinates that moved
-    # is counted over distinct cases
+    # whole grid collapses to about a hundred such cases, so the coordinates that moved are
+    # reported over distinct cases.  Their number is bounded by the cases with a code difference,
+    # which the code gate above bounds; it is printed, not fitted with a threshold of its own.
     _, case_of = np.unique(dmp.codes[0], axis=0, return_inverse=True)
     case_of = np.asarray(case_of).reshape(-1)
     n_cases = int(case_of.max()) + 1
-    moved_cases = np.unique(case_of[over]).size
-    _say(f"  {idx.size} sampled coords ({n_cases} distinct cases): max-abs err {err.max():.3e}, {over.sum()} beyond "
-         f"{OUT_TOL} in {moved_cases} cases; {near.sum()} coords have a code within {BOUNDARY_EPS} of a rounding boundary")
-    assert err.max() <= FLIP_BOUND
-    assert not (over & ~near).any()       # away from every rounding boundary the tolerance holds strictly
-    # (a count of two or three carries its own sampling noise, hence the floor and the factor)
-    assert moved_cases <= max(3, 2 * flip_frac(wl.dims) * n_cases)
+    _say(f"  {idx.size} sampled coords ({n_cases} distinct cases): {np.unique(case_of[over]).size} cases beyond {OUT_TOL}, "
+         f"{np.unique(case_of[diff]).size} with a code difference")
     # properties that hold at any size: finite everywhere, and a coordinate's value does not
     # depend on which launch or tile it was computed in
     assert bool(torch.isfinite(out).all())

@@ -279,7 +279,7 @@ def test_wavelet_random_shapes_bits_modes_and_row_counts(block):
             err = np.abs(out.astype(np.float64) - exp).max(axis=1)
             over = err > OUT_TOL
             assert not (over & ~near).any(), f"case {i} flags {flags}: max-abs err {err.max():.3e}"
-            assert over.sum() <= max(2, 2 * flip_frac(dims) * n), f"case {i} flags {flags}: {over.sum()} of {n} beyond {OUT_TOL}"
+            assert over.sum() <= max(2, flip_frac(dims) * n), f"case {i} flags {flags}: {over.sum()} of {n} beyond {OUT_TOL}"
         m.close()
 
 
@@ -322,7 +322,7 @@ def test_wavelet_forward_replays_from_a_captured_graph(variant):
 def test_wavelet_full_grid_sampled_outputs_width_512():
     """The 512-wide network on its full 2048 x 2048 grid through the whole-network kernel, as the benchmark
     launches it: the oracle calibrates on a strided sub-grid and is compared on sampled coordinates."""
-    from test_gpu_parity import BOUNDARY_EPS, FLIP_BOUND, _near_boundary
+    from test_gpu_parity import check_fused_against_oracle
     torch = _torch()
     _say("wavelet full grid C5")
     wl, coords, W, b = synth.make("C5")
@@ -338,18 +338,16 @@ def test_wavelet_full_grid_sampled_outputs_width_512():
     idx = np.unique(np.concatenate([rng.integers(0, n, 3000), np.arange(0, 200), np.arange(n - 200, n)]))
     got = out[torch.from_numpy(idx).to("cuda")].cpu().numpy()
     exp, dmp = o.forward(net, coords[idx], dump=True)
-    err = np.abs(got.astype(np.float64) - exp).max(axis=1)
-    over = err > OUT_TOL
-    near = _near_boundary(net, dmp, 8)
-    _say(f"  {idx.size} sampled coords: max-abs err {err.max():.3e}, median {np.median(err):.1e}, {over.sum()} beyond {OUT_TOL}; "
-         f"{near.sum()} have a code within {BOUNDARY_EPS} of a rounding boundary (|out| max {np.abs(exp).max():.3f})")
-    assert err.max() <= FLIP_BOUND and not (over & ~near).any()
-    assert over.sum() <= max(3, 2 * flip_frac(wl.dims) * idx.size)
+    # every excess tied to a code difference in the kernel's own chain; the differing codes held to the
+    # code gate (0.1 %, 1 LSB) where they are teacher-forced comparisons
+    err, diff = check_fused_against_oracle(model, net, coords[idx], got, exp, dmp, "wavelet C5")
+    _say(f"  {idx.size} sampled coords: median err {np.median(err):.1e} (|out| max {np.abs(exp).max():.3f})")
     assert bool(torch.isfinite(out).all())
     lw = model.forward(_dev(coords[idx]), flags=dhq.DHQ_LAYERWISE)
     sub = model.forward(_dev(coords[idx]), flags=dhq.DHQ_FUSED)
     torch.cuda.synchronize()
     assert np.array_equal(sub.cpu().numpy(), got)
+    # the layer-by-layer path rounds its transform differently: either path may have moved a coordinate
     d = np.abs(lw.cpu().numpy() - got).max(axis=1)
-    assert (d > OUT_TOL).sum() <= max(3, 2 * flip_frac(wl.dims) * idx.size)
+    assert (d > OUT_TOL).sum() <= max(2, 2 * flip_frac(wl.dims) * idx.size)
     model.close()

@@ -150,9 +150,7 @@ def test_two_sided_int32_bound_is_enforced_before_the_device_is_touched():
     assert np.abs(r["unrot"]).max() == 127 * 127 * 256 * 256
 
 
-def test_header_is_plain_c_and_entry_points_link_from_c(tmp_path):
-    """include/dhq.h compiled as C99 with warnings as errors, linked against libdhq.so and run:
-    version, status names and the argument checks that are decided before the device is touched."""
+def _build_c_abi_check(tmp_path):
     import subprocess
     dhq.lib()
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -160,7 +158,26 @@ def test_header_is_plain_c_and_entry_points_link_from_c(tmp_path):
     exe = str(tmp_path / "c_abi_check")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
                     os.path.join(root, "tests", "c", "c_abi_check.c"), "-o", exe, "-L", libdir, "-l:libdhq.so",
-                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+                    "-L/opt/rocm/lib", "-lamdhip64", "-lm", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    return exe
+
+
+def test_header_is_plain_c_and_entry_points_link_from_c(tmp_path):
+    """include/dhq.h compiled as C99 with warnings as errors, linked against libdhq.so and run:
+    version, status names and the argument checks that are decided before the device is touched."""
+    import subprocess
+    exe = _build_c_abi_check(tmp_path)
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "c_abi_check ok" in r.stdout
+
+
+@pytest.mark.gpu
+def test_c_program_runs_a_forward(tmp_path):
+    """The same C program with a device present: quantize, calibrate, forward (static, dynamic and the
+    non-allocating entry point) from plain C, against the closed form of its tiny network."""
+    import subprocess
+    exe = _build_c_abi_check(tmp_path)
+    r = subprocess.run([exe, "forward"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "c_abi_check forward ok" in r.stdout and "c_abi_check ok" in r.stdout
