@@ -132,6 +132,9 @@ def main() -> int:
     ap.add_argument("--wavelet-s0", type=float, default=10.0, help="spread of the wavelet's Gaussian envelope")
     ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
                     help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
+    ap.add_argument("--wide-kernel", type=int, default=0, choices=[0, 1, 2],
+                    help="hidden width 512 only: 0 the library's default whole-network kernel, 1 the one with one wave "
+                         "per SIMD, 2 the one with two waves per SIMD that split the features")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-coords", type=int, default=32768, help="cap of the CPU-baseline sample")
     ap.add_argument("--copy-probe", action="store_true",
@@ -159,6 +162,8 @@ def main() -> int:
         mode = dhq.DHQ_W8A32 if args.variant == "w8a32" else dhq.DHQ_W32A32
     s0 = args.wavelet_s0 if args.activation == "wavelet" else None
     model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode, wavelet_s0=s0)
+    if args.wide_kernel:
+        model.select_wide_kernel(args.wide_kernel)
     x = torch.from_numpy(coords).to("cuda")
     out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
     if not floating:

@@ -285,6 +285,18 @@ int dhq_gemm_i8(const dhq_model *m, int32_t layer, const int8_t *codes_dev, int6
  * (negative status on error). */
 int dhq_has_fused(const dhq_model *m);
 
+/*
+ * Hidden width 512 has two whole-network kernels for the pipeline of Sec. 3.3, which compute the
+ * same steps in the same precision and differ in how the work of a layer is laid out: one wave
+ * per SIMD that holds all 512 features of its 32 coordinates (which = 1), or two waves per SIMD
+ * that share 32 coordinates and take half of every layer's output features each, exchanging
+ * through LDS what the rotation of Eq. 3 needs from the other half (which = 2).  which = 0
+ * returns to the library's default (the faster one).  The choice applies to dhq_forward and
+ * dhq_forward_debug_fused on this model from the next call on; it is not thread-safe against
+ * calls in flight on the same model.  DHQ_EUNSUPPORTED for a model of any other shape.
+ */
+int dhq_select_wide_kernel(dhq_model *m, int32_t which);
+
 void dhq_free(dhq_model *m);
 const char *dhq_strerror(int status);
 int dhq_version(void);

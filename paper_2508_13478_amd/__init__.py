@@ -25,7 +25,7 @@ DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 # every symbol include/dhq.h declares
 EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
            "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic", "dhq_forward_noalloc", "dhq_noalloc_max_rows",
-           "dhq_forward_debug", "dhq_forward_debug_fused", "dhq_gemm_i8", "dhq_has_fused",
+           "dhq_forward_debug", "dhq_forward_debug_fused", "dhq_gemm_i8", "dhq_has_fused", "dhq_select_wide_kernel",
            "dhq_free", "dhq_strerror", "dhq_version")
 
 
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
                                               C.c_void_p, C.c_void_p]
         L.dhq_gemm_i8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.dhq_has_fused.argtypes = [C.c_void_p]
+        L.dhq_select_wide_kernel.argtypes = [C.c_void_p, C.c_int32]
         L.dhq_free.argtypes = [C.c_void_p]
         L.dhq_free.restype = None
         L.dhq_strerror.argtypes = [C.c_int]
@@ -223,6 +224,10 @@ def dhq_has_fused(model: int) -> bool:
     return bool(rc)
 
 
+def dhq_select_wide_kernel(model: int, which: int) -> None:
+    _ok(lib().dhq_select_wide_kernel(model, int(which)), "dhq_select_wide_kernel")
+
+
 def dhq_free(model: int) -> None:
     lib().dhq_free(model)
 
@@ -277,6 +282,9 @@ class Model:
 
     def has_fused(self) -> bool:
         return dhq_has_fused(self.handle)
+
+    def select_wide_kernel(self, which: int) -> None:
+        dhq_select_wide_kernel(self.handle, which)
 
     def forward(self, coords, out=None, flags: int = DHQ_AUTO, stream=None):
         import torch

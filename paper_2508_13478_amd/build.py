@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdhq.so")
 SOURCES = ["dhq_api.hip", "dhq_layerwise.hip", "dhq_fused.hip", "dhq_fused_wide.hip", "dhq_float.hip",
-           "dhq_fused_two_sided.hip"]
+           "dhq_fused_two_sided.hip", "dhq_fused_pair.hip"]
 HEADERS = ["dhq_internal.h", "dhq_device.h", "dhq_fused_common.h"]
 
 

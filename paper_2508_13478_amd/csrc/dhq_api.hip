@@ -141,6 +141,7 @@ extern "C" void dhq_free(dhq_model *m)
     if (m->dyn_params) (void)hipFree(m->dyn_params);
     dhq_fused_destroy(m->fused);
     dhq_wide_destroy(m->wide);
+    dhq_pair_destroy(m->pair);
     dhq_float_destroy(m->flt);
     dhq_fused2_destroy(m->fused2);
     delete m;
@@ -412,6 +413,7 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
     if (rc == DHQ_OK) rc = scratch_on_device(m->device, &m->scratch);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
+    if (rc == DHQ_OK && !m->rot_out) rc = dhq_pair_create(m, &m->pair);
     if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
@@ -448,6 +450,7 @@ static int update_fused_scales(dhq_model *m)
     m->fused_sine_ok = sine_range_ok_static(m);
     int rc = dhq_fused_update_scales(m, m->fused);
     if (rc == DHQ_OK) rc = dhq_wide_update_scales(m, m->wide);
+    if (rc == DHQ_OK) rc = dhq_pair_update_scales(m, m->pair);
     if (rc == DHQ_OK) rc = dhq_fused2_update_scales(m, m->fused2);
     return rc;
 }
@@ -487,6 +490,14 @@ extern "C" int dhq_has_fused(const dhq_model *m)
     if (!m) return DHQ_EINVAL;
     if (m->flt) return (dhq_float_has_fused(m->flt) && m->fused_sine_ok) ? 1 : 0;
     return ((m->fused || m->wide || m->fused2) && (!m->have_scales || m->fused_sine_ok)) ? 1 : 0;
+}
+
+extern "C" int dhq_select_wide_kernel(dhq_model *m, int32_t which)
+{
+    if (!m || which < 0 || which > 2) return DHQ_EINVAL;
+    if (!m->wide || !m->pair) return DHQ_EUNSUPPORTED;
+    m->wide_kernel = which;
+    return DHQ_OK;
 }
 
 // Per-layer constant of the quantizer kernel.
@@ -720,7 +731,8 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
     if (path != DHQ_LAYERWISE && fused_ok) {
         const hipError_t e = m->fused2 ? dhq_fused2_launch(m->fused2, coords_dev, n, out_dev, st)
                              : m->fused ? dhq_fused_launch(m, coords_dev, n, out_dev, st)
-                                        : dhq_wide_launch(m->wide, coords_dev, n, out_dev, st);
+                             : dhq_use_pair(m) ? dhq_pair_launch(m->pair, coords_dev, n, out_dev, st)
+                                               : dhq_wide_launch(m->wide, coords_dev, n, out_dev, st);
         return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
     }
     const int K0 = m->dims[0], Mo = m->dims[m->n_layers];
@@ -836,7 +848,8 @@ extern "C" int dhq_forward_debug_fused(const dhq_model *m, const int8_t *codes_i
     hipStream_t st = (hipStream_t)stream;
     const hipError_t e = m->fused2 ? dhq_fused2_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st)
                          : m->fused ? dhq_fused_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st)
-                                    : dhq_wide_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st);
+                         : dhq_use_pair(m) ? dhq_pair_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st)
+                                           : dhq_wide_debug_launch(m, layer, codes_in_dev, n, xhat_dev, codes_out_dev, acc_dev, st);
     return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
 }
 

@@ -214,44 +214,6 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
     }
 }
 
-// A operand of the H_32 products: a lane supplies row c of H_32 at the eight contraction slots
-// 8 h + j of block kk, which stand for tile row 8 (v / 4) + 4 h + v % 4 with v = 8 kk + j (the row
-// lane half h holds in accumulator v), as binary16 +-1.
-__device__ __forceinline__ void fused_h32_operand(int c, int h, dhq_v4i (&hA)[2])
-{
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int v = 8 * kk + 2 * d;  // accumulators v and v + 1: consecutive tile rows
-            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
-            hA[kk][d] = (int)hm_h32_pair(c, row, row + 1);
-        }
-    }
-}
-
-// The coordinate vector of the input layer (fan-in <= 4): rotated and quantized into code dword 0.
-__device__ __forceinline__ int fused_input_codes(const float *__restrict__ coords, int64_t cl, int k0, int k0p, float inv, int qmax)
-{
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (k0 == 2) {
-        const float2 xy = *reinterpret_cast<const float2 *>(coords + cl * 2);
-        v[0] = xy.x; v[1] = xy.y;
-    } else {
-        for (int k = 0; k < k0; ++k) v[k] = coords[cl * k0 + k];
-    }
-    if (k0p >= 2) {
-        float a = v[0], b = v[1]; v[0] = a + b; v[1] = a - b;
-        a = v[2]; b = v[3]; v[2] = a + b; v[3] = a - b;
-    }
-    if (k0p == 4) {
-        float a = v[0], b = v[2]; v[0] = a + b; v[2] = a - b;
-        a = v[1]; b = v[3]; v[1] = a + b; v[3] = a - b;
-    }
-    return (int)dhq_pack4(dhq_quant_bits(v[0], inv, qmax), dhq_quant_bits(v[1], inv, qmax),
-                          dhq_quant_bits(v[2], inv, qmax), dhq_quant_bits(v[3], inv, qmax));
-}
-
 // The stages of the transform over the tile index: plain register add/sub.
 template <int NT>
 __device__ __forceinline__ void fused_tile_stages(dhq_v16f (&xt)[NT])

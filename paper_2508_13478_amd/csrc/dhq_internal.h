@@ -44,6 +44,7 @@ struct dhq_fused_plan;  // defined in dhq_fused.hip
 struct dhq_wide_plan;   // defined in dhq_fused_wide.hip
 struct dhq_float_plan;  // defined in dhq_float.hip
 struct dhq_fused2_plan; // defined in dhq_fused_two_sided.hip
+struct dhq_pair_plan;   // defined in dhq_fused_pair.hip
 
 struct dhq_model {
     int n_layers = 0;
@@ -74,7 +75,9 @@ struct dhq_model {
     unsigned *dyn_absmax = nullptr;  // DHQ_MAX_LAYERS absmax words, then 2 x DHQ_ABSMAX_PARTIALS floats of scratch
     float *dyn_params = nullptr;     // DHQ_MAX_LAYERS x 3
     dhq_fused_plan *fused = nullptr;  // hidden width 32..256; null if the shape has no such kernel
-    dhq_wide_plan *wide = nullptr;    // hidden width 512
+    dhq_wide_plan *wide = nullptr;    // hidden width 512, one wave per SIMD
+    dhq_pair_plan *pair = nullptr;    // hidden width 512, two waves per SIMD that split the features
+    int wide_kernel = 0;              // which of the two runs: 0 the default, 1 one wave, 2 two waves (dhq_select_wide_kernel)
     dhq_float_plan *flt = nullptr;    // floating-point activations (DHQ_W8A32 / DHQ_W32A32)
     dhq_fused2_plan *fused2 = nullptr;  // two-sided variant, hidden width 32..256, fan-out <= 4
     int device = 0;
@@ -188,6 +191,20 @@ int dhq_wide_update_scales(const dhq_model *m, dhq_wide_plan *plan);
 hipError_t dhq_wide_launch(const dhq_wide_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
 
 
+// Hidden width 512 on two waves per SIMD (defined in dhq_fused_pair.hip); same contract.
+int dhq_pair_create(const dhq_model *m, dhq_pair_plan **plan);
+void dhq_pair_destroy(dhq_pair_plan *plan);
+int dhq_pair_update_scales(const dhq_model *m, dhq_pair_plan *plan);
+hipError_t dhq_pair_launch(const dhq_pair_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
+// Which width-512 kernel a model runs at the moment.
+#define DHQ_WIDE_DEFAULT_TWO_WAVES 1
+static inline bool dhq_use_pair(const dhq_model *m)
+{
+    if (!m->pair) return false;
+    if (!m->wide) return true;
+    return m->wide_kernel == 2 || (m->wide_kernel == 0 && DHQ_WIDE_DEFAULT_TWO_WAVES);
+}
+
 // Two-sided variant, whole network in one kernel (defined in dhq_fused_two_sided.hip); same
 // contract as the dhq_fused_* functions.
 int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan);
@@ -206,6 +223,8 @@ hipError_t dhq_fused2_dynamic_launch(const dhq_model *m, const float *coords, in
 hipError_t dhq_fused_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
                                   int32_t *acc, hipStream_t st);
 hipError_t dhq_wide_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
+                                 int32_t *acc, hipStream_t st);
+hipError_t dhq_pair_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
                                  int32_t *acc, hipStream_t st);
 hipError_t dhq_fused2_debug_launch(const dhq_model *m, int layer, const int8_t *codes_in, int64_t n, float *xhat, int8_t *codes_out,
                                    int32_t *acc, hipStream_t st);

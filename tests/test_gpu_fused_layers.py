@@ -62,8 +62,9 @@ def _sample(side, rows, seed):
     return grid[idx]
 
 
-# name, dims, grid side, bits, two-sided, wavelet spread, rows (not a multiple of any tile size)
-CASES = [
+# name, dims, grid side, bits, two-sided, wavelet spread, rows (not a multiple of any tile size);
+# hidden width 512 has two whole-network kernels (dhq_select_wide_kernel): every such case runs on both
+_CASES = [
     ("C1", synth.WORKLOADS["C1"].dims, 64, 8, False, None, 4096),
     ("C2", synth.WORKLOADS["C2"].dims, 256, 8, False, None, 8192 + 77),
     ("C4-4bit", synth.WORKLOADS["C4"].dims, 1024, 4, False, None, 4096 + 33),
@@ -76,10 +77,17 @@ CASES = [
     ("C2-wavelet", synth.WORKLOADS["C2"].dims, 256, 8, False, 10.0, 4096 + 77),
     ("C5-wavelet", synth.WORKLOADS["C5"].dims, 2048, 8, False, 10.0, 1024 + 50),
 ]
+CASES = []
+for _c in _CASES:
+    if _c[1][1] == 512:
+        CASES.append((_c[0] + "-one-wave",) + _c[1:] + (1,))
+        CASES.append((_c[0] + "-two-waves",) + _c[1:] + (2,))
+    else:
+        CASES.append(_c + (0,))
 
 
-@pytest.mark.parametrize("name,dims,side,bits,two_sided,s0,rows", CASES, ids=[c[0] for c in CASES])
-def test_fused_layer_teacher_forced(name, dims, side, bits, two_sided, s0, rows):
+@pytest.mark.parametrize("name,dims,side,bits,two_sided,s0,rows,wide_kernel", CASES, ids=[c[0] for c in CASES])
+def test_fused_layer_teacher_forced(name, dims, side, bits, two_sided, s0, rows, wide_kernel):
     import torch
     dims = list(dims)
     seed = synth.WORKLOADS[name.split("-")[0]].seed if name.split("-")[0] in synth.WORKLOADS else 0x5EED
@@ -91,6 +99,8 @@ def test_fused_layer_teacher_forced(name, dims, side, bits, two_sided, s0, rows)
     model = dhq.Model(dims, 30.0, W, b, bits, bits, mode=mode, wavelet_s0=s0)
     model.set_act_scales(net.s_a)
     assert model.has_fused()
+    if wide_kernel:
+        model.select_wide_kernel(wide_kernel)
     L = len(dims) - 1
     qm = o.qmax(bits)
     total_codes = total_diff = 0

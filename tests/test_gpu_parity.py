@@ -344,12 +344,14 @@ def test_forward_fused(name):
     assert np.array_equal(a, c)
 
 
-def test_forward_fused_width_512():
+@pytest.mark.parametrize("wide_kernel", [1, 2], ids=["one-wave", "two-waves"])
+def test_forward_fused_width_512(wide_kernel):
     """The C5 network (hidden width 512, six sine layers) on a strided sample of its grid:
-    the fused kernel for wide layers against the oracle and against the layer-by-layer path."""
-    _say("forward fused width 512")
+    each of the two fused kernels for wide layers against the oracle and against the layer-by-layer path."""
+    _say(f"forward fused width 512, kernel {wide_kernel}")
     cs = case("C5", stride=811)          # 5172 coordinates: 40 full tiles of 128 and a ragged one
     assert cs.model.has_fused()
+    cs.model.select_wide_kernel(wide_kernel)
     for l in range(len(cs.dims) - 1):
         assert np.array_equal(cs.model.weight_codes(l), cs.net.Wq[l]), f"layer {l}"
     a = _check_forward(cs, dhq.DHQ_FUSED, "fused-512")
@@ -370,10 +372,11 @@ def test_forward_fused_width_512():
         _say(f"  layer {l}: code mismatch rate {rate:.2e} max {mx}")
         assert rate <= CODE_RATE and mx <= 1
         assert np.array_equal(acc.cpu().numpy(), int_matmul(codes.cpu().numpy(), cs.net.Wq[l]))
+    cs.model.select_wide_kernel(0)   # the cached model goes back to the library's default
 
 
-@pytest.mark.parametrize("name,bits", [("C3", 8), ("C4", 4), ("C4", 6), ("C4", 8), ("C5", 8)])
-def test_full_grid_sampled_outputs(name, bits):
+@pytest.mark.parametrize("name,bits,wide_kernel", [("C3", 8, 0), ("C4", 4, 0), ("C4", 6, 0), ("C4", 8, 0), ("C5", 8, 1), ("C5", 8, 2)])
+def test_full_grid_sampled_outputs(name, bits, wide_kernel):
     """The full-size grids, in the launch configuration the benchmark times (one fused launch
     over the whole grid, static scales).  The oracle cannot run millions of coordinates, but
     with static scales every coordinate is independent: it calibrates the scales on a strided
@@ -388,6 +391,8 @@ def test_full_grid_sampled_outputs(name, bits):
     model = dhq.Model(wl.dims, wl.omega0, W, b, bits, bits)
     model.set_act_scales(net.s_a)
     assert model.has_fused()
+    if wide_kernel:
+        model.select_wide_kernel(wide_kernel)   # hidden width 512: the kernel with one wave per SIMD, then the one with two
     x = _dev(coords)
     out = model.forward(x, flags=dhq.DHQ_FUSED)
     torch.cuda.synchronize()
