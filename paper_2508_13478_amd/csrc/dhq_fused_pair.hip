@@ -29,8 +29,9 @@
 // wave-uniform run-time value: an LDS or fragment offset, the H_32 operand, one sign.
 //
 // LDS: two 32 KiB weight buffers (a 512 x 512 layer is streamed in eight chunks, one M tile per
-// role each, copied global -> registers -> LDS by all eight waves while the previous chunk is
-// consumed) and a 64 KiB exchange area.  Biases are read from device memory (L1-resident).
+// role each, copied straight from device memory into LDS by all eight waves while the previous
+// chunk is consumed), a 64 KiB exchange area and three 2 KiB bias blocks (the input layer's, and
+// those of the hidden / output layers by layer parity, each copied in while the layer before runs).
 #include <math.h>
 #include <string.h>
 
@@ -49,6 +50,7 @@
 #define PAIR_KB 16             // k blocks of a hidden layer
 #define PAIR_BUF 32768         // bytes per weight buffer = bytes per chunk
 #define PAIR_X 65536           // exchange area
+#define PAIR_BIAS (2 * PAIR_BUF + PAIR_X)  // LDS offset of the bias blocks, 2 KiB each: [layer parity 0, 1, input layer]
 #define PAIR_PF 2              // LDS prefetch distance of the A fragments, in MFMAs
 #define PAIR_EARLY 4           // tiles whose outgoing rows leave during the GEMM phase
 
@@ -84,8 +86,40 @@ struct pair_stream {
     unsigned char *lds;        // buffer 0, buffer 1, exchange area
     int wave, lane, role, grp;
     const unsigned char *cp_src;  // chunk being copied in: this wave's first block (uniform)
-    unsigned char *cp_dst;        // where this lane's 16 bytes of that block go
+    unsigned cp_dst;              // LDS address of that block in the buffer it goes to (uniform)
+    unsigned voff;                // lane * 16
 };
+
+__device__ __forceinline__ unsigned pair_lds_addr(const unsigned char *p)
+{
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+
+// One KiB from device memory straight into LDS: lane i's 16 bytes go to LDS address dst + 16 i
+// (dst travels in M0).  Inline assembly for the reason given at fused_issue_copy: the kernel orders
+// these copies itself -- a destination is never read between the load and the "s_waitcnt vmcnt(0)" +
+// barrier that precedes its first use -- and loads the compiler does not know about can only make its
+// own vmcnt waits longer, never shorter.
+__device__ __forceinline__ void pair_copy_kib(const pair_stream &S, const unsigned char *src, unsigned dst)
+{
+    // the source is wave-uniform; its halves go through readfirstlane so that the operand is a scalar register pair
+    // whatever the compiler knows about it
+    const unsigned long long a = (unsigned long long)src;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    const unsigned long long sa = ((unsigned long long)hi << 32) | lo;
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(dst);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(S.voff), "s"(sa), "s"(m0v) : "memory", "m0");
+}
+
+// LDS block of layer l's biases.
+__device__ __forceinline__ int pair_bias_slot(int l) { return l == 0 ? 2 : (l & 1); }
+// Layer l's biases (2 KiB) into their block: waves 0 and 1 move one KiB each.
+__device__ __forceinline__ void pair_copy_bias(const pair_stream &S, int l)
+{
+    if (S.wave < 2)
+        pair_copy_kib(S, S.A->blob + S.A->bias_off + (size_t)l * 2048 + S.wave * 1024,
+                      pair_lds_addr(S.lds) + PAIR_BIAS + pair_bias_slot(l) * 2048 + S.wave * 1024);
+}
 
 // Entering chunk `cc` (a running count; chunk cc lives in buffer cc & 1): every wave has written
 // its share of it (the wait, then the barrier) and nobody reads chunk cc - 1 any more, so chunk
@@ -96,19 +130,14 @@ __device__ __forceinline__ void pair_enter_chunk(pair_stream &S, int cc)
     __syncthreads();
     const int j = (cc + 1) % S.A->n_chunks;
     S.cp_src = S.A->blob + (size_t)j * PAIR_BUF + S.wave * 1024;
-    S.cp_dst = S.lds + ((cc + 1) & 1) * PAIR_BUF + S.wave * 1024 + S.lane * 16;
+    S.cp_dst = pair_lds_addr(S.lds) + ((cc + 1) & 1) * PAIR_BUF + S.wave * 1024;
 }
 
 // Slot i of a chunk's copy moves the 1 KiB block wave + 8 i (i = 0..3: 32 blocks, eight waves).
 template <int I>
-__device__ __forceinline__ dhq_v4i pair_copy_load(const pair_stream &S)
+__device__ __forceinline__ void pair_copy_slot(const pair_stream &S)
 {
-    return reinterpret_cast<const dhq_v4i *>(S.cp_src + I * 8192)[S.lane];
-}
-template <int I>
-__device__ __forceinline__ void pair_copy_store(const pair_stream &S, const dhq_v4i &v)
-{
-    *reinterpret_cast<dhq_v4i *>(S.cp_dst + I * 8192) = v;
+    pair_copy_kib(S, S.cp_src + I * 8192, S.cp_dst + I * 8192);
 }
 
 // Where wave w parks the outgoing half of tile t (slot t & 3), as two float4 per lane.
@@ -124,8 +153,8 @@ struct pair_ctx {
     dhq_v16f (&y)[PAIR_NT];       // H_32 products of this wave's tiles
     const dhq_v4i (&hA)[2];       // H_32 (rows in this role's order) as an MFMA A operand, two k blocks
     const unsigned char *bufs[2];
-    const float4 *bias;           // this layer's biases, this wave's first tile, lane half folded in
-    int cc;
+    const float4 *bias;           // this layer's biases in LDS, this wave's first tile, lane half folded in
+    int cc, layer;
     float c1, c2;
     dhq_v4i fr[PAIR_PF + 1];
     float4 bq[3];
@@ -135,7 +164,6 @@ struct pair_ctx {
     float ex, ey;
     float ar[4];
     float er[2];
-    dhq_v4i st[2];                // staging of the weight copy
     __device__ __forceinline__ pair_ctx(pair_stream &S_, dhq_v4i (&cd_)[PAIR_KB], dhq_v16f (&y_)[PAIR_NT], const dhq_v4i (&hA_)[2])
         : S(S_), cd(cd_), y(y_), hA(hA_)
     {
@@ -172,16 +200,14 @@ __device__ __forceinline__ void pair_send(pair_ctx<ACTK> &C)
 }
 
 // The weight copy that runs while a hidden layer's chunk is consumed, by steps since the chunk was
-// entered: two staging tuples, each used twice.
+// entered.
 template <int REL, int ACTK>
 __device__ __forceinline__ void pair_copy_rel(pair_ctx<ACTK> &C)
 {
-    if constexpr (REL == 1) C.st[0] = pair_copy_load<0>(C.S);
-    if constexpr (REL == 2) C.st[1] = pair_copy_load<1>(C.S);
-    if constexpr (REL == 7) { pair_copy_store<0>(C.S, C.st[0]); C.st[0] = pair_copy_load<2>(C.S); }
-    if constexpr (REL == 8) { pair_copy_store<1>(C.S, C.st[1]); C.st[1] = pair_copy_load<3>(C.S); }
-    if constexpr (REL == 13) pair_copy_store<2>(C.S, C.st[0]);
-    if constexpr (REL == 14) pair_copy_store<3>(C.S, C.st[1]);
+    if constexpr (REL == 1) pair_copy_slot<0>(C.S);
+    if constexpr (REL == 3) pair_copy_slot<1>(C.S);
+    if constexpr (REL == 5) pair_copy_slot<2>(C.S);
+    if constexpr (REL == 7) pair_copy_slot<3>(C.S);
 }
 
 // One step of a hidden layer's GEMM + epilogue + H_32 pipeline (every step is its own template
@@ -205,6 +231,7 @@ __device__ __forceinline__ void pair_step(pair_ctx<ACTK> &C)
         }
     }
     if constexpr (G + PF >= 0 && G + PF < NM) pair_copy_rel<(G + PF) % PAIR_KB>(C);
+    if constexpr (G == 9) pair_copy_bias(C.S, C.layer + 1);  // the next layer's biases; in place long before its first step
     if constexpr (G >= 0 && G < NM) {
         constexpr int t = G / PAIR_KB, kb = G % PAIR_KB;
         if constexpr (kb == 0) {
@@ -267,7 +294,8 @@ __device__ __forceinline__ void pair_hidden(pair_stream &S, int &cc, int layer, 
     C.c1 = S.A->c1[layer];
     C.c2 = S.A->c2;
     C.ex = C.ey = 0.f;
-    C.bias = reinterpret_cast<const float4 *>(S.A->blob + S.A->bias_off) + ((size_t)layer * 16 + S.role * 8) * 8 + h;
+    C.layer = layer;
+    C.bias = reinterpret_cast<const float4 *>(S.lds + PAIR_BIAS + pair_bias_slot(layer) * 2048) + S.role * 64 + h;
     pair_enter_chunk(S, cc);
     {
         const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(S.lds + 2 * PAIR_BUF + S.grp * 16384) + S.lane;
@@ -289,12 +317,11 @@ __device__ __forceinline__ void pair_step0(pair_ctx<ACTK> &C, int h)
 {
     constexpr int PF = PAIR_PF;
     if constexpr (G + PF < PAIR_NT) C.fr[(G + PF) % (PF + 1)] = reinterpret_cast<const dhq_v4i *>(C.bufs[0])[(G + PF) * 64 + C.S.lane];
-    if constexpr (G == 0) { C.st[0] = pair_copy_load<0>(C.S); C.st[1] = pair_copy_load<1>(C.S); }
-    if constexpr (G == 3) {
-        pair_copy_store<0>(C.S, C.st[0]); pair_copy_store<1>(C.S, C.st[1]);
-        C.st[0] = pair_copy_load<2>(C.S); C.st[1] = pair_copy_load<3>(C.S);
-    }
-    if constexpr (G == 6) { pair_copy_store<2>(C.S, C.st[0]); pair_copy_store<3>(C.S, C.st[1]); }
+    if constexpr (G == 0) pair_copy_slot<0>(C.S);
+    if constexpr (G == 1) pair_copy_slot<1>(C.S);
+    if constexpr (G == 2) pair_copy_slot<2>(C.S);
+    if constexpr (G == 3) pair_copy_slot<3>(C.S);
+    if constexpr (G == 4) pair_copy_bias(C.S, 1);
     if constexpr (G < PAIR_NT) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) C.acc[0][v] = 0;
@@ -339,7 +366,8 @@ __device__ __forceinline__ void pair_input_layer(pair_stream &S, int &cc, dhq_v4
     C.cc = cc;
     C.c1 = S.A->c1[0];
     C.c2 = S.A->c2;
-    C.bias = reinterpret_cast<const float4 *>(S.A->blob + S.A->bias_off) + (size_t)(S.role * 8) * 8 + h;
+    C.layer = 0;
+    C.bias = reinterpret_cast<const float4 *>(S.lds + PAIR_BIAS + pair_bias_slot(0) * 2048) + S.role * 64 + h;
     pair_enter_chunk(S, cc);
     C.bufs[0] = S.lds + (cc & 1) * PAIR_BUF + S.role * 8192;  // fragments [tile 0..15], 1 KiB each
     C.bufs[1] = C.bufs[0];
@@ -467,7 +495,8 @@ __device__ __forceinline__ void pair_stream_init(pair_stream &S, const pair_args
     S.role = S.wave >> 2;
     S.grp = S.wave & 3;
     S.cp_src = A->blob;
-    S.cp_dst = lds;
+    S.cp_dst = pair_lds_addr(lds);
+    S.voff = (unsigned)lane * 16;
 }
 
 // Copies chunk j into buffer `buf` right now (the first chunk of a kernel has nobody to copy it in the background).
@@ -497,6 +526,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
     pair_stream_init(S, &A, lds, wave, lane);
     int cc = 0;
     pair_copy_now(S, 0, 0);
+    pair_copy_bias(S, 0);
 
     dhq_v4i hA[2];
     pair_h32_operand(c, h, S.role, hA);
@@ -524,7 +554,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
         {
             pair_enter_chunk(S, cc);
             const unsigned char *buf = lds + (cc & 1) * PAIR_BUF;
-            dhq_v4i s0 = pair_copy_load<0>(S), s1 = pair_copy_load<1>(S);
+            pair_copy_slot<0>(S); pair_copy_slot<1>(S); pair_copy_slot<2>(S); pair_copy_slot<3>(S);
+            pair_copy_bias(S, 0);
             if (S.role == 0) {
                 const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(lds + 2 * PAIR_BUF + S.grp * 16384) + lane;
                 const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(buf);
@@ -533,7 +564,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
                 for (int v = 0; v < 16; ++v) acc[v] = 0;
 #pragma unroll
                 for (int kb = 0; kb < PAIR_KB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wA[kb * 64 + lane], src[kb * 64], acc, 0, 0, 0);
-                const float *wB = reinterpret_cast<const float *>(A.blob + A.bias_off) + (size_t)(L - 1) * 512;
+                const float *wB = reinterpret_cast<const float *>(lds + PAIR_BIAS + pair_bias_slot(L - 1) * 2048);
                 const float c1 = A.c1[L - 1];
                 if (valid) {
 #pragma unroll
@@ -543,9 +574,6 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
                     }
                 }
             }
-            pair_copy_store<0>(S, s0); pair_copy_store<1>(S, s1);
-            s0 = pair_copy_load<2>(S); s1 = pair_copy_load<3>(S);
-            pair_copy_store<2>(S, s0); pair_copy_store<3>(S, s1);
             cc += 1;
         }
     }
@@ -615,6 +643,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel_debug(cons
     pair_stream_init(S, &A, lds, wave, lane);
     int cc = cc0;
     pair_copy_now(S, cc0, cc0 & 1);
+    pair_copy_bias(S, l);
     dhq_v4i hA[2];
     pair_h32_operand(c, h, S.role, hA);
     const int64_t ci = (int64_t)blockIdx.x * PAIR_TILE + S.grp * 32 + c;
@@ -727,7 +756,7 @@ int dhq_pair_create(const dhq_model *m, dhq_pair_plan **plan_out)
     P->args.bias_off = (uint32_t)bias_off;
     P->args.c2 = dhq_hidden_act(m).c2;
     P->act_kind = m->act_kind;
-    P->lds_bytes = (size_t)2 * PAIR_BUF + PAIR_X;
+    P->lds_bytes = (size_t)PAIR_BIAS + 3 * 2048;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
         (void)hipFree(P->blob_dev);
