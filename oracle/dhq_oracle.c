@@ -40,9 +40,16 @@
  * Wavelet activation: the real part of numpy's complex exponential, the
  * zero-spread case against the sine network with shifted biases, evenness,
  * zeros and envelope.
+ * Complex-valued wavelet layers (the WIRE architecture as published, see
+ * dhqo_activation_complex): the activation against numpy's complex
+ * exponential and against its expansion into real functions, the
+ * real-valued matrices against numpy's complex matrix product, the whole
+ * un-quantized network against a complex-valued numpy network, a purely
+ * real pre-activation against the real wavelet.
  * Parity unpinned: absolute image quality (Table 1) -- it needs the paper's
  * images and trained weights.
  */
+#include <complex.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -239,12 +246,74 @@ int dhqo_igemm(const int8_t *q, const int8_t *w, int64_t N, int M, int Kp, int32
 #define DHQO_ACT_NONE 0
 #define DHQO_ACT_SINE 1
 #define DHQO_ACT_GABOR 2
+#define DHQO_ACT_GABOR_COMPLEX 3
 
 double dhqo_activation(double y, int act, double omega0, double s0)
 {
     if (act == DHQO_ACT_SINE) return sin(omega0 * y);
     if (act == DHQO_ACT_GABOR) return cos(omega0 * y) * exp(-(s0 * y) * (s0 * y));
     return y;
+}
+
+/*
+ * DHQO_ACT_GABOR_COMPLEX: the WIRE architecture as its publication has it (Sec. 4.1 / Table 1 name
+ * it and cite that publication): hidden features are complex numbers, the weights of every
+ * layer after the first are complex, the activation is the complex Gabor wavelet
+ *     a = exp(j omega0 y - |s0 y|^2)          y = yr + j yi complex,
+ * and the network's output is the real part of the last (linear) layer.  Written out with the
+ * C library's complex exponential: this is the definition, not an expansion of it.
+ * Reading (the paper says nothing about complex numbers): such a network is run as a real one
+ * of twice the width -- feature 2m holds Re, feature 2m + 1 holds Im, a complex weight w
+ * becomes the 2 x 2 block [[Re w, -Im w], [Im w, Re w]] (dhqo_complex_layer_to_real) -- so that
+ * the rotation of Eq. 3-5, the quantizer and the integer product apply to it unchanged, and only
+ * the activation acts on pairs of features.
+ */
+void dhqo_activation_complex(double yr, double yi, double omega0, double s0, double *ar, double *ai)
+{
+    const double complex y = yr + yi * I;
+    const double mag = cabs(s0 * y);
+    const double complex a = cexp(I * omega0 * y - mag * mag);
+    *ar = creal(a);
+    *ai = cimag(a);
+}
+
+/*
+ * A layer with complex weights W = Wre + j Wim (M x K) and bias b = bre + j bim as the real layer
+ * that computes the same thing on interleaved (Re, Im) features:
+ *   in_complex  != 0: the input has K complex features = 2 K real ones (else K real ones);
+ *   out_complex != 0: the output has M complex features = 2 M real ones; else the output is
+ *                     the real part (the network's last layer), M real features.
+ * Wim / bim may be NULL (a real-valued layer, e.g. the first one).  W gets
+ * (out_complex ? 2 M : M) x (in_complex ? 2 K : K) floats, b as many as W has rows.
+ *   Re (w x) = Re w Re x - Im w Im x        Im (w x) = Im w Re x + Re w Im x
+ */
+int dhqo_complex_layer_to_real(const float *Wre, const float *Wim, const float *bre, const float *bim, int M, int K,
+                               int in_complex, int out_complex, float *W, float *b)
+{
+    if (!Wre || !bre || !W || !b || M < 1 || K < 1) return DHQO_EINVAL;
+    const int cols = in_complex ? 2 * K : K;
+    for (int m = 0; m < M; ++m) {
+        float *row_re = W + (size_t)(out_complex ? 2 * m : m) * cols;
+        float *row_im = out_complex ? row_re + cols : NULL;
+        for (int k = 0; k < K; ++k) {
+            const float wr = Wre[(size_t)m * K + k], wi = Wim ? Wim[(size_t)m * K + k] : 0.0f;
+            if (in_complex) {
+                row_re[2 * k] = wr;
+                row_re[2 * k + 1] = -wi;
+                if (row_im) { row_im[2 * k] = wi; row_im[2 * k + 1] = wr; }
+            } else {
+                row_re[k] = wr;
+                if (row_im) row_im[k] = wi;
+            }
+        }
+        if (out_complex) {
+            b[2 * m] = bre[m];
+            b[2 * m + 1] = bim ? bim[m] : 0.0f;
+        } else {
+            b[m] = bre[m];
+        }
+    }
+    return DHQO_OK;
 }
 
 /*
@@ -257,6 +326,20 @@ int dhqo_epilogue(const int32_t *acc, int64_t N, int M, float s_a, float s_w,
 {
     if (!acc || !b || !out) return DHQO_EINVAL;
     const double sc = (double)s_a * (double)s_w;
+    if (act == DHQO_ACT_GABOR_COMPLEX) {
+        if (M % 2) return DHQO_EINVAL;
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < N; ++i)
+            for (int j = 0; j < M; j += 2) {
+                double yr = (double)acc[i * M + j] * sc + (double)b[j];
+                double yi = (double)acc[i * M + j + 1] * sc + (double)b[j + 1];
+                double ar, ai;
+                dhqo_activation_complex(yr, yi, (double)omega0, (double)s0, &ar, &ai);
+                out[i * M + j] = (float)ar;
+                out[i * M + j + 1] = (float)ai;
+            }
+        return DHQO_OK;
+    }
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < N; ++i)
         for (int j = 0; j < M; ++j) {
@@ -464,11 +547,20 @@ int dhqo_layer_two_sided(const float *a_in, int64_t N, int K, int M, const int8_
     if (rc) goto done;
     {
         const double sc = (double)*s_a * (double)s_w / sqrt((double)Mp);
+        if (act == DHQO_ACT_GABOR_COMPLEX && M % 2) { rc = DHQO_EINVAL; goto done; }
 #pragma omp parallel for schedule(static)
         for (int64_t i = 0; i < N; ++i)
             for (int j = 0; j < M; ++j) {
                 double y = (double)z[i * Mp + j] * sc + (double)bias[j];
-                out[i * M + j] = (float)dhqo_activation(y, act, (double)omega0, (double)s0);
+                if (act == DHQO_ACT_GABOR_COMPLEX) {
+                    if (j % 2) continue;  /* the pair (j, j + 1) was taken at j */
+                    double yi = (double)z[i * Mp + j + 1] * sc + (double)bias[j + 1], ar, ai;
+                    dhqo_activation_complex(y, yi, (double)omega0, (double)s0, &ar, &ai);
+                    out[i * M + j] = (float)ar;
+                    out[i * M + j + 1] = (float)ai;
+                } else {
+                    out[i * M + j] = (float)dhqo_activation(y, act, (double)omega0, (double)s0);
+                }
             }
     }
 done:
@@ -547,6 +639,8 @@ int dhqo_mlp_float(int n_layers, const int32_t *dims, int act, float omega0, flo
                    float *out32)
 {
     if (n_layers < 1 || !dims || !W || !bias || !coords || N < 0) return DHQO_EINVAL;
+    if (act == DHQO_ACT_GABOR_COMPLEX)
+        for (int l = 1; l < n_layers; ++l) if (dims[l] % 2) return DHQO_EINVAL;
     int maxw = 0;
     for (int l = 0; l <= n_layers; ++l) if (dims[l] > maxw) maxw = dims[l];
     int fail = 0;
@@ -577,11 +671,28 @@ int dhqo_mlp_float(int n_layers, const int32_t *dims, int act, float omega0, flo
                         }
                         s += (double)bias[l][j];
                         sf += bias[l][j];
-                        y[j] = last ? s : dhqo_activation(s, act, (double)omega0, (double)s0);
-                        if (last) yf[j] = sf;
-                        else if (act == DHQO_ACT_GABOR) yf[j] = cosf(omega0 * sf) * expf(-(s0 * sf) * (s0 * sf));
-                        else if (act == DHQO_ACT_SINE) yf[j] = sinf(omega0 * sf);
-                        else yf[j] = sf;
+                        y[j] = s;
+                        yf[j] = sf;
+                    }
+                    if (!last && act == DHQO_ACT_GABOR_COMPLEX) {
+                        /* pairs (2m, 2m + 1) = (Re, Im); an odd width is refused by the caller's check below */
+                        for (int j = 0; j + 1 < M; j += 2) {
+                            double ar, ai;
+                            dhqo_activation_complex(y[j], y[j + 1], (double)omega0, (double)s0, &ar, &ai);
+                            const float complex zf = yf[j] + yf[j + 1] * I;
+                            const float mf = cabsf(s0 * zf);
+                            const float complex af = cexpf(I * omega0 * zf - mf * mf);
+                            y[j] = ar; y[j + 1] = ai;
+                            yf[j] = crealf(af); yf[j + 1] = cimagf(af);
+                        }
+                    } else if (!last) {
+                        for (int j = 0; j < M; ++j) {
+                            const double s = y[j];
+                            const float sf = yf[j];
+                            y[j] = dhqo_activation(s, act, (double)omega0, (double)s0);
+                            if (act == DHQO_ACT_GABOR) yf[j] = cosf(omega0 * sf) * expf(-(s0 * sf) * (s0 * sf));
+                            else if (act == DHQO_ACT_SINE) yf[j] = sinf(omega0 * sf);
+                        }
                     }
                     memcpy(a, y, sizeof(double) * (size_t)M);
                     memcpy(af, yf, sizeof(float) * (size_t)M);

@@ -63,6 +63,9 @@ def _declare(L: C.CDLL) -> None:
     L.dhqo_igemm.argtypes = [_i8p, _i8p, C.c_int64, C.c_int, C.c_int, _i32p]
     L.dhqo_activation.argtypes = [C.c_double, C.c_int, C.c_double, C.c_double]
     L.dhqo_activation.restype = C.c_double
+    L.dhqo_activation_complex.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, _dp, _dp]
+    L.dhqo_activation_complex.restype = None
+    L.dhqo_complex_layer_to_real.argtypes = [_fp, _fp, _fp, _fp, C.c_int, C.c_int, C.c_int, C.c_int, _fp, _fp]
     L.dhqo_epilogue.argtypes = [_i32p, C.c_int64, C.c_int, C.c_float, C.c_float, _fp, C.c_int,
                                 C.c_float, C.c_float, _fp]
     L.dhqo_quantize_weights.argtypes = [_fp, C.c_int, C.c_int, C.c_int, _i8p, _fp, _dp]
@@ -161,15 +164,58 @@ def igemm(q: np.ndarray, w: np.ndarray) -> np.ndarray:
     return acc
 
 
-ACT_NONE, ACT_SINE, ACT_GABOR = 0, 1, 2
+ACT_NONE, ACT_SINE, ACT_GABOR, ACT_GABOR_COMPLEX = 0, 1, 2, 3
+
+
+class ComplexSpread(float):
+    """A wavelet spread s0 that also says: the layers are complex-valued (features interleaved
+    as Re, Im; the activation is the complex Gabor wavelet on pairs).  Passed wherever a real
+    wavelet's spread is passed as `gabor_s0`."""
 
 
 def _act(apply_act: bool, gabor_s0: Optional[float]):
     """(activation code, spread) of a layer: none for the output layer, else the sine, or the
-    wavelet cos(omega0 y) exp(-(s0 y)^2) when a spread s0 is given."""
+    wavelet cos(omega0 y) exp(-(s0 y)^2) when a spread s0 is given, or the complex wavelet on
+    (Re, Im) pairs when the spread is a ComplexSpread."""
     if not apply_act:
         return ACT_NONE, 0.0
+    if isinstance(gabor_s0, ComplexSpread):
+        return ACT_GABOR_COMPLEX, float(gabor_s0)
     return (ACT_SINE, 0.0) if gabor_s0 is None else (ACT_GABOR, float(gabor_s0))
+
+
+def activation_complex(y: np.ndarray, omega0: float, s0: float) -> np.ndarray:
+    """The complex Gabor wavelet exp(j omega0 y - |s0 y|^2) of a complex array, in fp64."""
+    y = np.asarray(y, dtype=np.complex128)
+    out = np.empty(y.shape, dtype=np.complex128)
+    f = lib().dhqo_activation_complex
+    ar, ai = C.c_double(0), C.c_double(0)
+    for idx, v in np.ndenumerate(y):
+        f(float(v.real), float(v.imag), float(omega0), float(s0), C.byref(ar), C.byref(ai))
+        out[idx] = complex(ar.value, ai.value)
+    return out
+
+
+def complex_net_to_real(dims_c: Sequence[int], Wc: Sequence[np.ndarray], bc: Sequence[np.ndarray]):
+    """A network with complex weights (Wc[l] complex, dims_c[l+1] x dims_c[l]; real inputs, the real
+    part of the last layer as output) as the real network of interleaved (Re, Im) features that
+    computes the same thing.  Returns (dims, W, b) of that real network."""
+    L = len(dims_c) - 1
+    dims = [int(dims_c[0])] + [2 * int(d) for d in dims_c[1:-1]] + [int(dims_c[-1])]
+    W, b = [], []
+    for l in range(L):
+        M, K = int(dims_c[l + 1]), int(dims_c[l])
+        wre, wim = _c(np.real(Wc[l]), np.float32), _c(np.imag(Wc[l]), np.float32)
+        bre, bim = _c(np.real(bc[l]), np.float32), _c(np.imag(bc[l]), np.float32)
+        assert wre.shape == (M, K)
+        in_c, out_c = int(l > 0), int(l < L - 1)
+        Wl = np.empty((dims[l + 1], dims[l]), dtype=np.float32)
+        bl = np.empty(dims[l + 1], dtype=np.float32)
+        _check(lib().dhqo_complex_layer_to_real(_ptr(wre, _fp), _ptr(wim, _fp), _ptr(bre, _fp), _ptr(bim, _fp), M, K,
+                                                in_c, out_c, _ptr(Wl, _fp), _ptr(bl, _fp)), "complex_layer_to_real")
+        W.append(Wl)
+        b.append(bl)
+    return dims, W, b
 
 
 def activation(y: np.ndarray, omega0: float, gabor_s0: Optional[float] = None) -> np.ndarray:

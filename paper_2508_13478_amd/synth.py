@@ -68,6 +68,38 @@ def siren_init(dims: List[int], omega0: float, seed: int) -> Tuple[List[np.ndarr
     return W, b
 
 
+def wire_init(dims_c: List[int], omega0: float, seed: int) -> Tuple[List[np.ndarray], List[np.ndarray]]:
+    """Complex weights Wc[l] (dims_c[l+1] x dims_c[l], complex64) and biases bc[l] for a network
+    with complex-valued hidden features (the second architecture of the paper's Table 1): the
+    first layer real on [-1/2, 1/2] (real coordinates in), later layers with real and imaginary
+    parts each uniform on +-sqrt(3/fan_in)/omega0 (so that |w|^2 has the variance of the
+    real-valued initialisation above), biases likewise on +-1/sqrt(2 fan_in), the last layer's
+    bias real.  Draw order: Re W[0], Im W[0] (skipped for the first layer), Re b[0], Im b[0]
+    (skipped for the last layer), Re W[1], ..."""
+    W, b = [], []
+    pos = 0
+    L = len(dims_c) - 1
+    for l in range(L):
+        fan_in, fan_out = dims_c[l], dims_c[l + 1]
+        bound = 0.5 if l == 0 else float(np.sqrt(3.0 / fan_in) / omega0)
+        re = uniform(seed, pos, fan_out * fan_in, -bound, bound).reshape(fan_out, fan_in)
+        pos += fan_out * fan_in
+        im = np.zeros_like(re)
+        if l > 0:
+            im = uniform(seed, pos, fan_out * fan_in, -bound, bound).reshape(fan_out, fan_in)
+            pos += fan_out * fan_in
+        W.append((re + 1j * im).astype(np.complex64))
+        bb = float(1.0 / np.sqrt(2.0 * fan_in))
+        bre = uniform(seed, pos, fan_out, -bb, bb)
+        pos += fan_out
+        bim = np.zeros_like(bre)
+        if l < L - 1:
+            bim = uniform(seed, pos, fan_out, -bb, bb)
+            pos += fan_out
+        b.append((bre + 1j * bim).astype(np.complex64))
+    return W, b
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str

@@ -594,3 +594,143 @@ def test_wavelet_matches_complex_form_for_random_parameters():
         ref = np.real(np.exp(1j * w0 * y - np.abs(s0 * y) ** 2))
         assert np.abs(g - ref).max() <= 2e-15 and np.abs(g).max() <= 1.0
         assert np.array_equal(g, o.activation(-y, w0, s0))
+
+
+# ------------------------- complex-valued wavelet layers (Sec. 4.1, Table 1: WIRE as its publication has it)
+def _complex_numpy_net(dims_c, Wc, bc, x, omega0, s0):
+    """The network with complex weights, written with numpy's complex arithmetic: complex hidden
+    features, exp(j omega0 z - |s0 z|^2) after every layer but the last, real part out."""
+    a = x.astype(np.float64) + 0j
+    L = len(dims_c) - 1
+    for l in range(L):
+        z = a @ Wc[l].astype(np.complex128).T + bc[l].astype(np.complex128)
+        a = np.exp(1j * omega0 * z - np.abs(s0 * z) ** 2) if l < L - 1 else z
+    return a.real
+
+
+def test_complex_wavelet_against_numpy_and_its_expansion():
+    """exp(j w y - |s y|^2) of a complex y: numpy's complex exponential; the expansion into real functions
+    exp(-w yi - s^2 |y|^2) (cos w yr + j sin w yr) (what a real-valued implementation computes); its modulus;
+    a purely real y gives the real wavelet already pinned above as the real part and sin(w y) exp(-(s y)^2) as
+    the imaginary part; y = 0 gives 1."""
+    rng = np.random.default_rng(2508)
+    for _ in range(20):
+        w0, s0 = float(rng.uniform(0.5, 40.0)), float(rng.uniform(0.0, 12.0))
+        y = rng.uniform(-0.2, 0.2, size=32) + 1j * rng.uniform(-0.2, 0.2, size=32)
+        a = o.activation_complex(y, w0, s0)
+        ref = np.exp(1j * w0 * y - np.abs(s0 * y) ** 2)
+        assert np.abs(a - ref).max() <= 4e-15 * max(1.0, np.abs(ref).max())
+        mag = np.exp(-w0 * y.imag - s0 ** 2 * (y.real ** 2 + y.imag ** 2))
+        exp2 = mag * (np.cos(w0 * y.real) + 1j * np.sin(w0 * y.real))
+        assert np.abs(a - exp2).max() <= 1e-13 * max(1.0, mag.max())
+        assert np.abs(np.abs(a) - mag).max() <= 1e-13 * max(1.0, mag.max())
+        yr = y.real + 0j
+        ar = o.activation_complex(yr, w0, s0)
+        assert np.abs(ar.real - o.activation(yr.real, w0, s0)).max() <= 2e-15
+        assert np.abs(ar.imag - np.sin(w0 * yr.real) * np.exp(-(s0 * yr.real) ** 2)).max() <= 2e-15
+    assert o.activation_complex(np.zeros(1, complex), 30.0, 10.0)[0] == 1.0
+    # a positive imaginary part damps, a negative one amplifies: exp(-w yi)
+    up = o.activation_complex(np.array([0.05j, -0.05j]), 30.0, 0.0)
+    assert abs(up[0] - math.exp(-1.5)) <= 1e-15 and abs(up[1] - math.exp(1.5)) <= 1e-14
+
+
+@pytest.mark.parametrize("M,K", [(1, 1), (3, 5), (8, 2), (7, 7)])
+def test_complex_layers_as_real_matrices_are_numpy_complex_products(M, K):
+    """A complex layer written as a real one on interleaved (Re, Im) features against numpy's complex matrix
+    product: hidden layer (complex in, complex out), first layer (real in), last layer (real part out).  A wrong
+    sign or a transposed block changes the product (the weights are neither real nor symmetric)."""
+    rng = np.random.default_rng(100 * M + K)
+    Wc = (rng.normal(size=(M, K)) + 1j * rng.normal(size=(M, K))).astype(np.complex64)
+    bc = (rng.normal(size=M) + 1j * rng.normal(size=M)).astype(np.complex64)
+    x = (rng.normal(size=(9, K)) + 1j * rng.normal(size=(9, K)))
+    xi = np.stack([x.real, x.imag], axis=2).reshape(9, 2 * K)      # interleaved
+    z = x @ Wc.astype(np.complex128).T + bc.astype(np.complex128)
+    zi = np.stack([z.real, z.imag], axis=2).reshape(9, 2 * M)
+    # hidden: dims_c = [in, K, M, out] -> layer 1 of a four-entry network is complex -> complex
+    dims, W, b = o.complex_net_to_real([2, K, M, 3], [np.zeros((K, 2), np.complex64), Wc, np.zeros((3, M), np.complex64)],
+                                       [np.zeros(K, np.complex64), bc, np.zeros(3, np.complex64)])
+    assert dims == [2, 2 * K, 2 * M, 3] and W[1].shape == (2 * M, 2 * K)
+    assert np.abs(xi @ W[1].astype(np.float64).T + b[1] - zi).max() <= 1e-12
+    # first: real input
+    xr = rng.normal(size=(9, K))
+    z0 = xr @ Wc.astype(np.complex128).T + bc.astype(np.complex128)
+    dims, W, b = o.complex_net_to_real([K, M, 3], [Wc, np.zeros((3, M), np.complex64)], [bc, np.zeros(3, np.complex64)])
+    assert W[0].shape == (2 * M, K)
+    assert np.abs(xr @ W[0].astype(np.float64).T + b[0] - np.stack([z0.real, z0.imag], axis=2).reshape(9, 2 * M)).max() <= 1e-12
+    # last: the real part of the product
+    dims, W, b = o.complex_net_to_real([2, K, M], [np.zeros((K, 2), np.complex64), Wc], [np.zeros(K, np.complex64), bc])
+    assert W[1].shape == (M, 2 * K)
+    assert np.abs(xi @ W[1].astype(np.float64).T + b[1] - z.real).max() <= 1e-12
+
+
+def test_complex_network_is_the_numpy_complex_network():
+    """The whole un-quantized network with complex weights: the oracle's real network of interleaved features
+    with the pair activation against numpy's complex arithmetic end to end."""
+    dims_c = [2, 24, 17, 24, 3]
+    Wc, bc = synth.wire_init(dims_c, 30.0, 77)
+    assert np.abs(Wc[0].imag).max() == 0.0 and np.abs(Wc[1].imag).max() > 0.0 and np.abs(bc[-1].imag).max() == 0.0
+    x = synth.grid_coords(19)
+    dims, W, b = o.complex_net_to_real(dims_c, Wc, bc)
+    o64, o32 = o.mlp_float(dims, 30.0, W, b, x, gabor_s0=o.ComplexSpread(10.0))
+    ref = _complex_numpy_net(dims_c, Wc, bc, x, 30.0, 10.0)
+    assert np.abs(ref).max() > 0.05
+    assert np.abs(o64 - ref).max() <= 1e-12 and np.abs(o32 - ref).max() <= 1e-4
+    with pytest.raises(o.OracleError):      # an odd hidden width cannot hold (Re, Im) pairs
+        o.mlp_float([2, 5, 3], 30.0, [np.zeros((5, 2), np.float32), np.zeros((3, 5), np.float32)],
+                    [np.zeros(5, np.float32), np.zeros(3, np.float32)], x, gabor_s0=o.ComplexSpread(1.0))
+
+
+def test_complex_network_with_real_weights_and_one_wavelet_layer_is_the_real_wavelet_network():
+    """Real first-layer weights give a real pre-activation; if the last layer's weights are real too its real
+    part only sees the real part of the wavelet: the real-valued wavelet network pinned earlier is this
+    special case."""
+    rng = np.random.default_rng(3)
+    W0 = rng.uniform(-0.5, 0.5, size=(12, 2)).astype(np.float32)
+    W1 = rng.uniform(-0.3, 0.3, size=(3, 12)).astype(np.float32)
+    b0, b1 = rng.uniform(-0.5, 0.5, size=12).astype(np.float32), rng.uniform(-0.2, 0.2, size=3).astype(np.float32)
+    x = synth.grid_coords(11)
+    dims, W, b = o.complex_net_to_real([2, 12, 3], [W0 + 0j, W1 + 0j], [b0 + 0j, b1 + 0j])
+    got, _ = o.mlp_float(dims, 30.0, W, b, x, want_f32=False, gabor_s0=o.ComplexSpread(10.0))
+    ref, _ = o.mlp_float([2, 12, 3], 30.0, [W0, W1], [b0, b1], x, want_f32=False, gabor_s0=10.0)
+    assert np.abs(got - ref).max() <= 1e-14
+
+
+def test_complex_quantized_forward_is_composition_of_steps():
+    """The quantized forward of a complex-weight network, layer by layer from its own dumped integers: numpy's
+    dequantization and numpy's complex exponential on the (Re, Im) pairs give the dumped activations; rotating
+    and quantizing those gives the next layer's dumped codes; the integer product gives its accumulators."""
+    dims_c = [2, 32, 20, 3]
+    Wc, bc = synth.wire_init(dims_c, 30.0, 5)
+    dims, W, b = o.complex_net_to_real(dims_c, Wc, bc)
+    coords = synth.grid_coords(23)
+    net = o.quantize_net(dims, 30.0, 8, 8, W, b, gabor_s0=o.ComplexSpread(10.0))
+    out, d = o.forward(net, coords, calibrate=True, dump=True)
+    L = len(dims) - 1
+    a = coords.astype(np.float32)
+    for l in range(L):
+        rot = o.rotate_rows(a.astype(np.float64))
+        assert np.array_equal(o.quantize(rot, float(net.s_a[l]), 8), d.codes[l])
+        assert np.array_equal(d.codes[l].astype(np.int64) @ net.Wq[l].astype(np.int64).T, d.acc[l].astype(np.int64))
+        y = d.acc[l].astype(np.float64) * (float(net.s_a[l]) * float(net.s_w[l])) + b[l].astype(np.float64)
+        if l < L - 1:
+            z = y[:, 0::2] + 1j * y[:, 1::2]
+            g = np.exp(1j * 30.0 * z - np.abs(10.0 * z) ** 2)
+            ref = np.stack([g.real, g.imag], axis=2).reshape(y.shape)
+        else:
+            ref = y
+        assert np.abs(ref - d.act[l]).max() <= 1e-7 * max(1.0, np.abs(ref).max())      # one fp32 rounding
+        a = d.act[l]
+    assert np.array_equal(a, out)
+
+
+def test_complex_quantized_network_tracks_the_float_one():
+    dims_c = [2, 32, 32, 32, 3]
+    Wc, bc = synth.wire_init(dims_c, 30.0, 9)
+    dims, W, b = o.complex_net_to_real(dims_c, Wc, bc)
+    coords = synth.grid_coords(40)
+    ref = _complex_numpy_net(dims_c, Wc, bc, coords, 30.0, 10.0)
+    errs = []
+    for bits in (4, 6, 8):
+        net = o.quantize_net(dims, 30.0, bits, bits, W, b, gabor_s0=o.ComplexSpread(10.0))
+        errs.append(np.sqrt(np.mean((o.forward(net, coords, calibrate=True) - ref) ** 2)))
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 0.1 * np.abs(ref).max()
