@@ -89,6 +89,35 @@ def cpu_baseline(name, max_coords, two_sided=False, wavelet_s0=None):
                       f"calibration excluded)"}
 
 
+def cpu_baseline_complex(name, max_coords, s0):
+    """The CPU oracle's quantized forward of the complex-valued wavelet network (as a real network of interleaved
+    features) on a bounded sample."""
+    from oracle import dhq_oracle as o
+    from paper_2508_13478_amd import synth
+    wl, coords, _, _ = synth.make(name)
+    dims_c = [wl.dims[0]] + [d // 2 for d in wl.dims[1:-1]] + [wl.dims[-1]]
+    Wc, bc = synth.wire_init(dims_c, wl.omega0, wl.seed)
+    dims, W, b = o.complex_net_to_real(dims_c, Wc, bc)
+    stride = max(1, -(-coords.shape[0] // max_coords))
+    sample = coords[::stride]
+    net = o.quantize_net(dims, wl.omega0, 8, 8, W, b, gabor_s0=o.ComplexSpread(s0))
+    o.forward(net, sample, calibrate=True)
+    runs, t0 = 0, time.perf_counter()
+    while True:
+        o.forward(net, sample)
+        runs += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or runs >= 50:
+            break
+    try:
+        threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
+    except OSError:
+        threads = os.cpu_count() or 1
+    return {"value": runs * sample.shape[0] / dt, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{name} grid, every {stride}th coordinate ({sample.shape[0]} coords), {runs} runs, {dt:.2f} s, "
+                      f"quantized forward with static scales"}
+
+
 def cpu_baseline_float(name, max_coords, wavelet_s0=None):
     """The CPU oracle's plain fp64/fp32 MLP timed on a bounded sample."""
     from oracle import dhq_oracle as o
@@ -126,9 +155,11 @@ def main() -> int:
                          "dynamic / two_sided_dynamic: activation scales measured on line per call (one fused kernel "
                          "per layer where there is one); "
                          "w8a32 / w32a32: the comparison networks with fp32 activations (fused fp32 kernel)")
-    ap.add_argument("--activation", default="sine", choices=["sine", "wavelet"],
+    ap.add_argument("--activation", default="sine", choices=["sine", "wavelet", "wavelet_complex"],
                     help="sine: the SIREN of the workload; wavelet: the same shapes and weights with the activation "
-                         "cos(omega0 y) exp(-(s0 y)^2) of the second architecture the paper evaluates (same fused kernels)")
+                         "cos(omega0 y) exp(-(s0 y)^2) of the second architecture the paper evaluates (same fused kernels); "
+                         "wavelet_complex: that architecture with complex-valued hidden layers of half the workload's "
+                         "width (the same real width, seeded complex weights), base variant only")
     ap.add_argument("--wavelet-s0", type=float, default=10.0, help="spread of the wavelet's Gaussian envelope")
     ap.add_argument("--path", default="auto", choices=["auto", "layerwise"],
                     help="auto: the fused kernel where the model has one; layerwise: force the layer-by-layer path")
@@ -161,7 +192,16 @@ def main() -> int:
     if floating:
         mode = dhq.DHQ_W8A32 if args.variant == "w8a32" else dhq.DHQ_W32A32
     s0 = args.wavelet_s0 if args.activation == "wavelet" else None
-    model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode, wavelet_s0=s0)
+    cplx = args.activation == "wavelet_complex"
+    if cplx:
+        if args.variant != "base":
+            print("bench.py: --activation wavelet_complex runs the base variant only", file=sys.stderr)
+            return 2
+        dims_c = [wl.dims[0]] + [d // 2 for d in wl.dims[1:-1]] + [wl.dims[-1]]
+        Wc, bc = synth.wire_init(dims_c, wl.omega0, wl.seed)
+        model = dhq.Model.complex_wavelet(dims_c, wl.omega0, Wc, bc, args.wavelet_s0, 8, 8)
+    else:
+        model = dhq.Model(wl.dims, wl.omega0, W, b, 8, 8, mode=mode, wavelet_s0=s0)
     if args.wide_kernel:
         model.select_wide_kernel(args.wide_kernel)
     x = torch.from_numpy(coords).to("cuda")
@@ -274,7 +314,7 @@ def main() -> int:
     if fused and not floating:
         ms_lw, _ = time_forward(model, x, out, dhq.DHQ_LAYERWISE, max(10, args.steps // 20), 5)
         res["layerwise_ms_per_step"] = ms_lw
-    if not floating and not two_sided and not dynamic:
+    if not floating and not two_sided and not dynamic and not cplx:
         # the paper's W32A32-versus-W8A8 comparison (Table 2) on this GPU: the plain fp32 network through
         # the library's own fp32 kernels (one fused kernel up to width 256, layer by layer beyond), and how
         # far the quantized output is from it
@@ -307,6 +347,15 @@ def main() -> int:
             m2.close()
             del x2, out2
         res["other_workloads"] = others
+    if cplx:
+        res["config"]["workload"] = res["config"]["workload"].replace(
+            "SIREN", f"complex-valued wavelet MLP (s0={args.wavelet_s0:g}, {wl.dims[1] // 2} complex features per hidden layer), real dims")
+        res["config"]["activation"] = "wavelet_complex"
+        res["metric"] = res["metric"].replace("SIREN", "complex-wavelet-MLP")
+        res["roofline"]["traffic"] = None
+        if fused:
+            res["roofline"]["kernel"] = f"dhq_fused_kernel<{wl.dims[1]}, 3>"
+        res["alu"]["model"] += " (sine model; the complex wavelet takes 4.5 instructions per value where the sine takes 1)"
     if s0 is not None:
         res["config"]["workload"] = res["config"]["workload"].replace("SIREN", f"wavelet MLP (s0={s0:g})")
         res["config"]["activation"] = "wavelet"
@@ -317,7 +366,9 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cplx:
+        res["cpu_baseline"] = cpu_baseline_complex(args.workload, args.cpu_coords, args.wavelet_s0)
+    elif not args.no_cpu_baseline:
         res["cpu_baseline"] = (cpu_baseline_float(args.workload, args.cpu_coords, s0) if floating else
                                cpu_baseline(args.workload, args.cpu_coords, two_sided, s0))
     print(json.dumps(res))

@@ -146,6 +146,29 @@ int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float 
                                  const float *const *b_host, dhq_model **out);
 
 /*
+ * The same architecture as its publication has it (Sec. 4.1 / Table 1 name it and cite that
+ * publication; the paper itself prints no formula): hidden features are complex numbers, the
+ * weights of every layer after the first are complex, every layer but the last ends in the
+ * complex wavelet exp(j omega0 y - |s0 y|^2), and the network's output is the real part of the
+ * last layer.  Reading: the network runs as a real one on interleaved (Re, Im) features -- a
+ * complex weight w becomes the block [[Re w, -Im w], [Im w, Re w]] -- so that the rotation of
+ * Eq. 3-5, the quantizer and the integer product of Sec. 3.2-3.3 apply unchanged (DHQ_ROTATE_IN,
+ * W8A8), and only the activation acts on pairs of features.
+ *   desc->dims   fan-in (real coordinates), the COMPLEX widths of the hidden layers (each at
+ *                most 256), fan-out (real values)
+ *   W_re, W_im   host, per layer dims[l+1] x dims[l] fp32, row-major; W_im or W_im[l] may be
+ *                NULL (a real-valued layer: the first one in the published architecture)
+ *   b_re, b_im   host, per layer dims[l+1] fp32; b_im or b_im[l] may be NULL; the imaginary
+ *                part of the last layer's weights enters its real output, that of its bias does not
+ * The model that comes back has the real dims (fan-in, 2 x width, ..., fan-out): every other
+ * call (scales, calibration, forward, the test hooks, dhq_get_weight_codes) sees that real
+ * network.  Whole-network kernel: hidden widths 16 / 32 / 64 / 128 complex (32 .. 256 real).
+ */
+int dhq_quantize_weights_complex(const dhq_net_desc *desc, float s0, const float *const *W_re,
+                                 const float *const *W_im, const float *const *b_re,
+                                 const float *const *b_im, dhq_model **out);
+
+/*
  * Static per-layer activation scales for the quantization module between layers (Sec. 3.3; the
  * per-tensor scale of the "standard quantizer" of Sec. 3.2, Eq. 1's step size with zero-point 0):
  * s_a_host is a host array of n_layers entries, each finite and > 0; entry l divides the rotated

@@ -23,7 +23,7 @@ DHQ_ROTATE_IN, DHQ_ROTATE_BOTH = 0, 1
 DHQ_W8A8, DHQ_W8A32, DHQ_W32A32 = 0x00, 0x10, 0x20
 
 # every symbol include/dhq.h declares
-EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
+EXPORTS = ("dhq_quantize_weights", "dhq_quantize_weights_mode", "dhq_quantize_weights_wavelet", "dhq_quantize_weights_complex", "dhq_get_dynamic_scales", "dhq_set_act_scales", "dhq_calibrate", "dhq_get_scales",
            "dhq_get_weight_codes", "dhq_forward", "dhq_reserve_dynamic", "dhq_forward_noalloc", "dhq_noalloc_max_rows",
            "dhq_forward_debug", "dhq_forward_debug_fused", "dhq_gemm_i8", "dhq_has_fused", "dhq_select_wide_kernel",
            "dhq_free", "dhq_strerror", "dhq_version")
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
         L.dhq_quantize_weights_mode.argtypes = [C.POINTER(dhq_net_desc), C.c_uint32, _fpp, _fpp, C.POINTER(C.c_void_p)]
         L.dhq_quantize_weights_wavelet.argtypes = [C.POINTER(dhq_net_desc), C.c_uint32, C.c_float, _fpp, _fpp,
                                                    C.POINTER(C.c_void_p)]
+        L.dhq_quantize_weights_complex.argtypes = [C.POINTER(dhq_net_desc), C.c_float, _fpp, _fpp, _fpp, _fpp, C.POINTER(C.c_void_p)]
         L.dhq_get_dynamic_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_void_p]
         L.dhq_set_act_scales.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dhq_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
@@ -149,6 +150,28 @@ def _quantize(dims, omega0, bits_w, bits_a, mode, s0, W, b) -> int:
     else:
         _ok(lib().dhq_quantize_weights_wavelet(C.byref(desc), int(mode), C.c_float(s0), Wp, bp, C.byref(h)),
             "dhq_quantize_weights_wavelet")
+    return h.value
+
+
+def dhq_quantize_weights_complex(dims_c: Sequence[int], omega0: float, bits_w: int, bits_a: int, s0: float,
+                                 Wc: Sequence[np.ndarray], bc: Sequence[np.ndarray]) -> int:
+    """A network with complex-valued hidden layers: Wc[l] complex, dims_c[l+1] x dims_c[l] (dims_c holds the
+    complex widths of the hidden layers); the library runs it as a real network of interleaved (Re, Im) features."""
+    L = len(dims_c) - 1
+    dims_a = (C.c_int32 * (L + 1))(*[int(d) for d in dims_c])
+    desc = dhq_net_desc(L, dims_a, float(omega0), int(bits_w), int(bits_a))
+    parts = []
+    for arrs, shape_of in ((Wc, lambda l: (dims_c[l + 1], dims_c[l])), (bc, lambda l: (dims_c[l + 1],))):
+        for part in (np.real, np.imag):
+            a = [np.ascontiguousarray(part(x), dtype=np.float32) for x in arrs]
+            for l in range(L):
+                if a[l].shape != tuple(shape_of(l)):
+                    raise DhqError(DHQ_EINVAL, f"dhq_quantize_weights_complex: layer {l} has the wrong shape")
+            parts.append(a)
+    ptrs = [(C.POINTER(C.c_float) * L)(*[x.ctypes.data_as(C.POINTER(C.c_float)) for x in a]) for a in parts]
+    h = C.c_void_p()
+    _ok(lib().dhq_quantize_weights_complex(C.byref(desc), C.c_float(s0), ptrs[0], ptrs[1], ptrs[2], ptrs[3], C.byref(h)),
+        "dhq_quantize_weights_complex")
     return h.value
 
 
@@ -242,6 +265,17 @@ class Model:
         self.n_layers = len(self.dims) - 1
         self.mode = int(mode)
         self.handle = _quantize(self.dims, omega0, bits_w, bits_a, mode, wavelet_s0, W, b)
+
+    @classmethod
+    def complex_wavelet(cls, dims_c: Sequence[int], omega0: float, Wc, bc, s0: float, bits_w: int = 8, bits_a: int = 8):
+        """A network with complex-valued hidden layers (dims_c: their complex widths); the model has the real
+        dims [fan-in, 2 x width, ..., fan-out]."""
+        self = cls.__new__(cls)
+        self.dims = [int(dims_c[0])] + [2 * int(d) for d in dims_c[1:-1]] + [int(dims_c[-1])]
+        self.n_layers = len(self.dims) - 1
+        self.mode = DHQ_ROTATE_IN
+        self.handle = dhq_quantize_weights_complex(dims_c, omega0, bits_w, bits_a, s0, Wc, bc)
+        return self
 
     def close(self) -> None:
         if getattr(self, "handle", None):

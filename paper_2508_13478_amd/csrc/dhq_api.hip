@@ -296,7 +296,8 @@ static double sine_arg_bound(const dhq_model *m, int l, double s_a)
     const dhq_layer &Ly = m->layer[l];
     const double c_over = dhq_c1_over_sa(m, l);
     double bound = s_a * c_over * (double)m->qmax_a * (double)Ly.sum_abs_max;
-    if (l >= 1) {
+    // (the complex wavelet's modulus exp(-omega0 Im y - |s0 y|^2) is not bounded by 1: magnitudes only)
+    if (l >= 1 && m->act_kind != DHQ_ACT_KIND_WAVELET_COMPLEX) {
         const double by_norm = c_over * (sqrt((double)Ly.K) + s_a * sqrt((double)Ly.Kp) / 2.0) * Ly.norm2_max;
         if (by_norm < bound) bound = by_norm;
     }
@@ -312,6 +313,7 @@ static bool sine_range_ok_static(const dhq_model *m)
 // Scales measured on line: s_a = max|x^| / qmax_a <= sqrt(K) / qmax_a for the layers after the first.
 static bool sine_range_ok_dynamic(const dhq_model *m)
 {
+    if (m->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX && m->n_layers > 2) return false;  // no bound on a layer's input
     for (int l = 1; l < m->n_layers - 1; ++l)
         if (!(sine_arg_bound(m, l, sqrt((double)m->layer[l].K) / (double)m->qmax_a) <= DHQ_SINE_MAX_REV)) return false;
     return true;
@@ -327,6 +329,8 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
     if ((mode & ~0xffu) != 0 || (rotate != DHQ_ROTATE_IN && rotate != DHQ_ROTATE_BOTH)) return DHQ_EINVAL;
     if (precision != DHQ_W8A8 && precision != DHQ_W8A32 && precision != DHQ_W32A32) return DHQ_EINVAL;
     if (precision != DHQ_W8A8 && rotate != DHQ_ROTATE_IN) return DHQ_EUNSUPPORTED;
+    const bool cplx = (act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX);
+    if (cplx && (precision != DHQ_W8A8 || rotate != DHQ_ROTATE_IN)) return DHQ_EUNSUPPORTED;
     const int L = desc->n_layers;
     if (L < 1) return DHQ_EINVAL;
     if (L > DHQ_MAX_LAYERS) return DHQ_EUNSUPPORTED;
@@ -402,7 +406,7 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
         if (rc == DHQ_OK && hipMalloc((void **)&m->act1, act_bytes) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->codes, (size_t)DHQ_CHUNK * m->max_kp) != hipSuccess) rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->absmax_dev, sizeof(unsigned)) != hipSuccess) rc = DHQ_ENOMEM;
-        if (rc == DHQ_OK && m->rot_out &&
+        if (rc == DHQ_OK && (m->rot_out || cplx) &&
             hipMalloc((void **)&m->acc_ws, sizeof(int32_t) * (size_t)DHQ_CHUNK * m->max_mg) != hipSuccess)
             rc = DHQ_ENOMEM;
         if (rc == DHQ_OK && hipMalloc((void **)&m->dyn_absmax, sizeof(unsigned) * (DHQ_MAX_LAYERS + 2 * DHQ_ABSMAX_PARTIALS)) != hipSuccess) rc = DHQ_ENOMEM;
@@ -412,8 +416,8 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
     }
     if (rc == DHQ_OK) rc = scratch_on_device(m->device, &m->scratch);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
-    if (rc == DHQ_OK && !m->rot_out) rc = dhq_wide_create(m, &m->wide);
-    if (rc == DHQ_OK && !m->rot_out) rc = dhq_pair_create(m, &m->pair);
+    if (rc == DHQ_OK && !m->rot_out && !cplx) rc = dhq_wide_create(m, &m->wide);
+    if (rc == DHQ_OK && !m->rot_out && !cplx) rc = dhq_pair_create(m, &m->pair);
     if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
@@ -443,6 +447,62 @@ extern "C" int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t m
     // the sine and cosine take omega0 y / 2 pi; the envelope's argument is recovered from it
     if (desc && !(fabsf(desc->omega0) > 0.0f)) return DHQ_EINVAL;
     return create_model(desc, mode, DHQ_ACT_KIND_WAVELET, s0, W_host, b_host, out);
+}
+
+// A layer with complex weights as the real layer on interleaved (Re, Im) features:
+//   Re (w x) = Re w Re x - Im w Im x,   Im (w x) = Im w Re x + Re w Im x.
+// in_c: the inputs are complex (2 K real columns); out_c: so are the outputs (2 M real rows), else the
+// output is the real part (M rows).
+static void complex_layer_rows(const float *Wre, const float *Wim, const float *bre, const float *bim, int M, int K, bool in_c,
+                               bool out_c, std::vector<float> &W, std::vector<float> &b)
+{
+    const int cols = in_c ? 2 * K : K, rows = out_c ? 2 * M : M;
+    W.assign((size_t)rows * cols, 0.f);
+    b.assign((size_t)rows, 0.f);
+    for (int m = 0; m < M; ++m) {
+        const size_t r0 = (size_t)(out_c ? 2 * m : m) * cols, r1 = r0 + cols;
+        for (int k = 0; k < K; ++k) {
+            const float wr = Wre[(size_t)m * K + k], wi = Wim ? Wim[(size_t)m * K + k] : 0.f;
+            const int c0 = in_c ? 2 * k : k;
+            W[r0 + c0] = wr;
+            if (in_c) W[r0 + c0 + 1] = -wi;
+            if (out_c) {
+                W[r1 + c0] = wi;
+                if (in_c) W[r1 + c0 + 1] = wr;
+            }
+        }
+        b[out_c ? 2 * m : m] = bre[m];
+        if (out_c) b[2 * m + 1] = bim ? bim[m] : 0.f;
+    }
+}
+
+extern "C" int dhq_quantize_weights_complex(const dhq_net_desc *desc, float s0, const float *const *W_re, const float *const *W_im,
+                                            const float *const *b_re, const float *const *b_im, dhq_model **out)
+{
+    if (out) *out = nullptr;
+    if (!desc || !desc->dims || !W_re || !b_re || !out) return DHQ_EINVAL;
+    if (!isfinite(s0) || s0 < 0.0f || !(fabsf(desc->omega0) > 0.0f)) return DHQ_EINVAL;
+    const int L = desc->n_layers;
+    if (L < 2) return DHQ_EINVAL;  // without a hidden layer nothing is complex
+    if (L > DHQ_MAX_LAYERS) return DHQ_EUNSUPPORTED;
+    int32_t dims[DHQ_MAX_LAYERS + 1];
+    for (int l = 0; l <= L; ++l) {
+        if (desc->dims[l] < 1) return DHQ_EINVAL;
+        dims[l] = (l == 0 || l == L) ? desc->dims[l] : 2 * desc->dims[l];
+        if (dims[l] > DHQ_MAX_DIM) return DHQ_EUNSUPPORTED;
+    }
+    std::vector<std::vector<float>> W(L), b(L);
+    std::vector<const float *> Wp(L), bp(L);
+    for (int l = 0; l < L; ++l) {
+        if (!W_re[l] || !b_re[l]) return DHQ_EINVAL;
+        complex_layer_rows(W_re[l], W_im ? W_im[l] : nullptr, b_re[l], b_im ? b_im[l] : nullptr, desc->dims[l + 1], desc->dims[l],
+                           l > 0, l < L - 1, W[l], b[l]);
+        Wp[l] = W[l].data();
+        bp[l] = b[l].data();
+    }
+    dhq_net_desc real = *desc;
+    real.dims = dims;
+    return create_model(&real, DHQ_ROTATE_IN, DHQ_ACT_KIND_WAVELET_COMPLEX, s0, Wp.data(), bp.data(), out);
 }
 
 static int update_fused_scales(dhq_model *m)
@@ -520,6 +580,13 @@ static hipError_t gemm_epilogue(const dhq_model *m, int l, const int8_t *codes, 
     const bool last = (l == m->n_layers - 1);
     const float c1 = dyn ? 0.0f : dhq_c1(m, l);
     const float *bias = last ? Ly.bias_dev : Ly.bias_rev_dev;
+    if (!last && m->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX) {
+        // the complex wavelet pairs neighbouring features, which the GEMM's lanes hold one each: raw
+        // accumulators out, then one thread per pair
+        hipError_t e = dhq_launch_gemm(Ly, codes, rows, acc_ws, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st);
+        if (e != hipSuccess) return e;
+        return dhq_launch_epilogue_pairs(acc_ws, rows, Ly.M, c1, bias, dhq_layer_act(m, l), dyn, dst, st);
+    }
     if (!m->rot_out) return dhq_launch_gemm(Ly, codes, rows, nullptr, dst, c1, bias, dhq_layer_act(m, l), dyn, st);
     hipError_t e = dhq_launch_gemm(Ly, codes, rows, acc_ws, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st);
     if (e != hipSuccess) return e;
@@ -605,7 +672,7 @@ static dyn_sizes dyn_buffer_sizes(const dhq_model *m, int64_t n)
     dyn_sizes z;
     z.act = sizeof(float) * rows * m->max_dim;
     z.codes = (size_t)n * m->max_kp;
-    z.acc = m->rot_out ? sizeof(int32_t) * (size_t)n * m->max_mg : 0;
+    z.acc = (m->rot_out || m->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX) ? sizeof(int32_t) * (size_t)n * m->max_mg : 0;
     return z;
 }
 
@@ -831,6 +898,8 @@ extern "C" int dhq_forward_debug(const dhq_model *m, const float *in_dev, int64_
     // the int32 accumulators go through the workspace when the caller does not want them
     int32_t *acc = acc_dev ? acc_dev : reinterpret_cast<int32_t *>(m->act0);
     if (dhq_launch_gemm(Ly, codes, n, acc, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st) != hipSuccess) return DHQ_EHIP;
+    if (act_dev && !last && m->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX)
+        return dhq_launch_epilogue_pairs(acc, n, Ly.M, dhq_c1(m, layer), bias, dhq_layer_act(m, layer), nullptr, act_dev, st) == hipSuccess ? DHQ_OK : DHQ_EHIP;
     if (act_dev && dhq_launch_epilogue(acc, n, Ly.M, dhq_c1(m, layer), bias, dhq_layer_act(m, layer), act_dev, st) != hipSuccess) return DHQ_EHIP;
     return DHQ_OK;
 }

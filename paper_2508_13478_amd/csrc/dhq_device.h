@@ -46,6 +46,9 @@ __device__ __forceinline__ float dhq_sin_rev(float t)
 #define DHQ_ACT_KIND_NONE 0
 #define DHQ_ACT_KIND_SINE 1
 #define DHQ_ACT_KIND_WAVELET 2
+// the complex wavelet exp(j omega0 y - |s0 y|^2) on pairs of features (2m, 2m + 1) = (Re y, Im y): the
+// WIRE architecture with complex-valued hidden layers, run as a real network of interleaved features
+#define DHQ_ACT_KIND_WAVELET_COMPLEX 3
 struct dhq_act {
     int kind;
     float c2;
@@ -60,6 +63,21 @@ __device__ __forceinline__ float dhq_activate_rev(float t, dhq_act act)
         return __builtin_amdgcn_cosf(t) * __builtin_amdgcn_exp2f(-(g * g));
     }
     return dhq_sin_rev(t);
+}
+
+// The complex wavelet on a pair of arguments in revolutions, tr = omega0 Re y / 2 pi, ti = omega0 Im y / 2 pi:
+//   exp(j omega0 y - |s0 y|^2) = exp(-omega0 Im y - s0^2 |y|^2) (cos(omega0 Re y) + j sin(omega0 Re y)),
+// the envelope as a base-2 exponential: (c2 t)^2 = (s0 y)^2 log2 e as for the real wavelet, and
+// omega0 Im y log2 e = 2 pi log2(e) ti.  ANY: take the fractional part of tr first (any finite argument).
+template <bool ANY>
+__device__ __forceinline__ void dhq_activate_pair_rev(float tr, float ti, float c2, float &ar, float &ai)
+{
+    const float gr = tr * c2, gi = ti * c2;
+    const float e = __builtin_fmaf(gr, gr, __builtin_fmaf(gi, gi, ti * 9.0647202836543876f));
+    const float mag = __builtin_amdgcn_exp2f(-e);
+    const float f = ANY ? __builtin_amdgcn_fractf(tr) : tr;
+    ar = __builtin_amdgcn_cosf(f) * mag;
+    ai = __builtin_amdgcn_sinf(f) * mag;
 }
 
 // The same for any finite argument: the hardware sine and cosine are defined up to 256

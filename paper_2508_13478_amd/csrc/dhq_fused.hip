@@ -204,8 +204,15 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
                 const int v = S.drain_pos[g] * EPS + j;
                 const float4 bb = bq[Td % 3][v >> 2];
                 const float bias0 = (v & 2) ? bb.z : bb.x, bias1 = (v & 2) ? bb.w : bb.y;
-                const float a0 = dhq_activate_rev(__builtin_fmaf((float)acc[Td % 3][v], c1, bias0), dhq_act{ACTK, c2});
-                const float a1 = dhq_activate_rev(__builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1), dhq_act{ACTK, c2});
+                // accumulators v, v + 1 (v even) are neighbouring features 2m, 2m + 1: the pair the complex wavelet takes
+                const float t0 = __builtin_fmaf((float)acc[Td % 3][v], c1, bias0), t1 = __builtin_fmaf((float)acc[Td % 3][v + 1], c1, bias1);
+                float a0, a1;
+                if constexpr (ACTK == DHQ_ACT_KIND_WAVELET_COMPLEX) {
+                    dhq_activate_pair_rev<false>(t0, t1, c2, a0, a1);
+                } else {
+                    a0 = dhq_activate_rev(t0, dhq_act{ACTK, c2});
+                    a1 = dhq_activate_rev(t1, dhq_act{ACTK, c2});
+                }
                 hm_split_pair(a0, a1, hp[Td & 1][v >> 1], lp[Td & 1][v >> 1]);
             }
         }
@@ -664,6 +671,7 @@ static hipError_t fused_launch_act(const dhq_fused_plan *P, const fused_args &a,
 template <int NF>
 static hipError_t fused_launch_t(const dhq_fused_plan *P, const fused_args &a, int act_kind, unsigned grid, hipStream_t st)
 {
+    if (act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX) return fused_launch_act<NF, DHQ_ACT_KIND_WAVELET_COMPLEX>(P, a, grid, st);
     return act_kind == DHQ_ACT_KIND_WAVELET ? fused_launch_act<NF, DHQ_ACT_KIND_WAVELET>(P, a, grid, st)
                                             : fused_launch_act<NF, DHQ_ACT_KIND_SINE>(P, a, grid, st);
 }
@@ -710,6 +718,9 @@ template <int NF>
 static hipError_t fusedl_launch_mode(int mode, int act_kind, const fusedl_args &a, unsigned grid, int device, hipStream_t st)
 {
     const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
+    if (act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX && mode < 2)
+        return mode == 0 ? fusedl_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET_COMPLEX>(a, grid, device, st)
+                         : fusedl_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET_COMPLEX>(a, grid, device, st);
     switch (mode) {
         case 0: return wav ? fusedl_launch_t<NF, 0, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedl_launch_t<NF, 0, DHQ_ACT_KIND_SINE>(a, grid, device, st);
         case 1: return wav ? fusedl_launch_t<NF, 1, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedl_launch_t<NF, 1, DHQ_ACT_KIND_SINE>(a, grid, device, st);
@@ -780,6 +791,9 @@ template <int NF>
 static hipError_t fusedd_launch_nf(bool first, int act_kind, const fusedd_args &a, unsigned grid, int device, hipStream_t st)
 {
     const bool wav = (act_kind == DHQ_ACT_KIND_WAVELET);
+    if (act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX)
+        return first ? fusedd_launch_t<NF, true, DHQ_ACT_KIND_WAVELET_COMPLEX>(a, grid, device, st)
+                     : fusedd_launch_t<NF, false, DHQ_ACT_KIND_WAVELET_COMPLEX>(a, grid, device, st);
     if (first) return wav ? fusedd_launch_t<NF, true, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedd_launch_t<NF, true, DHQ_ACT_KIND_SINE>(a, grid, device, st);
     return wav ? fusedd_launch_t<NF, false, DHQ_ACT_KIND_WAVELET>(a, grid, device, st) : fusedd_launch_t<NF, false, DHQ_ACT_KIND_SINE>(a, grid, device, st);
 }

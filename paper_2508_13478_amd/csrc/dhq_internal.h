@@ -152,7 +152,7 @@ static inline dhq_act dhq_hidden_act(const dhq_model *m)
 {
     dhq_act a;
     a.kind = m->act_kind;
-    a.c2 = (a.kind == DHQ_ACT_KIND_WAVELET)
+    a.c2 = (a.kind == DHQ_ACT_KIND_WAVELET || a.kind == DHQ_ACT_KIND_WAVELET_COMPLEX)
                ? (float)(6.283185307179586476925286766559 * (double)m->wavelet_s0 * sqrt(1.4426950408889634074) / (double)m->omega0)
                : 0.f;
     return a;
@@ -166,6 +166,11 @@ static inline float dhq_c1(const dhq_model *m, int l) { return (float)((double)m
 // act_out = epilogue(acc) elementwise, same formula as above.
 hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, const float *bias,
                                dhq_act act, float *act_out, hipStream_t st);
+
+// The complex wavelet on the pairs (2p, 2p + 1) of every row of acc (n x M int32, M even): act_out = n x M fp32.
+// If dyn != nullptr, c1 is read from dyn[1].
+hipError_t dhq_launch_epilogue_pairs(const int32_t *acc, int64_t n, int M, float c1, const float *bias, dhq_act act,
+                                     const float *dyn, float *act_out, hipStream_t st);
 
 // ---- fused path (defined in dhq_fused.hip) -------------------------------------------------
 // Builds the packed weights for the whole-network kernel if the shape is supported.

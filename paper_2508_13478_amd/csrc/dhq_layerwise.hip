@@ -606,6 +606,31 @@ hipError_t dhq_launch_epilogue(const int32_t *acc, int64_t n, int M, float c1, c
     return hipGetLastError();
 }
 
+// The complex wavelet (DHQ_ACT_KIND_WAVELET_COMPLEX) acts on the pairs (2p, 2p + 1) of a row: one thread per pair.
+__global__ __launch_bounds__(256) void epilogue_pairs_kernel(const int32_t *__restrict__ acc, int64_t total_pairs, int half_m,
+                                                             float c1, const float *__restrict__ bias, float c2,
+                                                             const float *__restrict__ dyn, float *__restrict__ act_out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total_pairs) return;
+    if (dyn) c1 = dyn[1];
+    const int p = (int)(idx % half_m);
+    const int2 a = reinterpret_cast<const int2 *>(acc)[idx];
+    const float2 b = reinterpret_cast<const float2 *>(bias)[p];
+    float ar, ai;
+    dhq_activate_pair_rev<true>(__builtin_fmaf((float)a.x, c1, b.x), __builtin_fmaf((float)a.y, c1, b.y), c2, ar, ai);
+    reinterpret_cast<float2 *>(act_out)[idx] = make_float2(ar, ai);
+}
+
+hipError_t dhq_launch_epilogue_pairs(const int32_t *acc, int64_t n, int M, float c1, const float *bias, dhq_act act,
+                                     const float *dyn, float *act_out, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    if (M % 2 || act.kind != DHQ_ACT_KIND_WAVELET_COMPLEX) return hipErrorInvalidValue;
+    const int64_t total = n * (M / 2);
+    epilogue_pairs_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(acc, total, M / 2, c1, bias, act.c2, dyn, act_out);
+    return hipGetLastError();
+}
 
 // ------------------------------------------------------------ two-sided variant: un-rotation
 // z = acc' H_MP over the output features of every row, in int32 (H has entries +-1, and

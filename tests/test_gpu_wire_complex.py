@@ -1,0 +1,209 @@
+"""GPU parity of networks with complex-valued wavelet layers (the WIRE architecture of Sec. 4.1 /
+Table 1 as the publication the paper cites has it: complex hidden features and weights, the
+activation exp(j omega0 y - |s0 y|^2), real part out) against the CPU oracle.
+
+Both sides run such a network as a real one on interleaved (Re, Im) features; each builds that
+real network from the complex weights with its own code.  Everything but the activation is then
+the path of the other networks, so the gates are the same: weight codes and scales
+bit-identical, integer stages bit-exact, codes <= 0.1 % off by <= 1 LSB when teacher-forced,
+final values by the free-running rule of test_gpu_parity.py.  The activation's modulus reaches
+exp(omega0^2 / (4 s0^2)) (9.5 for omega0 = 30, s0 = 10), so its tolerance is relative to that.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import paper_2508_13478_amd as dhq
+from oracle import dhq_oracle as o
+from paper_2508_13478_amd import synth
+from test_gpu_parity import (CODE_RATE, OUT_TOL, _dev, _say, _torch, check_fused_against_oracle, code_stats, first_differences,
+                             int_matmul)
+
+pytestmark = pytest.mark.gpu
+
+OMEGA0, S0 = 30.0, 10.0
+ACT_MAX = math.exp(OMEGA0 ** 2 / (4.0 * S0 ** 2))
+
+
+class ComplexCase:
+    def __init__(self, dims_c, side, seed, bits=8, s0=S0):
+        self.dims_c = list(dims_c)
+        self.Wc, self.bc = synth.wire_init(self.dims_c, OMEGA0, seed)
+        self.dims, self.W, self.b = o.complex_net_to_real(self.dims_c, self.Wc, self.bc)
+        self.coords = synth.grid_coords(side)
+        self.net = o.quantize_net(self.dims, OMEGA0, bits, bits, self.W, self.b, gabor_s0=o.ComplexSpread(s0))
+        self.out, self.dump = o.forward(self.net, self.coords, calibrate=True, dump=True)
+        ref, _ = o.mlp_float(self.dims, OMEGA0, self.W, self.b, self.coords, want_f32=False, gabor_s0=o.ComplexSpread(s0))
+        self.quant_rms = float(np.sqrt(np.mean((self.out - ref) ** 2)))     # the network's own quantization error
+        self.model = dhq.Model.complex_wavelet(self.dims_c, OMEGA0, self.Wc, self.bc, s0, bits, bits)
+        self.model.set_act_scales(self.net.s_a)
+
+
+def _check_forward(cs, flags, label):
+    """Free-running gate.  The rule of test_gpu_parity.py, with two figures taken from this network instead of
+    the sine networks: a code that differs by one LSB perturbs x^ by s_a, as much as the rounding every code
+    carries, so the output moves by about the network's own quantization error -- which for these wavelet
+    networks (activations up to 9.5, heavy-tailed) is ten to thirty times that of the sine networks.  Hence
+    (1) codes compared while a coordinate still agrees with the oracle: <= 0.1 % differ, each by 1 LSB;
+    (2) every coordinate without a code difference within OUT_TOL (every excess is explained by one);
+    (3) no coordinate further off than ten times the rms quantization error (sine networks: 2e-2 = 10 x 2e-3).
+    The number of coordinates beyond OUT_TOL is bounded by those with a code difference, which (1) bounds."""
+    torch = _torch()
+    out = cs.model.forward(_dev(cs.coords), flags=flags)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    assert np.isfinite(out).all()
+    err = np.abs(out.astype(np.float64) - cs.out).max(axis=1)
+    bound = max(2e-2, 10.0 * cs.quant_rms)
+    if flags == dhq.DHQ_FUSED:
+        check_fused_against_oracle(cs.model, cs.net, cs.coords, out, cs.out, cs.dump, label, bound=bound)
+        return out
+    # layer by layer: replay the chain through the layer hook
+    x = _dev(cs.coords)
+    chain = []
+    for l in range(len(cs.dims) - 1):
+        codes, _, act = cs.model.forward_debug(x, l)
+        chain.append(codes.cpu().numpy())
+        x = act
+    torch.cuda.synchronize()
+    assert np.abs(x.cpu().numpy() - out).max() <= 1e-6      # the replay is what the forward computed
+    diff, compared, differing, worst = first_differences(chain, cs.dump.codes)
+    over = err > OUT_TOL
+    _say(f"  {label}: {differing} of {compared} codes differ where the input agreed ({differing / compared:.2e}, max {worst} LSB); "
+         f"{diff.sum()} of {err.size} coords with a code difference, {over.sum()} beyond {OUT_TOL}; max err without any "
+         f"{err[~diff].max():.3e}, overall {err.max():.3e} (bound {bound:.2e}, |out| max {np.abs(cs.out).max():.3f})")
+    assert worst <= 1 and differing <= CODE_RATE * compared
+    assert not (over & ~diff).any()
+    assert err.max() <= bound
+    return out
+
+
+_cache = {}
+
+
+def case(dims_c, side, seed=0xC0DE, bits=8):
+    key = (tuple(dims_c), side, seed, bits)
+    if key not in _cache:
+        _cache[key] = ComplexCase(dims_c, side, seed, bits)
+    return _cache[key]
+
+
+# complex widths: 32 and 128 have the whole-network kernel (real widths 64 and 256), 20 and 181 (the width the
+# published architecture uses next to a 256-wide real network) do not
+SHAPES = [([2, 32, 32, 32, 3], 64), ([2, 128, 128, 128, 128, 3], 96), ([2, 20, 20, 1], 50), ([2, 181, 181, 3], 40)]
+
+
+@pytest.mark.parametrize("dims_c,side", SHAPES, ids=[str(s[0][1]) for s in SHAPES])
+def test_complex_layers_teacher_forced(dims_c, side):
+    torch = _torch()
+    cs = case(dims_c, side)
+    assert cs.model.dims == cs.dims
+    sw, sa = cs.model.scales()
+    assert np.array_equal(sw, cs.net.s_w) and np.array_equal(sa, cs.net.s_a)
+    L = len(cs.dims) - 1
+    for l in range(L):
+        _say(f"complex wavelet {dims_c} layer {l}")
+        assert np.array_equal(cs.model.weight_codes(l), cs.net.Wq[l])
+        x = cs.coords if l == 0 else cs.dump.act[l - 1]
+        codes, acc, act = cs.model.forward_debug(_dev(x), l)
+        torch.cuda.synchronize()
+        codes, acc, act = codes.cpu().numpy(), acc.cpu().numpy(), act.cpu().numpy()
+        rate, mx = code_stats(codes, cs.dump.codes[l])
+        assert rate <= CODE_RATE and mx <= 1
+        assert np.array_equal(acc, int_matmul(codes, cs.net.Wq[l]))
+        same = (codes == cs.dump.codes[l]).all(axis=1)
+        exp = cs.dump.act[l][same]
+        err = np.abs(act[same].astype(np.float64) - exp).max()
+        scale = ACT_MAX if l < L - 1 else 1.0
+        _say(f"  code mismatch rate {rate:.2e}; epilogue max-abs err {err:.2e} (|act| max {np.abs(exp).max():.3f})")
+        # fp32 multiply-add, hardware sine / cosine / exponential: 2e-5 on values in [-1, 1], scaled by the modulus
+        assert err <= 2e-5 * scale
+        if l < L - 1:
+            assert np.abs(exp).max() <= ACT_MAX * (1 + 1e-6)
+
+
+@pytest.mark.parametrize("dims_c,side", SHAPES, ids=[str(s[0][1]) for s in SHAPES])
+def test_complex_forward(dims_c, side):
+    torch = _torch()
+    cs = case(dims_c, side)
+    _say(f"complex wavelet forward {dims_c}")
+    assert np.abs(cs.out).max() > 0.02
+    lw = _check_forward(cs, dhq.DHQ_LAYERWISE, "complex layer-by-layer")
+    fused_shape = dims_c[1] in (16, 32, 64, 128)
+    assert cs.model.has_fused() == fused_shape
+    if fused_shape:
+        fu = _check_forward(cs, dhq.DHQ_FUSED, "complex fused")
+        auto = cs.model.forward(_dev(cs.coords))
+        torch.cuda.synchronize()
+        assert np.array_equal(auto.cpu().numpy(), fu)
+        d = np.abs(fu - lw).max(axis=1)
+        _say(f"  fused vs layer-by-layer: max-abs {d.max():.3e}, {(d > OUT_TOL).sum()} coords beyond {OUT_TOL}")
+        # two independently rounded paths: each differs from the oracle on a few coordinates (gated above)
+        assert (d > OUT_TOL).mean() <= 2e-2
+    else:
+        with pytest.raises(dhq.DhqError) as e:
+            cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_FUSED)
+        assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    # on-line scales (Sec. 3.3's quantization module): the same bits as calibrate-then-static, scales as the oracle's
+    dyn = cs.model.forward(_dev(cs.coords), flags=dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC)
+    torch.cuda.synchronize()
+    sa = cs.model.dynamic_scales()
+    assert np.abs(sa / cs.net.s_a - 1).max() <= 1e-5
+    m2 = dhq.Model.complex_wavelet(cs.dims_c, OMEGA0, cs.Wc, cs.bc, S0)
+    m2.calibrate(_dev(cs.coords))
+    st = m2.forward(_dev(cs.coords), flags=dhq.DHQ_LAYERWISE)
+    torch.cuda.synchronize()
+    assert np.array_equal(m2.scales()[1], sa) and np.array_equal(st.cpu().numpy(), dyn.cpu().numpy())
+    m2.close()
+
+
+def test_complex_three_inputs_wide_and_ragged():
+    """Three real inputs, 181 complex features (362 real ones, padded to 512 for the rotation), two outputs,
+    a row count that is no multiple of any tile, through the layer-by-layer path."""
+    torch = _torch()
+    dims_c = [3, 181, 181, 2]
+    Wc, bc = synth.wire_init(dims_c, OMEGA0, 77)
+    dims, W, b = o.complex_net_to_real(dims_c, Wc, bc)
+    rng = np.random.default_rng(5)
+    x = rng.uniform(-1, 1, size=(3001, 3)).astype(np.float32)
+    net = o.quantize_net(dims, OMEGA0, 8, 8, W, b, gabor_s0=o.ComplexSpread(S0))
+    exp = o.forward(net, x, calibrate=True)
+    m = dhq.Model.complex_wavelet(dims_c, OMEGA0, Wc, bc, S0)
+    m.set_act_scales(net.s_a)
+    assert not m.has_fused()
+    for l in range(3):
+        assert np.array_equal(m.weight_codes(l), net.Wq[l])
+    out = m.forward(_dev(x))
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - exp).max(axis=1)
+    _say(f"  complex 181: {(err > OUT_TOL).sum()} of {err.size} coords beyond {OUT_TOL}, max {err.max():.2e}, median {np.median(err):.1e}")
+    assert (err > OUT_TOL).mean() <= 3e-3 and err.max() <= 5e-2 and np.median(err) <= 1e-5
+    m.close()
+
+
+def test_complex_low_bits_and_what_is_refused():
+    torch = _torch()
+    cs = case([2, 32, 32, 3], 48, bits=6)
+    _check_forward(cs, dhq.DHQ_LAYERWISE, "complex 6 bits")
+    _check_forward(cs, dhq.DHQ_FUSED, "complex 6 bits fused")
+    Wc, bc = synth.wire_init([2, 300, 3], OMEGA0, 1)
+    with pytest.raises(dhq.DhqError) as e:      # 600 real features exceed the library's widest layer
+        dhq.Model.complex_wavelet([2, 300, 3], OMEGA0, Wc, bc, S0)
+    assert e.value.status == dhq.DHQ_EUNSUPPORTED
+    # a purely real network through the complex entry point: one wavelet layer, real weights -> the real wavelet network
+    rng = np.random.default_rng(3)
+    W0 = rng.uniform(-0.5, 0.5, size=(32, 2)).astype(np.float32)
+    W1 = rng.uniform(-0.3, 0.3, size=(3, 32)).astype(np.float32)
+    b0, b1 = rng.uniform(-0.5, 0.5, size=32).astype(np.float32), rng.uniform(-0.2, 0.2, size=3).astype(np.float32)
+    x = _dev(synth.grid_coords(31))
+    mc = dhq.Model.complex_wavelet([2, 32, 3], OMEGA0, [W0 + 0j, W1 + 0j], [b0 + 0j, b1 + 0j], S0)
+    mr = dhq.Model([2, 32, 3], OMEGA0, [W0, W1], [b0, b1], wavelet_s0=S0)
+    mc.calibrate(x)
+    mr.calibrate(x)
+    a, b = mc.forward(x, flags=dhq.DHQ_LAYERWISE), mr.forward(x, flags=dhq.DHQ_LAYERWISE)
+    torch.cuda.synchronize()
+    # not the same quantized network (twice the features, other scales), but the same function up to quantization noise
+    assert np.abs(a.cpu().numpy() - b.cpu().numpy()).max() <= 0.05 * np.abs(b.cpu().numpy()).max() + 5e-3
+    mc.close()
+    mr.close()
