@@ -530,16 +530,23 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
 
     dhq_v4i hA[2];
     pair_h32_operand(c, h, S.role, hA);
-    dhq_v4i cd[PAIR_KB];
-#pragma unroll
-    for (int kb = 0; kb < PAIR_KB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
 
     for (int it = 0; it < my_tiles; ++it) {
         const int64_t tile = (int64_t)blockIdx.x + (int64_t)it * gridDim.x;
-        const int64_t ci = tile * PAIR_TILE + S.grp * 32 + c;
-        const bool valid = ci < A.n;
-        const int64_t cl = valid ? ci : A.n - 1;
-        cd[0][0] = fused_input_codes(A.coords, cl, A.k0, A.k0p, A.inv_in[0], A.qmax);
+        // the codes of a layer's input: the input layer uses k block 0 only (and of it only k positions 0..3, the
+        // rest of its fragments being zero), every hidden layer reads all sixteen from the exchange area first
+        dhq_v4i cd[PAIR_KB];
+#pragma unroll
+        for (int kb = 0; kb < PAIR_KB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        {
+            // (the lane's coordinate from the thread index afresh in every pass, like the output layer below: a
+            // loop-invariant per-lane address would be carried through all layers in registers it spills)
+            unsigned tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
+            const int64_t ci = tile * PAIR_TILE + S.grp * 32 + (tid & 31);
+            const int64_t cl = ci < A.n ? ci : A.n - 1;  // lanes past the end repeat the last coordinate and store nothing
+            cd[0][0] = fused_input_codes(A.coords, cl, A.k0, A.k0p, A.inv_in[0], A.qmax);
+        }
 
         dhq_v16f y[PAIR_NT];
         pair_input_layer<ACTK>(S, cc, cd, y, hA, h);
@@ -557,6 +564,14 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
             pair_copy_slot<0>(S); pair_copy_slot<1>(S); pair_copy_slot<2>(S); pair_copy_slot<3>(S);
             pair_copy_bias(S, 0);
             if (S.role == 0) {
+                // The coordinate index, the lane's place and its lane half are worked out again from the thread
+                // index (through an empty asm, so that the compiler cannot tell they are the values from the
+                // top of the pass): kept alive across all layers they would be spilled to scratch memory.
+                unsigned tid = threadIdx.x;
+                asm volatile("" : "+v"(tid));
+                const int lane = tid & 63, h = (tid >> 5) & 1;
+                const int64_t ci = tile * PAIR_TILE + S.grp * 32 + (tid & 31);
+                const bool valid = ci < A.n;
                 const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(lds + 2 * PAIR_BUF + S.grp * 16384) + lane;
                 const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(buf);
                 dhq_v16i acc;
