@@ -210,9 +210,9 @@ def main() -> int:
         model.calibrate(x)
     fused = model.has_fused() and not dynamic and args.path == "auto"
     flags = dhq.DHQ_FUSED if fused else dhq.DHQ_LAYERWISE
-    # dynamic scales: one fused kernel per layer where the library has them (hidden width <= 256;
-    # two-sided: fan-out <= 4 as well), the layer-by-layer kernels otherwise or with --path layerwise
-    dyn_fused = dynamic and args.path == "auto" and model.has_fused() and wl.dims[1] <= 256
+    # dynamic scales: one fused kernel per layer where the library has a whole-network kernel (two-sided: up to
+    # hidden width 256), the layer-by-layer kernels otherwise or with --path layerwise
+    dyn_fused = dynamic and args.path == "auto" and model.has_fused()
     if dynamic:
         flags = (dhq.DHQ_FUSED if dyn_fused else dhq.DHQ_LAYERWISE) | dhq.DHQ_DYNAMIC
 
@@ -305,7 +305,8 @@ def main() -> int:
         gbs = per_coord * n / (ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
                            "traffic": None,
-                           "kernel": (("dhq_fused2_layer_kernel" if two_sided else "dhq_fused_layer_kernel") +
+                           "kernel": (("dhq_fused2_layer_kernel" if two_sided else
+                                       "dhq_fused_pair_layer_kernel" if wl.dims[1] == 512 else "dhq_fused_layer_kernel") +
                                       ", all launches of one forward" if dyn_fused
                                       else "layer-by-layer path, all kernels of one forward"),
                            "algorithmic_hbm_bytes_per_launch": per_coord * n,

@@ -668,7 +668,7 @@ struct dyn_sizes {
 static dyn_sizes dyn_buffer_sizes(const dhq_model *m, int64_t n)
 {
     // the per-layer fused kernels store whole workgroup tiles
-    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : (m->fused2 ? dhq_fused2_dynamic_rows(n) : (size_t)n);
+    const size_t rows = m->fused ? dhq_fused_dynamic_rows(n) : m->fused2 ? dhq_fused2_dynamic_rows(n) : m->pair ? dhq_pair_dynamic_rows(n) : (size_t)n;
     dyn_sizes z;
     z.act = sizeof(float) * rows * m->max_dim;
     z.codes = (size_t)n * m->max_kp;
@@ -721,7 +721,8 @@ static int forward_dynamic(const dhq_model *m, const dyn_ws &ws, const float *co
     if (per_layer_fused) {
         const hipError_t e =
             m->fused2 ? dhq_fused2_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st)
-                      : dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st);
+            : m->fused ? dhq_fused_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st)
+                       : dhq_pair_dynamic_launch(m, coords_dev, n, out_dev, ws.act0, ws.act1, ws.partial, ws.params, st);
         return e == hipSuccess ? DHQ_OK : DHQ_EHIP;
     }
     const float *cur = coords_dev;
@@ -749,7 +750,7 @@ static int check_dynamic_call(const dhq_model *m, int64_t n, uint32_t path, bool
 {
     if (!m || n < 0) return DHQ_EINVAL;
     if (path == 3u) return DHQ_EINVAL;
-    const bool dyn_fused_ok = (m->fused || m->fused2) && m->dyn_sine_ok;  // per-layer fused kernels of the dynamic mode
+    const bool dyn_fused_ok = (m->fused || m->fused2 || m->pair) && m->dyn_sine_ok;  // per-layer fused kernels of the dynamic mode
     if (m->flt) return DHQ_EUNSUPPORTED;
     if (path == DHQ_FUSED && !dyn_fused_ok) return DHQ_EUNSUPPORTED;
     *per_layer_fused = path != DHQ_LAYERWISE && dyn_fused_ok;

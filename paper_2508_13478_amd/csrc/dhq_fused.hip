@@ -144,6 +144,9 @@ __device__ __forceinline__ void fused_gemm_sine_hm(const dhq_v4i *__restrict__ w
                                                    const dhq_v4i (&hA)[2], int lane, int h, float c2 = 0.f)
 {
     constexpr hm_sched<NT, KB> S{};
+    // the multiplier in a vector register: a multiply-add whose operands are all vector registers issues in about
+    // 3 clocks per wave, one with a scalar operand in about 4.5 (measured with a register-only loop)
+    asm volatile("" : "+v"(c1));
     constexpr int LAST = S.last;
     constexpr int NM = NT * KB;
     constexpr int EPS = 16 / KB;  // accumulators drained per step (KB <= 8: an even number)
@@ -245,6 +248,7 @@ __device__ __forceinline__ void fused_tile_stages(dhq_v16f (&xt)[NT])
 template <int NT>
 __device__ __forceinline__ void fused_quantize(const dhq_v16f (&xt)[NT], dhq_v4i (&cd)[NT], float inv, int qlo, int qhi)
 {
+    asm volatile("" : "+v"(inv));  // a vector-register multiplier, as in fused_gemm_sine_hm
 #pragma unroll
     for (int w = 0; w < NT * 4; ++w) {
         const int v = 4 * (w & 3);

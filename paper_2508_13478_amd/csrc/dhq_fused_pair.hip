@@ -63,7 +63,8 @@ struct pair_args {
     int k0, k0p;
     int m_out;
     int qmax;
-    int n_chunks;              // weight chunks per coordinate pass: 2 + 8 (n_layers - 2)
+    int n_chunks;              // weight chunks a coordinate pass goes through, in a cycle: 2 + 8 (n_layers - 2) (the whole network)
+    int chunk_base;            // first of them: 0 (the whole network), or a single layer's first chunk
     uint32_t bias_off;         // byte offset of the bias table in the blob: [layer][512] floats, bias_slot order per tile
     float c2;                  // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     float c1[DHQ_MAX_LAYERS];
@@ -128,7 +129,7 @@ __device__ __forceinline__ void pair_enter_chunk(pair_stream &S, int cc)
 {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
-    const int j = (cc + 1) % S.A->n_chunks;
+    const int j = S.A->chunk_base + (cc + 1) % S.A->n_chunks;
     S.cp_src = S.A->blob + (size_t)j * PAIR_BUF + S.wave * 1024;
     S.cp_dst = pair_lds_addr(S.lds) + ((cc + 1) & 1) * PAIR_BUF + S.wave * 1024;
 }
@@ -283,15 +284,15 @@ __device__ __forceinline__ void pair_steps(pair_ctx<ACTK> &C, std::integer_seque
 // A hidden layer: reads the input codes the transform left in the exchange area, then the GEMM
 // pipeline over this wave's eight tiles.  cc is the running chunk count and is advanced.
 template <int ACTK>
-__device__ __forceinline__ void pair_hidden(pair_stream &S, int &cc, int layer, dhq_v4i (&cd)[PAIR_KB], dhq_v16f (&y)[PAIR_NT],
-                                            const dhq_v4i (&hA)[2], int h)
+__device__ __forceinline__ void pair_hidden(pair_stream &S, int &cc, int layer, float c1, dhq_v4i (&cd)[PAIR_KB],
+                                            dhq_v16f (&y)[PAIR_NT], const dhq_v4i (&hA)[2], int h)
 {
     // last step with work: the send after the fourth H_32 product of the last tile would be
     // e2 - 11 = 16 * 7 + 12, the product itself 16 * 7 + 9
     constexpr int NSTEPS = 16 * (PAIR_NT - 1) + 9 + 11 + 2 + PAIR_KB + 1;
     pair_ctx<ACTK> C(S, cd, y, hA);
     C.cc = cc;
-    C.c1 = S.A->c1[layer];
+    C.c1 = c1;
     C.c2 = S.A->c2;
     C.ex = C.ey = 0.f;
     C.layer = layer;
@@ -359,12 +360,12 @@ __device__ __forceinline__ void pair_steps0(pair_ctx<ACTK> &C, int h, std::integ
 }
 
 template <int ACTK>
-__device__ __forceinline__ void pair_input_layer(pair_stream &S, int &cc, dhq_v4i (&cd)[PAIR_KB], dhq_v16f (&y)[PAIR_NT],
+__device__ __forceinline__ void pair_input_layer(pair_stream &S, int &cc, float c1, dhq_v4i (&cd)[PAIR_KB], dhq_v16f (&y)[PAIR_NT],
                                                  const dhq_v4i (&hA)[2], int h)
 {
     pair_ctx<ACTK> C(S, cd, y, hA);
     C.cc = cc;
-    C.c1 = S.A->c1[0];
+    C.c1 = c1;
     C.c2 = S.A->c2;
     C.layer = 0;
     C.bias = reinterpret_cast<const float4 *>(S.lds + PAIR_BIAS + pair_bias_slot(0) * 2048) + S.role * 64 + h;
@@ -402,14 +403,12 @@ __device__ __forceinline__ void pair_barrier()
     __syncthreads();
 }
 
-// The rest of the transform and the next layer's quantizer.  On return the exchange area holds,
-// per coordinate group, the next layer's whole B operand ([k block][lane] x 16 B); it may be read
-// after the next barrier.  xrow (test hook): where this lane's coordinate keeps its row of x^.
-template <bool DUMP, bool AFTER_INPUT_LAYER = true>
-__device__ __forceinline__ void pair_transform_quant(pair_stream &S, dhq_v16f (&y)[PAIR_NT], float inv, int qlo, int qhi, int h,
-                                                     float *xrow = nullptr, int *crow = nullptr)
+// The rest of the transform: on return zl[T][i] / zh[T][i] hold the un-normalised x^ of rotated features
+// 32 T + 8 (i / 4 + 2 role) + 4 h + i % 4 and 256 + the same (zh of role 1 with its sign flipped), and
+// the exchange area is free.
+template <bool AFTER_INPUT_LAYER>
+__device__ __forceinline__ void pair_transform(pair_stream &S, dhq_v16f (&y)[PAIR_NT], float (&zl)[PAIR_NT][8], float (&zh)[PAIR_NT][8])
 {
-    float zl[PAIR_NT][8], zh[PAIR_NT][8];
     // the halves sent during the GEMM phase are in place: a hidden layer's last sends precede its last chunk
     // barriers, the input layer has none
     if constexpr (AFTER_INPUT_LAYER) pair_barrier();
@@ -449,6 +448,17 @@ __device__ __forceinline__ void pair_transform_quant(pair_stream &S, dhq_v16f (&
             }
         }
     }
+}
+
+// The rest of the transform and the next layer's quantizer.  On return the exchange area holds,
+// per coordinate group, the next layer's whole B operand ([k block][lane] x 16 B); it may be read
+// after the next barrier.  xrow (test hook): where this lane's coordinate keeps its row of x^.
+template <bool DUMP, bool AFTER_INPUT_LAYER = true>
+__device__ __forceinline__ void pair_transform_quant(pair_stream &S, dhq_v16f (&y)[PAIR_NT], float inv, int qlo, int qhi, int h,
+                                                     float *xrow = nullptr, int *crow = nullptr)
+{
+    float zl[PAIR_NT][8], zh[PAIR_NT][8];
+    pair_transform<AFTER_INPUT_LAYER>(S, y, zl, zh);
     const float inv_hi = S.role ? -inv : inv;
     if constexpr (DUMP) {
         // rotated feature of zl[T][i]: 32 T + 8 (i / 4 + 2 role) + 4 h + i % 4; zh: tile T + 8, sign as above
@@ -549,10 +559,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
         }
 
         dhq_v16f y[PAIR_NT];
-        pair_input_layer<ACTK>(S, cc, cd, y, hA, h);
+        pair_input_layer<ACTK>(S, cc, A.c1[0], cd, y, hA, h);
         pair_transform_quant<false, true>(S, y, A.inv_in[1], qlo, qhi, h);
         for (int l = 1; l < L - 1; ++l) {
-            pair_hidden<ACTK>(S, cc, l, cd, y, hA, h);
+            pair_hidden<ACTK>(S, cc, l, A.c1[l], cd, y, hA, h);
             pair_transform_quant<false, false>(S, y, A.inv_in[l + 1], qlo, qhi, h);
         }
 
@@ -593,6 +603,159 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel(const pair
         }
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+}
+
+// ---- one layer per launch: the dynamic quantization module (Sec. 3.3) at this width -----------
+// With scales measured on line a layer's quantizer needs max |x^| over the whole batch before it
+// can emit a code, so the whole-network kernel is cut at exactly that point, as
+// dhq_fused_layer_kernel cuts the narrower one: a launch folds the per-workgroup maxima its
+// predecessor left into this layer's constants (every workgroup for itself), quantizes its input
+// with them, runs the layer with the code of the kernel above and writes the un-normalised
+// transform x^ of its output (fp32) plus the workgroup's max |x^|.  x^ crosses device memory in the
+// waves' register order: [128-coordinate tile][wave][q = 4 T + {zl 0..3, zl 4..7, zh 0..3, zh 4..7}][lane]
+// x 16 B, every access of a wave 1 KiB contiguous; a wave reads back exactly what the wave in its
+// place wrote (zh of role 1 with its sign flipped, which the negated multiplier undoes).
+//   MODE 0  input layer: coordinates in, x^ out        MODE 1  hidden layer: x^ in, x^ out
+//   MODE 2  output layer: x^ in, signal values out
+struct pair_largs {
+    pair_args w;               // n_chunks / chunk_base: this layer's chunks; c1 and inv_in are not used
+    const float4 *xin;         // MODE 1, 2
+    float4 *xout;              // MODE 0, 1
+    const float *partial_in;   // max |x^| of this layer's input, one float per workgroup of the launch before
+    int partial_count;
+    int kp;                    // length of this layer's rotated input
+    int layer;
+    double c1_over_sa;         // epilogue multiplier divided by the activation scale
+    float *dyn;                // this layer's {1 / (s_a sqrt(Kp)), epilogue multiplier, s_a}: written by workgroup 0
+    float *partial;            // MODE 0, 1: max |x^| of the output per workgroup (not the buffer partial_in points to)
+};
+
+template <int MODE, int ACTK>
+__global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_layer_kernel(const pair_largs D)
+{
+    const pair_args &A = D.w;
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ float red_in[PAIR_WAVES], red[PAIR_WAVES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int64_t n_tiles = (A.n + PAIR_TILE - 1) / PAIR_TILE;  // the grid has at most that many workgroups
+    const int my_tiles = (int)((n_tiles - 1 - blockIdx.x) / gridDim.x) + 1;
+    const int qlo = DHQ_MAGIC_I - A.qmax, qhi = DHQ_MAGIC_I + A.qmax;
+
+    pair_stream S;
+    pair_stream_init(S, &A, lds, wave, lane);
+    int cc = 0;
+    pair_copy_now(S, A.chunk_base, 0);
+    pair_copy_bias(S, D.layer);
+    dhq_v4i hA[2];
+    pair_h32_operand(c, h, S.role, hA);
+
+    // this layer's constants from the maxima of its input
+    float inv, c1, s_a;
+    {
+        float mi = 0.f;
+        for (int i = threadIdx.x; i < D.partial_count; i += PAIR_THREADS) mi = fmaxf(mi, D.partial_in[i]);
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mi = fmaxf(mi, __shfl_xor(mi, m, 64));
+        if (lane == 0) red_in[wave] = mi;
+        __syncthreads();
+        mi = red_in[0];
+#pragma unroll
+        for (int w = 1; w < PAIR_WAVES; ++w) mi = fmaxf(mi, red_in[w]);
+        dhq_dyn_constants(mi, D.kp, A.qmax, D.c1_over_sa, inv, c1, s_a);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            D.dyn[0] = inv; D.dyn[1] = c1; D.dyn[2] = s_a;
+        }
+    }
+    float mx = 0.f;
+    for (int it = 0; it < my_tiles; ++it) {
+        const int64_t tile = (int64_t)blockIdx.x + (int64_t)it * gridDim.x;
+        const size_t slot = ((size_t)tile * PAIR_WAVES + S.wave) * (4 * PAIR_NT) * 64 + lane;
+        dhq_v4i cd[PAIR_KB];
+#pragma unroll
+        for (int kb = 0; kb < PAIR_KB; ++kb) cd[kb] = dhq_v4i{0, 0, 0, 0};
+        if constexpr (MODE == 0) {
+            const int64_t ci = tile * PAIR_TILE + S.grp * 32 + c;
+            const int64_t cl = ci < A.n ? ci : A.n - 1;  // lanes past the end repeat the last coordinate: no effect on the maximum
+            cd[0][0] = fused_input_codes(A.coords, cl, A.k0, A.k0p, inv, A.qmax);
+        } else {
+            // the output layer's role-0 waves may still be reading the previous tile's codes
+            if constexpr (MODE == 2) pair_barrier();
+            // this wave's 128 values of the layer's input: quantized, its two dwords of every k block to the exchange
+            // area, where pair_transform_quant puts them in the whole-network kernel
+            const float inv_hi = S.role ? -inv : inv;
+            unsigned char *dst = lds + 2 * PAIR_BUF + S.grp * 16384 + lane * 16 + S.role * 8;
+#pragma unroll
+            for (int T = 0; T < PAIR_NT; ++T) {
+                const float4 l0 = D.xin[slot + (size_t)(4 * T) * 64], l1 = D.xin[slot + (size_t)(4 * T + 1) * 64];
+                const float4 h0 = D.xin[slot + (size_t)(4 * T + 2) * 64], h1 = D.xin[slot + (size_t)(4 * T + 3) * 64];
+                const unsigned a0 = fused_quant4(l0.x, l0.y, l0.z, l0.w, inv, qlo, qhi);
+                const unsigned a1 = fused_quant4(l1.x, l1.y, l1.z, l1.w, inv, qlo, qhi);
+                const unsigned b0 = fused_quant4(h0.x, h0.y, h0.z, h0.w, inv_hi, qlo, qhi);
+                const unsigned b1 = fused_quant4(h1.x, h1.y, h1.z, h1.w, inv_hi, qlo, qhi);
+                *reinterpret_cast<uint2 *>(dst + T * 1024) = make_uint2(a0, a1);
+                *reinterpret_cast<uint2 *>(dst + (T + 8) * 1024) = make_uint2(b0, b1);
+            }
+        }
+        if constexpr (MODE == 2) {
+            // one zero-padded M tile, no activation: role 0 computes it while all waves copy the chunk in again
+            pair_enter_chunk(S, cc);
+            const unsigned char *buf = lds + (cc & 1) * PAIR_BUF;
+            pair_copy_slot<0>(S); pair_copy_slot<1>(S); pair_copy_slot<2>(S); pair_copy_slot<3>(S);
+            if (S.role == 0) {
+                const int64_t ci = tile * PAIR_TILE + S.grp * 32 + c;
+                const dhq_v4i *src = reinterpret_cast<const dhq_v4i *>(lds + 2 * PAIR_BUF + S.grp * 16384) + lane;
+                const dhq_v4i *wA = reinterpret_cast<const dhq_v4i *>(buf);
+                dhq_v16i acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+                for (int kb = 0; kb < PAIR_KB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wA[kb * 64 + lane], src[kb * 64], acc, 0, 0, 0);
+                const float *wB = reinterpret_cast<const float *>(lds + PAIR_BIAS + pair_bias_slot(D.layer) * 2048);
+                if (ci < A.n) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+                        if (row < A.m_out) A.out[ci * A.m_out + row] = __builtin_fmaf((float)acc[v], c1, wB[((v >> 2) * 2 + h) * 4 + (v & 3)]);
+                    }
+                }
+            }
+            cc += 1;
+        } else {
+            dhq_v16f y[PAIR_NT];
+            float zl[PAIR_NT][8], zh[PAIR_NT][8];
+            if constexpr (MODE == 0) {
+                pair_input_layer<ACTK>(S, cc, c1, cd, y, hA, h);
+                pair_transform<true>(S, y, zl, zh);
+            } else {
+                pair_hidden<ACTK>(S, cc, D.layer, c1, cd, y, hA, h);
+                pair_transform<false>(S, y, zl, zh);
+            }
+#pragma unroll
+            for (int T = 0; T < PAIR_NT; ++T) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float(&z)[8] = (q < 2) ? zl[T] : zh[T];
+                    const float4 x = make_float4(z[4 * (q & 1)], z[4 * (q & 1) + 1], z[4 * (q & 1) + 2], z[4 * (q & 1) + 3]);
+                    mx = fmaxf(fmaxf(mx, fmaxf(fabsf(x.x), fabsf(x.y))), fmaxf(fabsf(x.z), fabsf(x.w)));
+                    D.xout[slot + (size_t)(4 * T + q) * 64] = x;
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if constexpr (MODE != 2) {
+#pragma unroll
+        for (int m = 1; m < 64; m *= 2) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        if (lane == 0) red[wave] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float r = red[0];
+#pragma unroll
+            for (int w = 1; w < PAIR_WAVES; ++w) r = fmaxf(r, red[w]);
+            D.partial[blockIdx.x] = r;
+        }
+    }
 }
 
 // ---- test hook: one layer of the kernel above on caller-supplied codes ------------------------
@@ -671,7 +834,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel_debug(cons
         unsigned w = 0;
         for (int k = 0; k < D.kp_in; ++k) w |= (unsigned)(uint8_t)D.codes_in[cl * D.kp_in + k] << (8 * k);
         cd[0][0] = (int)w;
-        pair_input_layer<ACTK>(S, cc, cd, y, hA, h);
+        pair_input_layer<ACTK>(S, cc, A.c1[0], cd, y, hA, h);
     } else {
         // the hidden layer reads its codes from the exchange area: [group][k block][lane] x 16 B,
         // dword q of k block T = rotated features 32 T + 8 q + 4 h .. + 3; role r brings in dwords 2 r, 2 r + 1
@@ -683,7 +846,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void dhq_fused_pair_kernel_debug(cons
             const unsigned a1 = *reinterpret_cast<const unsigned *>(D.codes_in + cl * D.kp_in + f + 8);
             *reinterpret_cast<uint2 *>(dst + T * 1024) = make_uint2(a0, a1);
         }
-        pair_hidden<ACTK>(S, cc, l, cd, y, hA, h);
+        pair_hidden<ACTK>(S, cc, l, A.c1[l], cd, y, hA, h);
     }
     // both outputs go to workspace buffers with room for whole workgroup tiles, so nothing here is conditional
     pair_transform_quant<true>(S, y, A.inv_in[l + 1], qlo, qhi, h, D.xhat + ci * 512, reinterpret_cast<int *>(D.codes_out + ci * 512));
@@ -817,6 +980,65 @@ hipError_t dhq_pair_launch(const dhq_pair_plan *P, const float *coords, int64_t 
     if (e != hipSuccess) return e;
     kern<<<grid, PAIR_THREADS, P->lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+
+// The dynamic mode on the per-layer kernels above (same contract as dhq_fused_dynamic_launch): ws0 / ws1 hold
+// dhq_pair_dynamic_rows(n) x 512 floats each.
+size_t dhq_pair_dynamic_rows(int64_t n) { return (size_t)((n + PAIR_TILE - 1) / PAIR_TILE) * PAIR_TILE; }
+
+template <int MODE, int ACTK>
+static hipError_t pairl_launch_t(const dhq_pair_plan *P, const pair_largs &a, unsigned grid, hipStream_t st)
+{
+    auto kern = dhq_fused_pair_layer_kernel<MODE, ACTK>;
+    hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
+    if (e != hipSuccess) return e;
+    kern<<<grid, PAIR_THREADS, P->lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t dhq_pair_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                   float *partial, float *dyn, hipStream_t st)
+{
+    const dhq_pair_plan *P = m->pair;
+    if (!P) return hipErrorInvalidValue;
+    if (n <= 0) return hipSuccess;
+    const int L = m->n_layers;
+    const bool wav = (P->act_kind == DHQ_ACT_KIND_WAVELET);
+    const int64_t tiles = (n + PAIR_TILE - 1) / PAIR_TILE;
+    const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
+    if (grid > DHQ_ABSMAX_PARTIALS) return hipErrorInvalidValue;
+    // the input layer's scale: max over the rotated coordinates, left as per-workgroup maxima
+    float *pbuf[2] = {partial, partial + DHQ_ABSMAX_PARTIALS};
+    int count = 0;
+    hipError_t e = dhq_launch_wht_absmax_partials(coords, n, m->layer[0].K, m->layer[0].Kp, pbuf[0], &count, st);
+    if (e != hipSuccess) return e;
+    float *bufs[2] = {ws0, ws1};
+    for (int l = 0; l < L; ++l) {
+        pair_largs a;
+        memset(&a, 0, sizeof(a));
+        a.w = P->args;
+        a.w.coords = coords;
+        a.w.out = out;
+        a.w.n = n;
+        // the chunks of this layer alone, in a cycle
+        a.w.chunk_base = (l == 0) ? 0 : (l == L - 1 ? P->args.n_chunks - 1 : 1 + 8 * (l - 1));
+        a.w.n_chunks = (l == 0 || l == L - 1) ? 1 : 8;
+        a.xin = reinterpret_cast<const float4 *>(bufs[(l + 1) & 1]);
+        a.xout = reinterpret_cast<float4 *>(bufs[l & 1]);
+        a.partial_in = pbuf[l & 1];
+        a.partial_count = count;
+        a.kp = m->layer[l].Kp;
+        a.layer = l;
+        a.c1_over_sa = dhq_c1_over_sa(m, l);
+        a.dyn = dyn + 3 * l;
+        a.partial = pbuf[(l + 1) & 1];
+        if (l == 0) e = wav ? pairl_launch_t<0, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : pairl_launch_t<0, DHQ_ACT_KIND_SINE>(P, a, grid, st);
+        else if (l < L - 1) e = wav ? pairl_launch_t<1, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : pairl_launch_t<1, DHQ_ACT_KIND_SINE>(P, a, grid, st);
+        else e = pairl_launch_t<2, DHQ_ACT_KIND_NONE>(P, a, grid, st);  // the output layer has no activation
+        if (e != hipSuccess) return e;
+        count = (int)grid;
+    }
+    return hipSuccess;
 }
 
 // Test hook behind dhq_forward_debug_fused for the two-wave kernel.

@@ -22,8 +22,9 @@
 // accumulator order.  Hence the next layer's weights are packed with
 // their k positions in P0 order, and again nothing is shuffled at run time.
 //
-// The output layer needs fan-out padded to at most 4 (one tile, rows e = 0..3 of lane half 0):
-// its un-rotation is two butterfly stages on four registers.
+// The output layer (fan-out padded to at most 32) is one tile whose rows are arranged so that its
+// un-rotation is butterfly stages on the lane's sixteen accumulators plus, for 32 outputs, one
+// exchange between the lane halves (f2_out_row).
 #include <math.h>
 #include <string.h>
 
@@ -52,7 +53,7 @@ struct f2_args {
     int64_t n;
     int n_layers;
     int k0, k0p;
-    int m_out, m_out_p;  // fan-out of the output layer and its power-of-two padding (<= 4)
+    int m_out, m_out_p;  // fan-out of the output layer and its power-of-two padding (<= 32)
     int qmax;
     float c2;            // wavelet activation: 2 pi s0 sqrt(log2 e) / omega0
     f2_layer_desc layer[DHQ_MAX_LAYERS];
@@ -217,8 +218,14 @@ __device__ __forceinline__ void f2_hidden_layer(const dhq_v4i *__restrict__ wA, 
     }
 }
 
-// Output layer: one zero-padded tile; rows e = 0..3 of lane half 0 carry the (<= 4) rotated
-// outputs, un-rotated by two butterfly stages.  wB: the biases in plain order.
+// Tile row that holds rotated output j (< 32) of the output layer: bits 0, 1 of j are the row-in-group e,
+// bits 2, 3 the row group g and bit 4 the lane half, so that accumulator v = j % 16 of lane half j / 16
+// holds it and the stages of the un-rotation over bits 0..3 of j never leave the lane.
+static inline int f2_out_row(int j) { return 8 * ((j >> 2) & 3) + 4 * (j >> 4) + (j & 3); }
+
+// Output layer: one zero-padded tile whose rows are arranged by f2_out_row; the (<= 32) rotated
+// outputs are un-rotated by butterfly stages over the accumulator index and, for 32 of them, one
+// exchange between the lane halves.  wB: the biases in plain order.
 template <int NKB>
 __device__ __forceinline__ void f2_output_layer(const dhq_v4i *__restrict__ wA, const float *__restrict__ wB,
                                                 const dhq_v4i (&cd)[NKB], float c1, float *__restrict__ out, int64_t ci, bool valid,
@@ -232,19 +239,35 @@ __device__ __forceinline__ void f2_output_layer(const dhq_v4i *__restrict__ wA, 
         const dhq_v4i a = wA[kb * 64 + lane];
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, cd[kb], acc, 0, 0, 0);
     }
-    unsigned z[4] = {(unsigned)acc[0], (unsigned)acc[1], (unsigned)acc[2], (unsigned)acc[3]};
-    if (m_out_p >= 2) {
-        unsigned a = z[0], b = z[1]; z[0] = a + b; z[1] = a - b;
-        a = z[2]; b = z[3]; z[2] = a + b; z[3] = a - b;
-    }
-    if (m_out_p == 4) {
-        unsigned a = z[0], b = z[2]; z[0] = a + b; z[2] = a - b;
-        a = z[1]; b = z[3]; z[1] = a + b; z[3] = a - b;
-    }
-    if (valid && h == 0) {
+    unsigned z[16];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (e < m_out) out[ci * m_out + e] = __builtin_fmaf((float)(int)z[e], c1, wB[e]);
+    for (int v = 0; v < 16; ++v) z[v] = (unsigned)acc[v];
+#pragma unroll
+    for (int s = 1; s < 16; s <<= 1) {
+        if (m_out_p > s) {  // wave-uniform
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                if ((v & s) == 0) {
+                    const unsigned a = z[v], b = z[v | s];
+                    z[v] = a + b;
+                    z[v | s] = a - b;
+                }
+            }
+        }
+    }
+    if (m_out_p > 16) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const unsigned p = (unsigned)__shfl_xor((int)z[v], 32, 64);
+            z[v] = h ? p - z[v] : z[v] + p;
+        }
+    }
+    if (valid) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int j = 16 * h + v;
+            if (j < m_out) out[ci * m_out + j] = __builtin_fmaf((float)(int)z[v], c1, wB[j]);
+        }
     }
 }
 
@@ -517,7 +540,7 @@ static bool fused2_shape_ok(const dhq_model *m, int *nf_out)
 {
     const int L = m->n_layers;
     if (!m->rot_out || L < 2) return false;
-    if (m->dims[0] > 4 || m->dims[L] > 4) return false;
+    if (m->dims[0] > 4 || m->dims[L] > 32) return false;
     const int nf = m->dims[1];
     if (nf != 32 && nf != 64 && nf != 128 && nf != 256) return false;
     for (int l = 1; l < L; ++l)
@@ -550,7 +573,10 @@ int dhq_fused2_create(const dhq_model *m, dhq_fused2_plan **plan_out)
         for (int T = 0; T < Mt; ++T)
             for (int kb = 0; kb < Kb; ++kb)
                 for (int ln = 0; ln < 64; ++ln) {
-                    const int row = 32 * T + (ln & 31), u = ln >> 5;
+                    // rotated output index this lane's A row stands for: tile rows in natural order, except in the
+                    // output layer, whose rows are arranged for the in-lane un-rotation (inverse of f2_out_row)
+                    const int tr = ln & 31, u = ln >> 5;
+                    const int row = (l == L - 1) ? ((tr & 3) | ((tr >> 3) << 2) | (((tr >> 2) & 1) << 4)) : 32 * T + tr;
                     for (int jj = 0; jj < 16; ++jj) {
                         int8_t val = 0;
                         if (row < Ly.Mg) {

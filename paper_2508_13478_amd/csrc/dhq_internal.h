@@ -201,6 +201,11 @@ int dhq_pair_create(const dhq_model *m, dhq_pair_plan **plan);
 void dhq_pair_destroy(dhq_pair_plan *plan);
 int dhq_pair_update_scales(const dhq_model *m, dhq_pair_plan *plan);
 hipError_t dhq_pair_launch(const dhq_pair_plan *plan, const float *coords, int64_t n, float *out, hipStream_t st);
+// Dynamic mode at this width, one launch per layer (same contract as dhq_fused_dynamic_launch; ws0 / ws1:
+// dhq_pair_dynamic_rows(n) x 512 floats each).
+size_t dhq_pair_dynamic_rows(int64_t n);
+hipError_t dhq_pair_dynamic_launch(const dhq_model *m, const float *coords, int64_t n, float *out, float *ws0, float *ws1,
+                                   float *partial, float *dyn, hipStream_t st);
 // Which width-512 kernel a model runs at the moment.
 #define DHQ_WIDE_DEFAULT_TWO_WAVES 1
 static inline bool dhq_use_pair(const dhq_model *m)
