@@ -66,8 +66,8 @@ typedef enum {
  * quantization module ... between layers").  With DHQ_LAYERWISE: an absmax pass added to every layer, any
  * shape.  With DHQ_FUSED (and DHQ_AUTO where available): one kernel per layer that keeps the
  * layer's arithmetic in registers and passes only the transformed activations through device
- * memory; exists on the shapes the whole-network kernels for hidden widths 32 .. 256 cover
- * (either rotation mode), DHQ_EUNSUPPORTED otherwise. */
+ * memory; exists on every shape that has a whole-network kernel (either rotation mode),
+ * DHQ_EUNSUPPORTED otherwise. */
 #define DHQ_DYNAMIC 4u
 
 /* dhq_quantize_weights_mode: which sides of the weight matrix are rotated. */
@@ -111,7 +111,7 @@ int dhq_quantize_weights(const dhq_net_desc *desc, const float *const *W_host,
  *     y    = z[:, :M] * (s_a s_w / sqrt(Mp)) + b
  * Weights for which |z| could leave int32 (bound: qmax_a * sum_k |(H_Mp W'q)[j][k]| for some
  * output j) are refused with DHQ_EUNSUPPORTED.  Such a model has a fused kernel when fan-in
- * <= 4, all hidden widths are equal and 32 / 64 / 128 / 256, and fan-out <= 4; otherwise it
+ * <= 4, all hidden widths are equal and 32 / 64 / 128 / 256, and fan-out <= 32; otherwise it
  * runs on the layer-by-layer path only.  dhq_get_weight_codes returns Mp x Kp codes,
  * dhq_gemm_i8 the rotated accumulators (n x Mp) and dhq_forward_debug the un-rotated ones
  * (n x Mp).
@@ -249,7 +249,7 @@ int dhq_reserve_dynamic(dhq_model *m, int64_t n);
  *   flags  DHQ_AUTO / DHQ_LAYERWISE / DHQ_FUSED (the dynamic mode is implied)
  *   n      at most dhq_noalloc_max_rows(m) rows, else DHQ_ETOOBIG and nothing is enqueued.  The buffer
  *          is 32 MiB per device (held by every device that has loaded the library, until the process
- *          ends): e.g. 14336 rows for a 256-wide network, 7281 for a 512-wide one.
+ *          ends): e.g. 14336 rows for a 256-wide network, about 7200 for a 512-wide one.
  * All calls on one device share that device's buffer, whichever model they use: calls that overlap
  * in time on one device (different streams or threads) race and give wrong results; calls on one
  * stream, or otherwise ordered, are fine.  The buffer keeps the last call's contents; nothing in it
