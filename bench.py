@@ -29,7 +29,7 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 # this script (profiles/ has the summaries), each counter scaled by what it reads for a plain
 # 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
 # the hash below is compared with the current sources and the figure is dropped if they differ.
-TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_wide.hip", "dhq_fused_common.h", "dhq_device.h")
+TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_pair.hip", "dhq_fused_common.h", "dhq_device.h")
 TRAFFIC_SHA256 = "606abad06a56a5e1be04ae723d0bf922c1e99e0cacb73e58a6bc8573eb22b452"
 TRAFFIC_BYTES = {"C2": (2524.8 + 768.0) * 1024, "C5": (44537.6 + 49152.0) * 1024}
 
@@ -250,7 +250,8 @@ def main() -> int:
                      "traffic_unit": "HBM bytes per launch, stored from the rocprofv3 --pmc runs summarised in "
                                      "profiles/dhq_fused_hbm_traffic_pmc.md (null when the kernel sources have changed since)",
                      "kernel": ((f"dhq_fused2_kernel<{wl.dims[1]}>" if two_sided else
-                                 f"dhq_fused_wide_kernel<512, {2 if s0 is not None else 1}>" if wl.dims[1] == 512 else
+                                 (f"dhq_fused_wide_kernel<512, {2 if s0 is not None else 1}>" if args.wide_kernel == 1 else
+                                  f"dhq_fused_pair_kernel<{2 if s0 is not None else 1}>") if wl.dims[1] == 512 else
                                  f"dhq_fused_kernel<{wl.dims[1]}, {2 if s0 is not None else 1}>")
                                 if fused else "layerwise kernels"),
                      "algorithmic_hbm_bytes_per_launch": 4 * (wl.dims[0] + wl.dims[-1]) * n,
