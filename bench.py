@@ -25,13 +25,15 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, 5.0 POP/s
 VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz fp32 lane-ops/s
 
 
-# HBM bytes per launch of the fused kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (profiles/ has the summaries), each counter scaled by what it reads for a plain
-# 256 MiB device copy in the same run.  Valid only for the kernel sources they were taken with:
-# the hash below is compared with the current sources and the figure is dropped if they differ.
+# Figures stored from rocprofv3 --pmc runs of this script (profiles/ has the summaries and the commands):
+# HBM bytes per launch of the fused kernel (FETCH_SIZE / WRITE_SIZE, each counter scaled by what it reads for
+# a plain 256 MiB device copy in the same run), and the fraction of SIMD cycles the vector ALU and the matrix
+# unit were busy.  Valid only for the kernel sources they were taken with: the hash below is compared with
+# the current sources and the figures are dropped if they differ.
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_pair.hip", "dhq_fused_common.h", "dhq_device.h")
-TRAFFIC_SHA256 = "606abad06a56a5e1be04ae723d0bf922c1e99e0cacb73e58a6bc8573eb22b452"
-TRAFFIC_BYTES = {"C2": (2524.8 + 768.0) * 1024, "C5": (44537.6 + 49152.0) * 1024}
+TRAFFIC_SHA256 = "8ac80e8df884c001dbeb3d412ab5d477c74c62dc63155fc71cd5a277a3728a72"
+TRAFFIC_BYTES = {"C2": 2593792 + 786432, "C5": 45164544 + 50331648}
+COUNTER_BUSY = {"C2": {"valu": 0.655, "mfma": 0.260}, "C4": {"valu": 0.889, "mfma": 0.370}, "C5": {"valu": 0.691, "mfma": 0.435}}
 
 
 def kernel_sources_sha256():
@@ -245,7 +247,8 @@ def main() -> int:
         # layer shapes
         "roofline": {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": tops / INT8_MFMA_PEAK_TOPS,
-                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and s0 is None and kernel_sources_sha256() == TRAFFIC_SHA256
+                     "traffic": (TRAFFIC_BYTES.get(wl.name) if fused and not two_sided and s0 is None and not cplx and args.wide_kernel != 1
+                                 and kernel_sources_sha256() == TRAFFIC_SHA256
                                  else None),
                      "traffic_unit": "HBM bytes per launch, stored from the rocprofv3 --pmc runs summarised in "
                                      "profiles/dhq_fused_hbm_traffic_pmc.md (null when the kernel sources have changed since)",
@@ -275,6 +278,12 @@ def main() -> int:
     res["alu"] = {"bound": "alu", "achieved": lane_instr / 64 / (ms * 1e-3), "peak": valu_peak,
                   "unit": "wave64 instr/s", "frac": lane_instr / 64 / (ms * 1e-3) / valu_peak,
                   "model": f"{per_feature:.1f} vector instructions per feature and sine layer"}
+    if fused and not two_sided and s0 is None and not cplx and args.wide_kernel != 1 and kernel_sources_sha256() == TRAFFIC_SHA256:
+        busy = COUNTER_BUSY.get(wl.name)
+        if busy:
+            res["alu"]["counter_valu_busy_frac"] = busy["valu"]
+            res["alu"]["counter_mfma_busy_frac"] = busy["mfma"]
+            res["alu"]["counter_source"] = "stored from the rocprofv3 --pmc run summarised in profiles/dhq_fused_utilisation_pmc.md"
     if floating:
         # fp32 activations: the same multiply-adds on the fp32 MFMA (157.3 TFLOP/s dense)
         tf = ops / (ms * 1e-3) / 1e12
@@ -335,7 +344,7 @@ def main() -> int:
     if args.workload == "C5" and args.variant == "base" and s0 is None and args.path == "auto" and not args.no_other_workloads:
         # the smaller configurations on the same kernels, for the record (not the headline)
         others = {}
-        for name, steps in (("C2", 400), ("C3", 100), ("C4", 40)):
+        for name, steps in (("C2", 2000), ("C3", 400), ("C4", 100)):
             wl2, coords2, W2, b2 = synth.make(name)
             m2 = dhq.Model(wl2.dims, wl2.omega0, W2, b2, 8, 8)
             x2 = torch.from_numpy(coords2).to("cuda")
