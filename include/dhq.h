@@ -162,7 +162,7 @@ int dhq_quantize_weights_wavelet(const dhq_net_desc *desc, uint32_t mode, float 
  *                part of the last layer's weights enters its real output, that of its bias does not
  * The model that comes back has the real dims (fan-in, 2 x width, ..., fan-out): every other
  * call (scales, calibration, forward, the test hooks, dhq_get_weight_codes) sees that real
- * network.  Whole-network kernel: hidden widths 16 / 32 / 64 / 128 complex (32 .. 256 real).
+ * network.  Whole-network kernel: hidden widths 16 / 32 / 64 / 128 / 256 complex (32 .. 512 real).
  */
 int dhq_quantize_weights_complex(const dhq_net_desc *desc, float s0, const float *const *W_re,
                                  const float *const *W_im, const float *const *b_re,

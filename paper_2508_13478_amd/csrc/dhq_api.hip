@@ -417,7 +417,7 @@ static int create_model(const dhq_net_desc *desc, uint32_t mode, int act_kind, f
     if (rc == DHQ_OK) rc = scratch_on_device(m->device, &m->scratch);
     if (rc == DHQ_OK && !m->rot_out) rc = dhq_fused_create(m, &m->fused);
     if (rc == DHQ_OK && !m->rot_out && !cplx) rc = dhq_wide_create(m, &m->wide);
-    if (rc == DHQ_OK && !m->rot_out && !cplx) rc = dhq_pair_create(m, &m->pair);
+    if (rc == DHQ_OK && !m->rot_out) rc = dhq_pair_create(m, &m->pair);  // (also the complex wavelet, which the one-wave kernel does not have)
     if (rc == DHQ_OK && m->rot_out) rc = dhq_fused2_create(m, &m->fused2);
     if (rc != DHQ_OK) {
         dhq_free(m);
@@ -549,7 +549,7 @@ extern "C" int dhq_has_fused(const dhq_model *m)
 {
     if (!m) return DHQ_EINVAL;
     if (m->flt) return (dhq_float_has_fused(m->flt) && m->fused_sine_ok) ? 1 : 0;
-    return ((m->fused || m->wide || m->fused2) && (!m->have_scales || m->fused_sine_ok)) ? 1 : 0;
+    return ((m->fused || m->wide || m->pair || m->fused2) && (!m->have_scales || m->fused_sine_ok)) ? 1 : 0;
 }
 
 extern "C" int dhq_select_wide_kernel(dhq_model *m, int32_t which)
@@ -790,8 +790,8 @@ extern "C" int dhq_forward(const dhq_model *m, const float *coords_dev, int64_t 
         return forward_dynamic(m, ws, coords_dev, n, out_dev, per_layer_fused, st);
     }
     // static scales; a whole-network kernel runs only where the sine's argument provably stays in range
-    const bool fused_ok = (m->fused || m->wide || m->fused2) && m->fused_sine_ok;
-    if (path == DHQ_FUSED && !(m->fused || m->wide || m->fused2)) return DHQ_EUNSUPPORTED;
+    const bool fused_ok = (m->fused || m->wide || m->pair || m->fused2) && m->fused_sine_ok;
+    if (path == DHQ_FUSED && !(m->fused || m->wide || m->pair || m->fused2)) return DHQ_EUNSUPPORTED;
     if (n == 0) return DHQ_OK;
     if (!coords_dev || !out_dev) return DHQ_EINVAL;
     if (!m->have_scales) return DHQ_ENOSCALE;
@@ -909,7 +909,7 @@ extern "C" int dhq_forward_debug_fused(const dhq_model *m, const int8_t *codes_i
                                        int8_t *codes_out_dev, int32_t *acc_dev, void *stream)
 {
     if (!m || n < 0 || layer < 0 || layer >= m->n_layers) return DHQ_EINVAL;
-    if (m->flt || !(m->fused || m->wide || m->fused2)) return DHQ_EUNSUPPORTED;
+    if (m->flt || !(m->fused || m->wide || m->pair || m->fused2)) return DHQ_EUNSUPPORTED;
     if (layer >= m->n_layers - 1) return DHQ_EUNSUPPORTED;  // the output layer has no transform after it
     if (n == 0) return DHQ_OK;
     if (!codes_in_dev) return DHQ_EINVAL;

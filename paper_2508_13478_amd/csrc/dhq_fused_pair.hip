@@ -162,7 +162,7 @@ struct pair_ctx {
     float4 bq0[4];
     dhq_v16i acc[2];
     unsigned hp[2][8], lp[2][8];  // binary16 pieces of the tile being drained and of the one before
-    float ex, ey;
+    float ex, ey, et;             // et: the complex wavelet's real-part argument, waiting for the imaginary one
     float ar[4];
     float er[2];
     __device__ __forceinline__ pair_ctx(pair_stream &S_, dhq_v4i (&cd_)[PAIR_KB], dhq_v16f (&y_)[PAIR_NT], const dhq_v4i (&hA_)[2])
@@ -262,7 +262,16 @@ __device__ __forceinline__ void pair_step(pair_ctx<ACTK> &C)
             if constexpr (e2 >= 3 && pm < NE / 2)
                 hm_remainders(C.ar[(e2 - 3) & 3], C.ar[(e2 - 2) & 3], C.hp[(pm / 8) & 1][pm % 8], C.er[0], C.er[1]);
         }
-        if constexpr (e2 >= 0 && e2 < NE) C.ar[e2 & 3] = dhq_activate_rev(C.ey, dhq_act{ACTK, C.c2});
+        if constexpr (e2 >= 0 && e2 < NE) {
+            if constexpr (ACTK == DHQ_ACT_KIND_WAVELET_COMPLEX) {
+                // accumulators e2 - 1, e2 (e2 odd) are the features 2m, 2m + 1 = (Re, Im) of one complex feature; both
+                // results are consumed from the step after this one on (the packing of the high pieces)
+                if constexpr ((e2 & 1) == 0) C.et = C.ey;
+                else dhq_activate_pair_rev<false>(C.et, C.ey, C.c2, C.ar[(e2 - 1) & 3], C.ar[e2 & 3]);
+            } else {
+                C.ar[e2 & 3] = dhq_activate_rev(C.ey, dhq_act{ACTK, C.c2});
+            }
+        }
         if constexpr (e1 >= 0 && e1 < NE) C.ey = __builtin_fmaf(C.ex, C.c1, pair_comp(C.bq[(e1 / 4) % 3], e1 % 4));
         if constexpr (e0 >= 0 && e0 < NE) C.ex = (float)C.acc[(e0 / 16) & 1][e0 % 16];
         if constexpr (e0 + 8 >= 0 && (e0 + 8) % 4 == 0 && e0 + 8 < NE) {
@@ -294,7 +303,7 @@ __device__ __forceinline__ void pair_hidden(pair_stream &S, int &cc, int layer, 
     C.cc = cc;
     C.c1 = c1;
     C.c2 = S.A->c2;
-    C.ex = C.ey = 0.f;
+    C.ex = C.ey = C.et = 0.f;
     C.layer = layer;
     C.bias = reinterpret_cast<const float4 *>(S.lds + PAIR_BIAS + pair_bias_slot(layer) * 2048) + S.role * 64 + h;
     pair_enter_chunk(S, cc);
@@ -342,8 +351,13 @@ __device__ __forceinline__ void pair_step0(pair_ctx<ACTK> &C, int h)
         for (int v = 0; v < 16; ++v) x[v] = (float)C.acc[0][v];
 #pragma unroll
         for (int v = 0; v < 16; ++v) x[v] = __builtin_fmaf(x[v], C.c1, pair_comp(C.bq0[v >> 2], v & 3));
+        if constexpr (ACTK == DHQ_ACT_KIND_WAVELET_COMPLEX) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) x[v] = dhq_activate_rev(x[v], dhq_act{ACTK, C.c2});
+            for (int d = 0; d < 8; ++d) dhq_activate_pair_rev<false>(x[2 * d], x[2 * d + 1], C.c2, x[2 * d], x[2 * d + 1]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) x[v] = dhq_activate_rev(x[v], dhq_act{ACTK, C.c2});
+        }
 #pragma unroll
         for (int d = 0; d < 8; ++d) hm_split_pair(x[2 * d], x[2 * d + 1], C.hp[G & 1][d], C.lp[G & 1][d]);
     }
@@ -975,7 +989,8 @@ hipError_t dhq_pair_launch(const dhq_pair_plan *P, const float *coords, int64_t 
     a.n = n;
     const int64_t tiles = (n + PAIR_TILE - 1) / PAIR_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
-    auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_pair_kernel<DHQ_ACT_KIND_WAVELET> : dhq_fused_pair_kernel<DHQ_ACT_KIND_SINE>;
+    auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_pair_kernel<DHQ_ACT_KIND_WAVELET>
+                : (P->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX) ? dhq_fused_pair_kernel<DHQ_ACT_KIND_WAVELET_COMPLEX> : dhq_fused_pair_kernel<DHQ_ACT_KIND_SINE>;
     hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
     if (e != hipSuccess) return e;
     kern<<<grid, PAIR_THREADS, P->lds_bytes, st>>>(a);
@@ -1003,7 +1018,7 @@ hipError_t dhq_pair_dynamic_launch(const dhq_model *m, const float *coords, int6
     if (!P) return hipErrorInvalidValue;
     if (n <= 0) return hipSuccess;
     const int L = m->n_layers;
-    const bool wav = (P->act_kind == DHQ_ACT_KIND_WAVELET);
+    const bool wav = (P->act_kind == DHQ_ACT_KIND_WAVELET), cpx = (P->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX);
     const int64_t tiles = (n + PAIR_TILE - 1) / PAIR_TILE;
     const unsigned grid = (unsigned)(tiles < P->n_cu ? tiles : P->n_cu);
     if (grid > DHQ_ABSMAX_PARTIALS) return hipErrorInvalidValue;
@@ -1032,8 +1047,10 @@ hipError_t dhq_pair_dynamic_launch(const dhq_model *m, const float *coords, int6
         a.c1_over_sa = dhq_c1_over_sa(m, l);
         a.dyn = dyn + 3 * l;
         a.partial = pbuf[(l + 1) & 1];
-        if (l == 0) e = wav ? pairl_launch_t<0, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : pairl_launch_t<0, DHQ_ACT_KIND_SINE>(P, a, grid, st);
-        else if (l < L - 1) e = wav ? pairl_launch_t<1, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : pairl_launch_t<1, DHQ_ACT_KIND_SINE>(P, a, grid, st);
+        if (l == 0) e = wav ? pairl_launch_t<0, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : cpx ? pairl_launch_t<0, DHQ_ACT_KIND_WAVELET_COMPLEX>(P, a, grid, st)
+                                                                                        : pairl_launch_t<0, DHQ_ACT_KIND_SINE>(P, a, grid, st);
+        else if (l < L - 1) e = wav ? pairl_launch_t<1, DHQ_ACT_KIND_WAVELET>(P, a, grid, st) : cpx ? pairl_launch_t<1, DHQ_ACT_KIND_WAVELET_COMPLEX>(P, a, grid, st)
+                                                                                                : pairl_launch_t<1, DHQ_ACT_KIND_SINE>(P, a, grid, st);
         else e = pairl_launch_t<2, DHQ_ACT_KIND_NONE>(P, a, grid, st);  // the output layer has no activation
         if (e != hipSuccess) return e;
         count = (int)grid;
@@ -1061,7 +1078,8 @@ hipError_t dhq_pair_debug_launch(const dhq_model *m, int layer, const int8_t *co
     d.kp_in = m->layer[layer].Kp;
     const unsigned grid = (unsigned)((n + PAIR_TILE - 1) / PAIR_TILE);
     auto kern = (P->act_kind == DHQ_ACT_KIND_WAVELET) ? dhq_fused_pair_kernel_debug<DHQ_ACT_KIND_WAVELET>
-                                                      : dhq_fused_pair_kernel_debug<DHQ_ACT_KIND_SINE>;
+                : (P->act_kind == DHQ_ACT_KIND_WAVELET_COMPLEX) ? dhq_fused_pair_kernel_debug<DHQ_ACT_KIND_WAVELET_COMPLEX>
+                                                                : dhq_fused_pair_kernel_debug<DHQ_ACT_KIND_SINE>;
     hipError_t e = dhq_lds_limit_once(kern, P->lds_bytes, P->device);
     if (e != hipSuccess) return e;
     if (acc) {

@@ -89,9 +89,10 @@ def case(dims_c, side, seed=0xC0DE, bits=8):
     return _cache[key]
 
 
-# complex widths: 32 and 128 have the whole-network kernel (real widths 64 and 256), 20 and 181 (the width the
-# published architecture uses next to a 256-wide real network) do not
-SHAPES = [([2, 32, 32, 32, 3], 64), ([2, 128, 128, 128, 128, 3], 96), ([2, 20, 20, 1], 50), ([2, 181, 181, 3], 40)]
+# complex widths: 32, 128 and 256 have a whole-network kernel (real widths 64, 256 and 512: the last on the two-wave
+# kernel), 20 and 181 (the width the published architecture uses next to a 256-wide real network) do not
+SHAPES = [([2, 32, 32, 32, 3], 64), ([2, 128, 128, 128, 128, 3], 96), ([2, 20, 20, 1], 50), ([2, 181, 181, 3], 40),
+          ([2, 256, 256, 256, 3], 72)]
 
 
 @pytest.mark.parametrize("dims_c,side", SHAPES, ids=[str(s[0][1]) for s in SHAPES])
@@ -130,7 +131,7 @@ def test_complex_forward(dims_c, side):
     _say(f"complex wavelet forward {dims_c}")
     assert np.abs(cs.out).max() > 0.02
     lw = _check_forward(cs, dhq.DHQ_LAYERWISE, "complex layer-by-layer")
-    fused_shape = dims_c[1] in (16, 32, 64, 128)
+    fused_shape = dims_c[1] in (16, 32, 64, 128, 256)
     assert cs.model.has_fused() == fused_shape
     if fused_shape:
         fu = _check_forward(cs, dhq.DHQ_FUSED, "complex fused")
