@@ -795,7 +795,7 @@ def test_models_give_back_their_device_memory():
 
 
 @pytest.mark.parametrize("variant", ["fused", "layerwise", "two_sided", "dynamic", "dynamic_fused", "dynamic_fused_two_sided",
-                                     "w32a32", "w32a32_layerwise"])
+                                     "w32a32", "w32a32_layerwise", "fused_512", "dynamic_fused_512"])
 def test_forward_replays_from_a_captured_graph(variant):
     """dhq_forward only enqueues kernels (no memset, no allocation, no synchronisation once the
     workspace exists), so a stream capture of it replays to the same bits as the eager call --
@@ -804,16 +804,21 @@ def test_forward_replays_from_a_captured_graph(variant):
     _say(f"graph replay {variant}")
     wl, coords, W, b = synth.make("C1")
     x = _dev(coords)
+    dims = list(wl.dims)
+    if variant.endswith("_512"):                             # the two-wave width-512 kernels, whole network and per layer
+        dims = [2, 512, 512, 512, 3]
+        W, b = synth.siren_init(dims, wl.omega0, 512)
     mode = {"two_sided": dhq.DHQ_ROTATE_BOTH, "dynamic_fused_two_sided": dhq.DHQ_ROTATE_BOTH,
             "w32a32": dhq.DHQ_W32A32, "w32a32_layerwise": dhq.DHQ_W32A32}.get(variant, dhq.DHQ_ROTATE_IN)
     flags = {"fused": dhq.DHQ_FUSED, "layerwise": dhq.DHQ_LAYERWISE, "dynamic": dhq.DHQ_LAYERWISE | dhq.DHQ_DYNAMIC,
              "dynamic_fused": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
              "dynamic_fused_two_sided": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
+             "fused_512": dhq.DHQ_FUSED, "dynamic_fused_512": dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC,
              "w32a32_layerwise": dhq.DHQ_LAYERWISE}.get(variant, dhq.DHQ_AUTO)
-    m = dhq.Model(wl.dims, wl.omega0, W, b, mode=mode)
+    m = dhq.Model(dims, wl.omega0, W, b, mode=mode)
     if not variant.startswith("w32a32"):
         m.calibrate(x)
-    out = torch.empty((x.shape[0], wl.dims[-1]), dtype=torch.float32, device="cuda")
+    out = torch.empty((x.shape[0], dims[-1]), dtype=torch.float32, device="cuda")
     eager = m.forward(x, flags=flags).clone()                # also grows the dynamic workspace before capture
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
