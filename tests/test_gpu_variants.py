@@ -437,6 +437,40 @@ def test_dynamic_whole_batch_buffers_beyond_4_gib(mode):
     m.close()
 
 
+def test_dynamic_width_512_at_the_full_size_of_the_largest_workload():
+    """The C5 network with on-line scales on as many coordinates as its grid has (4.2 million: 128 passes for every
+    workgroup of the per-layer kernels, each whole-batch buffer 8.6 GB), in the launch configuration bench.py
+    times with --variant dynamic.  The batch is 128 copies of one block of 32 813 coordinates of the grid plus a
+    ragged piece, so that the oracle's calibrating forward on the block gives the scales and every expected value."""
+    torch = _torch()
+    wl, coords, W, b = synth.make("C5")
+    nb, copies, tail = 32768 + 45, 128, 19
+    block = np.ascontiguousarray(coords[::127][:nb])
+    assert block.shape[0] == nb
+    _say(f"dynamic width 512 at full size, n = {nb * copies + tail}")
+    net = o.quantize_net(wl.dims, wl.omega0, 8, 8, W, b)
+    exp = o.forward(net, block, calibrate=True)
+    xb = _dev(block)
+    x = torch.cat([xb] * copies + [xb[:tail]])
+    m = dhq.Model(wl.dims, wl.omega0, W, b)
+    dyn = m.forward(x, flags=dhq.DHQ_FUSED | dhq.DHQ_DYNAMIC)
+    s_dyn = m.dynamic_scales()
+    m.set_act_scales(s_dyn)
+    m.select_wide_kernel(2)
+    sta = m.forward(x, flags=dhq.DHQ_FUSED)
+    torch.cuda.synchronize()
+    first = dyn[:nb]
+    for k in range(1, copies):
+        assert bool((dyn[k * nb:(k + 1) * nb] == first).all()), f"copy {k}"
+    assert bool((dyn[copies * nb:] == first[:tail]).all()), "ragged piece"
+    assert bool((dyn == sta).all())
+    rel = np.abs(s_dyn.astype(np.float64) - net.s_a) / net.s_a
+    _say(f"  scale rel err vs oracle max {rel.max():.2e}")
+    assert rel.max() <= 1e-5
+    _gate(first.cpu().numpy(), exp, wl.dims, False, "per-layer kernels at full size, first block vs oracle")
+    m.close()
+
+
 def test_dynamic_scales_follow_the_batch_and_workspace_grows():
     torch = _torch()
     wl, coords, W, b = synth.make("C2")
