@@ -33,7 +33,7 @@ VALU_LANE_RATE = 256 * 4 * 16 * 2.4e9  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 
 TRAFFIC_SOURCES = ("dhq_fused.hip", "dhq_fused_pair.hip", "dhq_fused_common.h", "dhq_device.h")
 TRAFFIC_SHA256 = "65b13a8ddb13a56b6236e6b308681aa04ecb6c6338faa39a6fb6bfdb11c2315a"
 TRAFFIC_BYTES = {"C2": 2593792 + 786432, "C5": 45164544 + 50331648}
-COUNTER_BUSY = {"C2": {"valu": 0.655, "mfma": 0.260}, "C4": {"valu": 0.889, "mfma": 0.370}, "C5": {"valu": 0.691, "mfma": 0.435}}
+COUNTER_BUSY = {"C2": {"valu": 0.655, "mfma": 0.260}, "C4": {"valu": 0.886, "mfma": 0.369}, "C5": {"valu": 0.693, "mfma": 0.437}}
 
 
 def kernel_sources_sha256():
