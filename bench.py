@@ -307,6 +307,14 @@ def main() -> int:
         for l in range(len(wl.dims) - 1):
             K, M = wl.dims[l], wl.dims[l + 1]
             per_coord += 4 * K * (2 if dynamic else 1) + 2 * p2(K) + 4 * M + (8 * p2(M) if two_sided else 0)
+        if two_sided and not dynamic:
+            # static scales: a layer's un-rotation kernel also rotates and quantizes the next layer's input, so only
+            # the coordinates, codes and rotated accumulators cross device memory
+            nl = len(wl.dims) - 1
+            per_coord = 4 * wl.dims[0] + p2(wl.dims[0])
+            for l in range(nl):
+                K, M = wl.dims[l], wl.dims[l + 1]
+                per_coord += p2(K) + 8 * p2(M) + (p2(M) if l < nl - 1 else 4 * M)
         if dyn_fused:
             # one kernel per layer: the coordinates are read twice (scale of the input layer, then the layer),
             # every hidden boundary is one write and one read of the transformed activations (fp32)

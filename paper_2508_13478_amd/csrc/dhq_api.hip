@@ -601,11 +601,27 @@ static hipError_t run_layers(const dhq_model *m, const layer_ws &ws, const float
 {
     const float *cur = in;
     int which = 0;
+    // Two-sided variant, whole network: a layer's un-rotation kernel goes on to rotate and quantize the next layer's
+    // input in the same lanes, so between two layers only codes and rotated accumulators cross device memory.
+    // (Not for a prefix of the network, whose last activations the caller wants, nor for the complex wavelet,
+    // whose activation is a kernel of its own.)
+    const bool chain = m->rot_out && upto == m->n_layers && m->act_kind != DHQ_ACT_KIND_WAVELET_COMPLEX;
     for (int l = 0; l < upto; ++l) {
         const dhq_layer &Ly = m->layer[l];
         const bool last = (l == m->n_layers - 1);
-        hipError_t e = dhq_launch_wht_quant(cur, rows, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, ws.codes, nullptr, st);
-        if (e != hipSuccess) return e;
+        hipError_t e = hipSuccess;
+        if (!(chain && l > 0)) {
+            e = dhq_launch_wht_quant(cur, rows, Ly.K, Ly.Kp, quant_inv(Ly), m->qmax_a, ws.codes, nullptr, st);
+            if (e != hipSuccess) return e;
+        }
+        if (chain && !last) {
+            e = dhq_launch_gemm(Ly, ws.codes, rows, ws.acc, nullptr, 0.0f, nullptr, dhq_act{DHQ_ACT_KIND_NONE, 0.f}, nullptr, st);
+            if (e != hipSuccess) return e;
+            e = dhq_launch_unrotate_quant(ws.acc, rows, Ly.Mp, Ly.M, dhq_c1(m, l), Ly.bias_rev_dev, dhq_layer_act(m, l),
+                                          quant_inv(m->layer[l + 1]), m->qmax_a, ws.codes, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         float *dst = (last && final_out) ? final_out : ws.act[which];
         e = gemm_epilogue(m, l, ws.codes, rows, ws.acc, nullptr, dst, st);
         if (e != hipSuccess) return e;

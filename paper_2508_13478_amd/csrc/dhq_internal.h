@@ -130,6 +130,11 @@ hipError_t dhq_launch_gemm(const dhq_layer &L, const int8_t *codes, int64_t n, i
 hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, dhq_act act,
                                const float *dyn, int32_t *z_out, float *act_out, hipStream_t st);
 
+// Two-sided variant, static scales: un-rotation and epilogue of a layer (sine or wavelet) and, in the same lanes, the
+// rotation and quantizer of the next layer (whose rotated length is Mp): codes = n x Mp int8.
+hipError_t dhq_launch_unrotate_quant(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, dhq_act act,
+                                     float inv_next, int qmax, int8_t *codes, hipStream_t st);
+
 // The first of the two launches of dhq_launch_wht_absmax only: partial[0 .. *count) holds the
 // workgroups' maxima and the caller folds them.
 hipError_t dhq_launch_wht_absmax_partials(const float *in, int64_t n, int K, int Kp, float *partial, int *count,

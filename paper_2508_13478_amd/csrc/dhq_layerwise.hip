@@ -9,6 +9,8 @@
 //   epilogue    dequantize + bias + sine from stored accumulators
 //   unrotate    two-sided variant (Eq. 4-5 with both factors): multiplies the rotated
 //               accumulators by H over the output features, exactly in int32, then the epilogue
+//   unrotate_quant  the same, going on to the next layer's rotation and quantizer in the same lanes
+//               (static scales: rotated accumulators in, the next layer's codes out)
 //   dyn_scale   on-line per-tensor scale (the dynamic quantization module of Sec. 3.3): the per-workgroup
 //               maxima of a layer input become the constants the kernels read -- folded by the quantizing
 //               kernel itself in a forward pass, by a one-workgroup kernel during calibration
@@ -731,6 +733,92 @@ hipError_t dhq_launch_unrotate(const int32_t *acc, int64_t n, int Mp, int M, flo
         case 128: return launch_unrotate<128>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
         case 256: return launch_unrotate<256>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
         case 512: return launch_unrotate<512>(acc, n, M, c1, bias, act, dyn, z_out, act_out, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Two-sided variant, static scales: the un-rotation and epilogue of a layer fused with the rotation and
+// quantizer of the next one.  Both are transforms of one row with the same lane layout (the next layer's
+// rotated length is this layer's padded fan-out), so the layer's activations stay in the lanes' registers
+// instead of crossing device memory as fp32: rotated accumulators in, the next layer's codes out.
+// The arithmetic is that of unrotate_epilogue_kernel followed by wht_quant_kernel (same functions, same order).
+template <int MP, int KIND>
+__global__ __launch_bounds__(256) void unrotate_quant_kernel(const int32_t *__restrict__ acc, int64_t n, int M, float c1,
+                                                             const float *__restrict__ bias, float c2, float inv_next, int qmax,
+                                                             int8_t *__restrict__ codes)
+{
+    using S = wht_shape<MP>;
+    constexpr int EPL = S::EPL;
+    constexpr int LPR = S::LPR;
+    const dhq_act act{KIND, c2};
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = gtid / LPR;
+    const int t = (int)(gtid % LPR);
+    const bool live = row < n;
+    int v[EPL];
+    if (live && EPL >= 4) {
+#pragma unroll
+        for (int g = 0; g < EPL / 4; ++g) {
+            const int4 x = *reinterpret_cast<const int4 *>(acc + row * MP + S::index(t, 4 * g));
+            v[(4 * g) % EPL] = x.x; v[(4 * g + 1) % EPL] = x.y; v[(4 * g + 2) % EPL] = x.z; v[(4 * g + 3) % EPL] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) v[e] = live ? acc[row * MP + S::index(t, e)] : 0;
+    }
+    wht_butterflies<MP>(v, t);
+    // the layer's output: features beyond the fan-out are the zero padding of the next layer's input
+    float a[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int f = S::index(t, e);
+        a[e] = (live && f < M) ? dhq_epilogue(v[e], c1, bias[f], act) : 0.0f;
+    }
+    wht_butterflies<MP>(a, t);
+    if (!live) return;
+    if constexpr (EPL >= 4) {
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4) {
+            const unsigned w = dhq_pack4(dhq_quant_bits(a[e], inv_next, qmax), dhq_quant_bits(a[e + 1], inv_next, qmax),
+                                         dhq_quant_bits(a[e + 2], inv_next, qmax), dhq_quant_bits(a[e + 3], inv_next, qmax));
+            *reinterpret_cast<unsigned *>(codes + row * MP + S::index(t, e)) = w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) codes[row * MP + S::index(t, e)] = (int8_t)(dhq_quant_bits(a[e], inv_next, qmax) & 0xff);
+    }
+}
+
+template <int MP>
+static hipError_t launch_unrotate_quant(const int32_t *acc, int64_t n, int M, float c1, const float *bias, dhq_act act,
+                                        float inv_next, int qmax, int8_t *codes, hipStream_t st)
+{
+    constexpr int LPR = wht_shape<MP>::LPR;
+    const unsigned grid = (unsigned)((n * LPR + 255) / 256);
+    if (act.kind == DHQ_ACT_KIND_SINE)
+        unrotate_quant_kernel<MP, DHQ_ACT_KIND_SINE><<<grid, 256, 0, st>>>(acc, n, M, c1, bias, act.c2, inv_next, qmax, codes);
+    else if (act.kind == DHQ_ACT_KIND_WAVELET)
+        unrotate_quant_kernel<MP, DHQ_ACT_KIND_WAVELET><<<grid, 256, 0, st>>>(acc, n, M, c1, bias, act.c2, inv_next, qmax, codes);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t dhq_launch_unrotate_quant(const int32_t *acc, int64_t n, int Mp, int M, float c1, const float *bias, dhq_act act,
+                                     float inv_next, int qmax, int8_t *codes, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    switch (Mp) {
+        case 1: return launch_unrotate_quant<1>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 2: return launch_unrotate_quant<2>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 4: return launch_unrotate_quant<4>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 8: return launch_unrotate_quant<8>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 16: return launch_unrotate_quant<16>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 32: return launch_unrotate_quant<32>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 64: return launch_unrotate_quant<64>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 128: return launch_unrotate_quant<128>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 256: return launch_unrotate_quant<256>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
+        case 512: return launch_unrotate_quant<512>(acc, n, M, c1, bias, act, inv_next, qmax, codes, st);
         default: return hipErrorInvalidValue;
     }
 }
