@@ -265,12 +265,12 @@ def main() -> int:
     # byte-permute/or instructions per four codes.  The
     # transform: the fused kernels give its 32-row factor to the matrix unit (two vector
     # instructions to split an activation into binary16 pieces) and keep log2(n / 32) add/sub
-    # (width 512: plus one move out of the accumulation registers).
+    # (the one-wave width-512 kernel: plus one move out of the accumulation registers).
     # A SIMD issues one wave64 vector instruction per 4 clocks, i.e. 256 CUs x 4 SIMDs x 2.4 GHz / 4
     # per second.
     import math
     nf = wl.dims[1]
-    per_feature = 3 + 2 + math.log2(nf / 32) + (1 if nf == 512 else 0) + 2.75
+    per_feature = 3 + 2 + math.log2(nf / 32) + (1 if nf == 512 and args.wide_kernel == 1 else 0) + 2.75
     if two_sided:
         per_feature += math.log2(nf) + 0.5   # the integer un-rotation: log2(n) add/sub and half a lane swap
     lane_instr = sum(wl.dims[l + 1] for l in range(len(wl.dims) - 2)) * per_feature * n
